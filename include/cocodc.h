@@ -1,0 +1,208 @@
+/*
+ * cocodc.h -- C ABI of the MI355X (gfx950) library for the CoCoDC per-fragment
+ * outer-synchronisation path (Zhu et al., "Cross-region Model Training with
+ * Communication-Computation Overlapping and Delay Compensation").
+ *
+ * What the path computes, once per fragment synchronisation (paper Sec. 2 and 3):
+ *   - the local pseudo-gradient of a fragment (Sec. 2.1, text before Eq. 1),
+ *   - the outer-optimiser update of the fragment's global state from the averaged,
+ *     delayed global pseudo-gradient (Eq. 2; SGD with Nesterov momentum),
+ *   - the Taylor delay-compensation merge into the local parameters (Algorithm 1,
+ *     Eq. 4, 7, 8),
+ *   - the adaptive-transmission change score of each fragment (Eq. 11) and the choice
+ *     of the next fragments to send (Algorithm 2, Eq. 12).
+ * The cross-worker average of Eq. 1 is an INPUT (delta_g); no collective is issued.
+ *
+ * ---------------------------------------------------------------------------------
+ * Conventions that hold for every entry point
+ * ---------------------------------------------------------------------------------
+ * Buffers.  Parameter-like buffers (theta_m, theta_m_send, theta_g, momentum, delta_g,
+ *   delta_m_out, x) are DEVICE pointers to flat fp32 arrays of n_total elements.  A
+ *   fragment is the contiguous element range [offset, offset+length) of every such
+ *   buffer (Sec. 2.1: K disjoint fragments along the depth of the model).  R_out,
+ *   sums_out, sel_out and n_sel_out are DEVICE pointers.  The fragment table, I_p,
+ *   t_b and the hyper-parameter struct are HOST pointers; they are consumed before the
+ *   call returns and may be freed or changed right after it.
+ * Ownership.  The caller owns every buffer, including the workspace.  The library
+ *   allocates no device memory.  A workspace of cocodc_workspace_bytes(K, n_total)
+ *   bytes, 256-byte aligned, holds the device copy of the fragment table and the
+ *   partial sums; it carries no state between calls, but two calls that are in flight
+ *   at the same time (different streams) must use different workspaces.
+ * Alignment.  fp32 buffers must be 4-byte aligned.  When all of them are 16-byte
+ *   aligned the kernels use 128-bit accesses (fragment offsets may still be odd: the
+ *   unaligned head and tail of a fragment are handled element-wise); otherwise a
+ *   slower element-wise variant of the same kernel runs.  Results are identical.
+ * Aliasing.  Distinct arguments must not overlap, with one exception: delta_m_out may
+ *   be exactly delta_g (the all-reduce buffer is reused in place).
+ * Streams.  `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *   All work is enqueued on it and the call returns without synchronising.
+ * Errors.  Every function returns COCODC_OK (0) or a negative cocodc_status_t.
+ *   Arguments are validated on the host before anything is enqueued: on an error
+ *   other than COCODC_ERR_HIP nothing has been launched and no buffer was touched.
+ *   Device-side NaN/Inf values are not errors: they propagate as IEEE arithmetic
+ *   dictates, and a NaN score ranks last in the selection.
+ * Arithmetic.  Every fp32 input is widened to fp64, the update is evaluated in fp64
+ *   registers and each stored fp32 value is rounded once.  Per-fragment sums are
+ *   accumulated in fp64 in a fixed order that depends only on the fragment table, so
+ *   repeated calls on the same bytes give bit-identical scores and selections (the
+ *   property Sec. 3.2 relies on for coordination-free selection).
+ * Limits.  1 <= K <= COCODC_MAX_FRAGMENTS.
+ */
+#ifndef COCODC_H
+#define COCODC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define COCODC_MAX_FRAGMENTS 1024
+
+typedef enum {
+  COCODC_OK = 0,
+  COCODC_ERR_NULL = -1,      /* a required pointer is NULL                                */
+  COCODC_ERR_ALIGN = -2,     /* fp32 buffer not 4-byte, R/sums not 8-byte, workspace not  */
+                             /* 256-byte aligned                                          */
+  COCODC_ERR_RANGE = -3,     /* K, tau, H, budget, enum-like field, or fragment table     */
+                             /* (out of n_total, overlapping) out of range                */
+  COCODC_ERR_NONFINITE = -4, /* lambda, eta, mu or alpha is NaN or infinite               */
+  COCODC_ERR_WORKSPACE = -5, /* workspace_bytes < cocodc_workspace_bytes(K, n_total)      */
+  COCODC_ERR_HIP = -6,       /* a HIP runtime call failed; see cocodc_last_hip_error()    */
+  COCODC_ERR_ALIAS = -7      /* two buffers overlap where the contract forbids it         */
+} cocodc_status_t;
+
+/* One fragment theta_p: a contiguous element range of every flat buffer (Sec. 2.1). */
+typedef struct {
+  uint64_t offset; /* first element                                    */
+  uint64_t length; /* number of elements; 0 is allowed (empty fragment) */
+} cocodc_fragment_t;
+
+/* Hyper-parameters, in the paper's notation. */
+typedef struct {
+  int32_t tau;        /* overlap depth tau >= 0: inner steps the all-reduce took (Sec. 2.1) */
+  int32_t H;          /* local computation period H >= 1 (Sec. 2.1; divisor in Eq. 5-7)     */
+  double lambda;      /* compensation strength lambda (Eq. 7)                               */
+  double eta;         /* learning rate of the outer optimiser (Eq. 2)                       */
+  double mu;          /* momentum of the outer optimiser (Eq. 2)                            */
+  int32_t nesterov;   /* 1 = Nesterov look-ahead (the paper's example), 0 = heavy-ball      */
+  int32_t drift_sign; /* +1: change rate exactly as Eq. 4 prints it (send-time minus        */
+                      /*     current local); -1: current minus send-time                    */
+  int32_t score_src;  /* 0: score ||delta_g||, Eq. 11; 1: score the local drift over the    */
+                      /*    overlap (same kernel, other sum)                                */
+  int32_t norm_kind;  /* 2: L2 norm (Eq. 11); 1: L1 norm                                    */
+  int32_t merge_mode; /* 0: delay compensation (Eq. 8); 1: Streaming-DiLoCo blend (Eq. 3);  */
+                      /* 2: adopt the new global state (blocking DiLoCo)                    */
+  double alpha;       /* mixing factor of Eq. 3; read only when merge_mode == 1             */
+} cocodc_hparams_t;
+
+/* Bytes of device workspace that any entry point below needs for (K, n_total).
+ * Returns 0 if K is outside [1, COCODC_MAX_FRAGMENTS]. */
+size_t cocodc_workspace_bytes(int32_t K, uint64_t n_total);
+
+/* Local pseudo-gradient (Sec. 2.1, text before Eq. 1), in the descent sign convention
+ * used throughout this library: delta_m_out[i] = theta_g_snap[i] - theta_m[i]
+ * (the negative of the summand of Eq. 1), for every i of every listed fragment.
+ * If theta_m_send_out is not NULL it also records theta_m_send_out[i] = theta_m[i],
+ * the send-time copy theta^m_{p,t_p} that Algorithm 1 needs tau steps later.
+ * Elements outside the listed fragments are not touched. */
+int cocodc_pseudograd(const cocodc_fragment_t* frags, int32_t K, uint64_t n_total,
+                      const float* theta_g_snap, const float* theta_m, float* delta_m_out,
+                      float* theta_m_send_out /* nullable */, void* workspace,
+                      size_t workspace_bytes, void* stream);
+
+/* Outer optimiser, Eq. 2, as SGD with momentum on the "gradient" delta_g:
+ *   m' = mu*m + delta_g ;  step = nesterov ? delta_g + mu*m' : m' ;
+ *   theta_g <- theta_g - eta*step.
+ * In place: theta_g holds theta^g_{p,t_p-H} on entry and theta^g_{p,t_p} on exit;
+ * momentum is updated to m'. */
+int cocodc_outer_nesterov(const cocodc_fragment_t* frags, int32_t K, uint64_t n_total,
+                          float* theta_g, float* momentum, const float* delta_g,
+                          const cocodc_hparams_t* hp, void* workspace, size_t workspace_bytes,
+                          void* stream);
+
+/* Delay-compensation merge, Algorithm 1.  With d = drift_sign*(theta_m_send - theta_m)
+ * (= tau times the change rate g of Eq. 4) and Delta = theta_g - theta_m_send (the
+ * difference introduced with Eq. 5), element by element:
+ *   theta_m <- theta_g + d + lambda * d*d*Delta / (tau*H)      (Eq. 7 put into Eq. 8)
+ * The last term is dropped when tau == 0.  merge_mode 1 computes Eq. 3 instead,
+ * merge_mode 2 copies theta_g.  theta_g must already be the NEW global state. */
+int cocodc_delay_compensate(const cocodc_fragment_t* frags, int32_t K, uint64_t n_total,
+                            float* theta_m, const float* theta_m_send, const float* theta_g,
+                            const cocodc_hparams_t* hp, void* workspace, size_t workspace_bytes,
+                            void* stream);
+
+/* Change score, Eq. 11: R_out[p] = norm(x over fragment p) / I_p[p], and +inf when
+ * I_p[p] <= 0 (a fragment that never completed a synchronisation, Sec. 3.2).
+ * x: any flat fp32 buffer (normally delta_g).  I_p: host, K entries.  R_out: device, K
+ * doubles.  sum_out (device, K doubles, nullable): the raw fp64 sum (of squares for
+ * norm_kind 2, of magnitudes for norm_kind 1). */
+int cocodc_fragment_scores(const cocodc_fragment_t* frags, int32_t K, uint64_t n_total,
+                           const float* x, const int64_t* I_p, int32_t norm_kind, double* R_out,
+                           double* sum_out /* nullable */, void* workspace,
+                           size_t workspace_bytes, void* stream);
+
+/* Fragment selection, Algorithm 2 / Eq. 12, applied `budget` times without replacement:
+ * first every fragment with t_g - t_b[p] >= H in ascending p, then the remaining ones by
+ * descending R[p] (ties: lower p; NaN last).  Writes n = min(budget, K) indices to
+ * sel_out (device, >= n int32) and n to n_sel_out (device).  R: device, K doubles.
+ * t_b: host, K entries (step at which fragment p last completed a synchronisation). */
+int cocodc_select_fragments(int32_t K, const double* R, const int64_t* t_b, int64_t t_g, int32_t H,
+                            int32_t budget, int32_t* sel_out, int32_t* n_sel_out, void* workspace,
+                            size_t workspace_bytes, void* stream);
+
+/* The whole path in one pass over memory: every element of every listed fragment is
+ * read once from theta_m, theta_m_send, theta_g, momentum, delta_g and written once to
+ * theta_m, theta_g, momentum (and delta_m_out if not NULL).  Equivalent, bit for bit,
+ * to cocodc_pseudograd(theta_m_send_out = NULL) -> cocodc_outer_nesterov ->
+ * cocodc_delay_compensate -> cocodc_fragment_scores(delta_g) ->
+ * cocodc_select_fragments when score_src == 0.
+ *   delta_m_out: nullable; may be exactly delta_g.
+ *   I_p, t_b:    host, K entries each.      t_g: current global step.
+ *   R_out:       device, K doubles.         sel_out / n_sel_out: as above.
+ *   sums_out:    device, 4*K doubles, nullable: per fragment
+ *                {sum delta_g^2, sum |delta_g|, sum d^2, sum |d|}.
+ * It does not modify theta_m_send, I_p or t_b: recording a send belongs to the moment
+ * the caller launches the next all-reduce (cocodc_pseudograd does it). */
+int cocodc_sync_step(const cocodc_fragment_t* frags, int32_t K, uint64_t n_total, float* theta_m,
+                     const float* theta_m_send, float* theta_g, float* momentum,
+                     const float* delta_g, float* delta_m_out /* nullable */, const int64_t* I_p,
+                     const int64_t* t_b, int64_t t_g, int32_t budget, const cocodc_hparams_t* hp,
+                     double* R_out, int32_t* sel_out, int32_t* n_sel_out,
+                     double* sums_out /* nullable */, void* workspace, size_t workspace_bytes,
+                     void* stream);
+
+/* Host-only planner, Eq. 9 and Eq. 10: N = max(K, floor(gamma*H*T_c/T_s)) target
+ * synchronisations per H steps and h = floor(H/N) steps between two sends.
+ * gamma in (0,1]; T_c, T_s > 0 (any common unit).  No GPU work. */
+int cocodc_sync_plan(int32_t K, int32_t H, double gamma, double T_c, double T_s, int64_t* N_out,
+                     int64_t* h_out);
+
+/* ---- diagnostics and measurement aids (no paper counterpart) ---- */
+
+/* hipError_t of the most recent failing HIP call on this thread (0 if none). */
+int cocodc_last_hip_error(void);
+
+/* Static, human-readable name of a status code. */
+const char* cocodc_status_string(int status);
+
+/* Launch shape of the streaming kernels: blocks_per_cu > 0 launches a persistent grid
+ * of (compute units x blocks_per_cu) workgroups that stride over the tiles; 0 launches
+ * one workgroup per tile.  Results never depend on it.  Returns the previous value. */
+int cocodc_set_blocks_per_cu(int blocks_per_cu);
+
+/* Kernel timer for benchmarks.  After cocodc_profiler_enable(n) every cocodc_sync_step
+ * call brackets its fused elementwise kernel with a pair of HIP events on the caller's
+ * stream (up to n calls).  cocodc_profiler_collect synchronises those events, writes
+ * up to `capacity` per-call durations in milliseconds to ms_out (host) and returns how
+ * many it wrote; cocodc_profiler_disable releases the events.  Process-wide state:
+ * not for concurrent use from several threads. */
+int cocodc_profiler_enable(int32_t max_records);
+int cocodc_profiler_collect(float* ms_out, int32_t capacity);
+int cocodc_profiler_disable(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* COCODC_H */

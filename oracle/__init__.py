@@ -1,0 +1,172 @@
+"""ctypes front end of the CPU oracle (oracle/cocodc_ref.cpp).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by the smoke check and by the benchmark's
+CPU-baseline leg.  The product package never imports this module, and this module never
+imports the product package.  It only marshals numpy arrays into the C functions; all
+arithmetic lives in cocodc_ref.cpp.
+
+All arrays are host numpy arrays: float32 and C-contiguous for parameter buffers (updated
+in place where the C function updates in place), int64 for I_p / t_b, float64 for scores.
+"""
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libcocodc_ref.so")
+_lib = None
+
+
+class Fragment(C.Structure):
+    _fields_ = [("offset", C.c_uint64), ("length", C.c_uint64)]
+
+
+class HParams(C.Structure):
+    _fields_ = [
+        ("tau", C.c_int32), ("H", C.c_int32),
+        ("lambda_", C.c_double), ("eta", C.c_double), ("mu", C.c_double),
+        ("nesterov", C.c_int32), ("drift_sign", C.c_int32),
+        ("score_src", C.c_int32), ("norm_kind", C.c_int32),
+        ("merge_mode", C.c_int32), ("alpha", C.c_double),
+    ]
+
+
+class Shadow(C.Structure):
+    _fields_ = [("theta_m", C.c_void_p), ("theta_g", C.c_void_p), ("momentum", C.c_void_p)]
+
+
+def hparams(tau, H, lam=0.5, eta=0.7, mu=0.9, nesterov=1, drift_sign=1, score_src=0, norm_kind=2,
+            merge_mode=0, alpha=1.0):
+    return HParams(int(tau), int(H), float(lam), float(eta), float(mu), int(nesterov),
+                   int(drift_sign), int(score_src), int(norm_kind), int(merge_mode), float(alpha))
+
+
+def lib():
+    """Load (building it first if it is missing) the oracle shared library."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            from . import build as _build
+            _build.build(force=True)
+        _lib = C.CDLL(_LIB_PATH)
+        for name in ("pseudograd", "outer_nesterov", "delay_compensate", "fragment_scores",
+                     "select_fragments", "sync_step", "sync_step_mt", "sync_plan"):
+            getattr(_lib, "cocodc_ref_" + name).restype = C.c_int
+    return _lib
+
+
+def _frag_array(frags):
+    arr = (Fragment * len(frags))()
+    for i, (off, length) in enumerate(frags):
+        arr[i].offset = int(off)
+        arr[i].length = int(length)
+    return arr
+
+
+def _f32(a, allow_none=False):
+    if a is None:
+        assert allow_none
+        return None
+    assert isinstance(a, np.ndarray) and a.dtype == np.float32 and a.flags["C_CONTIGUOUS"]
+    return C.c_void_p(a.ctypes.data)
+
+
+def _i64(a):
+    a = np.ascontiguousarray(a, dtype=np.int64)
+    return a, C.c_void_p(a.ctypes.data)
+
+
+def pseudograd(frags, theta_g_snap, theta_m, delta_m_out, theta_m_send_out=None):
+    n = theta_m.size
+    return lib().cocodc_ref_pseudograd(_frag_array(frags), C.c_int32(len(frags)), C.c_uint64(n),
+                                       _f32(theta_g_snap), _f32(theta_m), _f32(delta_m_out),
+                                       _f32(theta_m_send_out, True))
+
+
+def outer_nesterov(frags, theta_g, momentum, delta_g, hp):
+    n = theta_g.size
+    return lib().cocodc_ref_outer_nesterov(_frag_array(frags), C.c_int32(len(frags)), C.c_uint64(n),
+                                           _f32(theta_g), _f32(momentum), _f32(delta_g),
+                                           C.byref(hp))
+
+
+def delay_compensate(frags, theta_m, theta_m_send, theta_g, hp):
+    n = theta_m.size
+    return lib().cocodc_ref_delay_compensate(_frag_array(frags), C.c_int32(len(frags)),
+                                             C.c_uint64(n), _f32(theta_m), _f32(theta_m_send),
+                                             _f32(theta_g), C.byref(hp))
+
+
+def fragment_scores(frags, x, I_p, norm_kind=2):
+    """Returns (rc, R[K], sums[K])."""
+    K = len(frags)
+    R = np.zeros(K, dtype=np.float64)
+    S = np.zeros(K, dtype=np.float64)
+    keep, ip = _i64(I_p)
+    rc = lib().cocodc_ref_fragment_scores(_frag_array(frags), C.c_int32(K), C.c_uint64(x.size),
+                                          _f32(x), ip, C.c_int32(norm_kind),
+                                          C.c_void_p(R.ctypes.data), C.c_void_p(S.ctypes.data))
+    return rc, R, S
+
+
+def select_fragments(R, t_b, t_g, H, budget):
+    """Returns (rc, sel[n_sel])."""
+    R = np.ascontiguousarray(R, dtype=np.float64)
+    K = R.size
+    keep, tb = _i64(t_b)
+    sel = np.full(max(K, 1), -1, dtype=np.int32)
+    n_sel = C.c_int32(-1)
+    rc = lib().cocodc_ref_select_fragments(C.c_int32(K), C.c_void_p(R.ctypes.data), tb,
+                                           C.c_int64(t_g), C.c_int32(H), C.c_int32(budget),
+                                           C.c_void_p(sel.ctypes.data), C.byref(n_sel))
+    if rc != 0:
+        return rc, None
+    return rc, sel[:n_sel.value].copy()
+
+
+def sync_step(frags, theta_m, theta_m_send, theta_g, momentum, delta_g, delta_m_out, I_p, t_b, t_g,
+              budget, hp, shadow=False, n_threads=None):
+    """Fused step, in place on theta_m / theta_g / momentum (and delta_m_out).
+
+    Returns a dict: rc, R[K], sel[n_sel], sums[K,4] and, with shadow=True, the unrounded
+    fp64 theta_m / theta_g / momentum.  n_threads selects the chunk-parallel timing variant.
+    """
+    K = len(frags)
+    n = theta_m.size
+    R = np.zeros(K, dtype=np.float64)
+    sums = np.zeros((K, 4), dtype=np.float64)
+    sel = np.full(K, -1, dtype=np.int32)
+    n_sel = C.c_int32(-1)
+    keep1, ip = _i64(I_p)
+    keep2, tb = _i64(t_b)
+    out = {}
+    common = (_frag_array(frags), C.c_int32(K), C.c_uint64(n), _f32(theta_m), _f32(theta_m_send),
+              _f32(theta_g), _f32(momentum), _f32(delta_g), _f32(delta_m_out, True), ip, tb,
+              C.c_int64(t_g), C.c_int32(budget), C.byref(hp), C.c_void_p(R.ctypes.data),
+              C.c_void_p(sel.ctypes.data), C.byref(n_sel), C.c_void_p(sums.ctypes.data))
+    if n_threads is None:
+        sh_ptr = None
+        if shadow:
+            out["theta_m64"] = np.zeros(n, dtype=np.float64)
+            out["theta_g64"] = np.zeros(n, dtype=np.float64)
+            out["momentum64"] = np.zeros(n, dtype=np.float64)
+            sh = Shadow(out["theta_m64"].ctypes.data, out["theta_g64"].ctypes.data,
+                        out["momentum64"].ctypes.data)
+            sh_ptr = C.byref(sh)
+        rc = lib().cocodc_ref_sync_step(*common, sh_ptr)
+    else:
+        rc = lib().cocodc_ref_sync_step_mt(*common, C.c_int32(n_threads))
+        out["threads"] = rc
+        rc = 0 if rc > 0 else rc
+    out.update(rc=rc, R=R, sums=sums, sel=sel[:max(n_sel.value, 0)].copy())
+    return out
+
+
+def sync_plan(K, H, gamma, T_c, T_s):
+    """Returns (rc, N, h)."""
+    N = C.c_int64(0)
+    h = C.c_int64(0)
+    rc = lib().cocodc_ref_sync_plan(C.c_int32(K), C.c_int32(H), C.c_double(gamma), C.c_double(T_c),
+                                    C.c_double(T_s), C.byref(N), C.byref(h))
+    return rc, N.value, h.value

@@ -1,0 +1,347 @@
+// cocodc_ref.cpp -- CPU oracle (fp64, index order) for the CoCoDC outer-sync path.
+//
+// TEST INFRASTRUCTURE ONLY; see cocodc_ref.h.  Shares nothing with the HIP sources.
+// Build: g++ -O2 -ffp-contract=off -fopenmp -shared -fPIC (no fast-math: the order
+// and rounding of every operation below is part of the definition).
+//
+// Notation (paper Sec. 2 and 3):
+//   theta_g   : global state of a fragment; on entry theta^g_{p,t_p-H}, on exit theta^g_{p,t_p}
+//   theta_m   : the worker's current local parameters theta^m_{p,t_l}
+//   theta_send: the local parameters recorded when the fragment was sent, theta^m_{p,t_p}
+//   delta_g   : the averaged global pseudo-gradient of Eq. 1, arriving tau steps late,
+//               in the sign convention "global minus local" (descent direction)
+//   m         : momentum buffer of the outer optimiser of Eq. 2
+
+#include "cocodc_ref.h"
+
+#include <cmath>
+#include <cstdint>
+#include <limits>
+#include <vector>
+
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+namespace {
+
+constexpr int kOk = 0;
+constexpr int kErrNull = -1;
+constexpr int kErrRange = -3;
+
+int check_table(const cocodc_ref_fragment_t* frags, int32_t K, uint64_t n_total) {
+  if (frags == nullptr) return kErrNull;
+  if (K < 1) return kErrRange;
+  for (int32_t p = 0; p < K; ++p) {
+    if (frags[p].offset > n_total || frags[p].length > n_total - frags[p].offset) return kErrRange;
+  }
+  for (int32_t p = 0; p < K; ++p) {
+    for (int32_t q = p + 1; q < K; ++q) {
+      if (frags[p].length == 0 || frags[q].length == 0) continue;
+      const uint64_t a0 = frags[p].offset, a1 = a0 + frags[p].length;
+      const uint64_t b0 = frags[q].offset, b1 = b0 + frags[q].length;
+      if (a0 < b1 && b0 < a1) return kErrRange;  // fragments must be disjoint
+    }
+  }
+  return kOk;
+}
+
+int check_hparams(const cocodc_ref_hparams_t* hp) {
+  if (hp == nullptr) return kErrNull;
+  if (hp->tau < 0 || hp->H < 1) return kErrRange;
+  if (hp->drift_sign != 1 && hp->drift_sign != -1) return kErrRange;
+  if (hp->score_src != 0 && hp->score_src != 1) return kErrRange;
+  if (hp->norm_kind != 1 && hp->norm_kind != 2) return kErrRange;
+  if (hp->merge_mode < 0 || hp->merge_mode > 2) return kErrRange;
+  if (!std::isfinite(hp->lambda) || !std::isfinite(hp->eta) || !std::isfinite(hp->mu) ||
+      !std::isfinite(hp->alpha))
+    return kErrRange;
+  return kOk;
+}
+
+// Eq. 2, OuterOptim = SGD with momentum mu and learning rate eta applied to the
+// "gradient" delta_g:  m' = mu*m + delta_g ; step = delta_g + mu*m' (Nesterov) or m' ;
+// theta^g_{p,t_p} = theta^g_{p,t_p-H} - eta*step.  Returns the unrounded new state.
+inline double outer_update(double theta_g_old, double m_old, double dg,
+                           const cocodc_ref_hparams_t& hp, double* m_new) {
+  const double m1 = hp.mu * m_old + dg;
+  const double step = hp.nesterov ? (dg + hp.mu * m1) : m1;
+  *m_new = m1;
+  return theta_g_old - hp.eta * step;
+}
+
+// d = tau * g, with g the change rate of Eq. 4: g = (theta^m_{p,t_p} - theta^m_{p,t_l}) / tau.
+inline double drift_times_tau(double theta_send, double theta_m, const cocodc_ref_hparams_t& hp) {
+  return static_cast<double>(hp.drift_sign) * (theta_send - theta_m);
+}
+
+// The merge of the new global state G (already rounded to fp32) into the local
+// parameters.  merge_mode 0 is Algorithm 1:
+//   Eq. 4:  g      = d / tau
+//   Eq. 7:  g_corr = g + lambda * g*g * Delta / H,  Delta = G - theta_send (the difference
+//           defined with Eq. 5), products taken element by element
+//   Eq. 8:  theta^m_{p,t_l} <- G + g_corr * tau = G + d + lambda * d*d*Delta / (tau*H)
+// Written in terms of d so that tau = 0 (no overlap, hence d = 0) needs no division.
+inline double merge_local(double G, double theta_send, double theta_m, double d,
+                          const cocodc_ref_hparams_t& hp) {
+  if (hp.merge_mode == 1) return (1.0 - hp.alpha) * theta_m + hp.alpha * G;  // Eq. 3
+  if (hp.merge_mode == 2) return G;  // blocking DiLoCo: adopt the global state
+  const double Delta = G - theta_send;
+  double corr = 0.0;
+  if (hp.tau >= 1) {
+    const double tauH = static_cast<double>(hp.tau) * static_cast<double>(hp.H);
+    corr = hp.lambda * d * d * Delta / tauH;
+  }
+  return G + d + corr;
+}
+
+struct Sums {
+  double g2 = 0.0, g1 = 0.0, d2 = 0.0, d1 = 0.0;
+};
+
+// One element of the fused step.  Reads everything first (delta_m_out may alias delta_g).
+inline void sync_element(uint64_t i, float* theta_m, const float* theta_send, float* theta_g,
+                         float* momentum, const float* delta_g, float* delta_m_out,
+                         const cocodc_ref_hparams_t& hp, Sums* s, const cocodc_ref_shadow_t* sh) {
+  const double tg = theta_g[i], tm = theta_m[i], ts = theta_send[i];
+  const double m0 = momentum[i], dg = delta_g[i];
+
+  const float pg = static_cast<float>(tg - tm);  // pseudo-gradient, global minus local
+
+  double m1;
+  const double G64 = outer_update(tg, m0, dg, hp, &m1);
+  const float G = static_cast<float>(G64);  // what an unfused caller would read back
+
+  const double d = drift_times_tau(ts, tm, hp);
+  const double tm_new = merge_local(static_cast<double>(G), ts, tm, d, hp);
+
+  s->g2 += dg * dg;  // Eq. 11 numerator, squared
+  s->g1 += std::fabs(dg);
+  s->d2 += d * d;
+  s->d1 += std::fabs(d);
+
+  if (delta_m_out) delta_m_out[i] = pg;
+  momentum[i] = static_cast<float>(m1);
+  theta_g[i] = G;
+  theta_m[i] = static_cast<float>(tm_new);
+  if (sh) {
+    if (sh->theta_m) sh->theta_m[i] = tm_new;
+    if (sh->theta_g) sh->theta_g[i] = G64;
+    if (sh->momentum) sh->momentum[i] = m1;
+  }
+}
+
+// Eq. 11 from the accumulated sums.
+inline double score_from_sums(const Sums& s, int64_t I_p, const cocodc_ref_hparams_t& hp) {
+  if (I_p <= 0) return std::numeric_limits<double>::infinity();
+  const double s2 = hp.score_src ? s.d2 : s.g2;
+  const double s1 = hp.score_src ? s.d1 : s.g1;
+  const double norm = (hp.norm_kind == 2) ? std::sqrt(s2) : s1;
+  return norm / static_cast<double>(I_p);
+}
+
+}  // namespace
+
+extern "C" {
+
+int cocodc_ref_pseudograd(const cocodc_ref_fragment_t* frags, int32_t K, uint64_t n_total,
+                          const float* theta_g_snap, const float* theta_m, float* delta_m_out,
+                          float* theta_m_send_out) {
+  if (!theta_g_snap || !theta_m || !delta_m_out) return kErrNull;
+  if (int rc = check_table(frags, K, n_total)) return rc;
+  for (int32_t p = 0; p < K; ++p) {
+    for (uint64_t i = frags[p].offset; i < frags[p].offset + frags[p].length; ++i) {
+      const double tg = theta_g_snap[i], tm = theta_m[i];
+      delta_m_out[i] = static_cast<float>(tg - tm);
+      if (theta_m_send_out) theta_m_send_out[i] = theta_m[i];
+    }
+  }
+  return kOk;
+}
+
+int cocodc_ref_outer_nesterov(const cocodc_ref_fragment_t* frags, int32_t K, uint64_t n_total,
+                              float* theta_g, float* momentum, const float* delta_g,
+                              const cocodc_ref_hparams_t* hp) {
+  if (!theta_g || !momentum || !delta_g) return kErrNull;
+  if (int rc = check_table(frags, K, n_total)) return rc;
+  if (int rc = check_hparams(hp)) return rc;
+  for (int32_t p = 0; p < K; ++p) {
+    for (uint64_t i = frags[p].offset; i < frags[p].offset + frags[p].length; ++i) {
+      double m1;
+      const double G = outer_update(theta_g[i], momentum[i], delta_g[i], *hp, &m1);
+      momentum[i] = static_cast<float>(m1);
+      theta_g[i] = static_cast<float>(G);
+    }
+  }
+  return kOk;
+}
+
+int cocodc_ref_delay_compensate(const cocodc_ref_fragment_t* frags, int32_t K, uint64_t n_total,
+                                float* theta_m, const float* theta_m_send, const float* theta_g,
+                                const cocodc_ref_hparams_t* hp) {
+  if (!theta_m || !theta_m_send || !theta_g) return kErrNull;
+  if (int rc = check_table(frags, K, n_total)) return rc;
+  if (int rc = check_hparams(hp)) return rc;
+  for (int32_t p = 0; p < K; ++p) {
+    for (uint64_t i = frags[p].offset; i < frags[p].offset + frags[p].length; ++i) {
+      const double tm = theta_m[i], ts = theta_m_send[i], G = theta_g[i];
+      const double d = drift_times_tau(ts, tm, *hp);
+      theta_m[i] = static_cast<float>(merge_local(G, ts, tm, d, *hp));
+    }
+  }
+  return kOk;
+}
+
+int cocodc_ref_fragment_scores(const cocodc_ref_fragment_t* frags, int32_t K, uint64_t n_total,
+                               const float* x, const int64_t* I_p, int32_t norm_kind,
+                               double* R_out, double* sum_out) {
+  if (!x || !I_p || !R_out) return kErrNull;
+  if (int rc = check_table(frags, K, n_total)) return rc;
+  if (norm_kind != 1 && norm_kind != 2) return kErrRange;
+  for (int32_t p = 0; p < K; ++p) {
+    double acc = 0.0;
+    for (uint64_t i = frags[p].offset; i < frags[p].offset + frags[p].length; ++i) {
+      const double v = x[i];
+      acc += (norm_kind == 2) ? v * v : std::fabs(v);
+    }
+    if (sum_out) sum_out[p] = acc;
+    const double norm = (norm_kind == 2) ? std::sqrt(acc) : acc;
+    R_out[p] = (I_p[p] <= 0) ? std::numeric_limits<double>::infinity()
+                             : norm / static_cast<double>(I_p[p]);
+  }
+  return kOk;
+}
+
+// Algorithm 2, run `budget` times; a fragment already chosen in this call is skipped.
+// Each run: the first fragment (lowest index) not synchronised for at least H steps
+// wins; otherwise the fragment with the largest R_p, the first one on ties.  A NaN
+// score never beats a number (it can only be chosen when nothing else is left).
+int cocodc_ref_select_fragments(int32_t K, const double* R, const int64_t* t_b, int64_t t_g,
+                                int32_t H, int32_t budget, int32_t* sel_out, int32_t* n_sel_out) {
+  if (!R || !t_b || !sel_out || !n_sel_out) return kErrNull;
+  if (K < 1 || H < 1 || budget < 0) return kErrRange;
+  std::vector<char> taken(static_cast<size_t>(K), 0);
+  const int32_t n_sel = budget < K ? budget : K;
+  for (int32_t b = 0; b < n_sel; ++b) {
+    int32_t p_star = -1;
+    for (int32_t p = 0; p < K; ++p) {
+      if (taken[p]) continue;
+      if (t_g - t_b[p] >= static_cast<int64_t>(H)) {
+        p_star = p;
+        break;
+      }
+    }
+    if (p_star < 0) {
+      for (int32_t p = 0; p < K; ++p) {
+        if (taken[p]) continue;
+        if (p_star < 0) {
+          p_star = p;
+        } else if (std::isnan(R[p_star]) ? !std::isnan(R[p]) : (R[p] > R[p_star])) {
+          p_star = p;
+        }
+      }
+    }
+    taken[p_star] = 1;
+    sel_out[b] = p_star;
+  }
+  *n_sel_out = n_sel;
+  return kOk;
+}
+
+int cocodc_ref_sync_step(const cocodc_ref_fragment_t* frags, int32_t K, uint64_t n_total,
+                         float* theta_m, const float* theta_m_send, float* theta_g,
+                         float* momentum, const float* delta_g, float* delta_m_out,
+                         const int64_t* I_p, const int64_t* t_b, int64_t t_g, int32_t budget,
+                         const cocodc_ref_hparams_t* hp, double* R_out, int32_t* sel_out,
+                         int32_t* n_sel_out, double* sums_out, const cocodc_ref_shadow_t* shadow) {
+  if (!theta_m || !theta_m_send || !theta_g || !momentum || !delta_g) return kErrNull;
+  if (!I_p || !t_b || !R_out || !sel_out || !n_sel_out) return kErrNull;
+  if (int rc = check_table(frags, K, n_total)) return rc;
+  if (int rc = check_hparams(hp)) return rc;
+  if (budget < 0) return kErrRange;
+  for (int32_t p = 0; p < K; ++p) {
+    Sums s;
+    for (uint64_t i = frags[p].offset; i < frags[p].offset + frags[p].length; ++i) {
+      sync_element(i, theta_m, theta_m_send, theta_g, momentum, delta_g, delta_m_out, *hp, &s,
+                   shadow);
+    }
+    R_out[p] = score_from_sums(s, I_p[p], *hp);
+    if (sums_out) {
+      sums_out[4 * p + 0] = s.g2;
+      sums_out[4 * p + 1] = s.g1;
+      sums_out[4 * p + 2] = s.d2;
+      sums_out[4 * p + 3] = s.d1;
+    }
+  }
+  return cocodc_ref_select_fragments(K, R_out, t_b, t_g, hp->H, budget, sel_out, n_sel_out);
+}
+
+int cocodc_ref_sync_step_mt(const cocodc_ref_fragment_t* frags, int32_t K, uint64_t n_total,
+                            float* theta_m, const float* theta_m_send, float* theta_g,
+                            float* momentum, const float* delta_g, float* delta_m_out,
+                            const int64_t* I_p, const int64_t* t_b, int64_t t_g, int32_t budget,
+                            const cocodc_ref_hparams_t* hp, double* R_out, int32_t* sel_out,
+                            int32_t* n_sel_out, double* sums_out, int32_t n_threads) {
+  if (!theta_m || !theta_m_send || !theta_g || !momentum || !delta_g) return kErrNull;
+  if (!I_p || !t_b || !R_out || !sel_out || !n_sel_out) return kErrNull;
+  if (int rc = check_table(frags, K, n_total)) return rc;
+  if (int rc = check_hparams(hp)) return rc;
+  if (budget < 0) return kErrRange;
+  constexpr uint64_t kChunk = 65536;
+  int used = 1;
+#ifdef _OPENMP
+  if (n_threads > 0) omp_set_num_threads(n_threads);
+  used = omp_get_max_threads();
+#else
+  (void)n_threads;
+#endif
+  for (int32_t p = 0; p < K; ++p) {
+    const uint64_t off = frags[p].offset, len = frags[p].length;
+    const int64_t n_chunks = static_cast<int64_t>((len + kChunk - 1) / kChunk);
+    std::vector<Sums> part(static_cast<size_t>(n_chunks));
+#pragma omp parallel for schedule(static)
+    for (int64_t c = 0; c < n_chunks; ++c) {
+      const uint64_t lo = off + static_cast<uint64_t>(c) * kChunk;
+      const uint64_t hi = (lo + kChunk < off + len) ? lo + kChunk : off + len;
+      Sums s;
+      for (uint64_t i = lo; i < hi; ++i) {
+        sync_element(i, theta_m, theta_m_send, theta_g, momentum, delta_g, delta_m_out, *hp, &s,
+                     nullptr);
+      }
+      part[static_cast<size_t>(c)] = s;
+    }
+    Sums s;
+    for (int64_t c = 0; c < n_chunks; ++c) {
+      s.g2 += part[c].g2;
+      s.g1 += part[c].g1;
+      s.d2 += part[c].d2;
+      s.d1 += part[c].d1;
+    }
+    R_out[p] = score_from_sums(s, I_p[p], *hp);
+    if (sums_out) {
+      sums_out[4 * p + 0] = s.g2;
+      sums_out[4 * p + 1] = s.g1;
+      sums_out[4 * p + 2] = s.d2;
+      sums_out[4 * p + 3] = s.d1;
+    }
+  }
+  int rc = cocodc_ref_select_fragments(K, R_out, t_b, t_g, hp->H, budget, sel_out, n_sel_out);
+  return rc < 0 ? rc : used;
+}
+
+// Eq. 9: N = max(K, floor(gamma * H * T_c / T_s)); Eq. 10: h = floor(H / N).
+int cocodc_ref_sync_plan(int32_t K, int32_t H, double gamma, double T_c, double T_s,
+                         int64_t* N_out, int64_t* h_out) {
+  if (!N_out || !h_out) return kErrNull;
+  if (K < 1 || H < 1) return kErrRange;
+  if (!(gamma > 0.0) || !(gamma <= 1.0) || !(T_c > 0.0) || !(T_s > 0.0)) return kErrRange;
+  if (!std::isfinite(T_c) || !std::isfinite(T_s)) return kErrRange;
+  const double cap = std::floor(gamma * ((static_cast<double>(H) * T_c) / T_s));
+  int64_t N = static_cast<int64_t>(K);
+  if (cap > static_cast<double>(N)) N = (cap < 9.0e18) ? static_cast<int64_t>(cap) : INT64_MAX;
+  *N_out = N;
+  *h_out = static_cast<int64_t>(H) / N;
+  return kOk;
+}
+
+}  // extern "C"

@@ -1,0 +1,119 @@
+/*
+ * cocodc_ref.h -- CPU oracle for the CoCoDC per-fragment outer-synchronisation path.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This is the slow, plain, fp64 definition that the GPU
+ * library is checked against.  Nothing in the product path may include, link or call
+ * it; it shares no header, helper, table or constant with the HIP sources and
+ * therefore declares its own copies of the (layout-compatible) argument structs.
+ *
+ * Every pointer is a HOST pointer.  All parameter buffers are flat fp32 arrays of
+ * n_total elements; a fragment is a contiguous range {offset, length} of elements
+ * (paper Sec. 2.1: the model is split along depth into K disjoint fragments).
+ *
+ * Arithmetic: every fp32 input is widened to fp64, the step is evaluated in fp64 in
+ * the order the paper states it, and each stored fp32 output is rounded exactly once.
+ * The new global state is rounded to fp32 BEFORE it enters the delay-compensation
+ * step, because in the unfused sequence that step reads it back from an fp32 buffer.
+ *
+ * Pinned by tests/test_oracle_*.py (hand-computed scalars, closed forms, textbook /
+ * library special cases, brute force, exhaustive enumeration).  The composition of all
+ * steps on random data has no value printed in the paper: end-to-end parity unpinned
+ * by the paper, pinned only through its parts.
+ *
+ * Return value of every function: 0 on success, negative on invalid arguments
+ * (-1 null pointer, -3 out-of-range scalar or fragment table).
+ */
+#ifndef COCODC_REF_H
+#define COCODC_REF_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct {
+  uint64_t offset; /* first element of the fragment in every flat buffer */
+  uint64_t length; /* number of elements (0 allowed: empty fragment)     */
+} cocodc_ref_fragment_t;
+
+typedef struct {
+  int32_t tau;        /* overlap depth tau >= 0 (Sec. 2.1)                              */
+  int32_t H;          /* local period H >= 1 (Sec. 2.1, Eq. 5-7)                        */
+  double lambda;      /* compensation strength lambda (Eq. 7)                           */
+  double eta;         /* outer learning rate (Eq. 2; value not given by the paper)      */
+  double mu;          /* outer momentum (Eq. 2; value not given by the paper)           */
+  int32_t nesterov;   /* 1: Nesterov look-ahead step, 0: heavy-ball                     */
+  int32_t drift_sign; /* +1: Eq. 4 as printed (send-time minus current); -1: reversed   */
+  int32_t score_src;  /* 0: score the global pseudo-gradient (Eq. 11); 1: score drift d */
+  int32_t norm_kind;  /* 2: L2 norm (Eq. 11); 1: L1 norm                                */
+  int32_t merge_mode; /* 0: delay compensation (Eq. 8); 1: blend (Eq. 3); 2: replace    */
+  double alpha;       /* mixing factor of Eq. 3, used by merge_mode 1 only              */
+} cocodc_ref_hparams_t;
+
+/* Optional fp64 (unrounded) copies of the three stored outputs of the fused step. */
+typedef struct {
+  double* theta_m;  /* n_total, nullable */
+  double* theta_g;  /* n_total, nullable */
+  double* momentum; /* n_total, nullable */
+} cocodc_ref_shadow_t;
+
+/* Sec. 2.1 (text before Eq. 1): pseudo-gradient of each fragment, with the sign
+ * "global snapshot minus local" (the negative of the summand of Eq. 1); optionally
+ * records the send-time local parameters. */
+int cocodc_ref_pseudograd(const cocodc_ref_fragment_t* frags, int32_t K, uint64_t n_total,
+                          const float* theta_g_snap, const float* theta_m, float* delta_m_out,
+                          float* theta_m_send_out /* nullable */);
+
+/* Eq. 2 with OuterOptim = SGD with (Nesterov) momentum, descent on delta_g. */
+int cocodc_ref_outer_nesterov(const cocodc_ref_fragment_t* frags, int32_t K, uint64_t n_total,
+                              float* theta_g, float* momentum, const float* delta_g,
+                              const cocodc_ref_hparams_t* hp);
+
+/* Algorithm 1 (Eq. 4, 7, 8), or Eq. 3 / plain replacement for the other merge modes. */
+int cocodc_ref_delay_compensate(const cocodc_ref_fragment_t* frags, int32_t K, uint64_t n_total,
+                                float* theta_m, const float* theta_m_send, const float* theta_g,
+                                const cocodc_ref_hparams_t* hp);
+
+/* Eq. 11: R_p = ||x_p|| / I_p, +inf when I_p <= 0 (never synchronised).
+ * sum_out (nullable, K): the raw sum (of squares for L2, of magnitudes for L1). */
+int cocodc_ref_fragment_scores(const cocodc_ref_fragment_t* frags, int32_t K, uint64_t n_total,
+                               const float* x, const int64_t* I_p, int32_t norm_kind,
+                               double* R_out, double* sum_out /* nullable */);
+
+/* Algorithm 2 applied `budget` times without replacement. */
+int cocodc_ref_select_fragments(int32_t K, const double* R, const int64_t* t_b, int64_t t_g,
+                                int32_t H, int32_t budget, int32_t* sel_out, int32_t* n_sel_out);
+
+/* All of the above in one pass per element.  sums_out (nullable, 4*K):
+ * per fragment {sum dg^2, sum |dg|, sum d^2, sum |d|}. */
+int cocodc_ref_sync_step(const cocodc_ref_fragment_t* frags, int32_t K, uint64_t n_total,
+                         float* theta_m, const float* theta_m_send, float* theta_g,
+                         float* momentum, const float* delta_g,
+                         float* delta_m_out /* nullable; may alias delta_g */,
+                         const int64_t* I_p, const int64_t* t_b, int64_t t_g, int32_t budget,
+                         const cocodc_ref_hparams_t* hp, double* R_out, int32_t* sel_out,
+                         int32_t* n_sel_out, double* sums_out /* nullable */,
+                         const cocodc_ref_shadow_t* shadow /* nullable */);
+
+/* Same per-element arithmetic as cocodc_ref_sync_step, spread over host threads in
+ * fixed 65536-element chunks whose partial sums are added in chunk order (so the
+ * result does not depend on n_threads).  Exists only so the CPU baseline can be timed
+ * on all host cores; n_threads <= 0 uses the OpenMP default.  Returns the number of
+ * threads used (> 0) or a negative error. */
+int cocodc_ref_sync_step_mt(const cocodc_ref_fragment_t* frags, int32_t K, uint64_t n_total,
+                            float* theta_m, const float* theta_m_send, float* theta_g,
+                            float* momentum, const float* delta_g, float* delta_m_out,
+                            const int64_t* I_p, const int64_t* t_b, int64_t t_g, int32_t budget,
+                            const cocodc_ref_hparams_t* hp, double* R_out, int32_t* sel_out,
+                            int32_t* n_sel_out, double* sums_out, int32_t n_threads);
+
+/* Eq. 9 and Eq. 10: N = max(K, floor(gamma*H*T_c/T_s)), h = floor(H/N). */
+int cocodc_ref_sync_plan(int32_t K, int32_t H, double gamma, double T_c, double T_s,
+                         int64_t* N_out, int64_t* h_out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* COCODC_REF_H */
