@@ -1,0 +1,159 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused CoCoDC sync step (cocodc_sync_step) on ONE MI355X.
+
+A "step" is one pass of the whole path -- pseudo-gradient, outer Nesterov update, delay
+compensation merge, fragment scores, fragment selection -- over every fragment of one
+synthetic, model-shaped fragment set that is already resident in HBM.
+
+Prints one JSON line: whole-job throughput in Gparams/s, the HBM roofline of the fused
+element-wise kernel (algorithmic bytes / its HIP-event duration, measured in the same timed
+region) and the CPU oracle timed on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published peak
+BYTES_PER_PARAM = 36   # 5 fp32 reads + 4 fp32 writes (theta_m, theta_g, momentum, pseudo-gradient)
+
+# HBM bytes per launch of the fused kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
+# this command (see profiles/); None until such a run exists for the workload.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def cpu_baseline(wl, st, bk, sample_frag, repeats=2):
+    """Times the oracle (as it stands) on one fragment of the workload, on the host cores."""
+    import numpy as np
+    import oracle as ref
+    off, ln = wl.frags[sample_frag]
+    host0 = {k: v[off:off + ln].cpu().numpy().copy() for k, v in st.items()}
+    frags = [(0, ln)]
+    hp = ref.hparams(wl.tau, wl.H, wl.lam, wl.eta, wl.mu)
+    I_p, t_b = [bk.I_p[sample_frag]], [bk.t_b[sample_frag]]
+    pg = np.empty(ln, np.float32)
+
+    def run(n_threads):
+        best, used = float("inf"), 1
+        for _ in range(repeats):
+            h = {k: v.copy() for k, v in host0.items()}
+            t0 = time.perf_counter()
+            out = ref.sync_step(frags, h["theta_m"], h["theta_m_send"], h["theta_g"], h["momentum"],
+                                h["delta_g"], pg, I_p, t_b, bk.t_g, 1, hp, n_threads=n_threads)
+            dt = time.perf_counter() - t0
+            assert out["rc"] == 0
+            used = out.get("threads", 1)
+            best = min(best, dt)
+        return best, used
+
+    t1, _ = run(None)
+    avail = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else (os.cpu_count() or 1)
+    env = os.environ.get("OMP_NUM_THREADS")
+    want = min(avail, int(env)) if env and env.isdigit() else avail
+    tm, used = run(max(1, want))
+    return {
+        "value": round(ln / tm / 1e9, 4), "unit": "Gparams/s", "cores": int(used), "kind": "oracle",
+        "sample": f"fragment {sample_frag} of {wl.name} ({ln} params), fused oracle step, "
+                  f"chunk-parallel over {used} threads, best of {repeats}",
+        "single_thread_value": round(ln / t1 / 1e9, 4),
+        "host_cpus_visible": avail,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="7B", help="tiny | 125M | 350M | 1.3B | 7B")
+    ap.add_argument("--blocks-per-cu", type=int, default=None, help="launch-shape override (tuning)")
+    ap.add_argument("--no-pg", action="store_true", help="skip the pseudo-gradient output (32 B/param)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
+    ap.add_argument("--pad-kib", type=int, default=0, help="stagger buffer bases by multiples of this")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives are part of the path); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2504_17672_amd import binding as B
+    from paper_2504_17672_amd import synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    wl = synth.WORKLOADS[args.workload]
+    K, n = wl.K, wl.n_total
+    print(f"[bench] workload {wl.name}: K={K} n={n} resident {5 * 4 * n / 1e9:.1f} GB", file=sys.stderr, flush=True)
+    st = synth.make_state(wl, dev, seed=0)
+    bk = synth.bookkeeping(wl)
+    pg = None if args.no_pg else torch.empty(n, dtype=torch.float32, device=dev)
+    R = torch.zeros(K, dtype=torch.float64, device=dev)
+    sel = torch.full((K,), -1, dtype=torch.int32, device=dev)
+    n_sel = torch.zeros(1, dtype=torch.int32, device=dev)
+    ws = B.new_workspace(K, n, dev)
+    hp = B.hparams(wl.tau, wl.H, wl.lam, wl.eta, wl.mu)
+    if args.blocks_per_cu is not None:
+        B.cocodc_set_blocks_per_cu(args.blocks_per_cu)
+    torch.cuda.synchronize()
+
+    cpu = None
+    if not args.no_cpu:
+        sample = 1 if K > 1 else 0
+        print(f"[bench] timing the CPU oracle on fragment {sample}", file=sys.stderr, flush=True)
+        cpu = cpu_baseline(wl, st, bk, sample)
+        print(f"[bench] cpu baseline {cpu}", file=sys.stderr, flush=True)
+
+    def step():
+        B.check(B.cocodc_sync_step(wl.frags, n, st["theta_m"], st["theta_m_send"], st["theta_g"], st["momentum"],
+                                   st["delta_g"], pg, bk.I_p, bk.t_b, bk.t_g, wl.budget, hp, R, sel, n_sel, None,
+                                   ws))
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    B.check(B.cocodc_profiler_enable(args.steps))
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    cnt, k1_ms = B.cocodc_profiler_collect(args.steps)
+    B.cocodc_profiler_disable()
+    assert cnt == args.steps, cnt
+    finite = bool(torch.isfinite(st["theta_m"][:1 << 20]).all().item())
+    assert finite, "state went non-finite during the timed steps"
+
+    ms_per_step = elapsed / args.steps * 1e3
+    k1_avg = sum(k1_ms) / len(k1_ms)
+    bpp = 32 if args.no_pg else BYTES_PER_PARAM
+    achieved = bpp * n / (k1_avg * 1e-3) / 1e9
+    out = {
+        "metric": "fused sync-step Gparams/s and achieved HBM GB/s (% of peak), 1xMI355X",
+        "value": round(n / (elapsed / args.steps) / 1e9, 3),
+        "unit": "Gparams/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f64", "data": "synthetic",
+        "config": {"workload": wl.name, "K": K, "params": n, "tau": wl.tau, "H": wl.H, "budget": wl.budget,
+                   "bytes_per_param": bpp, "selected": sel[:int(n_sel.item())].cpu().tolist()},
+        "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBS, 4),
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name),
+                     "kernel": "k_walk<FusedOp>", "kernel_ms_avg": round(k1_avg, 4),
+                     "kernel_ms_min": round(min(k1_ms), 4), "algorithmic_bytes": bpp * n},
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

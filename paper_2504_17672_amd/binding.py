@@ -1,0 +1,238 @@
+"""ctypes binding of include/cocodc.h: same names, argument marshalling only.
+
+Every step of the path runs in the HIP kernels of libcocodc.so; there is no fallback.  If the
+library has not been built (python -m paper_2504_17672_amd.build) importing this module
+raises.  Buffers are torch CUDA(HIP) tensors (or raw integer device addresses); host-side
+tables are Python sequences.  Every function returns the library's status code; wrap a call
+in check() to turn a failure into an exception.
+"""
+import ctypes as C
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libcocodc.so")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(
+        f"{LIB_PATH} is missing: build the HIP library first (python -m paper_2504_17672_amd.build). "
+        "There is no CPU fallback.")
+
+_lib = C.CDLL(LIB_PATH)
+
+COCODC_MAX_FRAGMENTS = 1024
+COCODC_OK = 0
+COCODC_ERR_NULL = -1
+COCODC_ERR_ALIGN = -2
+COCODC_ERR_RANGE = -3
+COCODC_ERR_NONFINITE = -4
+COCODC_ERR_WORKSPACE = -5
+COCODC_ERR_HIP = -6
+COCODC_ERR_ALIAS = -7
+
+EXPORTS = (
+    "cocodc_workspace_bytes", "cocodc_pseudograd", "cocodc_outer_nesterov", "cocodc_delay_compensate",
+    "cocodc_fragment_scores", "cocodc_select_fragments", "cocodc_sync_step", "cocodc_sync_plan",
+    "cocodc_last_hip_error", "cocodc_status_string", "cocodc_set_blocks_per_cu",
+    "cocodc_profiler_enable", "cocodc_profiler_collect", "cocodc_profiler_disable",
+)
+
+
+class cocodc_fragment_t(C.Structure):
+    _fields_ = [("offset", C.c_uint64), ("length", C.c_uint64)]
+
+
+class cocodc_hparams_t(C.Structure):
+    _fields_ = [
+        ("tau", C.c_int32), ("H", C.c_int32),
+        ("lambda_", C.c_double), ("eta", C.c_double), ("mu", C.c_double),
+        ("nesterov", C.c_int32), ("drift_sign", C.c_int32),
+        ("score_src", C.c_int32), ("norm_kind", C.c_int32),
+        ("merge_mode", C.c_int32), ("alpha", C.c_double),
+    ]
+
+
+_P = C.c_void_p
+_frag_p = C.POINTER(cocodc_fragment_t)
+_hp_p = C.POINTER(cocodc_hparams_t)
+_i64_p = C.POINTER(C.c_int64)
+
+_lib.cocodc_workspace_bytes.restype = C.c_size_t
+_lib.cocodc_workspace_bytes.argtypes = [C.c_int32, C.c_uint64]
+_lib.cocodc_pseudograd.argtypes = [_frag_p, C.c_int32, C.c_uint64, _P, _P, _P, _P, _P, C.c_size_t, _P]
+_lib.cocodc_outer_nesterov.argtypes = [_frag_p, C.c_int32, C.c_uint64, _P, _P, _P, _hp_p, _P, C.c_size_t, _P]
+_lib.cocodc_delay_compensate.argtypes = [_frag_p, C.c_int32, C.c_uint64, _P, _P, _P, _hp_p, _P, C.c_size_t, _P]
+_lib.cocodc_fragment_scores.argtypes = [_frag_p, C.c_int32, C.c_uint64, _P, _i64_p, C.c_int32, _P, _P, _P,
+                                        C.c_size_t, _P]
+_lib.cocodc_select_fragments.argtypes = [C.c_int32, _P, _i64_p, C.c_int64, C.c_int32, C.c_int32, _P, _P, _P,
+                                         C.c_size_t, _P]
+_lib.cocodc_sync_step.argtypes = [_frag_p, C.c_int32, C.c_uint64, _P, _P, _P, _P, _P, _P, _i64_p, _i64_p,
+                                  C.c_int64, C.c_int32, _hp_p, _P, _P, _P, _P, _P, C.c_size_t, _P]
+_lib.cocodc_sync_plan.argtypes = [C.c_int32, C.c_int32, C.c_double, C.c_double, C.c_double, _i64_p, _i64_p]
+_lib.cocodc_status_string.restype = C.c_char_p
+_lib.cocodc_status_string.argtypes = [C.c_int]
+_lib.cocodc_set_blocks_per_cu.argtypes = [C.c_int]
+_lib.cocodc_profiler_enable.argtypes = [C.c_int32]
+_lib.cocodc_profiler_collect.argtypes = [C.POINTER(C.c_float), C.c_int32]
+for _name in EXPORTS:
+    if _name not in ("cocodc_workspace_bytes", "cocodc_status_string"):
+        getattr(_lib, _name).restype = C.c_int
+
+
+class CocodcError(RuntimeError):
+    def __init__(self, status):
+        self.status = status
+        super().__init__(f"{cocodc_status_string(status)} ({status}), hip error {cocodc_last_hip_error()}")
+
+
+def check(status):
+    if status < 0:
+        raise CocodcError(status)
+    return status
+
+
+def hparams(tau, H, lam=0.5, eta=0.7, mu=0.9, nesterov=1, drift_sign=1, score_src=0, norm_kind=2,
+            merge_mode=0, alpha=1.0):
+    return cocodc_hparams_t(int(tau), int(H), float(lam), float(eta), float(mu), int(nesterov),
+                            int(drift_sign), int(score_src), int(norm_kind), int(merge_mode),
+                            float(alpha))
+
+
+def _ptr(x):
+    """Device address of a torch tensor, a raw integer address, or NULL for None."""
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return C.c_void_p(x)
+    return C.c_void_p(x.data_ptr())
+
+
+def _frags(frags):
+    if frags is None:
+        return None, 0
+    arr = (cocodc_fragment_t * max(len(frags), 1))()
+    for i, (off, length) in enumerate(frags):
+        arr[i].offset = int(off)
+        arr[i].length = int(length)
+    return arr, len(frags)
+
+
+def _i64(seq):
+    if seq is None:
+        return None
+    return (C.c_int64 * max(len(seq), 1))(*[int(v) for v in seq])
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+    if isinstance(stream, int):
+        return C.c_void_p(stream)
+    return C.c_void_p(stream.cuda_stream)
+
+
+def _ws(workspace, workspace_bytes):
+    if workspace is None or isinstance(workspace, int):
+        return _ptr(workspace), int(workspace_bytes or 0)
+    nbytes = workspace.numel() * workspace.element_size()
+    return _ptr(workspace), int(nbytes if workspace_bytes is None else workspace_bytes)
+
+
+def cocodc_workspace_bytes(K, n_total):
+    return int(_lib.cocodc_workspace_bytes(int(K), int(n_total)))
+
+
+def new_workspace(K, n_total, device="cuda"):
+    """A torch byte tensor large enough for any entry point at (K, n_total)."""
+    import torch
+    nbytes = cocodc_workspace_bytes(K, n_total)
+    if nbytes == 0:
+        raise CocodcError(COCODC_ERR_RANGE)
+    return torch.empty(nbytes, dtype=torch.uint8, device=device)
+
+
+def cocodc_pseudograd(frags, n_total, theta_g_snap, theta_m, delta_m_out, theta_m_send_out, workspace,
+                      workspace_bytes=None, stream=None, K=None):
+    fa, k = _frags(frags)
+    wp, wb = _ws(workspace, workspace_bytes)
+    return _lib.cocodc_pseudograd(fa, k if K is None else K, int(n_total), _ptr(theta_g_snap), _ptr(theta_m),
+                                  _ptr(delta_m_out), _ptr(theta_m_send_out), wp, wb, _stream(stream))
+
+
+def cocodc_outer_nesterov(frags, n_total, theta_g, momentum, delta_g, hp, workspace, workspace_bytes=None,
+                          stream=None, K=None):
+    fa, k = _frags(frags)
+    wp, wb = _ws(workspace, workspace_bytes)
+    return _lib.cocodc_outer_nesterov(fa, k if K is None else K, int(n_total), _ptr(theta_g), _ptr(momentum),
+                                      _ptr(delta_g), C.byref(hp) if hp is not None else None, wp, wb,
+                                      _stream(stream))
+
+
+def cocodc_delay_compensate(frags, n_total, theta_m, theta_m_send, theta_g, hp, workspace,
+                            workspace_bytes=None, stream=None, K=None):
+    fa, k = _frags(frags)
+    wp, wb = _ws(workspace, workspace_bytes)
+    return _lib.cocodc_delay_compensate(fa, k if K is None else K, int(n_total), _ptr(theta_m),
+                                        _ptr(theta_m_send), _ptr(theta_g),
+                                        C.byref(hp) if hp is not None else None, wp, wb, _stream(stream))
+
+
+def cocodc_fragment_scores(frags, n_total, x, I_p, norm_kind, R_out, sum_out, workspace, workspace_bytes=None,
+                           stream=None, K=None):
+    fa, k = _frags(frags)
+    wp, wb = _ws(workspace, workspace_bytes)
+    return _lib.cocodc_fragment_scores(fa, k if K is None else K, int(n_total), _ptr(x), _i64(I_p),
+                                       int(norm_kind), _ptr(R_out), _ptr(sum_out), wp, wb, _stream(stream))
+
+
+def cocodc_select_fragments(K, R, t_b, t_g, H, budget, sel_out, n_sel_out, workspace, workspace_bytes=None,
+                            stream=None):
+    wp, wb = _ws(workspace, workspace_bytes)
+    return _lib.cocodc_select_fragments(int(K), _ptr(R), _i64(t_b), int(t_g), int(H), int(budget),
+                                        _ptr(sel_out), _ptr(n_sel_out), wp, wb, _stream(stream))
+
+
+def cocodc_sync_step(frags, n_total, theta_m, theta_m_send, theta_g, momentum, delta_g, delta_m_out, I_p, t_b,
+                     t_g, budget, hp, R_out, sel_out, n_sel_out, sums_out, workspace, workspace_bytes=None,
+                     stream=None, K=None):
+    fa, k = _frags(frags)
+    wp, wb = _ws(workspace, workspace_bytes)
+    return _lib.cocodc_sync_step(fa, k if K is None else K, int(n_total), _ptr(theta_m), _ptr(theta_m_send),
+                                 _ptr(theta_g), _ptr(momentum), _ptr(delta_g), _ptr(delta_m_out), _i64(I_p),
+                                 _i64(t_b), int(t_g), int(budget), C.byref(hp) if hp is not None else None,
+                                 _ptr(R_out), _ptr(sel_out), _ptr(n_sel_out), _ptr(sums_out), wp, wb,
+                                 _stream(stream))
+
+
+def cocodc_sync_plan(K, H, gamma, T_c, T_s):
+    """Returns (status, N, h)."""
+    N, h = C.c_int64(0), C.c_int64(0)
+    rc = _lib.cocodc_sync_plan(int(K), int(H), float(gamma), float(T_c), float(T_s), C.byref(N), C.byref(h))
+    return rc, N.value, h.value
+
+
+def cocodc_last_hip_error():
+    return int(_lib.cocodc_last_hip_error())
+
+
+def cocodc_status_string(status):
+    return _lib.cocodc_status_string(int(status)).decode()
+
+
+def cocodc_set_blocks_per_cu(n):
+    return int(_lib.cocodc_set_blocks_per_cu(int(n)))
+
+
+def cocodc_profiler_enable(max_records):
+    return int(_lib.cocodc_profiler_enable(int(max_records)))
+
+
+def cocodc_profiler_collect(capacity):
+    """Returns (status_or_count, [ms, ...])."""
+    buf = (C.c_float * max(int(capacity), 1))()
+    n = int(_lib.cocodc_profiler_collect(buf, int(capacity)))
+    return n, [float(buf[i]) for i in range(max(n, 0))]
+
+
+def cocodc_profiler_disable():
+    return int(_lib.cocodc_profiler_disable())
