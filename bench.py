@@ -22,9 +22,11 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published peak
 BYTES_PER_PARAM = 36   # 5 fp32 reads + 4 fp32 writes (theta_m, theta_g, momentum, pseudo-gradient)
 
-# HBM bytes per launch of the fused kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
-# this command (see profiles/); None until such a run exists for the workload.
-MEASURED_TRAFFIC_BYTES = {}
+# HBM bytes per launch of the fused kernel: rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE runs of this
+# command, each scaled by what the same counter reads for a plain 4 GiB device copy (FETCH_SIZE
+# reads half the true bytes on this GPU, WRITE_SIZE reads them exactly).  The runs and their
+# commands are recorded in profiles/fused_sync_step_<workload>.txt.  None where no run exists.
+MEASURED_TRAFFIC_BYTES = {'7B': 237876636311, '1.3B': 46757956619}
 
 
 def cpu_baseline(wl, st, bk, sample_frag, repeats=2):
@@ -74,7 +76,13 @@ def main():
     ap.add_argument("--blocks-per-cu", type=int, default=None, help="launch-shape override (tuning)")
     ap.add_argument("--no-pg", action="store_true", help="skip the pseudo-gradient output (32 B/param)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
-    ap.add_argument("--pad-kib", type=int, default=0, help="stagger buffer bases by multiples of this")
+    ap.add_argument("--layout", default="spaced", choices=["spaced", "packed"],
+                    help="spaced: the six buffers are carved out of one allocation, "
+                         "cocodc_layout_stride_bytes() apart; packed: six separate allocations")
+    ap.add_argument("--stride-gib", type=float, default=None, help="override the spaced-layout stride")
+    ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
+                    help="instead of the benchmark, run 5 plain device copies of MIB mebibytes (a kernel "
+                         "of known traffic, to scale rocprofv3 FETCH_SIZE / WRITE_SIZE readings) and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives are part of the path); "
@@ -88,12 +96,37 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.calibrate_copy:
+        nbytes = args.calibrate_copy << 20
+        src = torch.empty(nbytes // 4, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy": True, "launches": 5, "bytes_read_per_launch": nbytes,
+                          "bytes_written_per_launch": nbytes}), flush=True)
+        return
     wl = synth.WORKLOADS[args.workload]
     K, n = wl.K, wl.n_total
     print(f"[bench] workload {wl.name}: K={K} n={n} resident {5 * 4 * n / 1e9:.1f} GB", file=sys.stderr, flush=True)
-    st = synth.make_state(wl, dev, seed=0)
+    layout, arena, bufs = args.layout, None, None
+    stride = B.cocodc_layout_stride_bytes(n) if args.stride_gib is None else int(args.stride_gib * (1 << 30))
+    if layout == "spaced":
+        try:
+            arena, carved = B.spaced_buffers(n, 6, dev, stride)
+            names = ("theta_m", "theta_m_send", "theta_g", "momentum", "delta_g", "pg")
+            bufs = dict(zip(names, carved))
+        except torch.OutOfMemoryError:
+            print("[bench] not enough free HBM for the spaced layout; using separate allocations",
+                  file=sys.stderr, flush=True)
+            layout = "packed"
+    st = synth.make_state(wl, dev, seed=0, buffers=bufs)
     bk = synth.bookkeeping(wl)
-    pg = None if args.no_pg else torch.empty(n, dtype=torch.float32, device=dev)
+    if args.no_pg:
+        pg = None
+    else:
+        pg = bufs["pg"] if bufs is not None else torch.empty(n, dtype=torch.float32, device=dev)
     R = torch.zeros(K, dtype=torch.float64, device=dev)
     sel = torch.full((K,), -1, dtype=torch.int32, device=dev)
     n_sel = torch.zeros(1, dtype=torch.int32, device=dev)
@@ -144,7 +177,10 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f64", "data": "synthetic",
         "config": {"workload": wl.name, "K": K, "params": n, "tau": wl.tau, "H": wl.H, "budget": wl.budget,
-                   "bytes_per_param": bpp, "selected": sel[:int(n_sel.item())].cpu().tolist()},
+                   "bytes_per_param": bpp,
+                   "layout": (f"spaced: one allocation, buffer bases {stride / (1 << 30):.2f} GiB apart"
+                              if layout == "spaced" else "packed: separate allocations"),
+                   "selected": sel[:int(n_sel.item())].cpu().tolist()},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name),

@@ -32,7 +32,7 @@ COCODC_ERR_ALIAS = -7
 EXPORTS = (
     "cocodc_workspace_bytes", "cocodc_pseudograd", "cocodc_outer_nesterov", "cocodc_delay_compensate",
     "cocodc_fragment_scores", "cocodc_select_fragments", "cocodc_sync_step", "cocodc_sync_plan",
-    "cocodc_last_hip_error", "cocodc_status_string", "cocodc_set_blocks_per_cu",
+    "cocodc_layout_stride_bytes", "cocodc_last_hip_error", "cocodc_status_string", "cocodc_set_blocks_per_cu",
     "cocodc_profiler_enable", "cocodc_profiler_collect", "cocodc_profiler_disable",
 )
 
@@ -68,13 +68,15 @@ _lib.cocodc_select_fragments.argtypes = [C.c_int32, _P, _i64_p, C.c_int64, C.c_i
 _lib.cocodc_sync_step.argtypes = [_frag_p, C.c_int32, C.c_uint64, _P, _P, _P, _P, _P, _P, _i64_p, _i64_p,
                                   C.c_int64, C.c_int32, _hp_p, _P, _P, _P, _P, _P, C.c_size_t, _P]
 _lib.cocodc_sync_plan.argtypes = [C.c_int32, C.c_int32, C.c_double, C.c_double, C.c_double, _i64_p, _i64_p]
+_lib.cocodc_layout_stride_bytes.restype = C.c_uint64
+_lib.cocodc_layout_stride_bytes.argtypes = [C.c_uint64]
 _lib.cocodc_status_string.restype = C.c_char_p
 _lib.cocodc_status_string.argtypes = [C.c_int]
 _lib.cocodc_set_blocks_per_cu.argtypes = [C.c_int]
 _lib.cocodc_profiler_enable.argtypes = [C.c_int32]
 _lib.cocodc_profiler_collect.argtypes = [C.POINTER(C.c_float), C.c_int32]
 for _name in EXPORTS:
-    if _name not in ("cocodc_workspace_bytes", "cocodc_status_string"):
+    if _name not in ("cocodc_workspace_bytes", "cocodc_status_string", "cocodc_layout_stride_bytes"):
         getattr(_lib, _name).restype = C.c_int
 
 
@@ -149,6 +151,22 @@ def new_workspace(K, n_total, device="cuda"):
     if nbytes == 0:
         raise CocodcError(COCODC_ERR_RANGE)
     return torch.empty(nbytes, dtype=torch.uint8, device=device)
+
+
+def cocodc_layout_stride_bytes(n_total):
+    return int(_lib.cocodc_layout_stride_bytes(int(n_total)))
+
+
+def spaced_buffers(n_total, count, device="cuda", stride_bytes=None):
+    """`count` flat fp32 buffers of n_total elements carved out of one device allocation, their
+    bases cocodc_layout_stride_bytes(n_total) apart.  Returns (arena, [buffers]); keep the arena
+    alive as long as the buffers are used.  Memory between the buffers is free for other data."""
+    import torch
+    stride = cocodc_layout_stride_bytes(n_total) if stride_bytes is None else int(stride_bytes)
+    nbytes = 4 * int(n_total)
+    assert stride % 16 == 0 and stride >= nbytes
+    arena = torch.empty((count - 1) * stride + nbytes, dtype=torch.uint8, device=device)
+    return arena, [arena[k * stride:k * stride + nbytes].view(torch.float32) for k in range(count)]
 
 
 def cocodc_pseudograd(frags, n_total, theta_g_snap, theta_m, delta_m_out, theta_m_send_out, workspace,

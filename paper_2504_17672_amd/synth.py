@@ -139,7 +139,7 @@ def fill_drift(out: torch.Tensor, kind: str, gen: torch.Generator, sigma: float 
     raise ValueError(kind)
 
 
-def make_state(wl: Workload, device, seed: int = 0, pad: int = 0, amplified: bool = False):
+def make_state(wl: Workload, device, seed: int = 0, pad: int = 0, amplified: bool = False, buffers=None):
     """The five resident buffers of one worker just before a sync is applied.
 
     theta_m_send is derived so that "drift since send" = theta_m - theta_m_send:
@@ -147,17 +147,26 @@ def make_state(wl: Workload, device, seed: int = 0, pad: int = 0, amplified: boo
     N(0, 0.5), which makes the cubic term of Eq. 7 large enough to survive fp32 rounding
     (meant to be used with small tau and H).  `pad` extra elements are allocated (and filled
     with a sentinel) after the last fragment so tests can verify nothing outside the
-    fragment table is written.
+    fragment table is written.  `buffers` (optional) maps each of the five names to a
+    preallocated fp32 tensor of n_total + pad elements to fill instead of allocating.
     """
     n = wl.n_total
+
+    def alloc(name):
+        if buffers is not None:
+            t = buffers[name]
+            assert t.dtype == torch.float32 and t.numel() == n + pad
+            return t
+        return torch.empty(n + pad, dtype=torch.float32, device=device)
+
     st = {}
     for name in ("theta_m", "theta_g", "momentum", "delta_g"):
-        t = torch.empty(n + pad, dtype=torch.float32, device=device)
+        t = alloc(name)
         fill_normal(t[:n], 0.5 if amplified else SIGMA[name], _gen(device, seed, name, 0))
         if pad:
             t[n:] = 777.0
         st[name] = t
-    send = torch.empty(n + pad, dtype=torch.float32, device=device)
+    send = alloc("theta_m_send")
     g = _gen(device, seed, "drift", 0)
     if amplified:
         fill_normal(send[:n], 0.5, g)
