@@ -26,7 +26,7 @@ BYTES_PER_PARAM = 36   # 5 fp32 reads + 4 fp32 writes (theta_m, theta_g, momentu
 # command, each scaled by what the same counter reads for a plain 4 GiB device copy (FETCH_SIZE
 # reads half the true bytes on this GPU, WRITE_SIZE reads them exactly).  The runs and their
 # commands are recorded in profiles/fused_sync_step_<workload>.txt.  None where no run exists.
-MEASURED_TRAFFIC_BYTES = {'7B': 237876636311, '1.3B': 46757956619}
+MEASURED_TRAFFIC_BYTES = {'7B': 237876453252, '1.3B': 46757912976}
 
 
 def cpu_baseline(wl, st, bk, sample_frag, repeats=2):
@@ -76,9 +76,10 @@ def main():
     ap.add_argument("--blocks-per-cu", type=int, default=None, help="launch-shape override (tuning)")
     ap.add_argument("--no-pg", action="store_true", help="skip the pseudo-gradient output (32 B/param)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
-    ap.add_argument("--layout", default="spaced", choices=["spaced", "packed"],
-                    help="spaced: the six buffers are carved out of one allocation, "
-                         "cocodc_layout_stride_bytes() apart; packed: six separate allocations")
+    ap.add_argument("--layout", default="tuned", choices=["tuned", "spaced", "packed"],
+                    help="tuned: the six buffers are carved out of one allocation at the stride that a "
+                         "short probe at set-up finds fastest; spaced: fixed stride "
+                         "cocodc_layout_stride_bytes(); packed: six separate allocations")
     ap.add_argument("--stride-gib", type=float, default=None, help="override the spaced-layout stride")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
                     help="instead of the benchmark, run 5 plain device copies of MIB mebibytes (a kernel "
@@ -112,9 +113,14 @@ def main():
     print(f"[bench] workload {wl.name}: K={K} n={n} resident {5 * 4 * n / 1e9:.1f} GB", file=sys.stderr, flush=True)
     layout, arena, bufs = args.layout, None, None
     stride = B.cocodc_layout_stride_bytes(n) if args.stride_gib is None else int(args.stride_gib * (1 << 30))
-    if layout == "spaced":
+    if layout in ("spaced", "tuned"):
         try:
-            arena, carved = B.spaced_buffers(n, 6, dev, stride)
+            if layout == "tuned" and args.stride_gib is None:
+                arena, carved, stride, probe = B.tuned_spaced_buffers(
+                    n, wl.frags, dev, verbose=lambda m: print("[bench] layout probe:", m, file=sys.stderr, flush=True))
+            else:
+                arena, carved = B.spaced_buffers(n, 6, dev, None if args.stride_gib is None else stride)
+                stride = carved[1].data_ptr() - carved[0].data_ptr()
             names = ("theta_m", "theta_m_send", "theta_g", "momentum", "delta_g", "pg")
             bufs = dict(zip(names, carved))
         except torch.OutOfMemoryError:
@@ -178,8 +184,8 @@ def main():
         "dtype": "f64", "data": "synthetic",
         "config": {"workload": wl.name, "K": K, "params": n, "tau": wl.tau, "H": wl.H, "budget": wl.budget,
                    "bytes_per_param": bpp,
-                   "layout": (f"spaced: one allocation, buffer bases {stride / (1 << 30):.2f} GiB apart"
-                              if layout == "spaced" else "packed: separate allocations"),
+                   "layout": (f"{layout}: one allocation, buffer bases {stride / (1 << 30):.2f} GiB apart"
+                              if layout != "packed" else "packed: separate allocations"),
                    "selected": sel[:int(n_sel.item())].cpu().tolist()},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4),

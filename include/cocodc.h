@@ -184,11 +184,13 @@ int cocodc_sync_plan(int32_t K, int32_t H, double gamma, double T_c, double T_s,
 /* Recommended distance in bytes between the base addresses of the flat buffers that one
  * call streams through together (theta_m, theta_m_send, theta_g, momentum, delta_g,
  * delta_m_out), for buffers of n_total fp32 elements carved out of ONE device allocation.
- * On MI355X the fused pass runs about 20 % faster when the concurrently streamed buffers
- * lie at least ~13 GiB apart (best near 26-28 GiB, worst at multiples of 32 GiB) than
- * when they are packed back to back, whatever their size; the gaps can hold any other
- * data.  Returns max(26 GiB, buffer size rounded up to 1 GiB), moved off multiples of
- * 32 GiB.  Purely advisory: every entry point accepts any placement.  Host-only. */
+ * On MI355X the fused pass runs 20-25 % faster when the concurrently streamed buffers are
+ * spread over the whole HBM address range than when they are packed back to back,
+ * whatever their size: measured 5.1-5.4 TB/s for strides up to 12 GiB, 6.1-6.45 TB/s from
+ * 13 GiB on, with a broad optimum around 40-45 GiB and a dip at 32 GiB.  The gaps can hold
+ * any other data.  Returns max(40 GiB, buffer size rounded up to 1 GiB), moved off
+ * multiples of 32 GiB.  Purely advisory: every entry point accepts any placement, and a
+ * caller short of address space can use any stride >= 13 GiB.  Host-only. */
 uint64_t cocodc_layout_stride_bytes(uint64_t n_total);
 
 /* ---- diagnostics and measurement aids (no paper counterpart) ---- */

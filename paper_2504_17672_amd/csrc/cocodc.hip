@@ -963,7 +963,7 @@ int cocodc_sync_plan(int32_t K, int32_t H, double gamma, double T_c, double T_s,
 uint64_t cocodc_layout_stride_bytes(uint64_t n_total) {
   constexpr uint64_t GiB = 1ull << 30;
   const uint64_t bytes = n_total * sizeof(float);
-  uint64_t stride = std::max<uint64_t>(26 * GiB, (bytes + GiB - 1) / GiB * GiB);
+  uint64_t stride = std::max<uint64_t>(40 * GiB, (bytes + GiB - 1) / GiB * GiB);
   if (stride % (32 * GiB) == 0) stride += 2 * GiB;
   return stride;
 }
