@@ -76,6 +76,9 @@ def main():
     ap.add_argument("--blocks-per-cu", type=int, default=None, help="launch-shape override (tuning)")
     ap.add_argument("--no-pg", action="store_true", help="skip the pseudo-gradient output (32 B/param)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
+    ap.add_argument("--merge-mode", default="dc", choices=["dc", "blend", "replace"],
+                    help="dc: delay compensation (Eq. 8, default); blend: Streaming-DiLoCo merge (Eq. 3, "
+                         "alpha 0.5, no send-time record: 32 B/param); replace: blocking-DiLoCo merge")
     ap.add_argument("--layout", default="tuned", choices=["tuned", "spaced", "packed"],
                     help="tuned: the six buffers are carved out of one allocation at the stride that a "
                          "short probe at set-up finds fastest; spaced: fixed stride "
@@ -137,7 +140,9 @@ def main():
     sel = torch.full((K,), -1, dtype=torch.int32, device=dev)
     n_sel = torch.zeros(1, dtype=torch.int32, device=dev)
     ws = B.new_workspace(K, n, dev)
-    hp = B.hparams(wl.tau, wl.H, wl.lam, wl.eta, wl.mu)
+    mode = {"dc": 0, "blend": 1, "replace": 2}[args.merge_mode]
+    hp = B.hparams(wl.tau, wl.H, wl.lam, wl.eta, wl.mu, merge_mode=mode, alpha=0.5)
+    send = st["theta_m_send"] if mode == 0 else None
     if args.blocks_per_cu is not None:
         B.cocodc_set_blocks_per_cu(args.blocks_per_cu)
     torch.cuda.synchronize()
@@ -150,7 +155,7 @@ def main():
         print(f"[bench] cpu baseline {cpu}", file=sys.stderr, flush=True)
 
     def step():
-        B.check(B.cocodc_sync_step(wl.frags, n, st["theta_m"], st["theta_m_send"], st["theta_g"], st["momentum"],
+        B.check(B.cocodc_sync_step(wl.frags, n, st["theta_m"], send, st["theta_g"], st["momentum"],
                                    st["delta_g"], pg, bk.I_p, bk.t_b, bk.t_g, wl.budget, hp, R, sel, n_sel, None,
                                    ws))
 
@@ -172,7 +177,7 @@ def main():
 
     ms_per_step = elapsed / args.steps * 1e3
     k1_avg = sum(k1_ms) / len(k1_ms)
-    bpp = 32 if args.no_pg else BYTES_PER_PARAM
+    bpp = BYTES_PER_PARAM - (4 if args.no_pg else 0) - (4 if mode != 0 else 0)
     achieved = bpp * n / (k1_avg * 1e-3) / 1e9
     out = {
         "metric": "fused sync-step Gparams/s and achieved HBM GB/s (% of peak), 1xMI355X",
@@ -183,13 +188,13 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f64", "data": "synthetic",
         "config": {"workload": wl.name, "K": K, "params": n, "tau": wl.tau, "H": wl.H, "budget": wl.budget,
-                   "bytes_per_param": bpp,
+                   "bytes_per_param": bpp, "merge_mode": args.merge_mode,
                    "layout": (f"{layout}: one allocation, buffer bases {stride / (1 << 30):.2f} GiB apart"
                               if layout != "packed" else "packed: separate allocations"),
                    "selected": sel[:int(n_sel.item())].cpu().tolist()},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4),
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name),
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name) if bpp == BYTES_PER_PARAM else None,
                      "kernel": "k_walk<FusedOp>", "kernel_ms_avg": round(k1_avg, 4),
                      "kernel_ms_min": round(min(k1_ms), 4), "algorithmic_bytes": bpp * n},
         "cpu_baseline": cpu,

@@ -127,7 +127,8 @@ int cocodc_outer_nesterov(const cocodc_fragment_t* frags, int32_t K, uint64_t n_
  * difference introduced with Eq. 5), element by element:
  *   theta_m <- theta_g + d + lambda * d*d*Delta / (tau*H)      (Eq. 7 put into Eq. 8)
  * The last term is dropped when tau == 0.  merge_mode 1 computes Eq. 3 instead,
- * merge_mode 2 copies theta_g.  theta_g must already be the NEW global state. */
+ * merge_mode 2 copies theta_g; neither reads theta_m_send, which may then be NULL.
+ * theta_g must already be the NEW global state. */
 int cocodc_delay_compensate(const cocodc_fragment_t* frags, int32_t K, uint64_t n_total,
                             float* theta_m, const float* theta_m_send, const float* theta_g,
                             const cocodc_hparams_t* hp, void* workspace, size_t workspace_bytes,
@@ -158,6 +159,9 @@ int cocodc_select_fragments(int32_t K, const double* R, const int64_t* t_b, int6
  * to cocodc_pseudograd(theta_m_send_out = NULL) -> cocodc_outer_nesterov ->
  * cocodc_delay_compensate -> cocodc_fragment_scores(delta_g) ->
  * cocodc_select_fragments when score_src == 0.
+ *   theta_m_send: may be NULL when merge_mode is 1 or 2 and score_src is 0 (Eq. 3 and the
+ *                blocking merge keep no send-time record); the pass then moves 32 instead of
+ *                36 bytes per parameter and the two drift sums are reported as 0.
  *   delta_m_out: nullable; may be exactly delta_g.
  *   I_p, t_b:    host, K entries each.      t_g: current global step.
  *   R_out:       device, K doubles.         sel_out / n_sel_out: as above.

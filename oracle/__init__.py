@@ -94,7 +94,7 @@ def outer_nesterov(frags, theta_g, momentum, delta_g, hp):
 def delay_compensate(frags, theta_m, theta_m_send, theta_g, hp):
     n = theta_m.size
     return lib().cocodc_ref_delay_compensate(_frag_array(frags), C.c_int32(len(frags)),
-                                             C.c_uint64(n), _f32(theta_m), _f32(theta_m_send),
+                                             C.c_uint64(n), _f32(theta_m), _f32(theta_m_send, True),
                                              _f32(theta_g), C.byref(hp))
 
 
@@ -141,7 +141,7 @@ def sync_step(frags, theta_m, theta_m_send, theta_g, momentum, delta_g, delta_m_
     keep1, ip = _i64(I_p)
     keep2, tb = _i64(t_b)
     out = {}
-    common = (_frag_array(frags), C.c_int32(K), C.c_uint64(n), _f32(theta_m), _f32(theta_m_send),
+    common = (_frag_array(frags), C.c_int32(K), C.c_uint64(n), _f32(theta_m), _f32(theta_m_send, True),
               _f32(theta_g), _f32(momentum), _f32(delta_g), _f32(delta_m_out, True), ip, tb,
               C.c_int64(t_g), C.c_int32(budget), C.byref(hp), C.c_void_p(R.ctypes.data),
               C.c_void_p(sel.ctypes.data), C.byref(n_sel), C.c_void_p(sums.ctypes.data))

@@ -103,7 +103,9 @@ struct Sums {
 inline void sync_element(uint64_t i, float* theta_m, const float* theta_send, float* theta_g,
                          float* momentum, const float* delta_g, float* delta_m_out,
                          const cocodc_ref_hparams_t& hp, Sums* s, const cocodc_ref_shadow_t* sh) {
-  const double tg = theta_g[i], tm = theta_m[i], ts = theta_send[i];
+  const double tg = theta_g[i], tm = theta_m[i];
+  // Eq. 3 and the blocking merge have no send-time record: without one the drift is zero
+  const double ts = theta_send ? theta_send[i] : tm;
   const double m0 = momentum[i], dg = delta_g[i];
 
   const float pg = static_cast<float>(tg - tm);  // pseudo-gradient, global minus local
@@ -179,12 +181,13 @@ int cocodc_ref_outer_nesterov(const cocodc_ref_fragment_t* frags, int32_t K, uin
 int cocodc_ref_delay_compensate(const cocodc_ref_fragment_t* frags, int32_t K, uint64_t n_total,
                                 float* theta_m, const float* theta_m_send, const float* theta_g,
                                 const cocodc_ref_hparams_t* hp) {
-  if (!theta_m || !theta_m_send || !theta_g) return kErrNull;
+  if (!theta_m || !theta_g) return kErrNull;
   if (int rc = check_table(frags, K, n_total)) return rc;
   if (int rc = check_hparams(hp)) return rc;
+  if (!theta_m_send && hp->merge_mode == 0) return kErrNull;  // Algorithm 1 needs theta^m_{p,t_p}
   for (int32_t p = 0; p < K; ++p) {
     for (uint64_t i = frags[p].offset; i < frags[p].offset + frags[p].length; ++i) {
-      const double tm = theta_m[i], ts = theta_m_send[i], G = theta_g[i];
+      const double tm = theta_m[i], ts = theta_m_send ? theta_m_send[i] : tm, G = theta_g[i];
       const double d = drift_times_tau(ts, tm, *hp);
       theta_m[i] = static_cast<float>(merge_local(G, ts, tm, d, *hp));
     }
@@ -254,10 +257,11 @@ int cocodc_ref_sync_step(const cocodc_ref_fragment_t* frags, int32_t K, uint64_t
                          const int64_t* I_p, const int64_t* t_b, int64_t t_g, int32_t budget,
                          const cocodc_ref_hparams_t* hp, double* R_out, int32_t* sel_out,
                          int32_t* n_sel_out, double* sums_out, const cocodc_ref_shadow_t* shadow) {
-  if (!theta_m || !theta_m_send || !theta_g || !momentum || !delta_g) return kErrNull;
+  if (!theta_m || !theta_g || !momentum || !delta_g) return kErrNull;
   if (!I_p || !t_b || !R_out || !sel_out || !n_sel_out) return kErrNull;
   if (int rc = check_table(frags, K, n_total)) return rc;
   if (int rc = check_hparams(hp)) return rc;
+  if (!theta_m_send && (hp->merge_mode == 0 || hp->score_src == 1)) return kErrNull;
   if (budget < 0) return kErrRange;
   for (int32_t p = 0; p < K; ++p) {
     Sums s;
@@ -282,10 +286,11 @@ int cocodc_ref_sync_step_mt(const cocodc_ref_fragment_t* frags, int32_t K, uint6
                             const int64_t* I_p, const int64_t* t_b, int64_t t_g, int32_t budget,
                             const cocodc_ref_hparams_t* hp, double* R_out, int32_t* sel_out,
                             int32_t* n_sel_out, double* sums_out, int32_t n_threads) {
-  if (!theta_m || !theta_m_send || !theta_g || !momentum || !delta_g) return kErrNull;
+  if (!theta_m || !theta_g || !momentum || !delta_g) return kErrNull;
   if (!I_p || !t_b || !R_out || !sel_out || !n_sel_out) return kErrNull;
   if (int rc = check_table(frags, K, n_total)) return rc;
   if (int rc = check_hparams(hp)) return rc;
+  if (!theta_m_send && (hp->merge_mode == 0 || hp->score_src == 1)) return kErrNull;
   if (budget < 0) return kErrRange;
   constexpr uint64_t kChunk = 65536;
   int used = 1;

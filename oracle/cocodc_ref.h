@@ -71,7 +71,8 @@ int cocodc_ref_outer_nesterov(const cocodc_ref_fragment_t* frags, int32_t K, uin
                               float* theta_g, float* momentum, const float* delta_g,
                               const cocodc_ref_hparams_t* hp);
 
-/* Algorithm 1 (Eq. 4, 7, 8), or Eq. 3 / plain replacement for the other merge modes. */
+/* Algorithm 1 (Eq. 4, 7, 8), or Eq. 3 / plain replacement for the other merge modes.
+ * theta_m_send may be NULL for merge modes 1 and 2 (they do not use it). */
 int cocodc_ref_delay_compensate(const cocodc_ref_fragment_t* frags, int32_t K, uint64_t n_total,
                                 float* theta_m, const float* theta_m_send, const float* theta_g,
                                 const cocodc_ref_hparams_t* hp);
@@ -87,7 +88,8 @@ int cocodc_ref_select_fragments(int32_t K, const double* R, const int64_t* t_b, 
                                 int32_t H, int32_t budget, int32_t* sel_out, int32_t* n_sel_out);
 
 /* All of the above in one pass per element.  sums_out (nullable, 4*K):
- * per fragment {sum dg^2, sum |dg|, sum d^2, sum |d|}. */
+ * per fragment {sum dg^2, sum |dg|, sum d^2, sum |d|}.  theta_m_send may be NULL for merge
+ * modes 1 and 2 with score_src 0; the drift and its two sums are then zero. */
 int cocodc_ref_sync_step(const cocodc_ref_fragment_t* frags, int32_t K, uint64_t n_total,
                          float* theta_m, const float* theta_m_send, float* theta_g,
                          float* momentum, const float* delta_g,

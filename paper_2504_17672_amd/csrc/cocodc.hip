@@ -167,7 +167,8 @@ __device__ __forceinline__ float merge_local(float G, float theta_send, float th
 //   load<V>(i)        issues the loads of elements [i, i+V),
 //   apply<V>(i, r, a) computes, stores, and accumulates into a[kAcc].
 
-template <bool NESTEROV, int MERGE, bool HAS_PG>
+// HAS_SEND false: no send-time record (merge modes 1 and 2 only): the drift and its sums are 0.
+template <bool NESTEROV, int MERGE, bool HAS_PG, bool HAS_SEND = true>
 struct FusedOp {
   static constexpr int kAcc = 4;
   float* theta_m;
@@ -187,7 +188,7 @@ struct FusedOp {
   __device__ __forceinline__ Regs<V> load(uint64_t i) const {
     Regs<V> r;
     r.tm = load_stream<V>(theta_m + i);
-    r.ts = load_stream<V>(theta_send + i);
+    if (HAS_SEND) r.ts = load_stream<V>(theta_send + i);
     r.tg = load_stream<V>(theta_g + i);
     r.m = load_stream<V>(momentum + i);
     r.dg = load_stream<V>(delta_g + i);
@@ -199,17 +200,20 @@ struct FusedOp {
     typename Vec<V>::type o_tm, o_tg, o_m, o_pg;
 #pragma unroll
     for (int k = 0; k < V; ++k) {
-      const float tm = lane_get(r.tm, k), ts = lane_get(r.ts, k), tg = lane_get(r.tg, k);
+      const float tm = lane_get(r.tm, k), tg = lane_get(r.tg, k);
+      const float ts = HAS_SEND ? lane_get(r.ts, k) : tm;
       const float m = lane_get(r.m, k), dg = lane_get(r.dg, k);
       float m1;
       const float G = outer_update<NESTEROV>(tg, m, dg, hp, &m1);
-      const double d = drift(ts, tm, hp);
+      const double d = HAS_SEND ? drift(ts, tm, hp) : 0.0;
       const float tm1 = merge_local<MERGE>(G, ts, tm, d, hp);
       const double dgd = static_cast<double>(dg);
       a[0] = fma(dgd, dgd, a[0]);  // exact product: same as a plain multiply-then-add
       a[1] += fabs(dgd);
-      a[2] += d * d;
-      a[3] += fabs(d);
+      if (HAS_SEND) {
+        a[2] += d * d;
+        a[3] += fabs(d);
+      }
       lane_set(o_tm, k, tm1);
       lane_set(o_tg, k, G);
       lane_set(o_m, k, m1);
@@ -287,7 +291,7 @@ struct OuterOp {
   }
 };
 
-template <int MERGE>
+template <int MERGE, bool HAS_SEND = true>
 struct MergeOp {
   static constexpr int kAcc = 0;
   float* theta_m;
@@ -303,7 +307,7 @@ struct MergeOp {
   __device__ __forceinline__ Regs<V> load(uint64_t i) const {
     Regs<V> r;
     r.tm = load_stream<V>(theta_m + i);
-    r.ts = load_stream<V>(theta_send + i);
+    if (HAS_SEND) r.ts = load_stream<V>(theta_send + i);
     r.tg = load_stream<V>(theta_g + i);
     return r;
   }
@@ -312,8 +316,10 @@ struct MergeOp {
     typename Vec<V>::type o;
 #pragma unroll
     for (int k = 0; k < V; ++k) {
-      const float tm = lane_get(r.tm, k), ts = lane_get(r.ts, k);
-      lane_set(o, k, merge_local<MERGE>(lane_get(r.tg, k), ts, tm, drift(ts, tm, hp), hp));
+      const float tm = lane_get(r.tm, k);
+      const float ts = HAS_SEND ? lane_get(r.ts, k) : tm;
+      const double d = HAS_SEND ? drift(ts, tm, hp) : 0.0;
+      lane_set(o, k, merge_local<MERGE>(lane_get(r.tg, k), ts, tm, d, hp));
     }
     store_stream<V>(theta_m + i, o);
   }
@@ -704,6 +710,16 @@ struct Profiler {
 template <bool NESTEROV, int MERGE>
 int launch_fused(bool vec, const FragRec* tbl, uint64_t T, float* tm, const float* ts, float* tg,
                  float* m, const float* dg, float* pg, const DevHP& hp, double* partials, hipStream_t s) {
+  if (MERGE == 1 || MERGE == 2) {
+    if (!ts) {  // the blend and the plain replacement never look at the send-time record
+      if (pg) {
+        FusedOp<NESTEROV, (MERGE == 1 || MERGE == 2) ? MERGE : 1, true, false> op{tm, nullptr, tg, m, dg, pg, hp};
+        return launch_walk(vec, tbl, T, op, partials, s);
+      }
+      FusedOp<NESTEROV, (MERGE == 1 || MERGE == 2) ? MERGE : 1, false, false> op{tm, nullptr, tg, m, dg, nullptr, hp};
+      return launch_walk(vec, tbl, T, op, partials, s);
+    }
+  }
   if (pg) {
     FusedOp<NESTEROV, MERGE, true> op{tm, ts, tg, m, dg, pg, hp};
     return launch_walk(vec, tbl, T, op, partials, s);
@@ -791,9 +807,10 @@ int cocodc_outer_nesterov(const cocodc_fragment_t* frags, int32_t K, uint64_t n_
 int cocodc_delay_compensate(const cocodc_fragment_t* frags, int32_t K, uint64_t n_total, float* theta_m,
                             const float* theta_m_send, const float* theta_g, const cocodc_hparams_t* hp,
                             void* workspace, size_t workspace_bytes_, void* stream) {
-  if (!theta_m || !theta_m_send || !theta_g) return COCODC_ERR_NULL;
+  if (!theta_m || !theta_g) return COCODC_ERR_NULL;
   if (!all_aligned4({theta_m, theta_m_send, theta_g})) return COCODC_ERR_ALIGN;
   if (int rc = check_hparams(hp)) return rc;
+  if (!theta_m_send && hp->merge_mode == 0) return COCODC_ERR_NULL;  // Algorithm 1 needs theta^m_{p,t_p}
   std::vector<FragRec> recs;
   uint64_t T = 0;
   if (int rc = plan_table(frags, K, n_total, nullptr, nullptr, &recs, &T)) return rc;
@@ -813,11 +830,11 @@ int cocodc_delay_compensate(const cocodc_fragment_t* frags, int32_t K, uint64_t 
       return launch_walk(vec, v.table, T, op, v.partials, s);
     }
     case 1: {
-      MergeOp<1> op{theta_m, theta_m_send, theta_g, d};
+      MergeOp<1, false> op{theta_m, nullptr, theta_g, d};
       return launch_walk(vec, v.table, T, op, v.partials, s);
     }
     case 2: {
-      MergeOp<2> op{theta_m, theta_m_send, theta_g, d};
+      MergeOp<2, false> op{theta_m, nullptr, theta_g, d};
       return launch_walk(vec, v.table, T, op, v.partials, s);
     }
     default: {
@@ -891,12 +908,13 @@ int cocodc_sync_step(const cocodc_fragment_t* frags, int32_t K, uint64_t n_total
                      int32_t budget, const cocodc_hparams_t* hp, double* R_out, int32_t* sel_out,
                      int32_t* n_sel_out, double* sums_out, void* workspace, size_t workspace_bytes_,
                      void* stream) {
-  if (!theta_m || !theta_m_send || !theta_g || !momentum || !delta_g) return COCODC_ERR_NULL;
+  if (!theta_m || !theta_g || !momentum || !delta_g) return COCODC_ERR_NULL;
   if (!I_p || !t_b || !R_out || !sel_out || !n_sel_out) return COCODC_ERR_NULL;
   if (!all_aligned4({theta_m, theta_m_send, theta_g, momentum, delta_g, delta_m_out, sel_out, n_sel_out}))
     return COCODC_ERR_ALIGN;
   if (!aligned(R_out, 8) || !aligned(sums_out, 8)) return COCODC_ERR_ALIGN;
   if (int rc = check_hparams(hp)) return rc;
+  if (!theta_m_send && (hp->merge_mode == 0 || hp->score_src == 1)) return COCODC_ERR_NULL;
   if (budget < 0) return COCODC_ERR_RANGE;
   std::vector<FragRec> recs;
   uint64_t T = 0;

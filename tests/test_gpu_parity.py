@@ -146,6 +146,46 @@ def test_hyper_parameter_switches(B, ref, hpkw):
     _fused_case(B, ref, amp, seed=6, amplified=True, **hpkw)
 
 
+@pytest.mark.parametrize("mode", [1, 2])
+def test_baseline_merges_without_send_time_record(B, ref, mode):
+    """Eq. 3 / blocking merge with theta_m_send = NULL: 32-byte pass, drift sums zero."""
+    wl = synth.Workload("nosend", (50001, 16384, 3, 70000), tau=5, H=100, budget=2)
+    bk = synth.bookkeeping(wl)
+    st = synth.make_state(wl, "cuda", seed=12)
+    host = U.host_copy(st)
+    ghp = B.hparams(5, 100, merge_mode=mode, alpha=0.4)
+    rhp = ref.hparams(5, 100, merge_mode=mode, alpha=0.4)
+    ws = B.new_workspace(wl.K, wl.n_total)
+    out = U.gpu_outputs(wl.K)
+    pg = torch.full_like(st["delta_g"], 555.0)
+    send_before = st["theta_m_send"].clone()
+    assert B.cocodc_sync_step(wl.frags, wl.n_total, st["theta_m"], None, st["theta_g"], st["momentum"],
+                              st["delta_g"], pg, bk.I_p, bk.t_b, bk.t_g, 2, ghp, out["R"], out["sel"],
+                              out["n_sel"], out["sums"], ws) == 0
+    torch.cuda.synchronize()
+    out["pg"] = pg
+    out["sel_list"] = out["sel"][:int(out["n_sel"].item())].cpu().tolist()
+    h_pg = np.full(wl.n_total, 555.0, np.float32)
+    ro = ref.sync_step(wl.frags, host["theta_m"], None, host["theta_g"], host["momentum"], host["delta_g"], h_pg,
+                       bk.I_p, bk.t_b, bk.t_g, 2, rhp, shadow=True)
+    ro["pg"] = h_pg
+    U.compare_fused(st, out, host, ro, wl.frags)
+    U.compare_selection(out, ro, bk, 100)
+    assert torch.equal(out["sums"][:, 2:], torch.zeros_like(out["sums"][:, 2:]))
+    assert torch.equal(st["theta_m_send"], send_before)
+    # single-step entry point without the record
+    tm = torch.from_numpy(U.host_copy(synth.make_state(wl, "cuda", seed=12))["theta_m"]).cuda()
+    assert B.cocodc_delay_compensate(wl.frags, wl.n_total, tm, None, st["theta_g"], ghp, ws) == 0
+    torch.cuda.synchronize()
+    assert torch.equal(tm, st["theta_m"])
+    # Algorithm 1 and drift scoring refuse to run without it
+    assert B.cocodc_delay_compensate(wl.frags, wl.n_total, tm, None, st["theta_g"], B.hparams(5, 100), ws) \
+        == B.COCODC_ERR_NULL
+    assert B.cocodc_sync_step(wl.frags, wl.n_total, st["theta_m"], None, st["theta_g"], st["momentum"],
+                              st["delta_g"], pg, bk.I_p, bk.t_b, bk.t_g, 2, B.hparams(5, 100, merge_mode=mode, score_src=1),
+                              out["R"], out["sel"], out["n_sel"], out["sums"], ws) == B.COCODC_ERR_NULL
+
+
 def test_tau_zero_drops_the_correction(B, ref):
     wl = synth.Workload("tau0", (40000, 12345), tau=0, H=3, budget=1)
     _fused_case(B, ref, wl, seed=7, amplified=True)

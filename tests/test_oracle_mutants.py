@@ -73,6 +73,7 @@ BATTERY = [
     pins.test_change_rate_sign_flip_moves_result_by_twice_the_drift,
     pins.test_single_worker_sync_is_a_no_op_with_reversed_sign,
     pins.test_merge_modes_blend_and_replace,
+    pins.test_baseline_merges_need_no_send_time_record,
     pins.test_scores_brute_force_exact_rational,
     pins.test_scores_closed_forms,
     pins.test_score_is_infinite_before_first_sync,

@@ -23,6 +23,11 @@ def f32(*vals):
     return np.array(vals, dtype=np.float32)
 
 
+def _numpy_state(wl, seed, amplified=False):
+    st = synth.make_state(wl, "cpu", seed=seed, amplified=amplified)
+    return {k: v.numpy() for k, v in st.items()}
+
+
 def rnd(n, sigma, seed):
     g = torch.Generator().manual_seed(seed)
     return torch.empty(n, dtype=torch.float32).normal_(0.0, sigma, generator=g).numpy()
@@ -243,6 +248,38 @@ def test_merge_modes_blend_and_replace(ref):
     assert out.tolist() == [3.0, -2.0]
 
 
+def test_baseline_merges_need_no_send_time_record(ref):
+    """Eq. 3 and the blocking merge never look at theta^m_{p,t_p}: leaving it out changes
+    nothing but the drift sums (zero); Algorithm 1 refuses to run without it."""
+    wl = synth.Workload("t", (700, 301), tau=5, H=100, budget=1)
+    bk = synth.bookkeeping(wl)
+    base = _numpy_state(wl, 9)
+    for mode in (1, 2):
+        hp = ref.hparams(5, 100, merge_mode=mode, alpha=0.25)
+        a = {k: v.copy() for k, v in base.items()}
+        b = {k: v.copy() for k, v in base.items()}
+        fa = ref.sync_step(wl.frags, a["theta_m"], a["theta_m_send"], a["theta_g"], a["momentum"], a["delta_g"],
+                           None, bk.I_p, bk.t_b, bk.t_g, 1, hp)
+        fb = ref.sync_step(wl.frags, b["theta_m"], None, b["theta_g"], b["momentum"], b["delta_g"],
+                           None, bk.I_p, bk.t_b, bk.t_g, 1, hp)
+        assert fa["rc"] == 0 and fb["rc"] == 0
+        for k in ("theta_m", "theta_g", "momentum"):
+            assert np.array_equal(a[k], b[k])
+        assert np.array_equal(fa["sums"][:, :2], fb["sums"][:, :2]) and np.all(fb["sums"][:, 2:] == 0)
+        assert np.all(fa["sums"][:, 2:] > 0)
+        c = base["theta_m"].copy()
+        assert ref.delay_compensate(wl.frags, c, None, a["theta_g"], hp) == 0
+        assert np.array_equal(c, a["theta_m"])
+    x = {k: v.copy() for k, v in base.items()}
+    assert ref.sync_step(wl.frags, x["theta_m"], None, x["theta_g"], x["momentum"], x["delta_g"], None,
+                         bk.I_p, bk.t_b, bk.t_g, 1, ref.hparams(5, 100))["rc"] == -1
+    assert ref.sync_step(wl.frags, x["theta_m"], None, x["theta_g"], x["momentum"], x["delta_g"], None,
+                         bk.I_p, bk.t_b, bk.t_g, 1, ref.hparams(5, 100, merge_mode=1, score_src=1))["rc"] == -1
+    assert ref.delay_compensate(wl.frags, x["theta_m"], None, x["theta_g"], ref.hparams(5, 100)) == -1
+    for k in base:
+        assert np.array_equal(x[k], base[k])
+
+
 # ----------------------------------------------------------------------------- a4
 def test_scores_brute_force_exact_rational(ref):
     """Eq. 11 on tiny fragments against exact rational arithmetic."""
@@ -394,10 +431,6 @@ def test_planner_floor_of_k(ref):
 
 
 # ----------------------------------------------------------------------------- composition
-def _numpy_state(wl, seed, amplified=False):
-    st = synth.make_state(wl, "cpu", seed=seed, amplified=amplified)
-    return {k: v.numpy() for k, v in st.items()}
-
 
 @pytest.mark.parametrize("amplified", [False, True])
 def test_fused_equals_sequence_of_primitives(ref, amplified):
