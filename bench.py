@@ -84,6 +84,10 @@ def main():
                          "short probe at set-up finds fastest; spaced: fixed stride "
                          "cocodc_layout_stride_bytes(); packed: six separate allocations")
     ap.add_argument("--stride-gib", type=float, default=None, help="override the spaced-layout stride")
+    ap.add_argument("--loop-steps", type=int, default=0, metavar="T",
+                    help="instead of the fused-step benchmark, drive the Sec. 3.2 loop (cocodc_loop_step) for T "
+                         "inner steps with one worker and the in-place send/receive buffer, and report the "
+                         "time of its receive and send events")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
                     help="instead of the benchmark, run 5 plain device copies of MIB mebibytes (a kernel "
                          "of known traffic, to scale rocprofv3 FETCH_SIZE / WRITE_SIZE readings) and exit")
@@ -146,6 +150,40 @@ def main():
     if args.blocks_per_cu is not None:
         B.cocodc_set_blocks_per_cu(args.blocks_per_cu)
     torch.cuda.synchronize()
+
+    if args.loop_steps:
+        rc, loop = B.cocodc_loop_create(wl.frags, n, hp, 1.0, 1.0, float(wl.tau))  # T_s = tau * T_c
+        B.check(rc)
+        B.check(B.cocodc_loop_reset_scores(loop, R))
+        lb = B.loop_buffers(st["theta_m"], st["theta_m_send"], st["theta_g"], st["momentum"], st["delta_g"],
+                            st["delta_g"], R, sel, n_sel, ws)
+        _, N_plan, h_plan = B.cocodc_loop_plan(loop)
+        ev = []
+        torch.cuda.synchronize()
+        t_all = time.perf_counter()
+        for t in range(1, args.loop_steps + 1):
+            t0 = time.perf_counter()
+            rc, rec, sent = B.cocodc_loop_step(loop, t, lb)
+            B.check(rc)
+            if rec or sent >= 0:
+                torch.cuda.synchronize()
+                ev.append((time.perf_counter() - t0, rec, sent))
+        torch.cuda.synchronize()
+        t_all = time.perf_counter() - t_all
+        B.cocodc_loop_destroy(loop)
+        lens = [l for _, l in wl.frags]
+        rec_p = sum(lens[p] for _, rec, _ in ev for p in rec)
+        snd_p = sum(lens[s] for _, _, s in ev if s >= 0)
+        only_rec = [(dt, sum(lens[p] for p in rec)) for dt, rec, s in ev if rec and s < 0]
+        only_snd = [(dt, lens[s]) for dt, rec, s in ev if not rec and s >= 0]
+        out = {"mode": "loop", "workload": wl.name, "inner_steps": args.loop_steps, "tau": wl.tau, "H": wl.H,
+               "N": N_plan, "h": h_plan, "events": len(ev), "received_params": rec_p, "sent_params": snd_p,
+               "loop_seconds": round(t_all, 4),
+               "receive_Gparams_per_s": round(sum(p for _, p in only_rec) / max(sum(d for d, _ in only_rec), 1e-12) / 1e9, 2),
+               "send_Gparams_per_s": round(sum(p for _, p in only_snd) / max(sum(d for d, _ in only_snd), 1e-12) / 1e9, 2),
+               "receive_bytes_per_param": 32, "send_bytes_per_param": 16}
+        print(json.dumps(out), flush=True)
+        return
 
     cpu = None
     if not args.no_cpu:

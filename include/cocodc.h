@@ -183,6 +183,68 @@ int cocodc_sync_step(const cocodc_fragment_t* frags, int32_t K, uint64_t n_total
 int cocodc_sync_plan(int32_t K, int32_t H, double gamma, double T_c, double T_s, int64_t* N_out,
                      int64_t* h_out);
 
+/* ---- the adaptive-transmission loop of Sec. 3.2 around the kernels ---- */
+
+/* Host-side schedule state of one worker: which fragment was sent when, t_{p,b}, I_p, the
+ * moving averages of T_c and T_s and the resulting N and h (Eq. 9, Eq. 10).  Opaque; lives in
+ * host memory only. */
+typedef struct cocodc_loop cocodc_loop_t;
+
+/* Device buffers the loop works on (all caller-owned; see the conventions above). */
+typedef struct {
+  float* theta_m;        /* local parameters, advanced by the caller's inner optimiser          */
+  float* theta_m_send;   /* send-time records theta^m_{p,t_p}                                   */
+  float* theta_g;        /* global states of all fragments                                      */
+  float* momentum;       /* outer-optimiser momentum                                            */
+  float* delta_g;        /* where the averaged pseudo-gradient of a fragment has arrived        */
+  float* delta_m_out;    /* where a sent fragment's pseudo-gradient is written; may be delta_g  */
+                         /* (the in-place all-reduce buffer; with one worker the loop is closed) */
+  double* R;             /* K scores R_p                                                        */
+  int32_t* sel;          /* K int32 scratch for the selection                                   */
+  int32_t* n_sel;        /* 1 int32 scratch                                                     */
+  void* workspace;       /* cocodc_workspace_bytes(K, n_total)                                  */
+  size_t workspace_bytes;
+} cocodc_loop_buffers_t;
+
+/* Creates the schedule for K fragments.  hp->H and hp->tau are the period and the overlap
+ * depth; gamma, T_c, T_s feed Eq. 9 / Eq. 10 (N syncs per H steps, one send every
+ * h = max(1, floor(H/N)) steps).  All t_{p,b} start at 0 and every R_p at +infinity (Sec. 3.2:
+ * fragments that never completed a synchronisation go first). */
+int cocodc_loop_create(const cocodc_fragment_t* frags, int32_t K, uint64_t n_total,
+                       const cocodc_hparams_t* hp, double gamma, double T_c, double T_s,
+                       cocodc_loop_t** loop_out);
+void cocodc_loop_destroy(cocodc_loop_t* loop);
+
+/* Writes +infinity to the K scores (enqueued on `stream`); call once before the first step. */
+int cocodc_loop_reset_scores(cocodc_loop_t* loop, double* R, void* stream);
+
+/* Online moving averages of the measured step time and fragment synchronisation time
+ * (Sec. 3.2): T <- (1-beta)*T + beta*sample for each, then N and h are recomputed. */
+int cocodc_loop_observe(cocodc_loop_t* loop, double T_c_sample, double T_s_sample, double beta);
+
+/* Current plan: N (Eq. 9) and h (Eq. 10, at least 1). */
+int cocodc_loop_plan(const cocodc_loop_t* loop, int64_t* N_out, int64_t* h_out);
+
+/* Fragments whose all-reduce, launched at step t - tau, completes at step t (ascending).
+ * Lets the caller put their averaged pseudo-gradients into delta_g before cocodc_loop_step. */
+int cocodc_loop_due(const cocodc_loop_t* loop, int64_t t, int32_t* due_out, int32_t* n_due_out);
+
+/* One inner step t = 1, 2, ... of the worker, called after its local optimiser step:
+ *  1. every fragment due at t is received, in ascending index: the fused step
+ *     (cocodc_sync_step) on that fragment alone with I_p = t_p - t_{p,b} (Eq. 11), which
+ *     updates R_p; then t_{p,b} <- t.
+ *  2. if t is a multiple of h: Algorithm 2 picks p* among the fragments that are not in flight
+ *     (t_g = t); its pseudo-gradient goes to delta_m_out and theta_m_send records the
+ *     send-time parameters (cocodc_pseudograd); it will be due at t + tau.
+ * received_out (host, K int32), n_received_out, sent_out (host; -1 if nothing was sent).
+ * Synchronises the stream when it has to read the selection back (once per send). */
+int cocodc_loop_step(cocodc_loop_t* loop, int64_t t, const cocodc_loop_buffers_t* buf, void* stream,
+                     int32_t* received_out, int32_t* n_received_out, int32_t* sent_out);
+
+/* Copies the bookkeeping out (host arrays of K): t_{p,b}, the I_p used at the last receive
+ * (0 = never), and the send step of a fragment in flight (-1 = not in flight). */
+int cocodc_loop_state(const cocodc_loop_t* loop, int64_t* t_b_out, int64_t* I_p_out, int64_t* in_flight_out);
+
 /* ---- data layout in HBM (no paper counterpart) ---- */
 
 /* Recommended distance in bytes between the base addresses of the flat buffers that one

@@ -1,0 +1,69 @@
+"""CPU definition of the adaptive-transmission loop of the paper's Sec. 3.2 around the oracle's
+single steps.  TEST INFRASTRUCTURE ONLY (see oracle/cocodc_ref.h).
+
+One worker, inner steps t = 1, 2, ...; all buffers are host numpy arrays.  Per step, after the
+worker's local update:
+  1. every fragment whose all-reduce was launched tau steps ago completes: the fused oracle
+     step on that fragment alone, with I_p = t_p - t_{p,b} (Eq. 11); then t_{p,b} <- t
+     ("the step at which the previous synchronisation was completed");
+  2. every h steps (Eq. 10; h = floor(H/N), at least 1, N from Eq. 9) the next fragment is
+     chosen by Algorithm 2 with t_g = t among the fragments that are not in flight; its
+     pseudo-gradient is written to the send buffer and its parameters are recorded.
+All t_{p,b} start at 0 and all R_p at +infinity (never-synchronised fragments go first).
+Readings where the paper is silent: a fragment in flight is not eligible; h = 0 is taken as 1;
+receives happen before the send decision of the same step, in ascending fragment index.
+"""
+import numpy as np
+
+from . import pseudograd, select_fragments, sync_plan, sync_step
+
+
+class RefLoop:
+    def __init__(self, frags, hp, gamma, T_c, T_s):
+        self.frags = [(int(o), int(l)) for o, l in frags]
+        self.K = len(self.frags)
+        self.hp = hp
+        self.gamma, self.T_c, self.T_s = float(gamma), float(T_c), float(T_s)
+        self.t_b = [0] * self.K
+        self.I_p = [0] * self.K
+        self.in_flight = [-1] * self.K
+        self.R = np.full(self.K, np.inf)
+        self._replan()
+
+    def _replan(self):
+        rc, N, h = sync_plan(self.K, self.hp.H, self.gamma, self.T_c, self.T_s)
+        assert rc == 0
+        self.N, self.h = N, max(1, h)
+
+    def observe(self, T_c_sample, T_s_sample, beta):
+        self.T_c = (1.0 - beta) * self.T_c + beta * T_c_sample
+        self.T_s = (1.0 - beta) * self.T_s + beta * T_s_sample
+        self._replan()
+
+    def due(self, t):
+        return [p for p in range(self.K) if self.in_flight[p] >= 0 and self.in_flight[p] + self.hp.tau == t]
+
+    def step(self, t, theta_m, theta_m_send, theta_g, momentum, delta_g, delta_m_out):
+        received = []
+        for p in self.due(t):
+            I = self.in_flight[p] - self.t_b[p]
+            out = sync_step([self.frags[p]], theta_m, theta_m_send, theta_g, momentum, delta_g, None,
+                            [I], [self.t_b[p]], t, 0, self.hp)
+            assert out["rc"] == 0
+            self.R[p] = out["R"][0]
+            self.I_p[p] = I
+            self.t_b[p] = t
+            self.in_flight[p] = -1
+            received.append(p)
+        sent = -1
+        if t % self.h == 0:
+            rc, order = select_fragments(self.R, self.t_b, t, self.hp.H, self.K)
+            assert rc == 0
+            for q in order.tolist():
+                if self.in_flight[q] < 0:
+                    sent = q
+                    break
+            if sent >= 0:
+                assert pseudograd([self.frags[sent]], theta_g, theta_m, delta_m_out, theta_m_send) == 0
+                self.in_flight[sent] = t
+        return received, sent

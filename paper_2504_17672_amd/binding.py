@@ -32,6 +32,8 @@ COCODC_ERR_ALIAS = -7
 EXPORTS = (
     "cocodc_workspace_bytes", "cocodc_pseudograd", "cocodc_outer_nesterov", "cocodc_delay_compensate",
     "cocodc_fragment_scores", "cocodc_select_fragments", "cocodc_sync_step", "cocodc_sync_plan",
+    "cocodc_loop_create", "cocodc_loop_destroy", "cocodc_loop_reset_scores", "cocodc_loop_observe",
+    "cocodc_loop_plan", "cocodc_loop_due", "cocodc_loop_step", "cocodc_loop_state",
     "cocodc_layout_stride_bytes", "cocodc_last_hip_error", "cocodc_status_string", "cocodc_set_blocks_per_cu",
     "cocodc_profiler_enable", "cocodc_profiler_collect", "cocodc_profiler_disable",
 )
@@ -51,6 +53,13 @@ class cocodc_hparams_t(C.Structure):
     ]
 
 
+class cocodc_loop_buffers_t(C.Structure):
+    _fields_ = [("theta_m", C.c_void_p), ("theta_m_send", C.c_void_p), ("theta_g", C.c_void_p),
+                ("momentum", C.c_void_p), ("delta_g", C.c_void_p), ("delta_m_out", C.c_void_p),
+                ("R", C.c_void_p), ("sel", C.c_void_p), ("n_sel", C.c_void_p),
+                ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t)]
+
+
 _P = C.c_void_p
 _frag_p = C.POINTER(cocodc_fragment_t)
 _hp_p = C.POINTER(cocodc_hparams_t)
@@ -68,6 +77,17 @@ _lib.cocodc_select_fragments.argtypes = [C.c_int32, _P, _i64_p, C.c_int64, C.c_i
 _lib.cocodc_sync_step.argtypes = [_frag_p, C.c_int32, C.c_uint64, _P, _P, _P, _P, _P, _P, _i64_p, _i64_p,
                                   C.c_int64, C.c_int32, _hp_p, _P, _P, _P, _P, _P, C.c_size_t, _P]
 _lib.cocodc_sync_plan.argtypes = [C.c_int32, C.c_int32, C.c_double, C.c_double, C.c_double, _i64_p, _i64_p]
+_i32_p = C.POINTER(C.c_int32)
+_lib.cocodc_loop_create.argtypes = [_frag_p, C.c_int32, C.c_uint64, _hp_p, C.c_double, C.c_double, C.c_double,
+                                    C.POINTER(C.c_void_p)]
+_lib.cocodc_loop_destroy.argtypes = [_P]
+_lib.cocodc_loop_destroy.restype = None
+_lib.cocodc_loop_reset_scores.argtypes = [_P, _P, _P]
+_lib.cocodc_loop_observe.argtypes = [_P, C.c_double, C.c_double, C.c_double]
+_lib.cocodc_loop_plan.argtypes = [_P, _i64_p, _i64_p]
+_lib.cocodc_loop_due.argtypes = [_P, C.c_int64, _i32_p, _i32_p]
+_lib.cocodc_loop_step.argtypes = [_P, C.c_int64, C.POINTER(cocodc_loop_buffers_t), _P, _i32_p, _i32_p, _i32_p]
+_lib.cocodc_loop_state.argtypes = [_P, _i64_p, _i64_p, _i64_p]
 _lib.cocodc_layout_stride_bytes.restype = C.c_uint64
 _lib.cocodc_layout_stride_bytes.argtypes = [C.c_uint64]
 _lib.cocodc_status_string.restype = C.c_char_p
@@ -76,7 +96,8 @@ _lib.cocodc_set_blocks_per_cu.argtypes = [C.c_int]
 _lib.cocodc_profiler_enable.argtypes = [C.c_int32]
 _lib.cocodc_profiler_collect.argtypes = [C.POINTER(C.c_float), C.c_int32]
 for _name in EXPORTS:
-    if _name not in ("cocodc_workspace_bytes", "cocodc_status_string", "cocodc_layout_stride_bytes"):
+    if _name not in ("cocodc_workspace_bytes", "cocodc_status_string", "cocodc_layout_stride_bytes",
+                     "cocodc_loop_destroy"):
         getattr(_lib, _name).restype = C.c_int
 
 
@@ -311,3 +332,63 @@ def cocodc_profiler_collect(capacity):
 
 def cocodc_profiler_disable():
     return int(_lib.cocodc_profiler_disable())
+
+
+# ---- Sec. 3.2 loop ----
+def cocodc_loop_create(frags, n_total, hp, gamma, T_c, T_s, K=None):
+    """Returns (status, handle); the handle carries K for the other loop calls."""
+    fa, k = _frags(frags)
+    h = C.c_void_p(None)
+    rc = _lib.cocodc_loop_create(fa, k if K is None else K, int(n_total), C.byref(hp) if hp is not None else None,
+                                 float(gamma), float(T_c), float(T_s), C.byref(h))
+    return rc, ((h, k) if rc == 0 else None)
+
+
+def cocodc_loop_destroy(handle):
+    _lib.cocodc_loop_destroy(handle[0])
+
+
+def cocodc_loop_reset_scores(handle, R, stream=None):
+    return _lib.cocodc_loop_reset_scores(handle[0], _ptr(R), _stream(stream))
+
+
+def cocodc_loop_observe(handle, T_c_sample, T_s_sample, beta):
+    return _lib.cocodc_loop_observe(handle[0], float(T_c_sample), float(T_s_sample), float(beta))
+
+
+def cocodc_loop_plan(handle):
+    """Returns (status, N, h)."""
+    N, h = C.c_int64(0), C.c_int64(0)
+    rc = _lib.cocodc_loop_plan(handle[0], C.byref(N), C.byref(h))
+    return rc, N.value, h.value
+
+
+def cocodc_loop_due(handle, t):
+    """Returns (status, [fragments due at step t])."""
+    due = (C.c_int32 * max(handle[1], 1))()
+    n = C.c_int32(0)
+    rc = _lib.cocodc_loop_due(handle[0], int(t), due, C.byref(n))
+    return rc, [int(due[i]) for i in range(n.value)]
+
+
+def loop_buffers(theta_m, theta_m_send, theta_g, momentum, delta_g, delta_m_out, R, sel, n_sel, workspace):
+    wp, wb = _ws(workspace, None)
+    v = lambda x: None if x is None else x.data_ptr()  # noqa: E731
+    return cocodc_loop_buffers_t(v(theta_m), v(theta_m_send), v(theta_g), v(momentum), v(delta_g), v(delta_m_out),
+                                 v(R), v(sel), v(n_sel), workspace.data_ptr(), wb)
+
+
+def cocodc_loop_step(handle, t, buffers, stream=None):
+    """Returns (status, [received fragments], sent fragment or -1)."""
+    rec = (C.c_int32 * max(handle[1], 1))()
+    n, sent = C.c_int32(0), C.c_int32(-1)
+    rc = _lib.cocodc_loop_step(handle[0], int(t), C.byref(buffers), _stream(stream), rec, C.byref(n), C.byref(sent))
+    return rc, [int(rec[i]) for i in range(n.value)], sent.value
+
+
+def cocodc_loop_state(handle):
+    """Returns (status, t_b, I_p, in_flight) as lists of K ints."""
+    K = max(handle[1], 1)
+    a, b, c = (C.c_int64 * K)(), (C.c_int64 * K)(), (C.c_int64 * K)()
+    rc = _lib.cocodc_loop_state(handle[0], a, b, c)
+    return rc, list(a)[:handle[1]], list(b)[:handle[1]], list(c)[:handle[1]]

@@ -1,0 +1,119 @@
+"""GPU parity of the Sec. 3.2 loop (cocodc_loop_*) against the loop oracle: identical event
+log (who is received and who is sent at every inner step), identical bookkeeping, and stored
+buffers that match the oracle's at the end.  Needs an MI355X."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2504_17672_amd import synth
+
+import parity_util as U
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2504_17672_amd import binding
+    assert torch.cuda.is_available()
+    return binding
+
+
+def _run_both(B, ref, wl, gamma, T_c, T_s, steps, closed, seed=0, observe_at=None):
+    from oracle.loop import RefLoop
+    print(f"case loop {wl.name} K={wl.K} n={wl.n_total} steps={steps} closed={closed}", flush=True)
+    st = synth.make_state(wl, "cuda", seed=seed)
+    host = U.host_copy(st)
+    n, K = wl.n_total, wl.K
+    ghp = B.hparams(wl.tau, wl.H, wl.lam, wl.eta, wl.mu)
+    rhp = ref.hparams(wl.tau, wl.H, wl.lam, wl.eta, wl.mu)
+    rc, loop = B.cocodc_loop_create(wl.frags, n, ghp, gamma, T_c, T_s)
+    assert rc == 0
+    rloop = RefLoop(wl.frags, rhp, gamma, T_c, T_s)
+    R = torch.zeros(K, dtype=torch.float64, device="cuda")
+    sel = torch.zeros(K, dtype=torch.int32, device="cuda")
+    n_sel = torch.zeros(1, dtype=torch.int32, device="cuda")
+    ws = B.new_workspace(K, n)
+    assert B.cocodc_loop_reset_scores(loop, R) == 0
+    if closed:
+        send_dev, send_host = st["delta_g"], host["delta_g"]
+    else:
+        send_dev, send_host = torch.zeros(n, device="cuda"), np.zeros(n, np.float32)
+    bufs = B.loop_buffers(st["theta_m"], st["theta_m_send"], st["theta_g"], st["momentum"], st["delta_g"], send_dev,
+                          R, sel, n_sel, ws)
+    g = torch.Generator(device="cuda").manual_seed(77 + seed)
+    n_sent = n_received = 0
+    try:
+        for t in range(1, steps + 1):
+            drift = torch.empty(n, device="cuda").normal_(0.0, 1e-4, generator=g)
+            st["theta_m"] += drift
+            host["theta_m"] += drift.cpu().numpy()
+            rc, due = B.cocodc_loop_due(loop, t)
+            assert rc == 0 and due == rloop.due(t)
+            if not closed:
+                for p in due:
+                    o, l = wl.frags[p]
+                    fresh = torch.empty(l, device="cuda").normal_(0.0, 1e-3, generator=g)
+                    st["delta_g"][o:o + l] = fresh
+                    host["delta_g"][o:o + l] = fresh.cpu().numpy()
+            if observe_at and t in observe_at:
+                a, b, beta = observe_at[t]
+                assert B.cocodc_loop_observe(loop, a, b, beta) == 0
+                rloop.observe(a, b, beta)
+                assert B.cocodc_loop_plan(loop)[1:] == (rloop.N, rloop.h)
+            rc, rec, sent = B.cocodc_loop_step(loop, t, bufs)
+            assert rc == 0, B.cocodc_status_string(rc)
+            rrec, rsent = rloop.step(t, host["theta_m"], host["theta_m_send"], host["theta_g"], host["momentum"],
+                                     host["delta_g"], send_host)
+            assert (rec, sent) == (rrec, rsent), (t, rec, sent, rrec, rsent)
+            n_sent += sent >= 0
+            n_received += len(rec)
+            rc, t_b, I_p, fl = B.cocodc_loop_state(loop)
+            assert (t_b, I_p, fl) == (rloop.t_b, rloop.I_p, rloop.in_flight)
+        torch.cuda.synchronize()
+        for k in ("theta_m", "theta_m_send", "theta_g", "momentum", "delta_g"):
+            gk = st[k].cpu().numpy()
+            assert np.array_equal(np.isnan(gk), np.isnan(host[k]))
+            assert np.array_equal(gk, host[k]), k
+        assert np.array_equal(send_dev.cpu().numpy(), send_host)
+        Rg = R.cpu().numpy()
+        fin = np.isfinite(rloop.R)
+        assert np.array_equal(np.isposinf(Rg), np.isposinf(rloop.R))
+        assert U.rel_err(Rg[fin], rloop.R[fin]) <= U.SCORE_TOL_TIGHT
+    finally:
+        B.cocodc_loop_destroy(loop)
+    print(f"   {n_sent} sends, {n_received} receives, plan N={rloop.N} h={rloop.h}", flush=True)
+    return n_sent, n_received
+
+
+def test_loop_paper_setup_closed_single_worker(B, ref):
+    """K = 4, H = 100, tau = 5, gamma = 0.4 (Sec. 4.1) with the in-place send/receive buffer:
+    one worker's own pseudo-gradient comes back as the 'average' after tau steps."""
+    wl = synth.Workload("loop-paper", (300000, 250001, 199999, 150003), tau=5, H=100)
+    n_sent, n_rec = _run_both(B, ref, wl, 0.4, 1.0, 5.0, 250, closed=True)
+    assert n_sent == 250 // 12 and n_rec >= n_sent - 1
+
+
+def test_loop_external_average_and_replanning(B, ref):
+    wl = synth.MINI_WORKLOADS["125M-mini"]
+    n_sent, n_rec = _run_both(B, ref, wl, 0.5, 1.0, 2.0, 220, closed=False,
+                              observe_at={60: (1.0, 1.0, 1.0), 150: (1.0, 8.0, 0.5)})
+    assert n_sent > 30
+
+
+def test_loop_deep_overlap(B, ref):
+    wl = synth.Workload("loop-deep", (40000,) * 5, tau=30, H=50)
+    _run_both(B, ref, wl, 1.0, 1.0, 5.0, 200, closed=True)
+
+
+def test_loop_rejects_bad_arguments(B):
+    hp = B.hparams(5, 100)
+    assert B.cocodc_loop_create([(0, 10), (5, 10)], 20, hp, 0.4, 1.0, 5.0)[0] == B.COCODC_ERR_RANGE
+    assert B.cocodc_loop_create([(0, 10)], 20, hp, 1.4, 1.0, 5.0)[0] == B.COCODC_ERR_RANGE
+    assert B.cocodc_loop_create([(0, 10)], 20, B.hparams(5, 0), 0.4, 1.0, 5.0)[0] == B.COCODC_ERR_RANGE
+    rc, loop = B.cocodc_loop_create([(0, 10)], 20, hp, 0.4, 1.0, 5.0)
+    assert rc == 0
+    assert B.cocodc_loop_observe(loop, -1.0, 1.0, 0.5) == B.COCODC_ERR_RANGE
+    assert B.cocodc_loop_observe(loop, 1.0, 1.0, 1.5) == B.COCODC_ERR_RANGE
+    assert B.cocodc_loop_observe(loop, float("nan"), 1.0, 0.5) == B.COCODC_ERR_NONFINITE
+    B.cocodc_loop_destroy(loop)
