@@ -84,6 +84,9 @@ def main():
                          "short probe at set-up finds fastest; spaced: fixed stride "
                          "cocodc_layout_stride_bytes(); packed: six separate allocations")
     ap.add_argument("--stride-gib", type=float, default=None, help="override the spaced-layout stride")
+    ap.add_argument("--strided-shards", type=int, default=0, metavar="K",
+                    help="shard the workload's layers into K strided fragments (shard k = layers k, k+K, ...; "
+                         "Sec. 4.1) on a layer-ordered buffer and time cocodc_sync_step_segmented instead")
     ap.add_argument("--loop-steps", type=int, default=0, metavar="T",
                     help="instead of the fused-step benchmark, drive the Sec. 3.2 loop (cocodc_loop_step) for T "
                          "inner steps with one worker and the in-place send/receive buffer, and report the "
@@ -192,7 +195,23 @@ def main():
         cpu = cpu_baseline(wl, st, bk, sample)
         print(f"[bench] cpu baseline {cpu}", file=sys.stderr, flush=True)
 
+    segs = None
+    if args.strided_shards:
+        assert wl.model, "--strided-shards needs a model-shaped workload"
+        segs, n_seg = synth.strided_segments(*wl.model, args.strided_shards)
+        assert n_seg == n
+        Ks = args.strided_shards
+        h = max(1, wl.H // Ks)
+        I_s = [h * (1 + p % 3) for p in range(Ks)]
+        tb_s = [bk.t_g - i for i in I_s]
+        ws = B.new_workspace_segmented(len(segs), Ks, n, dev)
+
     def step():
+        if segs is not None:
+            B.check(B.cocodc_sync_step_segmented(segs, Ks, n, st["theta_m"], send, st["theta_g"], st["momentum"],
+                                                 st["delta_g"], pg, I_s, tb_s, bk.t_g, min(wl.budget, Ks), hp, R, sel,
+                                                 n_sel, None, ws))
+            return
         B.check(B.cocodc_sync_step(wl.frags, n, st["theta_m"], send, st["theta_g"], st["momentum"],
                                    st["delta_g"], pg, bk.I_p, bk.t_b, bk.t_g, wl.budget, hp, R, sel, n_sel, None,
                                    ws))
@@ -227,6 +246,8 @@ def main():
         "dtype": "f64", "data": "synthetic",
         "config": {"workload": wl.name, "K": K, "params": n, "tau": wl.tau, "H": wl.H, "budget": wl.budget,
                    "bytes_per_param": bpp, "merge_mode": args.merge_mode,
+                   "fragments": (f"{args.strided_shards} strided shards of {len(segs)} segments" if segs
+                                 else "contiguous"),
                    "layout": (f"{layout}: one allocation, buffer bases {stride / (1 << 30):.2f} GiB apart"
                               if layout != "packed" else "packed: separate allocations"),
                    "selected": sel[:int(n_sel.item())].cpu().tolist()},

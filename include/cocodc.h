@@ -59,6 +59,7 @@ extern "C" {
 #endif
 
 #define COCODC_MAX_FRAGMENTS 1024
+#define COCODC_MAX_SEGMENTS 4096
 
 typedef enum {
   COCODC_OK = 0,
@@ -78,6 +79,15 @@ typedef struct {
   uint64_t offset; /* first element                                    */
   uint64_t length; /* number of elements; 0 is allowed (empty fragment) */
 } cocodc_fragment_t;
+
+/* One contiguous piece of a fragment that is NOT contiguous in the flat buffers, e.g. the
+ * strided shards of Sec. 4.1 (shard k = layers k, k+4, k+8 of a layer-ordered buffer). */
+typedef struct {
+  uint64_t offset;   /* first element                      */
+  uint64_t length;   /* number of elements (0 allowed)     */
+  int32_t fragment;  /* which fragment it belongs to, 0..K-1 */
+  int32_t reserved;  /* set to 0                           */
+} cocodc_segment_t;
 
 /* Hyper-parameters, in the paper's notation. */
 typedef struct {
@@ -176,6 +186,25 @@ int cocodc_sync_step(const cocodc_fragment_t* frags, int32_t K, uint64_t n_total
                      double* R_out, int32_t* sel_out, int32_t* n_sel_out,
                      double* sums_out /* nullable */, void* workspace, size_t workspace_bytes,
                      void* stream);
+
+/* The same two calls for fragments made of several segments (Sec. 4.1: strided shards).
+ * segs: host, S entries in any order; the segments of one fragment are summed in the order
+ * listed.  Segments must not overlap; a fragment may have none.  I_p, t_b, R_out, sel_out,
+ * sums_out are per FRAGMENT (K entries) exactly as above.  The element-wise single steps need no
+ * segmented form: pass the segments to them as if each were a fragment.  Workspace size:
+ * cocodc_workspace_bytes_segmented(S, K, n_total) (0 if S or K is out of range). */
+size_t cocodc_workspace_bytes_segmented(int32_t S, int32_t K, uint64_t n_total);
+int cocodc_fragment_scores_segmented(const cocodc_segment_t* segs, int32_t S, int32_t K, uint64_t n_total,
+                                     const float* x, const int64_t* I_p, int32_t norm_kind, double* R_out,
+                                     double* sum_out /* nullable */, void* workspace,
+                                     size_t workspace_bytes, void* stream);
+int cocodc_sync_step_segmented(const cocodc_segment_t* segs, int32_t S, int32_t K, uint64_t n_total,
+                               float* theta_m, const float* theta_m_send, float* theta_g, float* momentum,
+                               const float* delta_g, float* delta_m_out /* nullable */, const int64_t* I_p,
+                               const int64_t* t_b, int64_t t_g, int32_t budget, const cocodc_hparams_t* hp,
+                               double* R_out, int32_t* sel_out, int32_t* n_sel_out,
+                               double* sums_out /* nullable */, void* workspace, size_t workspace_bytes,
+                               void* stream);
 
 /* Host-only planner, Eq. 9 and Eq. 10: N = max(K, floor(gamma*H*T_c/T_s)) target
  * synchronisations per H steps and h = floor(H/N) steps between two sends.

@@ -32,6 +32,10 @@ class HParams(C.Structure):
     ]
 
 
+class Segment(C.Structure):
+    _fields_ = [("offset", C.c_uint64), ("length", C.c_uint64), ("fragment", C.c_int32), ("reserved", C.c_int32)]
+
+
 class Shadow(C.Structure):
     _fields_ = [("theta_m", C.c_void_p), ("theta_g", C.c_void_p), ("momentum", C.c_void_p)]
 
@@ -51,7 +55,8 @@ def lib():
             _build.build(force=True)
         _lib = C.CDLL(_LIB_PATH)
         for name in ("pseudograd", "outer_nesterov", "delay_compensate", "fragment_scores",
-                     "select_fragments", "sync_step", "sync_step_mt", "sync_plan"):
+                     "select_fragments", "sync_step", "sync_step_mt", "sync_plan",
+                     "fragment_scores_segmented", "sync_step_segmented"):
             getattr(_lib, "cocodc_ref_" + name).restype = C.c_int
     return _lib
 
@@ -159,6 +164,51 @@ def sync_step(frags, theta_m, theta_m_send, theta_g, momentum, delta_g, delta_m_
         rc = lib().cocodc_ref_sync_step_mt(*common, C.c_int32(n_threads))
         out["threads"] = rc
         rc = 0 if rc > 0 else rc
+    out.update(rc=rc, R=R, sums=sums, sel=sel[:max(n_sel.value, 0)].copy())
+    return out
+
+
+def _seg_array(segs):
+    arr = (Segment * max(len(segs), 1))()
+    for i, (off, length, frag) in enumerate(segs):
+        arr[i].offset, arr[i].length, arr[i].fragment, arr[i].reserved = int(off), int(length), int(frag), 0
+    return arr
+
+
+def fragment_scores_segmented(segs, K, x, I_p, norm_kind=2):
+    """segs: [(offset, length, fragment), ...].  Returns (rc, R[K], sums[K])."""
+    R = np.zeros(K, dtype=np.float64)
+    S = np.zeros(K, dtype=np.float64)
+    keep, ip = _i64(I_p)
+    rc = lib().cocodc_ref_fragment_scores_segmented(_seg_array(segs), C.c_int32(len(segs)), C.c_int32(K),
+                                                    C.c_uint64(x.size), _f32(x), ip, C.c_int32(norm_kind),
+                                                    C.c_void_p(R.ctypes.data), C.c_void_p(S.ctypes.data))
+    return rc, R, S
+
+
+def sync_step_segmented(segs, K, theta_m, theta_m_send, theta_g, momentum, delta_g, delta_m_out, I_p, t_b,
+                        t_g, budget, hp, shadow=False):
+    """Fused step over fragments made of segments [(offset, length, fragment), ...]."""
+    n = theta_m.size
+    R = np.zeros(K, dtype=np.float64)
+    sums = np.zeros((K, 4), dtype=np.float64)
+    sel = np.full(K, -1, dtype=np.int32)
+    n_sel = C.c_int32(-1)
+    keep1, ip = _i64(I_p)
+    keep2, tb = _i64(t_b)
+    out = {}
+    sh_ptr = None
+    if shadow:
+        out["theta_m64"] = np.zeros(n, dtype=np.float64)
+        out["theta_g64"] = np.zeros(n, dtype=np.float64)
+        out["momentum64"] = np.zeros(n, dtype=np.float64)
+        sh = Shadow(out["theta_m64"].ctypes.data, out["theta_g64"].ctypes.data, out["momentum64"].ctypes.data)
+        sh_ptr = C.byref(sh)
+    rc = lib().cocodc_ref_sync_step_segmented(
+        _seg_array(segs), C.c_int32(len(segs)), C.c_int32(K), C.c_uint64(n), _f32(theta_m),
+        _f32(theta_m_send, True), _f32(theta_g), _f32(momentum), _f32(delta_g), _f32(delta_m_out, True), ip, tb,
+        C.c_int64(t_g), C.c_int32(budget), C.byref(hp), C.c_void_p(R.ctypes.data), C.c_void_p(sel.ctypes.data),
+        C.byref(n_sel), C.c_void_p(sums.ctypes.data), sh_ptr)
     out.update(rc=rc, R=R, sums=sums, sel=sel[:max(n_sel.value, 0)].copy())
     return out
 

@@ -334,6 +334,82 @@ int cocodc_ref_sync_step_mt(const cocodc_ref_fragment_t* frags, int32_t K, uint6
   return rc < 0 ? rc : used;
 }
 
+namespace {
+int check_segments(const cocodc_ref_segment_t* segs, int32_t S, int32_t K, uint64_t n_total) {
+  if (segs == nullptr && S > 0) return kErrNull;
+  if (K < 1 || S < 0) return kErrRange;
+  for (int32_t i = 0; i < S; ++i) {
+    if (segs[i].fragment < 0 || segs[i].fragment >= K) return kErrRange;
+    if (segs[i].offset > n_total || segs[i].length > n_total - segs[i].offset) return kErrRange;
+  }
+  for (int32_t i = 0; i < S; ++i) {
+    for (int32_t j = i + 1; j < S; ++j) {
+      if (segs[i].length == 0 || segs[j].length == 0) continue;
+      const uint64_t a0 = segs[i].offset, a1 = a0 + segs[i].length;
+      const uint64_t b0 = segs[j].offset, b1 = b0 + segs[j].length;
+      if (a0 < b1 && b0 < a1) return kErrRange;
+    }
+  }
+  return kOk;
+}
+}  // namespace
+
+int cocodc_ref_fragment_scores_segmented(const cocodc_ref_segment_t* segs, int32_t S, int32_t K,
+                                         uint64_t n_total, const float* x, const int64_t* I_p,
+                                         int32_t norm_kind, double* R_out, double* sum_out) {
+  if (!x || !I_p || !R_out) return kErrNull;
+  if (int rc = check_segments(segs, S, K, n_total)) return rc;
+  if (norm_kind != 1 && norm_kind != 2) return kErrRange;
+  for (int32_t p = 0; p < K; ++p) {
+    double acc = 0.0;
+    for (int32_t j = 0; j < S; ++j) {
+      if (segs[j].fragment != p) continue;
+      for (uint64_t i = segs[j].offset; i < segs[j].offset + segs[j].length; ++i) {
+        const double v = x[i];
+        acc += (norm_kind == 2) ? v * v : std::fabs(v);
+      }
+    }
+    if (sum_out) sum_out[p] = acc;
+    const double norm = (norm_kind == 2) ? std::sqrt(acc) : acc;
+    R_out[p] = (I_p[p] <= 0) ? std::numeric_limits<double>::infinity()
+                             : norm / static_cast<double>(I_p[p]);
+  }
+  return kOk;
+}
+
+int cocodc_ref_sync_step_segmented(const cocodc_ref_segment_t* segs, int32_t S, int32_t K,
+                                   uint64_t n_total, float* theta_m, const float* theta_m_send,
+                                   float* theta_g, float* momentum, const float* delta_g,
+                                   float* delta_m_out, const int64_t* I_p, const int64_t* t_b,
+                                   int64_t t_g, int32_t budget, const cocodc_ref_hparams_t* hp,
+                                   double* R_out, int32_t* sel_out, int32_t* n_sel_out,
+                                   double* sums_out, const cocodc_ref_shadow_t* shadow) {
+  if (!theta_m || !theta_g || !momentum || !delta_g) return kErrNull;
+  if (!I_p || !t_b || !R_out || !sel_out || !n_sel_out) return kErrNull;
+  if (int rc = check_segments(segs, S, K, n_total)) return rc;
+  if (int rc = check_hparams(hp)) return rc;
+  if (!theta_m_send && (hp->merge_mode == 0 || hp->score_src == 1)) return kErrNull;
+  if (budget < 0) return kErrRange;
+  for (int32_t p = 0; p < K; ++p) {
+    Sums s;
+    for (int32_t j = 0; j < S; ++j) {
+      if (segs[j].fragment != p) continue;
+      for (uint64_t i = segs[j].offset; i < segs[j].offset + segs[j].length; ++i) {
+        sync_element(i, theta_m, theta_m_send, theta_g, momentum, delta_g, delta_m_out, *hp, &s,
+                     shadow);
+      }
+    }
+    R_out[p] = score_from_sums(s, I_p[p], *hp);
+    if (sums_out) {
+      sums_out[4 * p + 0] = s.g2;
+      sums_out[4 * p + 1] = s.g1;
+      sums_out[4 * p + 2] = s.d2;
+      sums_out[4 * p + 3] = s.d1;
+    }
+  }
+  return cocodc_ref_select_fragments(K, R_out, t_b, t_g, hp->H, budget, sel_out, n_sel_out);
+}
+
 // Eq. 9: N = max(K, floor(gamma * H * T_c / T_s)); Eq. 10: h = floor(H / N).
 int cocodc_ref_sync_plan(int32_t K, int32_t H, double gamma, double T_c, double T_s,
                          int64_t* N_out, int64_t* h_out) {

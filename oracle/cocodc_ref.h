@@ -111,6 +111,27 @@ int cocodc_ref_sync_step_mt(const cocodc_ref_fragment_t* frags, int32_t K, uint6
                             const cocodc_ref_hparams_t* hp, double* R_out, int32_t* sel_out,
                             int32_t* n_sel_out, double* sums_out, int32_t n_threads);
 
+/* Fragments made of several contiguous segments (Sec. 4.1: strided shards).  A fragment's
+ * elements are visited segment by segment in the order the segments are listed, index order
+ * inside a segment.  Everything else as in the contiguous functions above. */
+typedef struct {
+  uint64_t offset, length;
+  int32_t fragment; /* 0..K-1 */
+  int32_t reserved;
+} cocodc_ref_segment_t;
+
+int cocodc_ref_fragment_scores_segmented(const cocodc_ref_segment_t* segs, int32_t S, int32_t K,
+                                         uint64_t n_total, const float* x, const int64_t* I_p,
+                                         int32_t norm_kind, double* R_out, double* sum_out);
+
+int cocodc_ref_sync_step_segmented(const cocodc_ref_segment_t* segs, int32_t S, int32_t K,
+                                   uint64_t n_total, float* theta_m, const float* theta_m_send,
+                                   float* theta_g, float* momentum, const float* delta_g,
+                                   float* delta_m_out, const int64_t* I_p, const int64_t* t_b,
+                                   int64_t t_g, int32_t budget, const cocodc_ref_hparams_t* hp,
+                                   double* R_out, int32_t* sel_out, int32_t* n_sel_out,
+                                   double* sums_out, const cocodc_ref_shadow_t* shadow);
+
 /* Eq. 9 and Eq. 10: N = max(K, floor(gamma*H*T_c/T_s)), h = floor(H/N). */
 int cocodc_ref_sync_plan(int32_t K, int32_t H, double gamma, double T_c, double T_s,
                          int64_t* N_out, int64_t* h_out);

@@ -32,6 +32,7 @@ COCODC_ERR_ALIAS = -7
 EXPORTS = (
     "cocodc_workspace_bytes", "cocodc_pseudograd", "cocodc_outer_nesterov", "cocodc_delay_compensate",
     "cocodc_fragment_scores", "cocodc_select_fragments", "cocodc_sync_step", "cocodc_sync_plan",
+    "cocodc_workspace_bytes_segmented", "cocodc_fragment_scores_segmented", "cocodc_sync_step_segmented",
     "cocodc_loop_create", "cocodc_loop_destroy", "cocodc_loop_reset_scores", "cocodc_loop_observe",
     "cocodc_loop_plan", "cocodc_loop_due", "cocodc_loop_step", "cocodc_loop_state",
     "cocodc_layout_stride_bytes", "cocodc_last_hip_error", "cocodc_status_string", "cocodc_set_blocks_per_cu",
@@ -41,6 +42,10 @@ EXPORTS = (
 
 class cocodc_fragment_t(C.Structure):
     _fields_ = [("offset", C.c_uint64), ("length", C.c_uint64)]
+
+
+class cocodc_segment_t(C.Structure):
+    _fields_ = [("offset", C.c_uint64), ("length", C.c_uint64), ("fragment", C.c_int32), ("reserved", C.c_int32)]
 
 
 class cocodc_hparams_t(C.Structure):
@@ -77,6 +82,13 @@ _lib.cocodc_select_fragments.argtypes = [C.c_int32, _P, _i64_p, C.c_int64, C.c_i
 _lib.cocodc_sync_step.argtypes = [_frag_p, C.c_int32, C.c_uint64, _P, _P, _P, _P, _P, _P, _i64_p, _i64_p,
                                   C.c_int64, C.c_int32, _hp_p, _P, _P, _P, _P, _P, C.c_size_t, _P]
 _lib.cocodc_sync_plan.argtypes = [C.c_int32, C.c_int32, C.c_double, C.c_double, C.c_double, _i64_p, _i64_p]
+_seg_p = C.POINTER(cocodc_segment_t)
+_lib.cocodc_workspace_bytes_segmented.restype = C.c_size_t
+_lib.cocodc_workspace_bytes_segmented.argtypes = [C.c_int32, C.c_int32, C.c_uint64]
+_lib.cocodc_fragment_scores_segmented.argtypes = [_seg_p, C.c_int32, C.c_int32, C.c_uint64, _P, _i64_p, C.c_int32,
+                                                  _P, _P, _P, C.c_size_t, _P]
+_lib.cocodc_sync_step_segmented.argtypes = [_seg_p, C.c_int32, C.c_int32, C.c_uint64, _P, _P, _P, _P, _P, _P, _i64_p,
+                                            _i64_p, C.c_int64, C.c_int32, _hp_p, _P, _P, _P, _P, _P, C.c_size_t, _P]
 _i32_p = C.POINTER(C.c_int32)
 _lib.cocodc_loop_create.argtypes = [_frag_p, C.c_int32, C.c_uint64, _hp_p, C.c_double, C.c_double, C.c_double,
                                     C.POINTER(C.c_void_p)]
@@ -96,8 +108,8 @@ _lib.cocodc_set_blocks_per_cu.argtypes = [C.c_int]
 _lib.cocodc_profiler_enable.argtypes = [C.c_int32]
 _lib.cocodc_profiler_collect.argtypes = [C.POINTER(C.c_float), C.c_int32]
 for _name in EXPORTS:
-    if _name not in ("cocodc_workspace_bytes", "cocodc_status_string", "cocodc_layout_stride_bytes",
-                     "cocodc_loop_destroy"):
+    if _name not in ("cocodc_workspace_bytes", "cocodc_workspace_bytes_segmented", "cocodc_status_string",
+                     "cocodc_layout_stride_bytes", "cocodc_loop_destroy"):
         getattr(_lib, _name).restype = C.c_int
 
 
@@ -392,3 +404,45 @@ def cocodc_loop_state(handle):
     a, b, c = (C.c_int64 * K)(), (C.c_int64 * K)(), (C.c_int64 * K)()
     rc = _lib.cocodc_loop_state(handle[0], a, b, c)
     return rc, list(a)[:handle[1]], list(b)[:handle[1]], list(c)[:handle[1]]
+
+
+# ---- fragments made of several segments (strided shards) ----
+def _segs(segs):
+    if segs is None:
+        return None, 0
+    arr = (cocodc_segment_t * max(len(segs), 1))()
+    for i, (off, length, frag) in enumerate(segs):
+        arr[i].offset, arr[i].length, arr[i].fragment, arr[i].reserved = int(off), int(length), int(frag), 0
+    return arr, len(segs)
+
+
+def cocodc_workspace_bytes_segmented(S, K, n_total):
+    return int(_lib.cocodc_workspace_bytes_segmented(int(S), int(K), int(n_total)))
+
+
+def new_workspace_segmented(S, K, n_total, device="cuda"):
+    import torch
+    nbytes = cocodc_workspace_bytes_segmented(S, K, n_total)
+    if nbytes == 0:
+        raise CocodcError(COCODC_ERR_RANGE)
+    return torch.empty(nbytes, dtype=torch.uint8, device=device)
+
+
+def cocodc_fragment_scores_segmented(segs, K, n_total, x, I_p, norm_kind, R_out, sum_out, workspace,
+                                     workspace_bytes=None, stream=None, S=None):
+    sa, n = _segs(segs)
+    wp, wb = _ws(workspace, workspace_bytes)
+    return _lib.cocodc_fragment_scores_segmented(sa, n if S is None else S, int(K), int(n_total), _ptr(x), _i64(I_p),
+                                                 int(norm_kind), _ptr(R_out), _ptr(sum_out), wp, wb, _stream(stream))
+
+
+def cocodc_sync_step_segmented(segs, K, n_total, theta_m, theta_m_send, theta_g, momentum, delta_g, delta_m_out,
+                               I_p, t_b, t_g, budget, hp, R_out, sel_out, n_sel_out, sums_out, workspace,
+                               workspace_bytes=None, stream=None, S=None):
+    sa, n = _segs(segs)
+    wp, wb = _ws(workspace, workspace_bytes)
+    return _lib.cocodc_sync_step_segmented(sa, n if S is None else S, int(K), int(n_total), _ptr(theta_m),
+                                           _ptr(theta_m_send), _ptr(theta_g), _ptr(momentum), _ptr(delta_g),
+                                           _ptr(delta_m_out), _i64(I_p), _i64(t_b), int(t_g), int(budget),
+                                           C.byref(hp) if hp is not None else None, _ptr(R_out), _ptr(sel_out),
+                                           _ptr(n_sel_out), _ptr(sums_out), wp, wb, _stream(stream))

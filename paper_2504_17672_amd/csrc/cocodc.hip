@@ -542,25 +542,31 @@ int hip_fail(hipError_t e) {
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
-uint64_t max_tiles(int32_t K, uint64_t n_total) {
-  // a fragment of length L overlaps at most L/kTile + 2 windows (1 if L < 2 and > 0)
-  return n_total / kTile + 2 * static_cast<uint64_t>(K) + 1;
+uint64_t max_tiles(int32_t S, uint64_t n_total) {
+  // a segment of length L overlaps at most L/kTile + 2 windows
+  return n_total / kTile + 2 * static_cast<uint64_t>(S) + 1;
 }
 
+// Device workspace: S+1 segment records (the tile walk), K+1 group records (one per fragment:
+// its range of tile slots, I_p, t_b), then one slot of kSums doubles per tile.
 struct WorkspaceView {
-  FragRec* table;    // K + 1 records
+  FragRec* table;    // S + 1 segment records; table[S].slot_begin == number of tiles
+  FragRec* groups;   // K + 1 fragment records; only slot_begin, I_p, t_b are meaningful
   double* partials;  // max_tiles * kSums
 };
 
-size_t table_bytes(int32_t K) { return align_up(sizeof(FragRec) * (static_cast<size_t>(K) + 1), 256); }
-
-size_t workspace_bytes(int32_t K, uint64_t n_total) {
-  return table_bytes(K) + align_up(max_tiles(K, n_total) * kSums * sizeof(double), 256);
+size_t table_bytes(int32_t S, int32_t K) {
+  return align_up(sizeof(FragRec) * (static_cast<size_t>(S) + 1 + static_cast<size_t>(K) + 1), 256);
 }
 
-WorkspaceView view(void* ws, int32_t K) {
+size_t workspace_bytes(int32_t S, int32_t K, uint64_t n_total) {
+  return table_bytes(S, K) + align_up(max_tiles(S, n_total) * kSums * sizeof(double), 256);
+}
+
+WorkspaceView view(void* ws, int32_t S, int32_t K) {
   char* b = static_cast<char*>(ws);
-  return WorkspaceView{reinterpret_cast<FragRec*>(b), reinterpret_cast<double*>(b + table_bytes(K))};
+  FragRec* t = reinterpret_cast<FragRec*>(b);
+  return WorkspaceView{t, t + S + 1, reinterpret_cast<double*>(b + table_bytes(S, K))};
 }
 
 bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
@@ -575,36 +581,70 @@ bool overlap(const Span& a, const Span& b) {
   return a0 < b0 + b.bytes && b0 < a0 + a.bytes;
 }
 
-// Validates the fragment table and lays out the tile list.  recs gets K+1 entries.
-int plan_table(const cocodc_fragment_t* frags, int32_t K, uint64_t n_total, const int64_t* I_p,
-               const int64_t* t_b, std::vector<FragRec>* recs, uint64_t* T_out) {
-  if (!frags) return COCODC_ERR_NULL;
-  if (K < 1 || K > COCODC_MAX_FRAGMENTS) return COCODC_ERR_RANGE;
+// Host-side plan of one call: the records to upload and the number of tiles.
+struct Plan {
+  std::vector<FragRec> recs;  // S+1 segment records followed by K+1 group records
+  int32_t S = 0, K = 0;
+  uint64_t T = 0;
+};
+
+// Validates a segment list (every segment inside n_total, no two overlapping, fragment ids in
+// [0, K)) and lays out the tile list: the segments of fragment 0 in the order given, then those
+// of fragment 1, ...  so that each fragment owns one contiguous range of tile slots.
+int plan_segments(const cocodc_segment_t* segs, int32_t S, int32_t K, uint64_t n_total, const int64_t* I_p,
+                  const int64_t* t_b, Plan* plan) {
+  if (!segs && S > 0) return COCODC_ERR_NULL;
+  if (K < 1 || K > COCODC_MAX_FRAGMENTS || S < 0 || S > COCODC_MAX_SEGMENTS) return COCODC_ERR_RANGE;
   std::vector<std::pair<uint64_t, uint64_t>> sorted;
-  sorted.reserve(K);
-  for (int32_t p = 0; p < K; ++p) {
-    if (frags[p].offset > n_total || frags[p].length > n_total - frags[p].offset) return COCODC_ERR_RANGE;
-    if (frags[p].length) sorted.emplace_back(frags[p].offset, frags[p].offset + frags[p].length);
+  sorted.reserve(S);
+  for (int32_t i = 0; i < S; ++i) {
+    if (segs[i].fragment < 0 || segs[i].fragment >= K) return COCODC_ERR_RANGE;
+    if (segs[i].offset > n_total || segs[i].length > n_total - segs[i].offset) return COCODC_ERR_RANGE;
+    if (segs[i].length) sorted.emplace_back(segs[i].offset, segs[i].offset + segs[i].length);
   }
   std::sort(sorted.begin(), sorted.end());
   for (size_t i = 1; i < sorted.size(); ++i) {
-    if (sorted[i].first < sorted[i - 1].second) return COCODC_ERR_RANGE;  // fragments overlap
+    if (sorted[i].first < sorted[i - 1].second) return COCODC_ERR_RANGE;  // segments overlap
   }
-  recs->assign(static_cast<size_t>(K) + 1, FragRec{});
+  std::vector<int32_t> order(static_cast<size_t>(S));
+  for (int32_t i = 0; i < S; ++i) order[i] = i;
+  std::stable_sort(order.begin(), order.end(),
+                   [&](int32_t a, int32_t b) { return segs[a].fragment < segs[b].fragment; });
+  plan->S = S;
+  plan->K = K;
+  plan->recs.assign(static_cast<size_t>(S) + 1 + static_cast<size_t>(K) + 1, FragRec{});
+  FragRec* seg_rec = plan->recs.data();
+  FragRec* grp_rec = plan->recs.data() + S + 1;
   uint64_t slot = 0;
-  for (int32_t p = 0; p < K; ++p) {
-    FragRec& r = (*recs)[p];
-    r.offset = frags[p].offset;
-    r.length = frags[p].length;
+  int32_t next_group = 0;
+  for (int32_t j = 0; j < S; ++j) {
+    const cocodc_segment_t& sg = segs[order[j]];
+    while (next_group <= sg.fragment) grp_rec[next_group++].slot_begin = slot;
+    FragRec& r = seg_rec[j];
+    r.offset = sg.offset;
+    r.length = sg.length;
     r.slot_begin = slot;
     r.tile0 = r.offset / kTile;
-    r.I_p = I_p ? I_p[p] : 0;
-    r.t_b = t_b ? t_b[p] : 0;
     if (r.length) slot += (r.offset + r.length - 1) / kTile - r.tile0 + 1;
   }
-  (*recs)[K].slot_begin = slot;
-  *T_out = slot;
+  while (next_group <= K) grp_rec[next_group++].slot_begin = slot;
+  seg_rec[S].slot_begin = slot;
+  for (int32_t p = 0; p < K; ++p) {
+    grp_rec[p].I_p = I_p ? I_p[p] : 0;
+    grp_rec[p].t_b = t_b ? t_b[p] : 0;
+  }
+  plan->T = slot;
   return COCODC_OK;
+}
+
+// Contiguous fragments: fragment p is the single segment frags[p].
+int plan_table(const cocodc_fragment_t* frags, int32_t K, uint64_t n_total, const int64_t* I_p,
+               const int64_t* t_b, Plan* plan) {
+  if (!frags) return COCODC_ERR_NULL;
+  if (K < 1 || K > COCODC_MAX_FRAGMENTS) return COCODC_ERR_RANGE;
+  std::vector<cocodc_segment_t> segs(static_cast<size_t>(K));
+  for (int32_t p = 0; p < K; ++p) segs[p] = cocodc_segment_t{frags[p].offset, frags[p].length, p, 0};
+  return plan_segments(segs.data(), K, K, n_total, I_p, t_b, plan);
 }
 
 int upload_table(const std::vector<FragRec>& recs, FragRec* dst, hipStream_t s) {
@@ -620,10 +660,10 @@ int upload_table(const std::vector<FragRec>& recs, FragRec* dst, hipStream_t s) 
   return COCODC_OK;
 }
 
-int check_workspace(void* ws, size_t bytes, int32_t K, uint64_t n_total) {
+int check_workspace(void* ws, size_t bytes, int32_t S, int32_t K, uint64_t n_total) {
   if (!ws) return COCODC_ERR_NULL;
   if (!aligned(ws, 256)) return COCODC_ERR_ALIGN;
-  if (bytes < workspace_bytes(K, n_total)) return COCODC_ERR_WORKSPACE;
+  if (bytes < workspace_bytes(S, K, n_total)) return COCODC_ERR_WORKSPACE;
   return COCODC_OK;
 }
 
@@ -750,9 +790,14 @@ int launch_fused_m(int merge, bool vec, const FragRec* tbl, uint64_t T, float* t
 // ====================================================================== C ABI
 extern "C" {
 
+size_t cocodc_workspace_bytes_segmented(int32_t S, int32_t K, uint64_t n_total) {
+  if (K < 1 || K > COCODC_MAX_FRAGMENTS || S < 0 || S > COCODC_MAX_SEGMENTS) return 0;
+  return workspace_bytes(S, K, n_total);
+}
+
 size_t cocodc_workspace_bytes(int32_t K, uint64_t n_total) {
   if (K < 1 || K > COCODC_MAX_FRAGMENTS) return 0;
-  return workspace_bytes(K, n_total);
+  return workspace_bytes(K, K, n_total);
 }
 
 int cocodc_pseudograd(const cocodc_fragment_t* frags, int32_t K, uint64_t n_total,
@@ -760,10 +805,9 @@ int cocodc_pseudograd(const cocodc_fragment_t* frags, int32_t K, uint64_t n_tota
                       float* theta_m_send_out, void* workspace, size_t workspace_bytes_, void* stream) {
   if (!theta_g_snap || !theta_m || !delta_m_out) return COCODC_ERR_NULL;
   if (!all_aligned4({theta_g_snap, theta_m, delta_m_out, theta_m_send_out})) return COCODC_ERR_ALIGN;
-  std::vector<FragRec> recs;
-  uint64_t T = 0;
-  if (int rc = plan_table(frags, K, n_total, nullptr, nullptr, &recs, &T)) return rc;
-  if (int rc = check_workspace(workspace, workspace_bytes_, K, n_total)) return rc;
+  Plan pl;
+  if (int rc = plan_table(frags, K, n_total, nullptr, nullptr, &pl)) return rc;
+  if (int rc = check_workspace(workspace, workspace_bytes_, pl.S, K, n_total)) return rc;
   const size_t nb = n_total * sizeof(float);
   const Span in1{theta_g_snap, nb}, in2{theta_m, nb}, o1{delta_m_out, nb}, o2{theta_m_send_out, nb};
   const Span ws{workspace, workspace_bytes_};
@@ -771,15 +815,15 @@ int cocodc_pseudograd(const cocodc_fragment_t* frags, int32_t K, uint64_t n_tota
       overlap(ws, in1) || overlap(ws, in2) || overlap(ws, o1) || overlap(ws, o2))
     return COCODC_ERR_ALIAS;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  WorkspaceView v = view(workspace, K);
-  if (int rc = upload_table(recs, v.table, s)) return rc;
+  WorkspaceView v = view(workspace, pl.S, K);
+  if (int rc = upload_table(pl.recs, v.table, s)) return rc;
   const bool vec = all_aligned16({theta_g_snap, theta_m, delta_m_out, theta_m_send_out});
   if (theta_m_send_out) {
     PseudoGradOp<true> op{theta_g_snap, theta_m, delta_m_out, theta_m_send_out};
-    return launch_walk(vec, v.table, T, op, v.partials, s);
+    return launch_walk(vec, v.table, pl.T, op, v.partials, s);
   }
   PseudoGradOp<false> op{theta_g_snap, theta_m, delta_m_out, nullptr};
-  return launch_walk(vec, v.table, T, op, v.partials, s);
+  return launch_walk(vec, v.table, pl.T, op, v.partials, s);
 }
 
 int cocodc_outer_nesterov(const cocodc_fragment_t* frags, int32_t K, uint64_t n_total, float* theta_g,
@@ -788,25 +832,24 @@ int cocodc_outer_nesterov(const cocodc_fragment_t* frags, int32_t K, uint64_t n_
   if (!theta_g || !momentum || !delta_g) return COCODC_ERR_NULL;
   if (!all_aligned4({theta_g, momentum, delta_g})) return COCODC_ERR_ALIGN;
   if (int rc = check_hparams(hp)) return rc;
-  std::vector<FragRec> recs;
-  uint64_t T = 0;
-  if (int rc = plan_table(frags, K, n_total, nullptr, nullptr, &recs, &T)) return rc;
-  if (int rc = check_workspace(workspace, workspace_bytes_, K, n_total)) return rc;
+  Plan pl;
+  if (int rc = plan_table(frags, K, n_total, nullptr, nullptr, &pl)) return rc;
+  if (int rc = check_workspace(workspace, workspace_bytes_, pl.S, K, n_total)) return rc;
   const size_t nb = n_total * sizeof(float);
   const Span a{theta_g, nb}, b{momentum, nb}, c{delta_g, nb}, ws{workspace, workspace_bytes_};
   if (overlap(a, b) || overlap(a, c) || overlap(b, c) || overlap(ws, a) || overlap(ws, b) || overlap(ws, c))
     return COCODC_ERR_ALIAS;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  WorkspaceView v = view(workspace, K);
-  if (int rc = upload_table(recs, v.table, s)) return rc;
+  WorkspaceView v = view(workspace, pl.S, K);
+  if (int rc = upload_table(pl.recs, v.table, s)) return rc;
   const bool vec = all_aligned16({theta_g, momentum, delta_g});
   const DevHP d = to_dev(*hp);
   if (hp->nesterov) {
     OuterOp<true> op{theta_g, momentum, delta_g, d};
-    return launch_walk(vec, v.table, T, op, v.partials, s);
+    return launch_walk(vec, v.table, pl.T, op, v.partials, s);
   }
   OuterOp<false> op{theta_g, momentum, delta_g, d};
-  return launch_walk(vec, v.table, T, op, v.partials, s);
+  return launch_walk(vec, v.table, pl.T, op, v.partials, s);
 }
 
 int cocodc_delay_compensate(const cocodc_fragment_t* frags, int32_t K, uint64_t n_total, float* theta_m,
@@ -816,37 +859,64 @@ int cocodc_delay_compensate(const cocodc_fragment_t* frags, int32_t K, uint64_t 
   if (!all_aligned4({theta_m, theta_m_send, theta_g})) return COCODC_ERR_ALIGN;
   if (int rc = check_hparams(hp)) return rc;
   if (!theta_m_send && hp->merge_mode == 0) return COCODC_ERR_NULL;  // Algorithm 1 needs theta^m_{p,t_p}
-  std::vector<FragRec> recs;
-  uint64_t T = 0;
-  if (int rc = plan_table(frags, K, n_total, nullptr, nullptr, &recs, &T)) return rc;
-  if (int rc = check_workspace(workspace, workspace_bytes_, K, n_total)) return rc;
+  Plan pl;
+  if (int rc = plan_table(frags, K, n_total, nullptr, nullptr, &pl)) return rc;
+  if (int rc = check_workspace(workspace, workspace_bytes_, pl.S, K, n_total)) return rc;
   const size_t nb = n_total * sizeof(float);
   const Span a{theta_m, nb}, b{theta_m_send, nb}, c{theta_g, nb}, ws{workspace, workspace_bytes_};
   if (overlap(a, b) || overlap(a, c) || overlap(ws, a) || overlap(ws, b) || overlap(ws, c))
     return COCODC_ERR_ALIAS;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  WorkspaceView v = view(workspace, K);
-  if (int rc = upload_table(recs, v.table, s)) return rc;
+  WorkspaceView v = view(workspace, pl.S, K);
+  if (int rc = upload_table(pl.recs, v.table, s)) return rc;
   const bool vec = all_aligned16({theta_m, theta_m_send, theta_g});
   const DevHP d = to_dev(*hp);
   switch (merge_variant(*hp)) {
     case 0: {
       MergeOp<0> op{theta_m, theta_m_send, theta_g, d};
-      return launch_walk(vec, v.table, T, op, v.partials, s);
+      return launch_walk(vec, v.table, pl.T, op, v.partials, s);
     }
     case 1: {
       MergeOp<1, false> op{theta_m, nullptr, theta_g, d};
-      return launch_walk(vec, v.table, T, op, v.partials, s);
+      return launch_walk(vec, v.table, pl.T, op, v.partials, s);
     }
     case 2: {
       MergeOp<2, false> op{theta_m, nullptr, theta_g, d};
-      return launch_walk(vec, v.table, T, op, v.partials, s);
+      return launch_walk(vec, v.table, pl.T, op, v.partials, s);
     }
     default: {
       MergeOp<3> op{theta_m, theta_m_send, theta_g, d};
-      return launch_walk(vec, v.table, T, op, v.partials, s);
+      return launch_walk(vec, v.table, pl.T, op, v.partials, s);
     }
   }
+}
+
+static int fragment_scores_impl(Plan& pl, int32_t K, uint64_t n_total, const float* x, int32_t norm_kind,
+                                double* R_out, double* sum_out, void* workspace, size_t workspace_bytes_,
+                                void* stream) {
+  if (int rc = check_workspace(workspace, workspace_bytes_, pl.S, K, n_total)) return rc;
+  const Span xs{x, n_total * sizeof(float)}, r{R_out, sizeof(double) * K}, so{sum_out, sizeof(double) * K};
+  const Span ws{workspace, workspace_bytes_};
+  if (overlap(r, xs) || overlap(so, xs) || overlap(r, so) || overlap(ws, xs) || overlap(ws, r) ||
+      overlap(ws, so))
+    return COCODC_ERR_ALIAS;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  WorkspaceView v = view(workspace, pl.S, K);
+  if (int rc = upload_table(pl.recs, v.table, s)) return rc;
+  const bool vec = aligned(x, 16);
+  int rc;
+  if (norm_kind == 2) {
+    ScoreOp<2> op{x};
+    rc = launch_walk(vec, v.table, pl.T, op, v.partials, s);
+  } else {
+    ScoreOp<1> op{x};
+    rc = launch_walk(vec, v.table, pl.T, op, v.partials, s);
+  }
+  if (rc) return rc;
+  hipLaunchKernelGGL(k_finalize, dim3(K), dim3(kThreads), 0, s, v.groups, v.partials, 1, 0,
+                     norm_kind == 2 ? 1 : 0, R_out, sum_out, 1);
+  HIP_TRY(hipGetLastError());
+  return COCODC_OK;
 }
 
 int cocodc_fragment_scores(const cocodc_fragment_t* frags, int32_t K, uint64_t n_total, const float* x,
@@ -855,32 +925,20 @@ int cocodc_fragment_scores(const cocodc_fragment_t* frags, int32_t K, uint64_t n
   if (!x || !I_p || !R_out) return COCODC_ERR_NULL;
   if (!aligned(x, 4) || !aligned(R_out, 8) || !aligned(sum_out, 8)) return COCODC_ERR_ALIGN;
   if (norm_kind != 1 && norm_kind != 2) return COCODC_ERR_RANGE;
-  std::vector<FragRec> recs;
-  uint64_t T = 0;
-  if (int rc = plan_table(frags, K, n_total, I_p, nullptr, &recs, &T)) return rc;
-  if (int rc = check_workspace(workspace, workspace_bytes_, K, n_total)) return rc;
-  const Span xs{x, n_total * sizeof(float)}, r{R_out, sizeof(double) * K}, so{sum_out, sizeof(double) * K};
-  const Span ws{workspace, workspace_bytes_};
-  if (overlap(r, xs) || overlap(so, xs) || overlap(r, so) || overlap(ws, xs) || overlap(ws, r) ||
-      overlap(ws, so))
-    return COCODC_ERR_ALIAS;
-  hipStream_t s = static_cast<hipStream_t>(stream);
-  WorkspaceView v = view(workspace, K);
-  if (int rc = upload_table(recs, v.table, s)) return rc;
-  const bool vec = aligned(x, 16);
-  int rc;
-  if (norm_kind == 2) {
-    ScoreOp<2> op{x};
-    rc = launch_walk(vec, v.table, T, op, v.partials, s);
-  } else {
-    ScoreOp<1> op{x};
-    rc = launch_walk(vec, v.table, T, op, v.partials, s);
-  }
-  if (rc) return rc;
-  hipLaunchKernelGGL(k_finalize, dim3(K), dim3(kThreads), 0, s, v.table, v.partials, 1, 0,
-                     norm_kind == 2 ? 1 : 0, R_out, sum_out, 1);
-  HIP_TRY(hipGetLastError());
-  return COCODC_OK;
+  Plan pl;
+  if (int rc = plan_table(frags, K, n_total, I_p, nullptr, &pl)) return rc;
+  return fragment_scores_impl(pl, K, n_total, x, norm_kind, R_out, sum_out, workspace, workspace_bytes_, stream);
+}
+
+int cocodc_fragment_scores_segmented(const cocodc_segment_t* segs, int32_t S, int32_t K, uint64_t n_total,
+                                     const float* x, const int64_t* I_p, int32_t norm_kind, double* R_out,
+                                     double* sum_out, void* workspace, size_t workspace_bytes_, void* stream) {
+  if (!x || !I_p || !R_out) return COCODC_ERR_NULL;
+  if (!aligned(x, 4) || !aligned(R_out, 8) || !aligned(sum_out, 8)) return COCODC_ERR_ALIGN;
+  if (norm_kind != 1 && norm_kind != 2) return COCODC_ERR_RANGE;
+  Plan pl;
+  if (int rc = plan_segments(segs, S, K, n_total, I_p, nullptr, &pl)) return rc;
+  return fragment_scores_impl(pl, K, n_total, x, norm_kind, R_out, sum_out, workspace, workspace_bytes_, stream);
 }
 
 int cocodc_select_fragments(int32_t K, const double* R, const int64_t* t_b, int64_t t_g, int32_t H,
@@ -889,42 +947,30 @@ int cocodc_select_fragments(int32_t K, const double* R, const int64_t* t_b, int6
   if (!R || !t_b || !sel_out || !n_sel_out) return COCODC_ERR_NULL;
   if (K < 1 || K > COCODC_MAX_FRAGMENTS || H < 1 || budget < 0) return COCODC_ERR_RANGE;
   if (!aligned(R, 8) || !aligned(sel_out, 4) || !aligned(n_sel_out, 4)) return COCODC_ERR_ALIGN;
-  if (int rc = check_workspace(workspace, workspace_bytes_, K, 0)) return rc;
+  if (int rc = check_workspace(workspace, workspace_bytes_, K, K, 0)) return rc;
   const int n = budget < K ? budget : K;
   const Span r{R, sizeof(double) * K}, so{sel_out, sizeof(int32_t) * n}, ns{n_sel_out, sizeof(int32_t)};
   const Span ws{workspace, workspace_bytes_};
   if (overlap(r, so) || overlap(r, ns) || overlap(so, ns) || overlap(ws, r) || overlap(ws, so) ||
       overlap(ws, ns))
     return COCODC_ERR_ALIAS;
-  std::vector<FragRec> recs(static_cast<size_t>(K) + 1, FragRec{});
-  for (int32_t p = 0; p < K; ++p) recs[p].t_b = t_b[p];
+  Plan pl;  // no segments: only the per-fragment records (t_b) are needed
+  if (int rc = plan_segments(nullptr, 0, K, 0, nullptr, t_b, &pl)) return rc;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  WorkspaceView v = view(workspace, K);
-  if (int rc = upload_table(recs, v.table, s)) return rc;
-  hipLaunchKernelGGL(k_select, dim3(1), dim3(kThreads), 0, s, v.table, K, R, t_g, static_cast<int64_t>(H),
+  WorkspaceView v = view(workspace, pl.S, K);
+  if (int rc = upload_table(pl.recs, v.table, s)) return rc;
+  hipLaunchKernelGGL(k_select, dim3(1), dim3(kThreads), 0, s, v.groups, K, R, t_g, static_cast<int64_t>(H),
                      n, sel_out, n_sel_out);
   HIP_TRY(hipGetLastError());
   return COCODC_OK;
 }
 
-int cocodc_sync_step(const cocodc_fragment_t* frags, int32_t K, uint64_t n_total, float* theta_m,
-                     const float* theta_m_send, float* theta_g, float* momentum, const float* delta_g,
-                     float* delta_m_out, const int64_t* I_p, const int64_t* t_b, int64_t t_g,
-                     int32_t budget, const cocodc_hparams_t* hp, double* R_out, int32_t* sel_out,
-                     int32_t* n_sel_out, double* sums_out, void* workspace, size_t workspace_bytes_,
-                     void* stream) {
-  if (!theta_m || !theta_g || !momentum || !delta_g) return COCODC_ERR_NULL;
-  if (!I_p || !t_b || !R_out || !sel_out || !n_sel_out) return COCODC_ERR_NULL;
-  if (!all_aligned4({theta_m, theta_m_send, theta_g, momentum, delta_g, delta_m_out, sel_out, n_sel_out}))
-    return COCODC_ERR_ALIGN;
-  if (!aligned(R_out, 8) || !aligned(sums_out, 8)) return COCODC_ERR_ALIGN;
-  if (int rc = check_hparams(hp)) return rc;
-  if (!theta_m_send && (hp->merge_mode == 0 || hp->score_src == 1)) return COCODC_ERR_NULL;
-  if (budget < 0) return COCODC_ERR_RANGE;
-  std::vector<FragRec> recs;
-  uint64_t T = 0;
-  if (int rc = plan_table(frags, K, n_total, I_p, t_b, &recs, &T)) return rc;
-  if (int rc = check_workspace(workspace, workspace_bytes_, K, n_total)) return rc;
+static int sync_step_impl(Plan& pl, int32_t K, uint64_t n_total, float* theta_m, const float* theta_m_send,
+                          float* theta_g, float* momentum, const float* delta_g, float* delta_m_out, int64_t t_g,
+                          int32_t budget, const cocodc_hparams_t* hp, double* R_out, int32_t* sel_out,
+                          int32_t* n_sel_out, double* sums_out, void* workspace, size_t workspace_bytes_,
+                          void* stream) {
+  if (int rc = check_workspace(workspace, workspace_bytes_, pl.S, K, n_total)) return rc;
   const int n = budget < K ? budget : K;
   const size_t nb = n_total * sizeof(float);
   const Span sp[] = {{theta_m, nb},     {theta_m_send, nb},           {theta_g, nb},
@@ -939,8 +985,8 @@ int cocodc_sync_step(const cocodc_fragment_t* frags, int32_t K, uint64_t n_total
     }
   }
   hipStream_t s = static_cast<hipStream_t>(stream);
-  WorkspaceView v = view(workspace, K);
-  if (int rc = upload_table(recs, v.table, s)) return rc;
+  WorkspaceView v = view(workspace, pl.S, K);
+  if (int rc = upload_table(pl.recs, v.table, s)) return rc;
   const bool vec = all_aligned16({theta_m, theta_m_send, theta_g, momentum, delta_g, delta_m_out});
   const DevHP d = to_dev(*hp);
 
@@ -950,21 +996,67 @@ int cocodc_sync_step(const cocodc_fragment_t* frags, int32_t K, uint64_t n_total
     if (g_prof.on && g_prof.used < static_cast<int>(g_prof.start.size())) slot = g_prof.used++;
   }
   if (slot >= 0) HIP_TRY(hipEventRecord(g_prof.start[slot], s));
-  int rc = hp->nesterov ? launch_fused_m<true>(merge_variant(*hp), vec, v.table, T, theta_m, theta_m_send, theta_g,
+  int rc = hp->nesterov ? launch_fused_m<true>(merge_variant(*hp), vec, v.table, pl.T, theta_m, theta_m_send, theta_g,
                                                momentum, delta_g, delta_m_out, d, v.partials, s)
-                        : launch_fused_m<false>(merge_variant(*hp), vec, v.table, T, theta_m, theta_m_send,
+                        : launch_fused_m<false>(merge_variant(*hp), vec, v.table, pl.T, theta_m, theta_m_send,
                                                 theta_g, momentum, delta_g, delta_m_out, d, v.partials, s);
   if (slot >= 0) HIP_TRY(hipEventRecord(g_prof.stop[slot], s));
   if (rc) return rc;
 
   const int which = (hp->score_src ? 2 : 0) + (hp->norm_kind == 2 ? 0 : 1);
-  hipLaunchKernelGGL(k_finalize, dim3(K), dim3(kThreads), 0, s, v.table, v.partials, kSums, which,
+  hipLaunchKernelGGL(k_finalize, dim3(K), dim3(kThreads), 0, s, v.groups, v.partials, kSums, which,
                      hp->norm_kind == 2 ? 1 : 0, R_out, sums_out, kSums);
   HIP_TRY(hipGetLastError());
-  hipLaunchKernelGGL(k_select, dim3(1), dim3(kThreads), 0, s, v.table, K, R_out, t_g,
+  hipLaunchKernelGGL(k_select, dim3(1), dim3(kThreads), 0, s, v.groups, K, R_out, t_g,
                      static_cast<int64_t>(hp->H), n, sel_out, n_sel_out);
   HIP_TRY(hipGetLastError());
   return COCODC_OK;
+}
+
+
+static int sync_step_check(float* theta_m, const float* theta_m_send, float* theta_g, float* momentum,
+                           const float* delta_g, float* delta_m_out, const int64_t* I_p, const int64_t* t_b,
+                           int32_t budget, const cocodc_hparams_t* hp, double* R_out, int32_t* sel_out,
+                           int32_t* n_sel_out, double* sums_out) {
+  if (!theta_m || !theta_g || !momentum || !delta_g) return COCODC_ERR_NULL;
+  if (!I_p || !t_b || !R_out || !sel_out || !n_sel_out) return COCODC_ERR_NULL;
+  if (!all_aligned4({theta_m, theta_m_send, theta_g, momentum, delta_g, delta_m_out, sel_out, n_sel_out}))
+    return COCODC_ERR_ALIGN;
+  if (!aligned(R_out, 8) || !aligned(sums_out, 8)) return COCODC_ERR_ALIGN;
+  if (int rc = check_hparams(hp)) return rc;
+  if (!theta_m_send && (hp->merge_mode == 0 || hp->score_src == 1)) return COCODC_ERR_NULL;
+  if (budget < 0) return COCODC_ERR_RANGE;
+  return COCODC_OK;
+}
+
+int cocodc_sync_step(const cocodc_fragment_t* frags, int32_t K, uint64_t n_total, float* theta_m,
+                     const float* theta_m_send, float* theta_g, float* momentum, const float* delta_g,
+                     float* delta_m_out, const int64_t* I_p, const int64_t* t_b, int64_t t_g,
+                     int32_t budget, const cocodc_hparams_t* hp, double* R_out, int32_t* sel_out,
+                     int32_t* n_sel_out, double* sums_out, void* workspace, size_t workspace_bytes_,
+                     void* stream) {
+  if (int rc = sync_step_check(theta_m, theta_m_send, theta_g, momentum, delta_g, delta_m_out, I_p, t_b, budget, hp,
+                               R_out, sel_out, n_sel_out, sums_out))
+    return rc;
+  Plan pl;
+  if (int rc = plan_table(frags, K, n_total, I_p, t_b, &pl)) return rc;
+  return sync_step_impl(pl, K, n_total, theta_m, theta_m_send, theta_g, momentum, delta_g, delta_m_out, t_g, budget,
+                        hp, R_out, sel_out, n_sel_out, sums_out, workspace, workspace_bytes_, stream);
+}
+
+int cocodc_sync_step_segmented(const cocodc_segment_t* segs, int32_t S, int32_t K, uint64_t n_total,
+                               float* theta_m, const float* theta_m_send, float* theta_g, float* momentum,
+                               const float* delta_g, float* delta_m_out, const int64_t* I_p, const int64_t* t_b,
+                               int64_t t_g, int32_t budget, const cocodc_hparams_t* hp, double* R_out,
+                               int32_t* sel_out, int32_t* n_sel_out, double* sums_out, void* workspace,
+                               size_t workspace_bytes_, void* stream) {
+  if (int rc = sync_step_check(theta_m, theta_m_send, theta_g, momentum, delta_g, delta_m_out, I_p, t_b, budget, hp,
+                               R_out, sel_out, n_sel_out, sums_out))
+    return rc;
+  Plan pl;
+  if (int rc = plan_segments(segs, S, K, n_total, I_p, t_b, &pl)) return rc;
+  return sync_step_impl(pl, K, n_total, theta_m, theta_m_send, theta_g, momentum, delta_g, delta_m_out, t_g, budget,
+                        hp, R_out, sel_out, n_sel_out, sums_out, workspace, workspace_bytes_, stream);
 }
 
 int cocodc_sync_plan(int32_t K, int32_t H, double gamma, double T_c, double T_s, int64_t* N_out,
@@ -1014,9 +1106,8 @@ int cocodc_loop_create(const cocodc_fragment_t* frags, int32_t K, uint64_t n_tot
   if (!loop_out) return COCODC_ERR_NULL;
   *loop_out = nullptr;
   if (int rc = check_hparams(hp)) return rc;
-  std::vector<FragRec> recs;
-  uint64_t T = 0;
-  if (int rc = plan_table(frags, K, n_total, nullptr, nullptr, &recs, &T)) return rc;
+  Plan pl;
+  if (int rc = plan_table(frags, K, n_total, nullptr, nullptr, &pl)) return rc;
   cocodc_loop* L = new cocodc_loop();
   L->frags.assign(frags, frags + K);
   L->n_total = n_total;

@@ -35,6 +35,7 @@ class Workload:
     drift: str = "normal"  # "normal" | "student_t3"
     lam_sweep: Tuple[float, ...] = ()
     n_syncs: int = 1
+    model: Tuple[int, int, int] = ()  # (n_layers, d, ffn) of model-shaped workloads
 
     @property
     def K(self) -> int:
@@ -72,7 +73,22 @@ def llama_fragments(n_layers: int, d: int, ffn: int, layers_per_fragment: int) -
 
 
 def _scaled(name, n_layers, d, ffn, lpf, **kw) -> Workload:
-    return Workload(name=name, frag_lengths=llama_fragments(n_layers, d, ffn, lpf), **kw)
+    return Workload(name=name, frag_lengths=llama_fragments(n_layers, d, ffn, lpf), model=(n_layers, d, ffn), **kw)
+
+
+def strided_segments(n_layers: int, d: int, ffn: int, n_shards: int):
+    """The strided sharding of the paper's experiments (Sec. 4.1: 12 layers, 4 shards of about 3
+    layers each, "strided pattern") on a layer-ordered flat buffer
+    [embedding + final norm | layer 0 | layer 1 | ...]: shard k owns layers k, k + n_shards, ...;
+    the embedding block goes with shard 0.  Returns [(offset, length, fragment), ...] in buffer
+    order and the total number of elements."""
+    segs = [(0, VOCAB * d + d, 0)]
+    off = VOCAB * d + d
+    per = layer_params(d, ffn)
+    for layer in range(n_layers):
+        segs.append((off, per, layer % n_shards))
+        off += per
+    return segs, off
 
 
 WORKLOADS: Dict[str, Workload] = {

@@ -1,0 +1,123 @@
+"""GPU parity of the segmented entry points (fragments = strided sets of layers, Sec. 4.1)
+against the oracle's segmented functions.  Needs an MI355X."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2504_17672_amd import synth
+
+import parity_util as U
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2504_17672_amd import binding
+    assert torch.cuda.is_available()
+    return binding
+
+
+def _case(B, ref, segs, K, n, I_p, t_b, t_g, budget, tau=5, H=100, seed=0, amplified=False, view_off=0, **hpkw):
+    print(f"case segmented S={len(segs)} K={K} n={n} view_off={view_off} amplified={amplified} hp={hpkw}", flush=True)
+    base = synth.Workload("seg", (n + view_off,), tau=tau, H=H)
+    st = {k: v[view_off:] for k, v in synth.make_state(base, "cuda", seed=seed, amplified=amplified).items()}
+    host = U.host_copy(st)
+    ghp, rhp = B.hparams(tau, H, **hpkw), ref.hparams(tau, H, **hpkw)
+    ws = B.new_workspace_segmented(len(segs), K, n)
+    out = U.gpu_outputs(K)
+    pg = torch.full((n,), 555.0, device="cuda")
+    rc = B.cocodc_sync_step_segmented(segs, K, n, st["theta_m"], st["theta_m_send"], st["theta_g"], st["momentum"],
+                                      st["delta_g"], pg, I_p, t_b, t_g, budget, ghp, out["R"], out["sel"],
+                                      out["n_sel"], out["sums"], ws)
+    assert rc == 0, B.cocodc_status_string(rc)
+    torch.cuda.synchronize()
+    out["pg"] = pg
+    out["sel_list"] = out["sel"][:int(out["n_sel"].item())].cpu().tolist()
+    h_pg = np.full(n, 555.0, np.float32)
+    ro = ref.sync_step_segmented(segs, K, host["theta_m"], host["theta_m_send"], host["theta_g"], host["momentum"],
+                                 host["delta_g"], h_pg, I_p, t_b, t_g, budget, rhp, shadow=True)
+    assert ro["rc"] == 0
+    ro["pg"] = h_pg
+    frags = [(o, l) for o, l, _ in segs]
+    obs = U.compare_fused(st, out, host, ro, frags)
+    outside = np.ones(n, bool)
+    for o, l in frags:
+        outside[o:o + l] = False
+    assert np.all(pg.cpu().numpy()[outside] == 555.0)
+    bk = synth.Bookkeeping(t_g=t_g, t_b=list(t_b), I_p=list(I_p))
+    U.compare_selection(out, ro, bk, H)
+    # the scores-only entry point gives the same R and raw sums
+    R2 = torch.zeros(K, dtype=torch.float64, device="cuda")
+    S2 = torch.zeros(K, dtype=torch.float64, device="cuda")
+    assert B.cocodc_fragment_scores_segmented(segs, K, n, st["delta_g"], I_p, 2, R2, S2, ws) == 0
+    torch.cuda.synchronize()
+    if hpkw.get("score_src", 0) == 0 and hpkw.get("norm_kind", 2) == 2:
+        assert torch.equal(R2, out["R"])
+    assert torch.equal(S2, out["sums"][:, 0].contiguous())
+    print("   observed", {k: (f"{v:.3g}" if isinstance(v, float) else v) for k, v in obs.items()},
+          "sel", out["sel_list"], flush=True)
+    return out
+
+
+def test_paper_strided_shards_full_125m_dims(B, ref):
+    """12 layers of the 125M dimensions in 4 strided shards (shard k = layers k, k+4, k+8)."""
+    segs, n = synth.strided_segments(12, 768, 2048, 4)
+    out = _case(B, ref, segs, 4, n, [12, 24, 36, 12], [988, 976, 964, 988], 1000, 2)
+    assert len(out["sel_list"]) == 2
+
+
+def test_strided_shards_amplified_and_switches(B, ref):
+    segs, n = synth.strided_segments(12, 96, 256, 4)
+    _case(B, ref, segs, 4, n, [12, 24, 36, 12], [988, 976, 964, 988], 1000, 3, tau=2, H=1, amplified=True)
+    _case(B, ref, segs, 4, n, [12, 24, 36, 12], [988, 976, 964, 988], 1000, 3, score_src=1, norm_kind=1)
+    _case(B, ref, segs, 4, n, [12, 0, 36, 12], [988, 976, 100, 988], 1000, 4, merge_mode=1, alpha=0.3)
+
+
+@pytest.mark.parametrize("view_off", [0, 1])
+def test_adversarial_segment_tables(B, ref, view_off):
+    segs = [(70001, 3, 2), (5, 1000, 0), (1013, 3, 1), (1030, 40000, 0), (41031, 16384, 1), (60001, 1, 0),
+            (16383 + 41031 + 2, 0, 1), (65000, 5001, 4)]  # fragment 3 has no segment; listed out of order
+    n = 70010
+    _case(B, ref, segs, 5, n, [7, 14, 21, 7, 0], [990, 980, 970, 100, 990], 1000, 3, view_off=view_off)
+
+
+def test_segmented_equals_contiguous_on_gpu(B, ref):
+    wl = synth.MINI_WORKLOADS["125M-mini"]
+    bk = synth.bookkeeping(wl)
+    st = synth.make_state(wl, "cuda", seed=3)
+    a = {k: v.clone() for k, v in st.items()}
+    b = {k: v.clone() for k, v in st.items()}
+    ghp = B.hparams(wl.tau, wl.H)
+    ws = B.new_workspace(wl.K, wl.n_total)
+    oa = U.run_gpu_fused(B, wl.frags, wl.n_total, a, bk, wl.budget, ghp, ws)
+    segs = [(o, l, p) for p, (o, l) in enumerate(wl.frags)]
+    ob = U.gpu_outputs(wl.K)
+    pg = torch.full_like(b["delta_g"], 555.0)
+    ws2 = B.new_workspace_segmented(len(segs), wl.K, wl.n_total)
+    assert B.cocodc_sync_step_segmented(segs, wl.K, wl.n_total, b["theta_m"], b["theta_m_send"], b["theta_g"],
+                                        b["momentum"], b["delta_g"], pg, bk.I_p, bk.t_b, bk.t_g, wl.budget, ghp,
+                                        ob["R"], ob["sel"], ob["n_sel"], ob["sums"], ws2) == 0
+    torch.cuda.synchronize()
+    for k in a:
+        assert torch.equal(a[k], b[k])
+    assert torch.equal(oa["pg"], pg) and torch.equal(oa["R"], ob["R"]) and torch.equal(oa["sums"], ob["sums"])
+    assert torch.equal(oa["sel"], ob["sel"])
+
+
+def test_segmented_rejections(B):
+    n = 4096
+    base = 0x10000000
+    tm, ts, tg, m, dg, R, sel, ns, ws = (base + i * 0x100000 for i in range(9))
+    hp = B.hparams(5, 100)
+    wsb = B.cocodc_workspace_bytes_segmented(3, 2, n)
+    assert wsb > 0 and B.cocodc_workspace_bytes_segmented(5000, 2, n) == 0
+
+    def call(segs, K=2, S=None, wsb=wsb):
+        return B.cocodc_sync_step_segmented(segs, K, n, tm, ts, tg, m, dg, None, [1] * K, [0] * K, 10, 1, hp, R, sel, ns,
+                                            None, ws, wsb, stream=0, S=S)
+    assert call([(0, 10, 0), (5, 10, 1)]) == B.COCODC_ERR_RANGE
+    assert call([(0, 10, 2)]) == B.COCODC_ERR_RANGE
+    assert call([(4090, 10, 0)]) == B.COCODC_ERR_RANGE
+    assert call(None, S=2) == B.COCODC_ERR_NULL
+    assert call([(0, 10, 0)] * 1, wsb=64) == B.COCODC_ERR_WORKSPACE
