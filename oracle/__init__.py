@@ -56,8 +56,12 @@ def lib():
         _lib = C.CDLL(_LIB_PATH)
         for name in ("pseudograd", "outer_nesterov", "delay_compensate", "fragment_scores",
                      "select_fragments", "sync_step", "sync_step_mt", "sync_plan",
-                     "fragment_scores_segmented", "sync_step_segmented"):
+                     "fragment_scores_segmented", "sync_step_segmented", "pseudograd_bf16", "sync_step_bf16"):
             getattr(_lib, "cocodc_ref_" + name).restype = C.c_int
+        _lib.cocodc_ref_round_bf16.restype = C.c_uint16
+        _lib.cocodc_ref_round_bf16.argtypes = [C.c_double]
+        _lib.cocodc_ref_widen_bf16.restype = C.c_double
+        _lib.cocodc_ref_widen_bf16.argtypes = [C.c_uint16]
     return _lib
 
 
@@ -209,6 +213,57 @@ def sync_step_segmented(segs, K, theta_m, theta_m_send, theta_g, momentum, delta
         _f32(theta_m_send, True), _f32(theta_g), _f32(momentum), _f32(delta_g), _f32(delta_m_out, True), ip, tb,
         C.c_int64(t_g), C.c_int32(budget), C.byref(hp), C.c_void_p(R.ctypes.data), C.c_void_p(sel.ctypes.data),
         C.byref(n_sel), C.c_void_p(sums.ctypes.data), sh_ptr)
+    out.update(rc=rc, R=R, sums=sums, sel=sel[:max(n_sel.value, 0)].copy())
+    return out
+
+
+def _u16(a, allow_none=False):
+    if a is None:
+        assert allow_none
+        return None
+    assert isinstance(a, np.ndarray) and a.dtype == np.uint16 and a.flags["C_CONTIGUOUS"]
+    return C.c_void_p(a.ctypes.data)
+
+
+def round_bf16(x):
+    return int(lib().cocodc_ref_round_bf16(float(x)))
+
+
+def widen_bf16(b):
+    return float(lib().cocodc_ref_widen_bf16(int(b)))
+
+
+def pseudograd_bf16(frags, theta_g_snap, theta_m, delta_m_out, theta_m_send_out=None):
+    """theta_m, delta_m_out, theta_m_send_out: uint16 arrays holding bf16 bit patterns."""
+    return lib().cocodc_ref_pseudograd_bf16(_frag_array(frags), C.c_int32(len(frags)), C.c_uint64(theta_m.size),
+                                            _f32(theta_g_snap), _u16(theta_m), _u16(delta_m_out),
+                                            _u16(theta_m_send_out, True))
+
+
+def sync_step_bf16(frags, theta_m, theta_m_send, theta_g, momentum, delta_g, delta_m_out, I_p, t_b, t_g, budget, hp,
+                   shadow=False):
+    """Fused step with bf16 (uint16 bit patterns) theta_m / theta_m_send / delta_m_out."""
+    K = len(frags)
+    n = theta_m.size
+    R = np.zeros(K, dtype=np.float64)
+    sums = np.zeros((K, 4), dtype=np.float64)
+    sel = np.full(K, -1, dtype=np.int32)
+    n_sel = C.c_int32(-1)
+    keep1, ip = _i64(I_p)
+    keep2, tb = _i64(t_b)
+    out = {}
+    sh_ptr = None
+    if shadow:
+        out["theta_m64"] = np.zeros(n, dtype=np.float64)
+        out["theta_g64"] = np.zeros(n, dtype=np.float64)
+        out["momentum64"] = np.zeros(n, dtype=np.float64)
+        sh = Shadow(out["theta_m64"].ctypes.data, out["theta_g64"].ctypes.data, out["momentum64"].ctypes.data)
+        sh_ptr = C.byref(sh)
+    rc = lib().cocodc_ref_sync_step_bf16(
+        _frag_array(frags), C.c_int32(K), C.c_uint64(n), _u16(theta_m), _u16(theta_m_send, True), _f32(theta_g),
+        _f32(momentum), _f32(delta_g), _u16(delta_m_out, True), ip, tb, C.c_int64(t_g), C.c_int32(budget),
+        C.byref(hp), C.c_void_p(R.ctypes.data), C.c_void_p(sel.ctypes.data), C.byref(n_sel),
+        C.c_void_p(sums.ctypes.data), sh_ptr)
     out.update(rc=rc, R=R, sums=sums, sel=sel[:max(n_sel.value, 0)].copy())
     return out
 

@@ -16,6 +16,7 @@
 
 #include <cmath>
 #include <cstdint>
+#include <cstring>
 #include <limits>
 #include <vector>
 
@@ -397,6 +398,98 @@ int cocodc_ref_sync_step_segmented(const cocodc_ref_segment_t* segs, int32_t S, 
       for (uint64_t i = segs[j].offset; i < segs[j].offset + segs[j].length; ++i) {
         sync_element(i, theta_m, theta_m_send, theta_g, momentum, delta_g, delta_m_out, *hp, &s,
                      shadow);
+      }
+    }
+    R_out[p] = score_from_sums(s, I_p[p], *hp);
+    if (sums_out) {
+      sums_out[4 * p + 0] = s.g2;
+      sums_out[4 * p + 1] = s.g1;
+      sums_out[4 * p + 2] = s.d2;
+      sums_out[4 * p + 3] = s.d1;
+    }
+  }
+  return cocodc_ref_select_fragments(K, R_out, t_b, t_g, hp->H, budget, sel_out, n_sel_out);
+}
+
+// ---- bf16 local parameters ------------------------------------------------------------
+// bfloat16 = the upper half of an IEEE binary32: 8 significant bits, exponents -126..127,
+// subnormal spacing 2^-133.
+double cocodc_ref_widen_bf16(uint16_t b) {
+  const uint32_t u = static_cast<uint32_t>(b) << 16;
+  float f;
+  std::memcpy(&f, &u, sizeof(f));
+  return static_cast<double>(f);
+}
+
+// Nearest bf16 to x, ties to even: scale so that one bf16 step becomes 1, round to the
+// nearest integer (current rounding mode = to nearest even), scale back.  All three steps
+// are exact except the rounding itself.
+uint16_t cocodc_ref_round_bf16(double x) {
+  if (std::isnan(x)) return 0x7FC0;
+  double r = x;
+  if (x != 0.0 && !std::isinf(x)) {
+    int e = std::ilogb(x);       // x = f * 2^e, 1 <= |f| < 2
+    if (e < -126) e = -126;      // subnormal range: fixed spacing
+    const int q = e - 7;         // exponent of one unit in the last place
+    r = std::ldexp(std::nearbyint(std::ldexp(x, -q)), q);
+  }
+  const float f = static_cast<float>(r);  // exact for every bf16 value; beyond the range -> inf
+  uint32_t u;
+  std::memcpy(&u, &f, sizeof(u));
+  return static_cast<uint16_t>(u >> 16);
+}
+
+int cocodc_ref_pseudograd_bf16(const cocodc_ref_fragment_t* frags, int32_t K, uint64_t n_total,
+                               const float* theta_g_snap, const uint16_t* theta_m,
+                               uint16_t* delta_m_out, uint16_t* theta_m_send_out) {
+  if (!theta_g_snap || !theta_m || !delta_m_out) return kErrNull;
+  if (int rc = check_table(frags, K, n_total)) return rc;
+  for (int32_t p = 0; p < K; ++p) {
+    for (uint64_t i = frags[p].offset; i < frags[p].offset + frags[p].length; ++i) {
+      const double tg = theta_g_snap[i], tm = cocodc_ref_widen_bf16(theta_m[i]);
+      delta_m_out[i] = cocodc_ref_round_bf16(tg - tm);
+      if (theta_m_send_out) theta_m_send_out[i] = theta_m[i];
+    }
+  }
+  return kOk;
+}
+
+int cocodc_ref_sync_step_bf16(const cocodc_ref_fragment_t* frags, int32_t K, uint64_t n_total,
+                              uint16_t* theta_m, const uint16_t* theta_m_send, float* theta_g,
+                              float* momentum, const float* delta_g, uint16_t* delta_m_out,
+                              const int64_t* I_p, const int64_t* t_b, int64_t t_g, int32_t budget,
+                              const cocodc_ref_hparams_t* hp, double* R_out, int32_t* sel_out,
+                              int32_t* n_sel_out, double* sums_out,
+                              const cocodc_ref_shadow_t* shadow) {
+  if (!theta_m || !theta_g || !momentum || !delta_g) return kErrNull;
+  if (!I_p || !t_b || !R_out || !sel_out || !n_sel_out) return kErrNull;
+  if (int rc = check_table(frags, K, n_total)) return rc;
+  if (int rc = check_hparams(hp)) return rc;
+  if (!theta_m_send && (hp->merge_mode == 0 || hp->score_src == 1)) return kErrNull;
+  if (budget < 0) return kErrRange;
+  for (int32_t p = 0; p < K; ++p) {
+    Sums s;
+    for (uint64_t i = frags[p].offset; i < frags[p].offset + frags[p].length; ++i) {
+      const double tg = theta_g[i], tm = cocodc_ref_widen_bf16(theta_m[i]);
+      const double ts = theta_m_send ? cocodc_ref_widen_bf16(theta_m_send[i]) : tm;
+      const double m0 = momentum[i], dg = delta_g[i];
+      double m1;
+      const double G64 = outer_update(tg, m0, dg, *hp, &m1);   // Eq. 2
+      const float G = static_cast<float>(G64);                  // the stored fp32 global state
+      const double d = drift_times_tau(ts, tm, *hp);            // Eq. 4 times tau
+      const double tm_new = merge_local(static_cast<double>(G), ts, tm, d, *hp);  // Eq. 7, 8
+      s.g2 += dg * dg;
+      s.g1 += std::fabs(dg);
+      s.d2 += d * d;
+      s.d1 += std::fabs(d);
+      if (delta_m_out) delta_m_out[i] = cocodc_ref_round_bf16(tg - tm);
+      momentum[i] = static_cast<float>(m1);
+      theta_g[i] = G;
+      theta_m[i] = cocodc_ref_round_bf16(tm_new);
+      if (shadow) {
+        if (shadow->theta_m) shadow->theta_m[i] = tm_new;
+        if (shadow->theta_g) shadow->theta_g[i] = G64;
+        if (shadow->momentum) shadow->momentum[i] = m1;
       }
     }
     R_out[p] = score_from_sums(s, I_p[p], *hp);

@@ -132,6 +132,29 @@ int cocodc_ref_sync_step_segmented(const cocodc_ref_segment_t* segs, int32_t S, 
                                    double* R_out, int32_t* sel_out, int32_t* n_sel_out,
                                    double* sums_out, const cocodc_ref_shadow_t* shadow);
 
+/* ---- bf16 local parameters (Sec. 4.1: the worker trains in bf16 mixed precision) ----
+ * theta_m, theta_m_send and the outgoing pseudo-gradient are bfloat16 (raw 16-bit patterns:
+ * 1 sign, 8 exponent, 7 fraction bits); the global state, the momentum and delta_g stay fp32.
+ * Every bf16 input is widened exactly, the step is evaluated in fp64 as above, and each bf16
+ * output is the fp64 value rounded ONCE to the nearest bf16 (ties to even; subnormals kept;
+ * overflow to infinity; any NaN becomes 0x7FC0). */
+uint16_t cocodc_ref_round_bf16(double x);
+double cocodc_ref_widen_bf16(uint16_t b);
+
+int cocodc_ref_pseudograd_bf16(const cocodc_ref_fragment_t* frags, int32_t K, uint64_t n_total,
+                               const float* theta_g_snap, const uint16_t* theta_m,
+                               uint16_t* delta_m_out, uint16_t* theta_m_send_out /* nullable */);
+
+/* shadow (nullable): unrounded fp64 theta_m / theta_g / momentum as in cocodc_ref_sync_step. */
+int cocodc_ref_sync_step_bf16(const cocodc_ref_fragment_t* frags, int32_t K, uint64_t n_total,
+                              uint16_t* theta_m, const uint16_t* theta_m_send, float* theta_g,
+                              float* momentum, const float* delta_g,
+                              uint16_t* delta_m_out /* nullable */, const int64_t* I_p,
+                              const int64_t* t_b, int64_t t_g, int32_t budget,
+                              const cocodc_ref_hparams_t* hp, double* R_out, int32_t* sel_out,
+                              int32_t* n_sel_out, double* sums_out /* nullable */,
+                              const cocodc_ref_shadow_t* shadow /* nullable */);
+
 /* Eq. 9 and Eq. 10: N = max(K, floor(gamma*H*T_c/T_s)), h = floor(H/N). */
 int cocodc_ref_sync_plan(int32_t K, int32_t H, double gamma, double T_c, double T_s,
                          int64_t* N_out, int64_t* h_out);
