@@ -84,6 +84,9 @@ def main():
                          "short probe at set-up finds fastest; spaced: fixed stride "
                          "cocodc_layout_stride_bytes(); packed: six separate allocations")
     ap.add_argument("--stride-gib", type=float, default=None, help="override the spaced-layout stride")
+    ap.add_argument("--bf16", action="store_true",
+                    help="bf16 local parameters, send-time record and pseudo-gradient, fp32 global state "
+                         "(cocodc_sync_step_bf16, 28 B/param)")
     ap.add_argument("--strided-shards", type=int, default=0, metavar="K",
                     help="shard the workload's layers into K strided fragments (shard k = layers k, k+K, ...; "
                          "Sec. 4.1) on a layer-ordered buffer and time cocodc_sync_step_segmented instead")
@@ -189,11 +192,26 @@ def main():
         return
 
     cpu = None
-    if not args.no_cpu:
+    if not args.no_cpu and not args.bf16:  # the timed CPU oracle is the fp32 step
         sample = 1 if K > 1 else 0
         print(f"[bench] timing the CPU oracle on fragment {sample}", file=sys.stderr, flush=True)
         cpu = cpu_baseline(wl, st, bk, sample)
         print(f"[bench] cpu baseline {cpu}", file=sys.stderr, flush=True)
+
+    if args.bf16:
+        # same placement: each bf16 buffer occupies the first half of its fp32-sized slot
+        # converted in place, chunk by chunk in ascending order: a converted chunk always lies below
+        # the fp32 chunk it came from, so no source element is overwritten before it is read
+        for name in ("theta_m", "theta_m_send"):
+            src = st[name]
+            dst = src.view(torch.bfloat16)
+            for lo in range(0, n, 1 << 28):
+                hi = min(n, lo + (1 << 28))
+                dst[lo:hi].copy_(src[lo:hi].to(torch.bfloat16))  # dst[lo:hi] lies below src[lo:hi]: safe ascending
+            st[name] = dst[:n]
+        if pg is not None:
+            pg = pg.view(torch.bfloat16)[:n]
+        send = st["theta_m_send"] if mode == 0 else None
 
     segs = None
     if args.strided_shards:
@@ -207,6 +225,11 @@ def main():
         ws = B.new_workspace_segmented(len(segs), Ks, n, dev)
 
     def step():
+        if args.bf16:
+            B.check(B.cocodc_sync_step_bf16(wl.frags, n, st["theta_m"], send, st["theta_g"], st["momentum"],
+                                            st["delta_g"], pg, bk.I_p, bk.t_b, bk.t_g, wl.budget, hp, R, sel, n_sel,
+                                            None, ws))
+            return
         if segs is not None:
             B.check(B.cocodc_sync_step_segmented(segs, Ks, n, st["theta_m"], send, st["theta_g"], st["momentum"],
                                                  st["delta_g"], pg, I_s, tb_s, bk.t_g, min(wl.budget, Ks), hp, R, sel,
@@ -235,6 +258,8 @@ def main():
     ms_per_step = elapsed / args.steps * 1e3
     k1_avg = sum(k1_ms) / len(k1_ms)
     bpp = BYTES_PER_PARAM - (4 if args.no_pg else 0) - (4 if mode != 0 else 0)
+    if args.bf16:  # theta_m read+written, theta_m_send read, pseudo-gradient written: 2 bytes each
+        bpp = (2 + 4 + 4 + 4 + (2 if mode == 0 else 0)) + (2 + 4 + 4 + (0 if args.no_pg else 2))
     achieved = bpp * n / (k1_avg * 1e-3) / 1e9
     out = {
         "metric": "fused sync-step Gparams/s and achieved HBM GB/s (% of peak), 1xMI355X",
@@ -246,6 +271,7 @@ def main():
         "dtype": "f64", "data": "synthetic",
         "config": {"workload": wl.name, "K": K, "params": n, "tau": wl.tau, "H": wl.H, "budget": wl.budget,
                    "bytes_per_param": bpp, "merge_mode": args.merge_mode,
+                   "local_dtype": "bf16" if args.bf16 else "f32",
                    "fragments": (f"{args.strided_shards} strided shards of {len(segs)} segments" if segs
                                  else "contiguous"),
                    "layout": (f"{layout}: one allocation, buffer bases {stride / (1 << 30):.2f} GiB apart"
@@ -254,7 +280,7 @@ def main():
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name) if bpp == BYTES_PER_PARAM else None,
-                     "kernel": "k_walk<FusedOp>", "kernel_ms_avg": round(k1_avg, 4),
+                     "kernel": "k_walk<FusedBf16Op>" if args.bf16 else "k_walk<FusedOp>", "kernel_ms_avg": round(k1_avg, 4),
                      "kernel_ms_min": round(min(k1_ms), 4), "algorithmic_bytes": bpp * n},
         "cpu_baseline": cpu,
     }

@@ -206,6 +206,27 @@ int cocodc_sync_step_segmented(const cocodc_segment_t* segs, int32_t S, int32_t 
                                double* sums_out /* nullable */, void* workspace, size_t workspace_bytes,
                                void* stream);
 
+/* ---- bfloat16 local parameters ----
+ * The paper's workers train in bf16 mixed precision (Sec. 4.1).  In these two calls theta_m,
+ * theta_m_send and the outgoing pseudo-gradient are bfloat16 (raw 16-bit patterns, 2-byte
+ * aligned; 16-byte aligned for the fast path), while the global state, the outer momentum and
+ * delta_g stay fp32 master copies.  Every bf16 input is widened exactly, the update is the
+ * same fp64 arithmetic as above, and each bf16 output is the fp64 value rounded ONCE to the
+ * nearest bf16 (ties to even, subnormals kept, overflow to infinity, NaN -> 0x7FC0).  The
+ * fused pass then moves 28 instead of 36 bytes per parameter.  delta_m_out cannot alias
+ * delta_g here (different element types).  Everything else as in the fp32 calls. */
+int cocodc_pseudograd_bf16(const cocodc_fragment_t* frags, int32_t K, uint64_t n_total,
+                           const float* theta_g_snap, const uint16_t* theta_m, uint16_t* delta_m_out,
+                           uint16_t* theta_m_send_out /* nullable */, void* workspace,
+                           size_t workspace_bytes, void* stream);
+int cocodc_sync_step_bf16(const cocodc_fragment_t* frags, int32_t K, uint64_t n_total, uint16_t* theta_m,
+                          const uint16_t* theta_m_send, float* theta_g, float* momentum,
+                          const float* delta_g, uint16_t* delta_m_out /* nullable */, const int64_t* I_p,
+                          const int64_t* t_b, int64_t t_g, int32_t budget, const cocodc_hparams_t* hp,
+                          double* R_out, int32_t* sel_out, int32_t* n_sel_out,
+                          double* sums_out /* nullable */, void* workspace, size_t workspace_bytes,
+                          void* stream);
+
 /* Host-only planner, Eq. 9 and Eq. 10: N = max(K, floor(gamma*H*T_c/T_s)) target
  * synchronisations per H steps and h = floor(H/N) steps between two sends.
  * gamma in (0,1]; T_c, T_s > 0 (any common unit).  No GPU work. */

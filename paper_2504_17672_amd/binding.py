@@ -33,6 +33,7 @@ EXPORTS = (
     "cocodc_workspace_bytes", "cocodc_pseudograd", "cocodc_outer_nesterov", "cocodc_delay_compensate",
     "cocodc_fragment_scores", "cocodc_select_fragments", "cocodc_sync_step", "cocodc_sync_plan",
     "cocodc_workspace_bytes_segmented", "cocodc_fragment_scores_segmented", "cocodc_sync_step_segmented",
+    "cocodc_pseudograd_bf16", "cocodc_sync_step_bf16",
     "cocodc_loop_create", "cocodc_loop_destroy", "cocodc_loop_reset_scores", "cocodc_loop_observe",
     "cocodc_loop_plan", "cocodc_loop_due", "cocodc_loop_step", "cocodc_loop_state",
     "cocodc_layout_stride_bytes", "cocodc_last_hip_error", "cocodc_status_string", "cocodc_set_blocks_per_cu",
@@ -89,6 +90,9 @@ _lib.cocodc_fragment_scores_segmented.argtypes = [_seg_p, C.c_int32, C.c_int32, 
                                                   _P, _P, _P, C.c_size_t, _P]
 _lib.cocodc_sync_step_segmented.argtypes = [_seg_p, C.c_int32, C.c_int32, C.c_uint64, _P, _P, _P, _P, _P, _P, _i64_p,
                                             _i64_p, C.c_int64, C.c_int32, _hp_p, _P, _P, _P, _P, _P, C.c_size_t, _P]
+_lib.cocodc_pseudograd_bf16.argtypes = [_frag_p, C.c_int32, C.c_uint64, _P, _P, _P, _P, _P, C.c_size_t, _P]
+_lib.cocodc_sync_step_bf16.argtypes = [_frag_p, C.c_int32, C.c_uint64, _P, _P, _P, _P, _P, _P, _i64_p, _i64_p,
+                                       C.c_int64, C.c_int32, _hp_p, _P, _P, _P, _P, _P, C.c_size_t, _P]
 _i32_p = C.POINTER(C.c_int32)
 _lib.cocodc_loop_create.argtypes = [_frag_p, C.c_int32, C.c_uint64, _hp_p, C.c_double, C.c_double, C.c_double,
                                     C.POINTER(C.c_void_p)]
@@ -446,3 +450,24 @@ def cocodc_sync_step_segmented(segs, K, n_total, theta_m, theta_m_send, theta_g,
                                            _ptr(delta_m_out), _i64(I_p), _i64(t_b), int(t_g), int(budget),
                                            C.byref(hp) if hp is not None else None, _ptr(R_out), _ptr(sel_out),
                                            _ptr(n_sel_out), _ptr(sums_out), wp, wb, _stream(stream))
+
+
+# ---- bfloat16 local parameters (torch.bfloat16 tensors, or int16/uint16 views of them) ----
+def cocodc_pseudograd_bf16(frags, n_total, theta_g_snap, theta_m, delta_m_out, theta_m_send_out, workspace,
+                           workspace_bytes=None, stream=None, K=None):
+    fa, k = _frags(frags)
+    wp, wb = _ws(workspace, workspace_bytes)
+    return _lib.cocodc_pseudograd_bf16(fa, k if K is None else K, int(n_total), _ptr(theta_g_snap), _ptr(theta_m),
+                                       _ptr(delta_m_out), _ptr(theta_m_send_out), wp, wb, _stream(stream))
+
+
+def cocodc_sync_step_bf16(frags, n_total, theta_m, theta_m_send, theta_g, momentum, delta_g, delta_m_out, I_p, t_b,
+                          t_g, budget, hp, R_out, sel_out, n_sel_out, sums_out, workspace, workspace_bytes=None,
+                          stream=None, K=None):
+    fa, k = _frags(frags)
+    wp, wb = _ws(workspace, workspace_bytes)
+    return _lib.cocodc_sync_step_bf16(fa, k if K is None else K, int(n_total), _ptr(theta_m), _ptr(theta_m_send),
+                                      _ptr(theta_g), _ptr(momentum), _ptr(delta_g), _ptr(delta_m_out), _i64(I_p),
+                                      _i64(t_b), int(t_g), int(budget), C.byref(hp) if hp is not None else None,
+                                      _ptr(R_out), _ptr(sel_out), _ptr(n_sel_out), _ptr(sums_out), wp, wb,
+                                      _stream(stream))

@@ -40,6 +40,9 @@
 #ifndef COCODC_EXACT_DIV
 #define COCODC_EXACT_DIV 1
 #endif
+#ifndef COCODC_WAVES_PER_EU
+#define COCODC_WAVES_PER_EU 0
+#endif
 #ifndef COCODC_NT_STORE
 #define COCODC_NT_STORE 1
 #endif
@@ -53,7 +56,7 @@ constexpr int kDepth = COCODC_DEPTH;  // independent 128-bit loads per stream ke
 constexpr int kTableChunk = 64;       // fragment records carried by one table-upload launch
 constexpr int kSums = 4;              // doubles per partial-sum slot
 
-static_assert(kTile % (4 * kThreads) == 0, "a tile must be a whole number of workgroup-wide float4 rows");
+static_assert(kTile % (4 * kThreads) == 0, "a tile must be a whole number of workgroup-wide vector rows");
 
 // Device-side description of one fragment.
 struct FragRec {
@@ -116,6 +119,64 @@ __device__ __forceinline__ float lane_get(const f32x4& v, int k) { return v[k]; 
 __device__ __forceinline__ void lane_set(float& v, int, float x) { v = x; }
 __device__ __forceinline__ void lane_set(f32x4& v, int k, float x) { v[k] = x; }
 
+// ---- 16-bit streams of the bf16 variant: four bf16 = one 64-bit access per lane.
+template <int V>
+struct VecU16;
+template <>
+struct VecU16<1> {
+  using type = unsigned short;
+};
+typedef unsigned short u16x4 __attribute__((ext_vector_type(4)));
+template <>
+struct VecU16<4> {
+  using type = u16x4;
+};
+
+template <int V>
+__device__ __forceinline__ typename VecU16<V>::type load_stream_u16(const unsigned short* p) {
+  using T = typename VecU16<V>::type;
+#if COCODC_NT_LOAD
+  return __builtin_nontemporal_load(reinterpret_cast<const T*>(p));
+#else
+  return *reinterpret_cast<const T*>(p);
+#endif
+}
+template <int V>
+__device__ __forceinline__ void store_stream_u16(unsigned short* p, typename VecU16<V>::type v) {
+  using T = typename VecU16<V>::type;
+#if COCODC_NT_STORE
+  __builtin_nontemporal_store(v, reinterpret_cast<T*>(p));
+#else
+  *reinterpret_cast<T*>(p) = v;
+#endif
+}
+__device__ __forceinline__ unsigned short lane_get(unsigned short v, int) { return v; }
+__device__ __forceinline__ unsigned short lane_get(const u16x4& v, int k) { return v[k]; }
+__device__ __forceinline__ void lane_set(u16x4& v, int k, unsigned short x) { v[k] = x; }
+__device__ __forceinline__ void lane_set(unsigned short& v, int, unsigned short x) { v = x; }
+
+// bfloat16 = upper half of a binary32.  Widening is exact.
+__device__ __forceinline__ float widen_bf16(unsigned short b) {
+  return __uint_as_float(static_cast<unsigned>(b) << 16);
+}
+
+// Nearest bfloat16 to an fp64 value in ONE rounding, ties to even; subnormals (spacing
+// 2^-133) kept, overflow to infinity, any NaN -> 0x7FC0.
+// The value is first rounded to binary32 by the hardware conversion, then to bf16 on the bit
+// pattern.  Rounding twice differs from rounding once only when the binary32 value sits
+// exactly half way between two bf16 values although the fp64 value did not: in that (rare)
+// case the pattern is nudged one step towards the fp64 value before the second rounding.
+__device__ __forceinline__ unsigned short round_bf16(double x) {
+  const float f = static_cast<float>(x);
+  unsigned u = __float_as_uint(f);
+  if ((u & 0xFFFFu) == 0x8000u) {
+    const double back = static_cast<double>(f);
+    if (back != x) u += (fabs(x) > fabs(back)) ? 1u : 0xFFFFFFFFu;
+  }
+  const unsigned r = (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+  return static_cast<unsigned short>(x != x ? 0x7FC0u : r);
+}
+
 // ------------------------------------------------------------------ per-element arithmetic
 // Eq. 2 with OuterOptim = SGD with momentum: m' = mu*m + dg ; step = dg + mu*m' (Nesterov)
 // or m' (heavy ball) ; G = theta_g - eta*step.  Returns G rounded to fp32 (the value that is
@@ -144,21 +205,25 @@ __device__ __forceinline__ double drift(float theta_send, float theta_m, const D
 // MERGE 3: the same with tau == 0 (no overlap): the last term is an exact zero.
 // MERGE 1: Eq. 3 blend.  MERGE 2: adopt G.
 template <int MERGE>
-__device__ __forceinline__ float merge_local(float G, float theta_send, float theta_m, double d,
-                                             const DevHP& hp) {
+__device__ __forceinline__ double merge_local_f64(float G, float theta_send, float theta_m, double d,
+                                                  const DevHP& hp) {
   const double Gd = static_cast<double>(G);
-  if (MERGE == 1) {
-    return static_cast<float>(hp.one_minus_alpha * static_cast<double>(theta_m) + hp.alpha * Gd);
-  }
-  if (MERGE == 2) return G;
-  if (MERGE == 3) return static_cast<float>(Gd + d + 0.0);
+  if (MERGE == 1) return hp.one_minus_alpha * static_cast<double>(theta_m) + hp.alpha * Gd;
+  if (MERGE == 2) return Gd;
+  if (MERGE == 3) return Gd + d + 0.0;
   const double Delta = Gd - static_cast<double>(theta_send);
 #if COCODC_EXACT_DIV
   const double corr = hp.lambda * d * d * Delta / hp.tauH;
 #else
   const double corr = hp.coef * d * d * Delta;
 #endif
-  return static_cast<float>(Gd + d + corr);
+  return Gd + d + corr;
+}
+
+template <int MERGE>
+__device__ __forceinline__ float merge_local(float G, float theta_send, float theta_m, double d,
+                                             const DevHP& hp) {
+  return static_cast<float>(merge_local_f64<MERGE>(G, theta_send, theta_m, d, hp));
 }
 
 // ------------------------------------------------------------------ streaming operations
@@ -171,6 +236,8 @@ __device__ __forceinline__ float merge_local(float G, float theta_send, float th
 template <bool NESTEROV, int MERGE, bool HAS_PG, bool HAS_SEND = true>
 struct FusedOp {
   static constexpr int kAcc = 4;
+  static constexpr int kVec = 4;       // elements per lane per access (128-bit fp32)
+  static constexpr int kLoads = kDepth;  // accesses per stream in flight per lane
   float* theta_m;
   const float* theta_send;
   float* theta_g;
@@ -229,6 +296,8 @@ struct FusedOp {
 template <bool HAS_SEND>
 struct PseudoGradOp {
   static constexpr int kAcc = 0;
+  static constexpr int kVec = 4;       // elements per lane per access (128-bit fp32)
+  static constexpr int kLoads = kDepth;  // accesses per stream in flight per lane
   const float* theta_g;
   const float* theta_m;
   float* pg;
@@ -258,6 +327,8 @@ struct PseudoGradOp {
 template <bool NESTEROV>
 struct OuterOp {
   static constexpr int kAcc = 0;
+  static constexpr int kVec = 4;       // elements per lane per access (128-bit fp32)
+  static constexpr int kLoads = kDepth;  // accesses per stream in flight per lane
   float* theta_g;
   float* momentum;
   const float* delta_g;
@@ -294,6 +365,8 @@ struct OuterOp {
 template <int MERGE, bool HAS_SEND = true>
 struct MergeOp {
   static constexpr int kAcc = 0;
+  static constexpr int kVec = 4;       // elements per lane per access (128-bit fp32)
+  static constexpr int kLoads = kDepth;  // accesses per stream in flight per lane
   float* theta_m;
   const float* theta_send;
   const float* theta_g;
@@ -325,10 +398,111 @@ struct MergeOp {
   }
 };
 
+// The fused step with bfloat16 local parameters: theta_m, theta_send and the outgoing
+// pseudo-gradient are bf16 (2 bytes), theta_g, momentum, delta_g stay fp32: 28 B/param.
+template <bool NESTEROV, int MERGE, bool HAS_PG, bool HAS_SEND = true>
+struct FusedBf16Op {
+  static constexpr int kAcc = 4;
+  static constexpr int kVec = 4;       // 128-bit fp32 accesses, 64-bit bf16 accesses (8-wide measured slower)
+  static constexpr int kLoads = kDepth;
+  unsigned short* theta_m;
+  const unsigned short* theta_send;
+  float* theta_g;
+  float* momentum;
+  const float* delta_g;
+  unsigned short* pg;
+  DevHP hp;
+
+  template <int V>
+  struct Regs {
+    typename VecU16<V>::type tm, ts;
+    typename Vec<V>::type tg, m, dg;
+  };
+
+  template <int V>
+  __device__ __forceinline__ Regs<V> load(uint64_t i) const {
+    Regs<V> r;
+    r.tm = load_stream_u16<V>(theta_m + i);
+    if (HAS_SEND) r.ts = load_stream_u16<V>(theta_send + i);
+    r.tg = load_stream<V>(theta_g + i);
+    r.m = load_stream<V>(momentum + i);
+    r.dg = load_stream<V>(delta_g + i);
+    return r;
+  }
+
+  template <int V>
+  __device__ __forceinline__ void apply(uint64_t i, const Regs<V>& r, double* a) const {
+    typename VecU16<V>::type o_tm, o_pg;
+    typename Vec<V>::type o_tg, o_m;
+#pragma unroll
+    for (int k = 0; k < V; ++k) {
+      const float tm = widen_bf16(lane_get(r.tm, k)), tg = lane_get(r.tg, k);
+      const float ts = HAS_SEND ? widen_bf16(lane_get(r.ts, k)) : tm;
+      const float m = lane_get(r.m, k), dg = lane_get(r.dg, k);
+      float m1;
+      const float G = outer_update<NESTEROV>(tg, m, dg, hp, &m1);
+      const double d = HAS_SEND ? drift(ts, tm, hp) : 0.0;
+      const double tm1 = merge_local_f64<MERGE>(G, ts, tm, d, hp);
+      const double dgd = static_cast<double>(dg);
+      a[0] = fma(dgd, dgd, a[0]);
+      a[1] += fabs(dgd);
+      if (HAS_SEND) {
+        a[2] += d * d;
+        a[3] += fabs(d);
+      }
+      lane_set(o_tm, k, round_bf16(tm1));
+      lane_set(o_tg, k, G);
+      lane_set(o_m, k, m1);
+      if (HAS_PG) lane_set(o_pg, k, round_bf16(static_cast<double>(tg) - static_cast<double>(tm)));
+    }
+    store_stream_u16<V>(theta_m + i, o_tm);
+    store_stream<V>(theta_g + i, o_tg);
+    store_stream<V>(momentum + i, o_m);
+    if (HAS_PG) store_stream_u16<V>(pg + i, o_pg);
+  }
+};
+
+template <bool HAS_SEND>
+struct PseudoGradBf16Op {
+  static constexpr int kAcc = 0;
+  static constexpr int kVec = 4;
+  static constexpr int kLoads = kDepth;
+  const float* theta_g;
+  const unsigned short* theta_m;
+  unsigned short* pg;
+  unsigned short* send_out;
+
+  template <int V>
+  struct Regs {
+    typename Vec<V>::type tg;
+    typename VecU16<V>::type tm;
+  };
+  template <int V>
+  __device__ __forceinline__ Regs<V> load(uint64_t i) const {
+    Regs<V> r;
+    r.tg = load_stream<V>(theta_g + i);
+    r.tm = load_stream_u16<V>(theta_m + i);
+    return r;
+  }
+  template <int V>
+  __device__ __forceinline__ void apply(uint64_t i, const Regs<V>& r, double*) const {
+    typename VecU16<V>::type o;
+#pragma unroll
+    for (int k = 0; k < V; ++k) {
+      lane_set(o, k, round_bf16(static_cast<double>(lane_get(r.tg, k)) -
+                                static_cast<double>(widen_bf16(lane_get(r.tm, k)))));
+    }
+    store_stream_u16<V>(pg + i, o);
+    if (HAS_SEND) store_stream_u16<V>(send_out + i, r.tm);
+  }
+};
+
 // Sum of squares (NORM 2) or of magnitudes (NORM 1) of any buffer: numerator of Eq. 11.
 template <int NORM>
 struct ScoreOp {
   static constexpr int kAcc = 1;
+  static constexpr int kVec = 4;       // elements per lane per access (128-bit fp32)
+  static constexpr int kLoads = kDepth;  // accesses per stream in flight per lane
   const float* x;
 
   template <int V>
@@ -392,8 +566,13 @@ __global__ void k_write_table(TableChunk chunk, FragRec* dst, int base, int coun
 }
 
 // Walks the tile list with stride gridDim.x.  tbl has K+1 records; tbl[K].slot_begin == T.
+#if COCODC_WAVES_PER_EU > 0
+#define COCODC_OCCUPANCY __attribute__((amdgpu_waves_per_eu(COCODC_WAVES_PER_EU)))
+#else
+#define COCODC_OCCUPANCY
+#endif
 template <class Op, bool VEC>
-__global__ __launch_bounds__(kThreads) void k_walk(const FragRec* __restrict__ tbl, uint64_t T,
+__global__ __launch_bounds__(kThreads) COCODC_OCCUPANCY void k_walk(const FragRec* __restrict__ tbl, uint64_t T,
                                                     Op op, double* __restrict__ partials) {
   __shared__ double lds[kWaves][kSums];
   const uint64_t tid = threadIdx.x;
@@ -410,29 +589,31 @@ __global__ __launch_bounds__(kThreads) void k_walk(const FragRec* __restrict__ t
     for (int k = 0; k < (Op::kAcc > 0 ? Op::kAcc : 1); ++k) acc[k] = 0.0;
 
     if (VEC) {
-      uint64_t lo4 = (lo + 3) & ~uint64_t(3);
+      constexpr int W = Op::kVec;      // elements per vector access
+      constexpr int D = Op::kLoads;    // vector accesses per stream in flight
+      uint64_t lo4 = (lo + (W - 1)) & ~uint64_t(W - 1);
       if (lo4 > hi) lo4 = hi;
-      uint64_t hi4 = hi & ~uint64_t(3);
+      uint64_t hi4 = hi & ~uint64_t(W - 1);
       if (hi4 < lo4) hi4 = lo4;
-      if (tid < lo4 - lo) {  // unaligned head of the fragment (at most 3 elements)
+      if (tid < lo4 - lo) {  // unaligned head of the fragment (at most W-1 elements)
         const auto r = op.template load<1>(lo + tid);
         op.template apply<1>(lo + tid, r, acc);
       }
-      const uint64_t nvec = (hi4 - lo4) >> 2;
-      for (uint64_t v = tid; v < nvec; v += uint64_t(kThreads) * kDepth) {
-        typename Op::template Regs<4> r[kDepth];
+      const uint64_t nvec = (hi4 - lo4) / W;
+      for (uint64_t v = tid; v < nvec; v += uint64_t(kThreads) * D) {
+        typename Op::template Regs<W> r[D];
 #pragma unroll
-        for (int k = 0; k < kDepth; ++k) {
+        for (int k = 0; k < D; ++k) {
           const uint64_t vk = v + uint64_t(k) * kThreads;
-          if (vk < nvec) r[k] = op.template load<4>(lo4 + (vk << 2));
+          if (vk < nvec) r[k] = op.template load<W>(lo4 + vk * W);
         }
 #pragma unroll
-        for (int k = 0; k < kDepth; ++k) {
+        for (int k = 0; k < D; ++k) {
           const uint64_t vk = v + uint64_t(k) * kThreads;
-          if (vk < nvec) op.template apply<4>(lo4 + (vk << 2), r[k], acc);
+          if (vk < nvec) op.template apply<W>(lo4 + vk * W, r[k], acc);
         }
       }
-      if (tid < hi - hi4) {  // unaligned tail (at most 3 elements)
+      if (tid < hi - hi4) {  // unaligned tail (at most W-1 elements)
         const auto r = op.template load<1>(hi4 + tid);
         op.template apply<1>(hi4 + tid, r, acc);
       }
@@ -785,6 +966,40 @@ int launch_fused_m(int merge, bool vec, const FragRec* tbl, uint64_t T, float* t
   }
 }
 
+template <bool NESTEROV, int MERGE>
+int launch_fused_bf16(bool vec, const FragRec* tbl, uint64_t T, unsigned short* tm, const unsigned short* ts,
+                      float* tg, float* m, const float* dg, unsigned short* pg, const DevHP& hp, double* partials,
+                      hipStream_t s) {
+  if (MERGE == 1 || MERGE == 2) {
+    if (!ts) {
+      if (pg) {
+        FusedBf16Op<NESTEROV, (MERGE == 1 || MERGE == 2) ? MERGE : 1, true, false> op{tm, nullptr, tg, m, dg, pg, hp};
+        return launch_walk(vec, tbl, T, op, partials, s);
+      }
+      FusedBf16Op<NESTEROV, (MERGE == 1 || MERGE == 2) ? MERGE : 1, false, false> op{tm, nullptr, tg, m, dg, nullptr, hp};
+      return launch_walk(vec, tbl, T, op, partials, s);
+    }
+  }
+  if (pg) {
+    FusedBf16Op<NESTEROV, MERGE, true> op{tm, ts, tg, m, dg, pg, hp};
+    return launch_walk(vec, tbl, T, op, partials, s);
+  }
+  FusedBf16Op<NESTEROV, MERGE, false> op{tm, ts, tg, m, dg, nullptr, hp};
+  return launch_walk(vec, tbl, T, op, partials, s);
+}
+
+template <bool NESTEROV>
+int launch_fused_bf16_m(int merge, bool vec, const FragRec* tbl, uint64_t T, unsigned short* tm,
+                        const unsigned short* ts, float* tg, float* m, const float* dg, unsigned short* pg,
+                        const DevHP& hp, double* partials, hipStream_t s) {
+  switch (merge) {
+    case 0: return launch_fused_bf16<NESTEROV, 0>(vec, tbl, T, tm, ts, tg, m, dg, pg, hp, partials, s);
+    case 1: return launch_fused_bf16<NESTEROV, 1>(vec, tbl, T, tm, ts, tg, m, dg, pg, hp, partials, s);
+    case 2: return launch_fused_bf16<NESTEROV, 2>(vec, tbl, T, tm, ts, tg, m, dg, pg, hp, partials, s);
+    default: return launch_fused_bf16<NESTEROV, 3>(vec, tbl, T, tm, ts, tg, m, dg, pg, hp, partials, s);
+  }
+}
+
 }  // namespace
 
 // ====================================================================== C ABI
@@ -1057,6 +1272,87 @@ int cocodc_sync_step_segmented(const cocodc_segment_t* segs, int32_t S, int32_t 
   if (int rc = plan_segments(segs, S, K, n_total, I_p, t_b, &pl)) return rc;
   return sync_step_impl(pl, K, n_total, theta_m, theta_m_send, theta_g, momentum, delta_g, delta_m_out, t_g, budget,
                         hp, R_out, sel_out, n_sel_out, sums_out, workspace, workspace_bytes_, stream);
+}
+
+int cocodc_pseudograd_bf16(const cocodc_fragment_t* frags, int32_t K, uint64_t n_total,
+                           const float* theta_g_snap, const uint16_t* theta_m, uint16_t* delta_m_out,
+                           uint16_t* theta_m_send_out, void* workspace, size_t workspace_bytes_, void* stream) {
+  if (!theta_g_snap || !theta_m || !delta_m_out) return COCODC_ERR_NULL;
+  if (!aligned(theta_g_snap, 4) || !aligned(theta_m, 2) || !aligned(delta_m_out, 2) || !aligned(theta_m_send_out, 2))
+    return COCODC_ERR_ALIGN;
+  Plan pl;
+  if (int rc = plan_table(frags, K, n_total, nullptr, nullptr, &pl)) return rc;
+  if (int rc = check_workspace(workspace, workspace_bytes_, pl.S, K, n_total)) return rc;
+  const Span in1{theta_g_snap, n_total * 4}, in2{theta_m, n_total * 2}, o1{delta_m_out, n_total * 2},
+      o2{theta_m_send_out, n_total * 2}, ws{workspace, workspace_bytes_};
+  if (overlap(o1, in1) || overlap(o1, in2) || overlap(o2, in1) || overlap(o2, in2) || overlap(o1, o2) ||
+      overlap(ws, in1) || overlap(ws, in2) || overlap(ws, o1) || overlap(ws, o2))
+    return COCODC_ERR_ALIAS;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  WorkspaceView v = view(workspace, pl.S, K);
+  if (int rc = upload_table(pl.recs, v.table, s)) return rc;
+  const bool vec = all_aligned16({theta_g_snap, theta_m, delta_m_out, theta_m_send_out});
+  if (theta_m_send_out) {
+    PseudoGradBf16Op<true> op{theta_g_snap, theta_m, delta_m_out, theta_m_send_out};
+    return launch_walk(vec, v.table, pl.T, op, v.partials, s);
+  }
+  PseudoGradBf16Op<false> op{theta_g_snap, theta_m, delta_m_out, nullptr};
+  return launch_walk(vec, v.table, pl.T, op, v.partials, s);
+}
+
+int cocodc_sync_step_bf16(const cocodc_fragment_t* frags, int32_t K, uint64_t n_total, uint16_t* theta_m,
+                          const uint16_t* theta_m_send, float* theta_g, float* momentum, const float* delta_g,
+                          uint16_t* delta_m_out, const int64_t* I_p, const int64_t* t_b, int64_t t_g,
+                          int32_t budget, const cocodc_hparams_t* hp, double* R_out, int32_t* sel_out,
+                          int32_t* n_sel_out, double* sums_out, void* workspace, size_t workspace_bytes_,
+                          void* stream) {
+  if (!theta_m || !theta_g || !momentum || !delta_g) return COCODC_ERR_NULL;
+  if (!I_p || !t_b || !R_out || !sel_out || !n_sel_out) return COCODC_ERR_NULL;
+  if (!all_aligned4({theta_g, momentum, delta_g, sel_out, n_sel_out})) return COCODC_ERR_ALIGN;
+  if (!aligned(theta_m, 2) || !aligned(theta_m_send, 2) || !aligned(delta_m_out, 2)) return COCODC_ERR_ALIGN;
+  if (!aligned(R_out, 8) || !aligned(sums_out, 8)) return COCODC_ERR_ALIGN;
+  if (int rc = check_hparams(hp)) return rc;
+  if (!theta_m_send && (hp->merge_mode == 0 || hp->score_src == 1)) return COCODC_ERR_NULL;
+  if (budget < 0) return COCODC_ERR_RANGE;
+  Plan pl;
+  if (int rc = plan_table(frags, K, n_total, I_p, t_b, &pl)) return rc;
+  if (int rc = check_workspace(workspace, workspace_bytes_, pl.S, K, n_total)) return rc;
+  const int n = budget < K ? budget : K;
+  const Span sp[] = {{theta_m, n_total * 2},      {theta_m_send, n_total * 2},    {theta_g, n_total * 4},
+                     {momentum, n_total * 4},     {delta_g, n_total * 4},         {delta_m_out, n_total * 2},
+                     {R_out, sizeof(double) * K}, {sel_out, sizeof(int32_t) * n}, {n_sel_out, sizeof(int32_t)},
+                     {sums_out, sizeof(double) * 4 * K}, {workspace, workspace_bytes_}};
+  const int ns = static_cast<int>(sizeof(sp) / sizeof(sp[0]));
+  for (int i = 0; i < ns; ++i) {
+    for (int j = i + 1; j < ns; ++j) {
+      if (overlap(sp[i], sp[j])) return COCODC_ERR_ALIAS;
+    }
+  }
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  WorkspaceView v = view(workspace, pl.S, K);
+  if (int rc = upload_table(pl.recs, v.table, s)) return rc;
+  const bool vec = all_aligned16({theta_m, theta_m_send, theta_g, momentum, delta_g, delta_m_out});
+  const DevHP d = to_dev(*hp);
+  int slot = -1;
+  {
+    std::lock_guard<std::mutex> lock(g_prof.mu);
+    if (g_prof.on && g_prof.used < static_cast<int>(g_prof.start.size())) slot = g_prof.used++;
+  }
+  if (slot >= 0) HIP_TRY(hipEventRecord(g_prof.start[slot], s));
+  int rc = hp->nesterov ? launch_fused_bf16_m<true>(merge_variant(*hp), vec, v.table, pl.T, theta_m, theta_m_send,
+                                                    theta_g, momentum, delta_g, delta_m_out, d, v.partials, s)
+                        : launch_fused_bf16_m<false>(merge_variant(*hp), vec, v.table, pl.T, theta_m, theta_m_send,
+                                                     theta_g, momentum, delta_g, delta_m_out, d, v.partials, s);
+  if (slot >= 0) HIP_TRY(hipEventRecord(g_prof.stop[slot], s));
+  if (rc) return rc;
+  const int which = (hp->score_src ? 2 : 0) + (hp->norm_kind == 2 ? 0 : 1);
+  hipLaunchKernelGGL(k_finalize, dim3(K), dim3(kThreads), 0, s, v.groups, v.partials, kSums, which,
+                     hp->norm_kind == 2 ? 1 : 0, R_out, sums_out, kSums);
+  HIP_TRY(hipGetLastError());
+  hipLaunchKernelGGL(k_select, dim3(1), dim3(kThreads), 0, s, v.groups, K, R_out, t_g,
+                     static_cast<int64_t>(hp->H), n, sel_out, n_sel_out);
+  HIP_TRY(hipGetLastError());
+  return COCODC_OK;
 }
 
 int cocodc_sync_plan(int32_t K, int32_t H, double gamma, double T_c, double T_s, int64_t* N_out,
