@@ -46,7 +46,7 @@
  *   accumulated in fp64 in a fixed order that depends only on the fragment table, so
  *   repeated calls on the same bytes give bit-identical scores and selections (the
  *   property Sec. 3.2 relies on for coordination-free selection).
- * Limits.  1 <= K <= COCODC_MAX_FRAGMENTS.
+ * Limits.  1 <= K <= COCODC_MAX_FRAGMENTS, n_total <= COCODC_MAX_ELEMENTS.
  */
 #ifndef COCODC_H
 #define COCODC_H
@@ -60,6 +60,7 @@ extern "C" {
 
 #define COCODC_MAX_FRAGMENTS 1024
 #define COCODC_MAX_SEGMENTS 4096
+#define COCODC_MAX_ELEMENTS (1ull << 44) /* n_total above this is rejected (COCODC_ERR_RANGE) */
 
 typedef enum {
   COCODC_OK = 0,
@@ -310,6 +311,19 @@ int cocodc_loop_state(const cocodc_loop_t* loop, int64_t* t_b_out, int64_t* I_p_
 uint64_t cocodc_layout_stride_bytes(uint64_t n_total);
 
 /* ---- diagnostics and measurement aids (no paper counterpart) ---- */
+
+/* Elements per tile (the aligned window of the flat buffers that one workgroup handles). */
+uint64_t cocodc_tile_elements(void);
+
+/* Host-only view of the tile list the kernels would walk for a segment table (for tests and
+ * debugging; no GPU work).  Segments are walked grouped by fragment, in the order listed within a
+ * fragment.  seg_offset_out / seg_slot_begin_out (S+1 entries): offset of the j-th walked segment
+ * and the index of its first tile; entry S holds the total number of tiles.
+ * frag_slot_begin_out (K+1 entries): fragment p owns tiles [p], [p+1]).  tile_capacity_out: the
+ * number of tile slots that cocodc_workspace_bytes_segmented(S, K, n_total) provides. */
+int cocodc_debug_tile_plan(const cocodc_segment_t* segs, int32_t S, int32_t K, uint64_t n_total,
+                           uint64_t* seg_offset_out, uint64_t* seg_slot_begin_out,
+                           uint64_t* frag_slot_begin_out, uint64_t* tile_capacity_out);
 
 /* hipError_t of the most recent failing HIP call on this thread (0 if none). */
 int cocodc_last_hip_error(void);

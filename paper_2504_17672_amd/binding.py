@@ -36,6 +36,7 @@ EXPORTS = (
     "cocodc_pseudograd_bf16", "cocodc_sync_step_bf16",
     "cocodc_loop_create", "cocodc_loop_destroy", "cocodc_loop_reset_scores", "cocodc_loop_observe",
     "cocodc_loop_plan", "cocodc_loop_due", "cocodc_loop_step", "cocodc_loop_state",
+    "cocodc_tile_elements", "cocodc_debug_tile_plan",
     "cocodc_layout_stride_bytes", "cocodc_last_hip_error", "cocodc_status_string", "cocodc_set_blocks_per_cu",
     "cocodc_profiler_enable", "cocodc_profiler_collect", "cocodc_profiler_disable",
 )
@@ -104,6 +105,8 @@ _lib.cocodc_loop_plan.argtypes = [_P, _i64_p, _i64_p]
 _lib.cocodc_loop_due.argtypes = [_P, C.c_int64, _i32_p, _i32_p]
 _lib.cocodc_loop_step.argtypes = [_P, C.c_int64, C.POINTER(cocodc_loop_buffers_t), _P, _i32_p, _i32_p, _i32_p]
 _lib.cocodc_loop_state.argtypes = [_P, _i64_p, _i64_p, _i64_p]
+_lib.cocodc_tile_elements.restype = C.c_uint64
+_lib.cocodc_debug_tile_plan.argtypes = [_seg_p, C.c_int32, C.c_int32, C.c_uint64, _P, _P, _P, _P]
 _lib.cocodc_layout_stride_bytes.restype = C.c_uint64
 _lib.cocodc_layout_stride_bytes.argtypes = [C.c_uint64]
 _lib.cocodc_status_string.restype = C.c_char_p
@@ -113,6 +116,7 @@ _lib.cocodc_profiler_enable.argtypes = [C.c_int32]
 _lib.cocodc_profiler_collect.argtypes = [C.POINTER(C.c_float), C.c_int32]
 for _name in EXPORTS:
     if _name not in ("cocodc_workspace_bytes", "cocodc_workspace_bytes_segmented", "cocodc_status_string",
+                     "cocodc_tile_elements",
                      "cocodc_layout_stride_bytes", "cocodc_loop_destroy"):
         getattr(_lib, _name).restype = C.c_int
 
@@ -471,3 +475,19 @@ def cocodc_sync_step_bf16(frags, n_total, theta_m, theta_m_send, theta_g, moment
                                       _i64(t_b), int(t_g), int(budget), C.byref(hp) if hp is not None else None,
                                       _ptr(R_out), _ptr(sel_out), _ptr(n_sel_out), _ptr(sums_out), wp, wb,
                                       _stream(stream))
+
+
+def cocodc_tile_elements():
+    return int(_lib.cocodc_tile_elements())
+
+
+def cocodc_debug_tile_plan(segs, K, n_total, S=None):
+    """Returns (status, seg_offsets[S+1], seg_slot_begin[S+1], frag_slot_begin[K+1], tile_capacity)."""
+    sa, n = _segs(segs)
+    n = n if S is None else S
+    so = (C.c_uint64 * (max(n, 0) + 1))()
+    ss = (C.c_uint64 * (max(n, 0) + 1))()
+    fs = (C.c_uint64 * (max(int(K), 0) + 1))()
+    cap = C.c_uint64(0)
+    rc = _lib.cocodc_debug_tile_plan(sa, n, int(K), int(n_total), so, ss, fs, C.byref(cap))
+    return rc, list(so), list(ss), list(fs), cap.value

@@ -776,6 +776,7 @@ int plan_segments(const cocodc_segment_t* segs, int32_t S, int32_t K, uint64_t n
                   const int64_t* t_b, Plan* plan) {
   if (!segs && S > 0) return COCODC_ERR_NULL;
   if (K < 1 || K > COCODC_MAX_FRAGMENTS || S < 0 || S > COCODC_MAX_SEGMENTS) return COCODC_ERR_RANGE;
+  if (n_total > COCODC_MAX_ELEMENTS) return COCODC_ERR_RANGE;  // keeps every byte count far from overflow
   std::vector<std::pair<uint64_t, uint64_t>> sorted;
   sorted.reserve(S);
   for (int32_t i = 0; i < S; ++i) {
@@ -1531,6 +1532,23 @@ uint64_t cocodc_layout_stride_bytes(uint64_t n_total) {
   uint64_t stride = std::max<uint64_t>(40 * GiB, (bytes + GiB - 1) / GiB * GiB);
   if (stride % (32 * GiB) == 0) stride += 2 * GiB;
   return stride;
+}
+
+uint64_t cocodc_tile_elements(void) { return kTile; }
+
+int cocodc_debug_tile_plan(const cocodc_segment_t* segs, int32_t S, int32_t K, uint64_t n_total,
+                           uint64_t* seg_offset_out, uint64_t* seg_slot_begin_out, uint64_t* frag_slot_begin_out,
+                           uint64_t* tile_capacity_out) {
+  if (!seg_offset_out || !seg_slot_begin_out || !frag_slot_begin_out || !tile_capacity_out) return COCODC_ERR_NULL;
+  Plan pl;
+  if (int rc = plan_segments(segs, S, K, n_total, nullptr, nullptr, &pl)) return rc;
+  for (int32_t j = 0; j <= S; ++j) {
+    seg_offset_out[j] = pl.recs[j].offset;
+    seg_slot_begin_out[j] = pl.recs[j].slot_begin;
+  }
+  for (int32_t p = 0; p <= K; ++p) frag_slot_begin_out[p] = pl.recs[static_cast<size_t>(S) + 1 + p].slot_begin;
+  *tile_capacity_out = max_tiles(S, n_total);
+  return COCODC_OK;
 }
 
 int cocodc_last_hip_error(void) { return g_last_hip_error; }

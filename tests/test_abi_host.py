@@ -102,6 +102,7 @@ def test_invalid_arguments_are_rejected_before_any_device_work(B):
     assert step(frags=[(0, 2048), (2048, 2049)]) == B.COCODC_ERR_RANGE
     assert step(frags=[(2 ** 63, 2 ** 63), (0, 1)]) == B.COCODC_ERR_RANGE
     assert step(budget=-1) == B.COCODC_ERR_RANGE
+    assert step(n=(1 << 44) + 4, wsb=1 << 62) == B.COCODC_ERR_RANGE
     for bad in (dict(tau=-1), dict(H=0), dict(nesterov=2), dict(drift_sign=0), dict(score_src=2),
                 dict(norm_kind=3), dict(merge_mode=3)):
         kw = dict(tau=5, H=100)
