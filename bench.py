@@ -87,6 +87,9 @@ def main():
     ap.add_argument("--bf16", action="store_true",
                     help="bf16 local parameters, send-time record and pseudo-gradient, fp32 global state "
                          "(cocodc_sync_step_bf16, 28 B/param)")
+    ap.add_argument("--graph", action="store_true",
+                    help="record one step into a HIP graph and time replays (launch-bound small workloads); "
+                         "the per-kernel HIP events are not available then, the roofline uses the whole step")
     ap.add_argument("--strided-shards", type=int, default=0, metavar="K",
                     help="shard the workload's layers into K strided fragments (shard k = layers k, k+K, ...; "
                          "Sec. 4.1) on a layer-ordered buffer and time cocodc_sync_step_segmented instead")
@@ -242,16 +245,31 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    B.check(B.cocodc_profiler_enable(args.steps))
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    cnt, k1_ms = B.cocodc_profiler_collect(args.steps)
-    B.cocodc_profiler_disable()
-    assert cnt == args.steps, cnt
+    if args.graph:
+        graph = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.graph(graph, stream=side):
+            step()
+        graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t0
+        k1_ms = [elapsed / args.steps * 1e3] * args.steps
+    else:
+        B.check(B.cocodc_profiler_enable(args.steps))
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t0
+        cnt, k1_ms = B.cocodc_profiler_collect(args.steps)
+        B.cocodc_profiler_disable()
+        assert cnt == args.steps, cnt
     finite = bool(torch.isfinite(st["theta_m"][:1 << 20]).all().item())
     assert finite, "state went non-finite during the timed steps"
 
@@ -271,7 +289,7 @@ def main():
         "dtype": "f64", "data": "synthetic",
         "config": {"workload": wl.name, "K": K, "params": n, "tau": wl.tau, "H": wl.H, "budget": wl.budget,
                    "bytes_per_param": bpp, "merge_mode": args.merge_mode,
-                   "local_dtype": "bf16" if args.bf16 else "f32",
+                   "local_dtype": "bf16" if args.bf16 else "f32", "launch": "hip graph replay" if args.graph else "eager",
                    "fragments": (f"{args.strided_shards} strided shards of {len(segs)} segments" if segs
                                  else "contiguous"),
                    "layout": (f"{layout}: one allocation, buffer bases {stride / (1 << 30):.2f} GiB apart"

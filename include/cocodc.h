@@ -312,8 +312,10 @@ uint64_t cocodc_layout_stride_bytes(uint64_t n_total);
 
 /* ---- diagnostics and measurement aids (no paper counterpart) ---- */
 
-/* Elements per tile (the aligned window of the flat buffers that one workgroup handles). */
-uint64_t cocodc_tile_elements(void);
+/* Elements per tile (the aligned window of the flat buffers that one workgroup handles) for
+ * buffers of n_total elements: 16384, or 2048 when n_total < 2^24 so that small calls still
+ * spread over the whole chip. */
+uint64_t cocodc_tile_elements(uint64_t n_total);
 
 /* Host-only view of the tile list the kernels would walk for a segment table (for tests and
  * debugging; no GPU work).  Segments are walked grouped by fragment, in the order listed within a

@@ -106,6 +106,7 @@ _lib.cocodc_loop_due.argtypes = [_P, C.c_int64, _i32_p, _i32_p]
 _lib.cocodc_loop_step.argtypes = [_P, C.c_int64, C.POINTER(cocodc_loop_buffers_t), _P, _i32_p, _i32_p, _i32_p]
 _lib.cocodc_loop_state.argtypes = [_P, _i64_p, _i64_p, _i64_p]
 _lib.cocodc_tile_elements.restype = C.c_uint64
+_lib.cocodc_tile_elements.argtypes = [C.c_uint64]
 _lib.cocodc_debug_tile_plan.argtypes = [_seg_p, C.c_int32, C.c_int32, C.c_uint64, _P, _P, _P, _P]
 _lib.cocodc_layout_stride_bytes.restype = C.c_uint64
 _lib.cocodc_layout_stride_bytes.argtypes = [C.c_uint64]
@@ -477,8 +478,8 @@ def cocodc_sync_step_bf16(frags, n_total, theta_m, theta_m_send, theta_g, moment
                                       _stream(stream))
 
 
-def cocodc_tile_elements():
-    return int(_lib.cocodc_tile_elements())
+def cocodc_tile_elements(n_total):
+    return int(_lib.cocodc_tile_elements(int(n_total)))
 
 
 def cocodc_debug_tile_plan(segs, K, n_total, S=None):

@@ -1,7 +1,7 @@
 // cocodc.hip -- gfx950 (MI355X) kernels and C ABI of the CoCoDC outer-synchronisation path.
 //
 // One streaming pass per call.  Every kernel walks the same list of TILES: a tile is the
-// part of one fragment that falls into one aligned window of kTile elements of the flat
+// part of one fragment that falls into one aligned window of 2^tile_shift elements of the flat
 // buffers, so a tile never straddles two fragments and, inside a tile, element indices that
 // are multiples of 4 are 16-byte aligned whenever the buffer bases are.  A workgroup of
 // 256 threads (4 wavefronts of 64) handles a tile with 128-bit loads and stores, several
@@ -51,19 +51,28 @@ namespace {
 
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / 64;
-constexpr uint64_t kTile = COCODC_TILE;
+// Tile size: 2^14 elements for large buffers; 2^11 for small ones (below 2^24 elements), so
+// that even a 1M-element call spreads over more workgroups than there are compute units.  It
+// depends on n_total alone, so the workspace size and the summation order are functions of
+// the arguments and not of the machine.
+constexpr int kTileShiftLarge = 14, kTileShiftSmall = 11;
+constexpr uint64_t kSmallBufferElements = 1ull << 24;
+static_assert((1u << kTileShiftLarge) == COCODC_TILE, "COCODC_TILE must match the large tile");
+inline int tile_shift_for(uint64_t n_total) {
+  return n_total < kSmallBufferElements ? kTileShiftSmall : kTileShiftLarge;
+}
 constexpr int kDepth = COCODC_DEPTH;  // independent 128-bit loads per stream kept in flight per lane
 constexpr int kTableChunk = 64;       // fragment records carried by one table-upload launch
 constexpr int kSums = 4;              // doubles per partial-sum slot
 
-static_assert(kTile % (4 * kThreads) == 0, "a tile must be a whole number of workgroup-wide vector rows");
+static_assert((1u << kTileShiftSmall) % (4 * kThreads) == 0, "a tile must be a whole number of workgroup-wide vector rows");
 
 // Device-side description of one fragment.
 struct FragRec {
   uint64_t offset;      // first element
   uint64_t length;      // elements
   uint64_t slot_begin;  // index of this fragment's first tile in the global tile list
-  uint64_t tile0;       // absolute window index (offset / kTile) of that first tile
+  uint64_t tile0;       // absolute window index (offset >> tile_shift) of that first tile
   int64_t I_p;          // steps between the fragment's last two completed syncs (Eq. 11)
   int64_t t_b;          // step of its last completed sync (Algorithm 2)
 };
@@ -573,16 +582,17 @@ __global__ void k_write_table(TableChunk chunk, FragRec* dst, int base, int coun
 #endif
 template <class Op, bool VEC>
 __global__ __launch_bounds__(kThreads) COCODC_OCCUPANCY void k_walk(const FragRec* __restrict__ tbl, uint64_t T,
-                                                    Op op, double* __restrict__ partials) {
+                                                    int tile_shift, Op op, double* __restrict__ partials) {
   __shared__ double lds[kWaves][kSums];
   const uint64_t tid = threadIdx.x;
   int p = 0;
   for (uint64_t w = blockIdx.x; w < T; w += gridDim.x) {
     while (w >= tbl[p + 1].slot_begin) ++p;  // uniform; skips empty fragments
     const uint64_t f_off = tbl[p].offset, f_end = f_off + tbl[p].length;
-    const uint64_t win = (tbl[p].tile0 + (w - tbl[p].slot_begin)) * kTile;
+    const uint64_t win = (tbl[p].tile0 + (w - tbl[p].slot_begin)) << tile_shift;
+    const uint64_t win_end = win + (uint64_t(1) << tile_shift);
     const uint64_t lo = f_off > win ? f_off : win;
-    const uint64_t hi = f_end < win + kTile ? f_end : win + kTile;
+    const uint64_t hi = f_end < win_end ? f_end : win_end;
 
     double acc[Op::kAcc > 0 ? Op::kAcc : 1];
 #pragma unroll
@@ -724,8 +734,8 @@ int hip_fail(hipError_t e) {
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 uint64_t max_tiles(int32_t S, uint64_t n_total) {
-  // a segment of length L overlaps at most L/kTile + 2 windows
-  return n_total / kTile + 2 * static_cast<uint64_t>(S) + 1;
+  // a segment of length L overlaps at most (L >> tile_shift) + 2 windows
+  return (n_total >> tile_shift_for(n_total)) + 2 * static_cast<uint64_t>(S) + 1;
 }
 
 // Device workspace: S+1 segment records (the tile walk), K+1 group records (one per fragment:
@@ -766,6 +776,7 @@ bool overlap(const Span& a, const Span& b) {
 struct Plan {
   std::vector<FragRec> recs;  // S+1 segment records followed by K+1 group records
   int32_t S = 0, K = 0;
+  int tile_shift = kTileShiftLarge;
   uint64_t T = 0;
 };
 
@@ -794,6 +805,8 @@ int plan_segments(const cocodc_segment_t* segs, int32_t S, int32_t K, uint64_t n
                    [&](int32_t a, int32_t b) { return segs[a].fragment < segs[b].fragment; });
   plan->S = S;
   plan->K = K;
+  plan->tile_shift = tile_shift_for(n_total);
+  const int sh = plan->tile_shift;
   plan->recs.assign(static_cast<size_t>(S) + 1 + static_cast<size_t>(K) + 1, FragRec{});
   FragRec* seg_rec = plan->recs.data();
   FragRec* grp_rec = plan->recs.data() + S + 1;
@@ -806,8 +819,8 @@ int plan_segments(const cocodc_segment_t* segs, int32_t S, int32_t K, uint64_t n
     r.offset = sg.offset;
     r.length = sg.length;
     r.slot_begin = slot;
-    r.tile0 = r.offset / kTile;
-    if (r.length) slot += (r.offset + r.length - 1) / kTile - r.tile0 + 1;
+    r.tile0 = r.offset >> sh;
+    if (r.length) slot += ((r.offset + r.length - 1) >> sh) - r.tile0 + 1;
   }
   while (next_group <= K) grp_rec[next_group++].slot_begin = slot;
   seg_rec[S].slot_begin = slot;
@@ -901,13 +914,14 @@ unsigned grid_for(uint64_t T) {
 }
 
 template <class Op>
-int launch_walk(bool vec, const FragRec* tbl, uint64_t T, const Op& op, double* partials, hipStream_t s) {
+int launch_walk(bool vec, const FragRec* tbl, uint64_t T, int tile_shift, const Op& op, double* partials,
+                hipStream_t s) {
   if (T == 0) return COCODC_OK;
   const dim3 grid(grid_for(T)), block(kThreads);
   if (vec) {
-    hipLaunchKernelGGL((k_walk<Op, true>), grid, block, 0, s, tbl, T, op, partials);
+    hipLaunchKernelGGL((k_walk<Op, true>), grid, block, 0, s, tbl, T, tile_shift, op, partials);
   } else {
-    hipLaunchKernelGGL((k_walk<Op, false>), grid, block, 0, s, tbl, T, op, partials);
+    hipLaunchKernelGGL((k_walk<Op, false>), grid, block, 0, s, tbl, T, tile_shift, op, partials);
   }
   HIP_TRY(hipGetLastError());
   return COCODC_OK;
@@ -935,69 +949,69 @@ struct Profiler {
 } g_prof;
 
 template <bool NESTEROV, int MERGE>
-int launch_fused(bool vec, const FragRec* tbl, uint64_t T, float* tm, const float* ts, float* tg,
+int launch_fused(bool vec, const FragRec* tbl, uint64_t T, int sh, float* tm, const float* ts, float* tg,
                  float* m, const float* dg, float* pg, const DevHP& hp, double* partials, hipStream_t s) {
   if (MERGE == 1 || MERGE == 2) {
     if (!ts) {  // the blend and the plain replacement never look at the send-time record
       if (pg) {
         FusedOp<NESTEROV, (MERGE == 1 || MERGE == 2) ? MERGE : 1, true, false> op{tm, nullptr, tg, m, dg, pg, hp};
-        return launch_walk(vec, tbl, T, op, partials, s);
+        return launch_walk(vec, tbl, T, sh, op, partials, s);
       }
       FusedOp<NESTEROV, (MERGE == 1 || MERGE == 2) ? MERGE : 1, false, false> op{tm, nullptr, tg, m, dg, nullptr, hp};
-      return launch_walk(vec, tbl, T, op, partials, s);
+      return launch_walk(vec, tbl, T, sh, op, partials, s);
     }
   }
   if (pg) {
     FusedOp<NESTEROV, MERGE, true> op{tm, ts, tg, m, dg, pg, hp};
-    return launch_walk(vec, tbl, T, op, partials, s);
+    return launch_walk(vec, tbl, T, sh, op, partials, s);
   }
   FusedOp<NESTEROV, MERGE, false> op{tm, ts, tg, m, dg, nullptr, hp};
-  return launch_walk(vec, tbl, T, op, partials, s);
+  return launch_walk(vec, tbl, T, sh, op, partials, s);
 }
 
 template <bool NESTEROV>
-int launch_fused_m(int merge, bool vec, const FragRec* tbl, uint64_t T, float* tm, const float* ts,
+int launch_fused_m(int merge, bool vec, const FragRec* tbl, uint64_t T, int sh, float* tm, const float* ts,
                    float* tg, float* m, const float* dg, float* pg, const DevHP& hp, double* partials,
                    hipStream_t s) {
   switch (merge) {
-    case 0: return launch_fused<NESTEROV, 0>(vec, tbl, T, tm, ts, tg, m, dg, pg, hp, partials, s);
-    case 1: return launch_fused<NESTEROV, 1>(vec, tbl, T, tm, ts, tg, m, dg, pg, hp, partials, s);
-    case 2: return launch_fused<NESTEROV, 2>(vec, tbl, T, tm, ts, tg, m, dg, pg, hp, partials, s);
-    default: return launch_fused<NESTEROV, 3>(vec, tbl, T, tm, ts, tg, m, dg, pg, hp, partials, s);
+    case 0: return launch_fused<NESTEROV, 0>(vec, tbl, T, sh, tm, ts, tg, m, dg, pg, hp, partials, s);
+    case 1: return launch_fused<NESTEROV, 1>(vec, tbl, T, sh, tm, ts, tg, m, dg, pg, hp, partials, s);
+    case 2: return launch_fused<NESTEROV, 2>(vec, tbl, T, sh, tm, ts, tg, m, dg, pg, hp, partials, s);
+    default: return launch_fused<NESTEROV, 3>(vec, tbl, T, sh, tm, ts, tg, m, dg, pg, hp, partials, s);
   }
 }
 
 template <bool NESTEROV, int MERGE>
-int launch_fused_bf16(bool vec, const FragRec* tbl, uint64_t T, unsigned short* tm, const unsigned short* ts,
+int launch_fused_bf16(bool vec, const FragRec* tbl, uint64_t T, int sh, unsigned short* tm, const unsigned short* ts,
                       float* tg, float* m, const float* dg, unsigned short* pg, const DevHP& hp, double* partials,
                       hipStream_t s) {
   if (MERGE == 1 || MERGE == 2) {
     if (!ts) {
       if (pg) {
         FusedBf16Op<NESTEROV, (MERGE == 1 || MERGE == 2) ? MERGE : 1, true, false> op{tm, nullptr, tg, m, dg, pg, hp};
-        return launch_walk(vec, tbl, T, op, partials, s);
+        return launch_walk(vec, tbl, T, sh, op, partials, s);
       }
       FusedBf16Op<NESTEROV, (MERGE == 1 || MERGE == 2) ? MERGE : 1, false, false> op{tm, nullptr, tg, m, dg, nullptr, hp};
-      return launch_walk(vec, tbl, T, op, partials, s);
+      return launch_walk(vec, tbl, T, sh, op, partials, s);
     }
   }
   if (pg) {
     FusedBf16Op<NESTEROV, MERGE, true> op{tm, ts, tg, m, dg, pg, hp};
-    return launch_walk(vec, tbl, T, op, partials, s);
+    return launch_walk(vec, tbl, T, sh, op, partials, s);
   }
   FusedBf16Op<NESTEROV, MERGE, false> op{tm, ts, tg, m, dg, nullptr, hp};
-  return launch_walk(vec, tbl, T, op, partials, s);
+  return launch_walk(vec, tbl, T, sh, op, partials, s);
 }
 
 template <bool NESTEROV>
-int launch_fused_bf16_m(int merge, bool vec, const FragRec* tbl, uint64_t T, unsigned short* tm,
+int launch_fused_bf16_m(int merge, bool vec, const FragRec* tbl, uint64_t T, int sh, unsigned short* tm,
                         const unsigned short* ts, float* tg, float* m, const float* dg, unsigned short* pg,
                         const DevHP& hp, double* partials, hipStream_t s) {
   switch (merge) {
-    case 0: return launch_fused_bf16<NESTEROV, 0>(vec, tbl, T, tm, ts, tg, m, dg, pg, hp, partials, s);
-    case 1: return launch_fused_bf16<NESTEROV, 1>(vec, tbl, T, tm, ts, tg, m, dg, pg, hp, partials, s);
-    case 2: return launch_fused_bf16<NESTEROV, 2>(vec, tbl, T, tm, ts, tg, m, dg, pg, hp, partials, s);
-    default: return launch_fused_bf16<NESTEROV, 3>(vec, tbl, T, tm, ts, tg, m, dg, pg, hp, partials, s);
+    case 0: return launch_fused_bf16<NESTEROV, 0>(vec, tbl, T, sh, tm, ts, tg, m, dg, pg, hp, partials, s);
+    case 1: return launch_fused_bf16<NESTEROV, 1>(vec, tbl, T, sh, tm, ts, tg, m, dg, pg, hp, partials, s);
+    case 2: return launch_fused_bf16<NESTEROV, 2>(vec, tbl, T, sh, tm, ts, tg, m, dg, pg, hp, partials, s);
+    default: return launch_fused_bf16<NESTEROV, 3>(vec, tbl, T, sh, tm, ts, tg, m, dg, pg, hp, partials, s);
   }
 }
 
@@ -1036,10 +1050,10 @@ int cocodc_pseudograd(const cocodc_fragment_t* frags, int32_t K, uint64_t n_tota
   const bool vec = all_aligned16({theta_g_snap, theta_m, delta_m_out, theta_m_send_out});
   if (theta_m_send_out) {
     PseudoGradOp<true> op{theta_g_snap, theta_m, delta_m_out, theta_m_send_out};
-    return launch_walk(vec, v.table, pl.T, op, v.partials, s);
+    return launch_walk(vec, v.table, pl.T, pl.tile_shift, op, v.partials, s);
   }
   PseudoGradOp<false> op{theta_g_snap, theta_m, delta_m_out, nullptr};
-  return launch_walk(vec, v.table, pl.T, op, v.partials, s);
+  return launch_walk(vec, v.table, pl.T, pl.tile_shift, op, v.partials, s);
 }
 
 int cocodc_outer_nesterov(const cocodc_fragment_t* frags, int32_t K, uint64_t n_total, float* theta_g,
@@ -1062,10 +1076,10 @@ int cocodc_outer_nesterov(const cocodc_fragment_t* frags, int32_t K, uint64_t n_
   const DevHP d = to_dev(*hp);
   if (hp->nesterov) {
     OuterOp<true> op{theta_g, momentum, delta_g, d};
-    return launch_walk(vec, v.table, pl.T, op, v.partials, s);
+    return launch_walk(vec, v.table, pl.T, pl.tile_shift, op, v.partials, s);
   }
   OuterOp<false> op{theta_g, momentum, delta_g, d};
-  return launch_walk(vec, v.table, pl.T, op, v.partials, s);
+  return launch_walk(vec, v.table, pl.T, pl.tile_shift, op, v.partials, s);
 }
 
 int cocodc_delay_compensate(const cocodc_fragment_t* frags, int32_t K, uint64_t n_total, float* theta_m,
@@ -1090,19 +1104,19 @@ int cocodc_delay_compensate(const cocodc_fragment_t* frags, int32_t K, uint64_t 
   switch (merge_variant(*hp)) {
     case 0: {
       MergeOp<0> op{theta_m, theta_m_send, theta_g, d};
-      return launch_walk(vec, v.table, pl.T, op, v.partials, s);
+      return launch_walk(vec, v.table, pl.T, pl.tile_shift, op, v.partials, s);
     }
     case 1: {
       MergeOp<1, false> op{theta_m, nullptr, theta_g, d};
-      return launch_walk(vec, v.table, pl.T, op, v.partials, s);
+      return launch_walk(vec, v.table, pl.T, pl.tile_shift, op, v.partials, s);
     }
     case 2: {
       MergeOp<2, false> op{theta_m, nullptr, theta_g, d};
-      return launch_walk(vec, v.table, pl.T, op, v.partials, s);
+      return launch_walk(vec, v.table, pl.T, pl.tile_shift, op, v.partials, s);
     }
     default: {
       MergeOp<3> op{theta_m, theta_m_send, theta_g, d};
-      return launch_walk(vec, v.table, pl.T, op, v.partials, s);
+      return launch_walk(vec, v.table, pl.T, pl.tile_shift, op, v.partials, s);
     }
   }
 }
@@ -1123,10 +1137,10 @@ static int fragment_scores_impl(Plan& pl, int32_t K, uint64_t n_total, const flo
   int rc;
   if (norm_kind == 2) {
     ScoreOp<2> op{x};
-    rc = launch_walk(vec, v.table, pl.T, op, v.partials, s);
+    rc = launch_walk(vec, v.table, pl.T, pl.tile_shift, op, v.partials, s);
   } else {
     ScoreOp<1> op{x};
-    rc = launch_walk(vec, v.table, pl.T, op, v.partials, s);
+    rc = launch_walk(vec, v.table, pl.T, pl.tile_shift, op, v.partials, s);
   }
   if (rc) return rc;
   hipLaunchKernelGGL(k_finalize, dim3(K), dim3(kThreads), 0, s, v.groups, v.partials, 1, 0,
@@ -1212,9 +1226,9 @@ static int sync_step_impl(Plan& pl, int32_t K, uint64_t n_total, float* theta_m,
     if (g_prof.on && g_prof.used < static_cast<int>(g_prof.start.size())) slot = g_prof.used++;
   }
   if (slot >= 0) HIP_TRY(hipEventRecord(g_prof.start[slot], s));
-  int rc = hp->nesterov ? launch_fused_m<true>(merge_variant(*hp), vec, v.table, pl.T, theta_m, theta_m_send, theta_g,
+  int rc = hp->nesterov ? launch_fused_m<true>(merge_variant(*hp), vec, v.table, pl.T, pl.tile_shift, theta_m, theta_m_send, theta_g,
                                                momentum, delta_g, delta_m_out, d, v.partials, s)
-                        : launch_fused_m<false>(merge_variant(*hp), vec, v.table, pl.T, theta_m, theta_m_send,
+                        : launch_fused_m<false>(merge_variant(*hp), vec, v.table, pl.T, pl.tile_shift, theta_m, theta_m_send,
                                                 theta_g, momentum, delta_g, delta_m_out, d, v.partials, s);
   if (slot >= 0) HIP_TRY(hipEventRecord(g_prof.stop[slot], s));
   if (rc) return rc;
@@ -1295,10 +1309,10 @@ int cocodc_pseudograd_bf16(const cocodc_fragment_t* frags, int32_t K, uint64_t n
   const bool vec = all_aligned16({theta_g_snap, theta_m, delta_m_out, theta_m_send_out});
   if (theta_m_send_out) {
     PseudoGradBf16Op<true> op{theta_g_snap, theta_m, delta_m_out, theta_m_send_out};
-    return launch_walk(vec, v.table, pl.T, op, v.partials, s);
+    return launch_walk(vec, v.table, pl.T, pl.tile_shift, op, v.partials, s);
   }
   PseudoGradBf16Op<false> op{theta_g_snap, theta_m, delta_m_out, nullptr};
-  return launch_walk(vec, v.table, pl.T, op, v.partials, s);
+  return launch_walk(vec, v.table, pl.T, pl.tile_shift, op, v.partials, s);
 }
 
 int cocodc_sync_step_bf16(const cocodc_fragment_t* frags, int32_t K, uint64_t n_total, uint16_t* theta_m,
@@ -1340,9 +1354,9 @@ int cocodc_sync_step_bf16(const cocodc_fragment_t* frags, int32_t K, uint64_t n_
     if (g_prof.on && g_prof.used < static_cast<int>(g_prof.start.size())) slot = g_prof.used++;
   }
   if (slot >= 0) HIP_TRY(hipEventRecord(g_prof.start[slot], s));
-  int rc = hp->nesterov ? launch_fused_bf16_m<true>(merge_variant(*hp), vec, v.table, pl.T, theta_m, theta_m_send,
+  int rc = hp->nesterov ? launch_fused_bf16_m<true>(merge_variant(*hp), vec, v.table, pl.T, pl.tile_shift, theta_m, theta_m_send,
                                                     theta_g, momentum, delta_g, delta_m_out, d, v.partials, s)
-                        : launch_fused_bf16_m<false>(merge_variant(*hp), vec, v.table, pl.T, theta_m, theta_m_send,
+                        : launch_fused_bf16_m<false>(merge_variant(*hp), vec, v.table, pl.T, pl.tile_shift, theta_m, theta_m_send,
                                                      theta_g, momentum, delta_g, delta_m_out, d, v.partials, s);
   if (slot >= 0) HIP_TRY(hipEventRecord(g_prof.stop[slot], s));
   if (rc) return rc;
@@ -1534,7 +1548,7 @@ uint64_t cocodc_layout_stride_bytes(uint64_t n_total) {
   return stride;
 }
 
-uint64_t cocodc_tile_elements(void) { return kTile; }
+uint64_t cocodc_tile_elements(uint64_t n_total) { return uint64_t(1) << tile_shift_for(n_total); }
 
 int cocodc_debug_tile_plan(const cocodc_segment_t* segs, int32_t S, int32_t K, uint64_t n_total,
                            uint64_t* seg_offset_out, uint64_t* seg_slot_begin_out, uint64_t* frag_slot_begin_out,

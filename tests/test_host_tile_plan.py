@@ -25,7 +25,7 @@ def random_table(rng, n_total, S, K):
 
 
 def check_plan(B, segs, K, n_total):
-    tile = B.cocodc_tile_elements()
+    tile = B.cocodc_tile_elements(n_total)
     rc, so, ss, fs, cap = B.cocodc_debug_tile_plan(segs, K, n_total)
     assert rc == 0
     S = len(segs)
@@ -50,14 +50,20 @@ def check_plan(B, segs, K, n_total):
 
 
 @settings(max_examples=150, deadline=None)
-@given(st.integers(0, 2 ** 32), st.integers(1, 400_000), st.integers(1, 40), st.integers(1, 9))
-def test_random_segment_tables(B, seed, n_total, S, K):
+@given(st.integers(0, 2 ** 32), st.integers(1, 400_000), st.integers(1, 40), st.integers(1, 9), st.booleans())
+def test_random_segment_tables(B, seed, n_used, S, K, large):
     rng = random.Random(seed)
-    check_plan(B, random_table(rng, n_total, S, K), K, n_total)
+    n_total = n_used + ((1 << 24) if large else 0)  # large: the 16384-element tile applies
+    check_plan(B, random_table(rng, n_used, S, K), K, n_total)
 
 
 def test_boundary_tables(B):
-    tile = B.cocodc_tile_elements()
+    assert B.cocodc_tile_elements(1 << 20) == 2048 and B.cocodc_tile_elements(1 << 24) == 16384
+    for n_big in (0, 1 << 24):  # both tile sizes
+        tile = B.cocodc_tile_elements(3 * 16384 + n_big)
+        check_plan(B, [(0, tile, 0)], 1, 3 * 16384 + n_big)
+        check_plan(B, [(tile - 1, 2, 0), (tile + 1, tile - 1, 1), (2 * tile, 1, 0)], 2, 3 * 16384 + n_big)
+    tile = 2048
     check_plan(B, [(0, tile, 0)], 1, tile)
     check_plan(B, [(tile - 1, 2, 0), (tile + 1, tile - 1, 1), (2 * tile, 1, 0)], 2, 3 * tile)
     check_plan(B, [(0, 0, 0)], 3, 10)
