@@ -13,9 +13,15 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libcocodc.so")
 
 if not os.path.exists(LIB_PATH):
-    raise ImportError(
-        f"{LIB_PATH} is missing: build the HIP library first (python -m paper_2504_17672_amd.build). "
-        "There is no CPU fallback.")
+    # Nothing built yet: compile the HIP library now (hipcc cross-compiles without a GPU).  If that
+    # is impossible the import fails: there is no CPU fallback for any entry point.
+    try:
+        from . import build as _build
+        _build.build()
+    except Exception as exc:  # noqa: BLE001
+        raise ImportError(
+            f"{LIB_PATH} is missing and could not be built (python -m paper_2504_17672_amd.build): {exc}. "
+            "There is no CPU fallback.") from exc
 
 _lib = C.CDLL(LIB_PATH)
 

@@ -48,8 +48,11 @@ def _checksum(t):
 def test_full_size_sampled(B, ref, name, sample_frags):
     wl = synth.WORKLOADS[name]
     n, K = wl.n_total, wl.K
-    print(f"case {name} full size K={K} n={n} layout=spaced", flush=True)
-    arena, carved = B.spaced_buffers(n, 6, "cuda")
+    torch.cuda.empty_cache()
+    free, _ = torch.cuda.mem_get_info()
+    # what bench.py does by default, leaving a fifth of the memory for this test's own temporaries
+    arena, carved, stride, _ = B.tuned_spaced_buffers(n, wl.frags, "cuda", max_arena_bytes=int(free * 0.8))
+    print(f"case {name} full size K={K} n={n} layout=tuned stride={stride / 2**30:.0f} GiB", flush=True)
     names = ("theta_m", "theta_m_send", "theta_g", "momentum", "delta_g", "pg")
     bufs = dict(zip(names, carved))
     st = synth.make_state(wl, "cuda", seed=0, buffers=bufs)
