@@ -106,6 +106,12 @@ typedef struct {
   int32_t merge_mode; /* 0: delay compensation (Eq. 8); 1: Streaming-DiLoCo blend (Eq. 3);  */
                       /* 2: adopt the new global state (blocking DiLoCo)                    */
   double alpha;       /* mixing factor of Eq. 3; read only when merge_mode == 1             */
+  int32_t delta_src;  /* the divergence term Delta of Eq. 5-7.  0: theta^g_{p,t_p} - theta^m_{p,t_p}, */
+                      /* the equation that introduces Eq. 5 (default).  1: theta^m_{p,t_p} -        */
+                      /* theta^g_{p,t_p-H}, the change accumulated over the last H steps that the   */
+                      /* text after Eq. 6 describes; it needs the previous global state, so only    */
+                      /* the fused calls accept it (cocodc_delay_compensate: COCODC_ERR_RANGE)      */
+  int32_t reserved;   /* set to 0                                                           */
 } cocodc_hparams_t;
 
 /* Bytes of device workspace that any entry point below needs for (K, n_total).

@@ -29,6 +29,7 @@ class HParams(C.Structure):
         ("nesterov", C.c_int32), ("drift_sign", C.c_int32),
         ("score_src", C.c_int32), ("norm_kind", C.c_int32),
         ("merge_mode", C.c_int32), ("alpha", C.c_double),
+        ("delta_src", C.c_int32), ("reserved", C.c_int32),
     ]
 
 
@@ -41,9 +42,10 @@ class Shadow(C.Structure):
 
 
 def hparams(tau, H, lam=0.5, eta=0.7, mu=0.9, nesterov=1, drift_sign=1, score_src=0, norm_kind=2,
-            merge_mode=0, alpha=1.0):
+            merge_mode=0, alpha=1.0, delta_src=0):
     return HParams(int(tau), int(H), float(lam), float(eta), float(mu), int(nesterov),
-                   int(drift_sign), int(score_src), int(norm_kind), int(merge_mode), float(alpha))
+                   int(drift_sign), int(score_src), int(norm_kind), int(merge_mode), float(alpha),
+                   int(delta_src), 0)
 
 
 def lib():

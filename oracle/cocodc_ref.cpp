@@ -54,6 +54,7 @@ int check_hparams(const cocodc_ref_hparams_t* hp) {
   if (hp->score_src != 0 && hp->score_src != 1) return kErrRange;
   if (hp->norm_kind != 1 && hp->norm_kind != 2) return kErrRange;
   if (hp->merge_mode < 0 || hp->merge_mode > 2) return kErrRange;
+  if (hp->delta_src != 0 && hp->delta_src != 1) return kErrRange;
   if (!std::isfinite(hp->lambda) || !std::isfinite(hp->eta) || !std::isfinite(hp->mu) ||
       !std::isfinite(hp->alpha))
     return kErrRange;
@@ -83,11 +84,12 @@ inline double drift_times_tau(double theta_send, double theta_m, const cocodc_re
 //           defined with Eq. 5), products taken element by element
 //   Eq. 8:  theta^m_{p,t_l} <- G + g_corr * tau = G + d + lambda * d*d*Delta / (tau*H)
 // Written in terms of d so that tau = 0 (no overlap, hence d = 0) needs no division.
+// theta_g_prev is the global state before the outer step; only delta_src 1 looks at it.
 inline double merge_local(double G, double theta_send, double theta_m, double d,
-                          const cocodc_ref_hparams_t& hp) {
+                          const cocodc_ref_hparams_t& hp, double theta_g_prev = 0.0) {
   if (hp.merge_mode == 1) return (1.0 - hp.alpha) * theta_m + hp.alpha * G;  // Eq. 3
   if (hp.merge_mode == 2) return G;  // blocking DiLoCo: adopt the global state
-  const double Delta = G - theta_send;
+  const double Delta = hp.delta_src ? (theta_send - theta_g_prev) : (G - theta_send);
   double corr = 0.0;
   if (hp.tau >= 1) {
     const double tauH = static_cast<double>(hp.tau) * static_cast<double>(hp.H);
@@ -116,7 +118,7 @@ inline void sync_element(uint64_t i, float* theta_m, const float* theta_send, fl
   const float G = static_cast<float>(G64);  // what an unfused caller would read back
 
   const double d = drift_times_tau(ts, tm, hp);
-  const double tm_new = merge_local(static_cast<double>(G), ts, tm, d, hp);
+  const double tm_new = merge_local(static_cast<double>(G), ts, tm, d, hp, tg);
 
   s->g2 += dg * dg;  // Eq. 11 numerator, squared
   s->g1 += std::fabs(dg);
@@ -186,6 +188,7 @@ int cocodc_ref_delay_compensate(const cocodc_ref_fragment_t* frags, int32_t K, u
   if (int rc = check_table(frags, K, n_total)) return rc;
   if (int rc = check_hparams(hp)) return rc;
   if (!theta_m_send && hp->merge_mode == 0) return kErrNull;  // Algorithm 1 needs theta^m_{p,t_p}
+  if (hp->delta_src == 1 && hp->merge_mode == 0) return kErrRange;  // needs theta^g_{p,t_p-H}: fused only
   for (int32_t p = 0; p < K; ++p) {
     for (uint64_t i = frags[p].offset; i < frags[p].offset + frags[p].length; ++i) {
       const double tm = theta_m[i], ts = theta_m_send ? theta_m_send[i] : tm, G = theta_g[i];
@@ -477,7 +480,7 @@ int cocodc_ref_sync_step_bf16(const cocodc_ref_fragment_t* frags, int32_t K, uin
       const double G64 = outer_update(tg, m0, dg, *hp, &m1);   // Eq. 2
       const float G = static_cast<float>(G64);                  // the stored fp32 global state
       const double d = drift_times_tau(ts, tm, *hp);            // Eq. 4 times tau
-      const double tm_new = merge_local(static_cast<double>(G), ts, tm, d, *hp);  // Eq. 7, 8
+      const double tm_new = merge_local(static_cast<double>(G), ts, tm, d, *hp, tg);  // Eq. 7, 8
       s.g2 += dg * dg;
       s.g1 += std::fabs(dg);
       s.d2 += d * d;

@@ -50,6 +50,11 @@ typedef struct {
   int32_t norm_kind;  /* 2: L2 norm (Eq. 11); 1: L1 norm                                */
   int32_t merge_mode; /* 0: delay compensation (Eq. 8); 1: blend (Eq. 3); 2: replace    */
   double alpha;       /* mixing factor of Eq. 3, used by merge_mode 1 only              */
+  int32_t delta_src;  /* divergence term of Eq. 5-7: 0 = theta^g_{p,t_p} - theta^m_{p,t_p} (the
+                         equation that introduces Eq. 5); 1 = theta^m_{p,t_p} - theta^g_{p,t_p-H}
+                         (the change accumulated over H steps that the text after Eq. 6 describes);
+                         1 needs the previous global state: fused step only              */
+  int32_t reserved;   /* 0 */
 } cocodc_ref_hparams_t;
 
 /* Optional fp64 (unrounded) copies of the three stored outputs of the fused step. */

@@ -215,12 +215,15 @@ __device__ __forceinline__ double drift(float theta_send, float theta_m, const D
 // MERGE 1: Eq. 3 blend.  MERGE 2: adopt G.
 template <int MERGE>
 __device__ __forceinline__ double merge_local_f64(float G, float theta_send, float theta_m, double d,
-                                                  const DevHP& hp) {
+                                                  const DevHP& hp, float theta_g_prev = 0.0f) {
   const double Gd = static_cast<double>(G);
   if (MERGE == 1) return hp.one_minus_alpha * static_cast<double>(theta_m) + hp.alpha * Gd;
   if (MERGE == 2) return Gd;
   if (MERGE == 3) return Gd + d + 0.0;
-  const double Delta = Gd - static_cast<double>(theta_send);
+  // MERGE 4: the divergence term is the change accumulated before the send,
+  // theta^m_{p,t_p} - theta^g_{p,t_p-H} (text after Eq. 6), instead of G - theta^m_{p,t_p}.
+  const double Delta = (MERGE == 4) ? static_cast<double>(theta_send) - static_cast<double>(theta_g_prev)
+                                    : Gd - static_cast<double>(theta_send);
 #if COCODC_EXACT_DIV
   const double corr = hp.lambda * d * d * Delta / hp.tauH;
 #else
@@ -282,7 +285,7 @@ struct FusedOp {
       float m1;
       const float G = outer_update<NESTEROV>(tg, m, dg, hp, &m1);
       const double d = HAS_SEND ? drift(ts, tm, hp) : 0.0;
-      const float tm1 = merge_local<MERGE>(G, ts, tm, d, hp);
+      const float tm1 = static_cast<float>(merge_local_f64<MERGE>(G, ts, tm, d, hp, tg));
       const double dgd = static_cast<double>(dg);
       a[0] = fma(dgd, dgd, a[0]);  // exact product: same as a plain multiply-then-add
       a[1] += fabs(dgd);
@@ -451,7 +454,7 @@ struct FusedBf16Op {
       float m1;
       const float G = outer_update<NESTEROV>(tg, m, dg, hp, &m1);
       const double d = HAS_SEND ? drift(ts, tm, hp) : 0.0;
-      const double tm1 = merge_local_f64<MERGE>(G, ts, tm, d, hp);
+      const double tm1 = merge_local_f64<MERGE>(G, ts, tm, d, hp, tg);
       const double dgd = static_cast<double>(dg);
       a[0] = fma(dgd, dgd, a[0]);
       a[1] += fabs(dgd);
@@ -870,14 +873,20 @@ int check_hparams(const cocodc_hparams_t* hp) {
   if (hp->score_src != 0 && hp->score_src != 1) return COCODC_ERR_RANGE;
   if (hp->norm_kind != 1 && hp->norm_kind != 2) return COCODC_ERR_RANGE;
   if (hp->merge_mode < 0 || hp->merge_mode > 2) return COCODC_ERR_RANGE;
+  if (hp->delta_src != 0 && hp->delta_src != 1) return COCODC_ERR_RANGE;
   if (!std::isfinite(hp->lambda) || !std::isfinite(hp->eta) || !std::isfinite(hp->mu) ||
       !std::isfinite(hp->alpha))
     return COCODC_ERR_NONFINITE;
   return COCODC_OK;
 }
 
-// Kernel variant of the merge: 0/1/2 as merge_mode, 3 = delay compensation with tau == 0.
-int merge_variant(const cocodc_hparams_t& hp) { return (hp.merge_mode == 0 && hp.tau < 1) ? 3 : hp.merge_mode; }
+// Kernel variant of the merge: 0/1/2 as merge_mode, 3 = delay compensation with tau == 0,
+// 4 = delay compensation with the accumulated-change reading of the divergence term.
+int merge_variant(const cocodc_hparams_t& hp) {
+  if (hp.merge_mode != 0) return hp.merge_mode;
+  if (hp.tau < 1) return 3;
+  return hp.delta_src == 1 ? 4 : 0;
+}
 
 DevHP to_dev(const cocodc_hparams_t& hp) {
   DevHP d;
@@ -977,6 +986,7 @@ int launch_fused_m(int merge, bool vec, const FragRec* tbl, uint64_t T, int sh, 
     case 0: return launch_fused<NESTEROV, 0>(vec, tbl, T, sh, tm, ts, tg, m, dg, pg, hp, partials, s);
     case 1: return launch_fused<NESTEROV, 1>(vec, tbl, T, sh, tm, ts, tg, m, dg, pg, hp, partials, s);
     case 2: return launch_fused<NESTEROV, 2>(vec, tbl, T, sh, tm, ts, tg, m, dg, pg, hp, partials, s);
+    case 4: return launch_fused<NESTEROV, 4>(vec, tbl, T, sh, tm, ts, tg, m, dg, pg, hp, partials, s);
     default: return launch_fused<NESTEROV, 3>(vec, tbl, T, sh, tm, ts, tg, m, dg, pg, hp, partials, s);
   }
 }
@@ -1011,6 +1021,7 @@ int launch_fused_bf16_m(int merge, bool vec, const FragRec* tbl, uint64_t T, int
     case 0: return launch_fused_bf16<NESTEROV, 0>(vec, tbl, T, sh, tm, ts, tg, m, dg, pg, hp, partials, s);
     case 1: return launch_fused_bf16<NESTEROV, 1>(vec, tbl, T, sh, tm, ts, tg, m, dg, pg, hp, partials, s);
     case 2: return launch_fused_bf16<NESTEROV, 2>(vec, tbl, T, sh, tm, ts, tg, m, dg, pg, hp, partials, s);
+    case 4: return launch_fused_bf16<NESTEROV, 4>(vec, tbl, T, sh, tm, ts, tg, m, dg, pg, hp, partials, s);
     default: return launch_fused_bf16<NESTEROV, 3>(vec, tbl, T, sh, tm, ts, tg, m, dg, pg, hp, partials, s);
   }
 }
@@ -1089,6 +1100,7 @@ int cocodc_delay_compensate(const cocodc_fragment_t* frags, int32_t K, uint64_t 
   if (!all_aligned4({theta_m, theta_m_send, theta_g})) return COCODC_ERR_ALIGN;
   if (int rc = check_hparams(hp)) return rc;
   if (!theta_m_send && hp->merge_mode == 0) return COCODC_ERR_NULL;  // Algorithm 1 needs theta^m_{p,t_p}
+  if (hp->delta_src == 1 && hp->merge_mode == 0) return COCODC_ERR_RANGE;  // needs theta^g_{p,t_p-H}: fused only
   Plan pl;
   if (int rc = plan_table(frags, K, n_total, nullptr, nullptr, &pl)) return rc;
   if (int rc = check_workspace(workspace, workspace_bytes_, pl.S, K, n_total)) return rc;

@@ -104,7 +104,7 @@ def test_invalid_arguments_are_rejected_before_any_device_work(B):
     assert step(budget=-1) == B.COCODC_ERR_RANGE
     assert step(n=(1 << 44) + 4, wsb=1 << 62) == B.COCODC_ERR_RANGE
     for bad in (dict(tau=-1), dict(H=0), dict(nesterov=2), dict(drift_sign=0), dict(score_src=2),
-                dict(norm_kind=3), dict(merge_mode=3)):
+                dict(norm_kind=3), dict(merge_mode=3), dict(delta_src=2)):
         kw = dict(tau=5, H=100)
         kw.update(bad)
         assert step(hp=B.hparams(**kw)) == B.COCODC_ERR_RANGE, bad
@@ -122,6 +122,8 @@ def test_invalid_arguments_are_rejected_before_any_device_work(B):
     assert B.cocodc_outer_nesterov(frags, n, tg, m, dg, None, ws, wsb, stream=0) == B.COCODC_ERR_NULL
     assert B.cocodc_delay_compensate(frags, n, tm, ts, tm, hp, ws, wsb, stream=0) == B.COCODC_ERR_ALIAS
     assert B.cocodc_delay_compensate(frags, n, tm, ts, tg, hp, ws, 8, stream=0) == B.COCODC_ERR_WORKSPACE
+    assert B.cocodc_delay_compensate(frags, n, tm, ts, tg, B.hparams(5, 100, delta_src=1), ws, wsb,
+                                     stream=0) == B.COCODC_ERR_RANGE  # needs the previous global state
     assert B.cocodc_fragment_scores(frags, n, dg, I_p, 3, R, None, ws, wsb, stream=0) == B.COCODC_ERR_RANGE
     assert B.cocodc_fragment_scores(frags, n, dg, None, 2, R, None, ws, wsb, stream=0) == B.COCODC_ERR_NULL
     assert B.cocodc_select_fragments(2, R, t_b, 10, 0, 1, sel, nsel, ws, wsb, stream=0) == B.COCODC_ERR_RANGE

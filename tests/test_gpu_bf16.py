@@ -103,6 +103,7 @@ def test_bf16_amplified_specials_and_switches(B, ref):
     wl = synth.Workload("bf16-amp", (40000, 33333, 12345), tau=2, H=1, budget=2)
     _case(B, ref, wl, seed=3, amplified=True)
     _case(B, ref, wl, seed=3, amplified=True, nesterov=0, drift_sign=-1)
+    _case(B, ref, wl, seed=3, amplified=True, delta_src=1)
     _case(B, ref, wl, seed=4, merge_mode=1, alpha=0.3, send=False)
     _case(B, ref, wl, seed=4, merge_mode=2)
     wl0 = synth.Workload("bf16-tau0", (40000, 12345), tau=0, H=3, budget=1)

@@ -162,6 +162,7 @@ def test_budget_at_least_k_and_zero(B, ref):
 @pytest.mark.parametrize("hpkw", [
     dict(nesterov=0), dict(drift_sign=-1), dict(merge_mode=1, alpha=0.3), dict(merge_mode=2),
     dict(score_src=1), dict(norm_kind=1), dict(score_src=1, norm_kind=1), dict(lam=0.0), dict(mu=0.0, eta=1.0),
+    dict(delta_src=1), dict(delta_src=1, nesterov=0, drift_sign=-1),
 ])
 def test_hyper_parameter_switches(B, ref, hpkw):
     wl = synth.Workload("hp", (40000, 33333, 12345), tau=5, H=100, budget=2)

@@ -25,8 +25,11 @@ MUTANTS = [
     ("outer_step_drops_lr", "theta_g_old - hp.eta * step", "theta_g_old - step"),
     ("drift_operands_swapped", "(theta_send - theta_m);", "(theta_m - theta_send);"),
     ("drift_ignores_sign_switch", "static_cast<double>(hp.drift_sign) * (theta_send - theta_m)", "(theta_send - theta_m)"),
-    ("delta_uses_current_params", "const double Delta = G - theta_send;", "const double Delta = G - theta_m;"),
-    ("delta_sign", "const double Delta = G - theta_send;", "const double Delta = theta_send - G;"),
+    ("delta_uses_current_params", ": (G - theta_send);", ": (G - theta_m);"),
+    ("delta_sign", ": (G - theta_send);", ": (theta_send - G);"),
+    ("delta_switch_ignored", "hp.delta_src ? (theta_send - theta_g_prev) : (G - theta_send)", "(G - theta_send)"),
+    ("delta_switch_sign", "hp.delta_src ? (theta_send - theta_g_prev)", "hp.delta_src ? (theta_g_prev - theta_send)"),
+    ("delta_switch_uses_new_state", "hp.delta_src ? (theta_send - theta_g_prev)", "hp.delta_src ? (theta_send - G)"),
     ("corr_linear_in_d", "hp.lambda * d * d * Delta / tauH", "hp.lambda * d * Delta / tauH"),
     ("corr_divides_by_H_only", "hp.lambda * d * d * Delta / tauH", "hp.lambda * d * d * Delta / static_cast<double>(hp.H)"),
     ("corr_divides_by_tau_only", "hp.lambda * d * d * Delta / tauH", "hp.lambda * d * d * Delta / static_cast<double>(hp.tau)"),
@@ -36,7 +39,7 @@ MUTANTS = [
     ("merge_subtracts_drift", "return G + d + corr;", "return G - d + corr;"),
     ("merge_starts_from_local", "return G + d + corr;", "return theta_m + d + corr;"),
     ("blend_weights_swapped", "(1.0 - hp.alpha) * theta_m + hp.alpha * G", "hp.alpha * theta_m + (1.0 - hp.alpha) * G"),
-    ("merge_sees_unrounded_global_state", "merge_local(static_cast<double>(G), ts, tm, d, hp)", "merge_local(G64, ts, tm, d, hp)"),
+    ("merge_sees_unrounded_global_state", "merge_local(static_cast<double>(G), ts, tm, d, hp, tg)", "merge_local(G64, ts, tm, d, hp, tg)"),
     ("score_sums_values_not_squares", "acc += (norm_kind == 2) ? v * v : std::fabs(v);", "acc += (norm_kind == 2) ? v : std::fabs(v);"),
     ("score_l1_without_abs", "acc += (norm_kind == 2) ? v * v : std::fabs(v);", "acc += (norm_kind == 2) ? v * v : v;"),
     ("score_no_sqrt", "const double norm = (norm_kind == 2) ? std::sqrt(acc) : acc;", "const double norm = acc;"),
@@ -72,6 +75,7 @@ BATTERY = [
     pins.test_eq_4_7_8_in_the_papers_own_variables,
     pins.test_change_rate_sign_flip_moves_result_by_twice_the_drift,
     pins.test_single_worker_sync_is_a_no_op_with_reversed_sign,
+    pins.test_divergence_term_as_accumulated_local_change,
     pins.test_merge_modes_blend_and_replace,
     pins.test_baseline_merges_need_no_send_time_record,
     pins.test_scores_brute_force_exact_rational,

@@ -237,6 +237,35 @@ def test_single_worker_sync_is_a_no_op_with_reversed_sign(ref):
     assert np.array_equal(tm_out, 2 * send - tm)
 
 
+def test_divergence_term_as_accumulated_local_change(ref):
+    """delta_src = 1: Delta = theta^m_{p,t_p} - theta^g_{p,t_p-H} (text after Eq. 6).  With eta = 0 the
+    global state does not move, so G = theta^g_{p,t_p-H} and the two readings of Delta are opposite."""
+    one = [(0, 1)]
+    for delta_src, want in ((1, 1.7500625), (0, 1.7499375)):
+        tm, tg, m = f32(1.0), f32(1.25), f32(0.0)
+        # d = 1.5 - 1.0 = 0.5 ; Delta = +-(1.5 - 1.25) = +-0.25 ; corr = 0.5 * 0.25 * (+-0.25) / (5 * 100)
+        out = ref.sync_step(one, tm, f32(1.5), tg, m, f32(0.125), None, [1], [0], 1, 1,
+                            ref.hparams(5, 100, lam=0.5, eta=0.0, mu=0.0, delta_src=delta_src), shadow=True)
+        assert out["rc"] == 0 and tg[0] == np.float32(1.25)
+        assert abs(out["theta_m64"][0] - want) < 1e-15
+    # general case, in the paper's variables: g, g_corr, theta
+    tau, H, lam = 3, 7, 0.5
+    hp = ref.hparams(tau, H, lam=lam, delta_src=1)
+    keep, _, out = _fused_shadow(ref, hp)
+    G = out["theta_g64"].astype(np.float32).astype(np.float64)
+    ts, tm, tg0 = (keep[k].astype(np.float64) for k in ("theta_m_send", "theta_m", "theta_g"))
+    g = (ts - tm) / tau
+    want = G + (g + lam * g * g * (ts - tg0) / H) * tau
+    np.testing.assert_allclose(out["theta_m64"], want, rtol=1e-13, atol=1e-15)
+    base = _fused_shadow(ref, ref.hparams(tau, H, lam=lam, delta_src=0))[2]["theta_m64"]
+    assert np.max(np.abs(out["theta_m64"] - base)) > 1e-3  # the switch really changes the result
+    # the single-step entry point cannot know the previous global state
+    x = keep["theta_m"].copy()
+    assert ref.delay_compensate([(0, x.size)], x, keep["theta_m_send"], keep["theta_g"], hp) == -3
+    assert ref.outer_nesterov([(0, x.size)], keep["theta_g"].copy(), keep["momentum"].copy(), keep["delta_g"],
+                              ref.hparams(tau, H, delta_src=2)) == -3
+
+
 def test_merge_modes_blend_and_replace(ref):
     tm, ts, G = f32(1.0, 2.0), f32(0.0, 0.0), f32(3.0, -2.0)
     for alpha, want in ((0.0, [1.0, 2.0]), (1.0, [3.0, -2.0]), (0.5, [2.0, 0.0]), (0.25, [1.5, 1.0])):
