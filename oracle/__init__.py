@@ -58,7 +58,8 @@ def lib():
         _lib = C.CDLL(_LIB_PATH)
         for name in ("pseudograd", "outer_nesterov", "delay_compensate", "fragment_scores",
                      "select_fragments", "sync_step", "sync_step_mt", "sync_plan",
-                     "fragment_scores_segmented", "sync_step_segmented", "pseudograd_bf16", "sync_step_bf16"):
+                     "fragment_scores_segmented", "sync_step_segmented", "pseudograd_bf16", "sync_step_bf16",
+                     "select_fragments_bytes"):
             getattr(_lib, "cocodc_ref_" + name).restype = C.c_int
         _lib.cocodc_ref_round_bf16.restype = C.c_uint16
         _lib.cocodc_ref_round_bf16.argtypes = [C.c_double]
@@ -131,6 +132,22 @@ def select_fragments(R, t_b, t_g, H, budget):
     rc = lib().cocodc_ref_select_fragments(C.c_int32(K), C.c_void_p(R.ctypes.data), tb,
                                            C.c_int64(t_g), C.c_int32(H), C.c_int32(budget),
                                            C.c_void_p(sel.ctypes.data), C.byref(n_sel))
+    if rc != 0:
+        return rc, None
+    return rc, sel[:n_sel.value].copy()
+
+
+def select_fragments_bytes(R, t_b, t_g, H, frag_bytes, byte_budget):
+    """Returns (rc, sel[n_sel])."""
+    R = np.ascontiguousarray(R, dtype=np.float64)
+    K = R.size
+    keep, tb = _i64(t_b)
+    fb = np.ascontiguousarray(frag_bytes, dtype=np.uint64)
+    sel = np.full(max(K, 1), -1, dtype=np.int32)
+    n_sel = C.c_int32(-1)
+    rc = lib().cocodc_ref_select_fragments_bytes(C.c_int32(K), C.c_void_p(R.ctypes.data), tb, C.c_int64(t_g),
+                                                 C.c_int32(H), C.c_void_p(fb.ctypes.data), C.c_uint64(byte_budget),
+                                                 C.c_void_p(sel.ctypes.data), C.byref(n_sel))
     if rc != 0:
         return rc, None
     return rc, sel[:n_sel.value].copy()

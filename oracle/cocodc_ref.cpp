@@ -255,6 +255,25 @@ int cocodc_ref_select_fragments(int32_t K, const double* R, const int64_t* t_b, 
   return kOk;
 }
 
+int cocodc_ref_select_fragments_bytes(int32_t K, const double* R, const int64_t* t_b, int64_t t_g,
+                                      int32_t H, const uint64_t* frag_bytes, uint64_t byte_budget,
+                                      int32_t* sel_out, int32_t* n_sel_out) {
+  if (!frag_bytes) return kErrNull;
+  std::vector<int32_t> order(static_cast<size_t>(K > 0 ? K : 1));
+  int32_t n_all = 0;
+  if (int rc = cocodc_ref_select_fragments(K, R, t_b, t_g, H, K, order.data(), &n_all)) return rc;
+  uint64_t left = byte_budget;
+  int32_t n = 0;
+  for (int32_t i = 0; i < n_all; ++i) {
+    const uint64_t need = frag_bytes[order[i]];
+    if (need > left) break;  // the next fragment in priority order does not fit: stop
+    left -= need;
+    sel_out[n++] = order[i];
+  }
+  *n_sel_out = n;
+  return kOk;
+}
+
 int cocodc_ref_sync_step(const cocodc_ref_fragment_t* frags, int32_t K, uint64_t n_total,
                          float* theta_m, const float* theta_m_send, float* theta_g,
                          float* momentum, const float* delta_g, float* delta_m_out,

@@ -92,6 +92,13 @@ int cocodc_ref_fragment_scores(const cocodc_ref_fragment_t* frags, int32_t K, ui
 int cocodc_ref_select_fragments(int32_t K, const double* R, const int64_t* t_b, int64_t t_g,
                                 int32_t H, int32_t budget, int32_t* sel_out, int32_t* n_sel_out);
 
+/* Algorithm 2 under a byte budget (a reading of "bandwidth budget"; the paper has none): Algorithm
+ * 2 is applied repeatedly; a chosen fragment is sent if its size still fits into what is left of
+ * byte_budget, otherwise the selection ends there (a lower-priority fragment never overtakes). */
+int cocodc_ref_select_fragments_bytes(int32_t K, const double* R, const int64_t* t_b, int64_t t_g,
+                                      int32_t H, const uint64_t* frag_bytes, uint64_t byte_budget,
+                                      int32_t* sel_out, int32_t* n_sel_out);
+
 /* All of the above in one pass per element.  sums_out (nullable, 4*K):
  * per fragment {sum dg^2, sum |dg|, sum d^2, sum |d|}.  theta_m_send may be NULL for merge
  * modes 1 and 2 with score_src 0; the drift and its two sums are then zero. */

@@ -54,6 +54,8 @@ MUTANTS = [
     ("argmin_instead_of_argmax", "(R[p] > R[p_star])", "(R[p] < R[p_star])"),
     ("nan_wins", "std::isnan(R[p_star]) ? !std::isnan(R[p]) : (R[p] > R[p_star])", "(R[p] > R[p_star]) || std::isnan(R[p])"),
     ("selection_with_replacement", "taken[p_star] = 1;", ""),
+    ("byte_budget_skips_instead_of_stopping", "if (need > left) break;", "if (need > left) continue;"),
+    ("byte_budget_off_by_one", "if (need > left) break;", "if (need >= left) break;"),
     ("planner_min_instead_of_max", "if (cap > static_cast<double>(N))", "if (cap < static_cast<double>(N))"),
     ("planner_ignores_gamma", "std::floor(gamma * ((static_cast<double>(H) * T_c) / T_s))", "std::floor((static_cast<double>(H) * T_c) / T_s)"),
     ("planner_interval_inverted", "static_cast<int64_t>(H) / N;", "N / static_cast<int64_t>(H);"),
@@ -82,6 +84,7 @@ BATTERY = [
     pins.test_scores_closed_forms,
     pins.test_score_is_infinite_before_first_sync,
     pins.test_selection_hand_cases,
+    pins.test_selection_under_a_byte_budget,
     pins.test_planner_worked_example_from_the_paper,
     pins.test_planner_floor_of_k,
     lambda ref: pins.test_fused_equals_sequence_of_primitives(ref, True),

@@ -441,6 +441,35 @@ def test_selection_hand_cases(ref):
     assert sel.tolist() == []
 
 
+def test_selection_under_a_byte_budget(ref):
+    H, t_g = 10, 100
+    vals = [0.0, 1.0, 2.0, math.inf]
+    sizes_pool = [0, 3, 5, 8]
+    n = 0
+    for K in (1, 2, 3, 4):
+        for R in itertools.product(vals, repeat=K):
+            for age in itertools.product([3, 12], repeat=K):
+                t_b = [t_g - a for a in age]
+                sizes = [sizes_pool[(p * 7 + len(R) + int(sum(x for x in R if x < 9))) % 4] for p in range(K)]
+                order = priority_sort(R, t_b, t_g, H, K)
+                for budget in (0, 4, 8, 13, 100):
+                    want, left = [], budget
+                    for p in order:
+                        if sizes[p] > left:
+                            break
+                        left -= sizes[p]
+                        want.append(p)
+                    rc, sel = ref.select_fragments_bytes(R, t_b, t_g, H, sizes, budget)
+                    assert rc == 0 and sel.tolist() == want, (R, age, sizes, budget)
+                    n += 1
+                rc, sel = ref.select_fragments_bytes(R, t_b, t_g, H, sizes, 2 ** 63)
+                assert sel.tolist() == ref.select_fragments(R, t_b, t_g, H, K)[1].tolist()
+    assert n > 5000
+    # strict priority: a small low-priority fragment does not jump the queue
+    rc, sel = ref.select_fragments_bytes([3.0, 2.0, 1.0], [95, 95, 95], 100, 10, [4, 10, 1], 6)
+    assert sel.tolist() == [0]
+
+
 # ----------------------------------------------------------------------------- planner
 def test_planner_worked_example_from_the_paper(ref):
     """Sec. 4.1: K = 4, H = 100, gamma = 0.4 and tau = 5 (T_s = 5 T_c) give 8 syncs per H."""
