@@ -170,6 +170,15 @@ int cocodc_select_fragments(int32_t K, const double* R, const int64_t* t_b, int6
                             int32_t budget, int32_t* sel_out, int32_t* n_sel_out, void* workspace,
                             size_t workspace_bytes, void* stream);
 
+/* The same selection under a BYTE budget (a reading of "bandwidth budget"; the paper itself sends
+ * one fragment per decision): the priority order above is walked and a fragment is taken while
+ * its size frag_bytes[p] (host, K entries) still fits into what is left of byte_budget; the first
+ * fragment that does not fit ends the selection, so a small low-priority fragment never overtakes
+ * a large high-priority one.  sel_out: device, K int32; n_sel_out: device. */
+int cocodc_select_fragments_bytes(int32_t K, const double* R, const int64_t* t_b, int64_t t_g, int32_t H,
+                                  const uint64_t* frag_bytes, uint64_t byte_budget, int32_t* sel_out,
+                                  int32_t* n_sel_out, void* workspace, size_t workspace_bytes, void* stream);
+
 /* The whole path in one pass over memory: every element of every listed fragment is
  * read once from theta_m, theta_m_send, theta_g, momentum, delta_g and written once to
  * theta_m, theta_g, momentum (and delta_m_out if not NULL).  Equivalent, bit for bit,

@@ -39,7 +39,7 @@ EXPORTS = (
     "cocodc_workspace_bytes", "cocodc_pseudograd", "cocodc_outer_nesterov", "cocodc_delay_compensate",
     "cocodc_fragment_scores", "cocodc_select_fragments", "cocodc_sync_step", "cocodc_sync_plan",
     "cocodc_workspace_bytes_segmented", "cocodc_fragment_scores_segmented", "cocodc_sync_step_segmented",
-    "cocodc_pseudograd_bf16", "cocodc_sync_step_bf16",
+    "cocodc_pseudograd_bf16", "cocodc_sync_step_bf16", "cocodc_select_fragments_bytes",
     "cocodc_loop_create", "cocodc_loop_destroy", "cocodc_loop_reset_scores", "cocodc_loop_observe",
     "cocodc_loop_plan", "cocodc_loop_due", "cocodc_loop_step", "cocodc_loop_state",
     "cocodc_tile_elements", "cocodc_debug_tile_plan",
@@ -101,6 +101,8 @@ _lib.cocodc_sync_step_segmented.argtypes = [_seg_p, C.c_int32, C.c_int32, C.c_ui
 _lib.cocodc_pseudograd_bf16.argtypes = [_frag_p, C.c_int32, C.c_uint64, _P, _P, _P, _P, _P, C.c_size_t, _P]
 _lib.cocodc_sync_step_bf16.argtypes = [_frag_p, C.c_int32, C.c_uint64, _P, _P, _P, _P, _P, _P, _i64_p, _i64_p,
                                        C.c_int64, C.c_int32, _hp_p, _P, _P, _P, _P, _P, C.c_size_t, _P]
+_lib.cocodc_select_fragments_bytes.argtypes = [C.c_int32, _P, _i64_p, C.c_int64, C.c_int32, C.POINTER(C.c_uint64),
+                                               C.c_uint64, _P, _P, _P, C.c_size_t, _P]
 _i32_p = C.POINTER(C.c_int32)
 _lib.cocodc_loop_create.argtypes = [_frag_p, C.c_int32, C.c_uint64, _hp_p, C.c_double, C.c_double, C.c_double,
                                     C.POINTER(C.c_void_p)]
@@ -499,3 +501,11 @@ def cocodc_debug_tile_plan(segs, K, n_total, S=None):
     cap = C.c_uint64(0)
     rc = _lib.cocodc_debug_tile_plan(sa, n, int(K), int(n_total), so, ss, fs, C.byref(cap))
     return rc, list(so), list(ss), list(fs), cap.value
+
+
+def cocodc_select_fragments_bytes(K, R, t_b, t_g, H, frag_bytes, byte_budget, sel_out, n_sel_out, workspace,
+                                  workspace_bytes=None, stream=None):
+    wp, wb = _ws(workspace, workspace_bytes)
+    fb = None if frag_bytes is None else (C.c_uint64 * max(len(frag_bytes), 1))(*[int(v) for v in frag_bytes])
+    return _lib.cocodc_select_fragments_bytes(int(K), _ptr(R), _i64(t_b), int(t_g), int(H), fb, int(byte_budget),
+                                              _ptr(sel_out), _ptr(n_sel_out), wp, wb, _stream(stream))

@@ -714,6 +714,57 @@ __global__ __launch_bounds__(kThreads) void k_select(const FragRec* __restrict__
   if (threadIdx.x == 0) *n_sel = n;
 }
 
+// Same priority order, cut by a byte budget: fragments are taken in rank order while their sizes
+// (FragRec::length of the group records, in bytes) still fit; the first that does not fit ends
+// the selection.
+__global__ __launch_bounds__(kThreads) void k_select_bytes(const FragRec* __restrict__ tbl, int K,
+                                                            const double* __restrict__ R, int64_t t_g,
+                                                            int64_t H, unsigned long long byte_budget,
+                                                            int* __restrict__ sel, int* __restrict__ n_sel) {
+  __shared__ double sR[COCODC_MAX_FRAGMENTS];
+  __shared__ unsigned char sC[COCODC_MAX_FRAGMENTS];
+  __shared__ int sOrder[COCODC_MAX_FRAGMENTS];
+  for (int p = threadIdx.x; p < K; p += kThreads) {
+    const double r = R[p];
+    const bool overdue = (t_g - tbl[p].t_b) >= H;
+    sR[p] = r;
+    sC[p] = overdue ? 0 : (r != r ? 2 : 1);
+  }
+  __syncthreads();
+  for (int p = threadIdx.x; p < K; p += kThreads) {
+    const int cp = sC[p];
+    const double rp = sR[p];
+    int rank = 0;
+    for (int q = 0; q < K; ++q) {
+      const int cq = sC[q];
+      bool before;
+      if (cq != cp) {
+        before = cq < cp;
+      } else if (cp == 1) {
+        const double rq = sR[q];
+        before = (rq > rp) || (rq == rp && q < p);
+      } else {
+        before = q < p;
+      }
+      rank += before ? 1 : 0;
+    }
+    sOrder[rank] = p;  // ranks are a permutation of 0..K-1
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    unsigned long long left = byte_budget;
+    int n = 0;
+    for (int r = 0; r < K; ++r) {
+      const int p = sOrder[r];
+      const unsigned long long need = tbl[p].length;
+      if (need > left) break;
+      left -= need;
+      sel[n++] = p;
+    }
+    *n_sel = n;
+  }
+}
+
 __global__ void k_fill_inf(double* R, int K) {
   const int p = blockIdx.x * blockDim.x + threadIdx.x;
   if (p < K) R[p] = __builtin_huge_val();
@@ -1378,6 +1429,30 @@ int cocodc_sync_step_bf16(const cocodc_fragment_t* frags, int32_t K, uint64_t n_
   HIP_TRY(hipGetLastError());
   hipLaunchKernelGGL(k_select, dim3(1), dim3(kThreads), 0, s, v.groups, K, R_out, t_g,
                      static_cast<int64_t>(hp->H), n, sel_out, n_sel_out);
+  HIP_TRY(hipGetLastError());
+  return COCODC_OK;
+}
+
+int cocodc_select_fragments_bytes(int32_t K, const double* R, const int64_t* t_b, int64_t t_g, int32_t H,
+                                  const uint64_t* frag_bytes, uint64_t byte_budget, int32_t* sel_out,
+                                  int32_t* n_sel_out, void* workspace, size_t workspace_bytes_, void* stream) {
+  if (!R || !t_b || !frag_bytes || !sel_out || !n_sel_out) return COCODC_ERR_NULL;
+  if (K < 1 || K > COCODC_MAX_FRAGMENTS || H < 1) return COCODC_ERR_RANGE;
+  if (!aligned(R, 8) || !aligned(sel_out, 4) || !aligned(n_sel_out, 4)) return COCODC_ERR_ALIGN;
+  if (int rc = check_workspace(workspace, workspace_bytes_, K, K, 0)) return rc;
+  const Span r{R, sizeof(double) * K}, so{sel_out, sizeof(int32_t) * K}, ns{n_sel_out, sizeof(int32_t)};
+  const Span ws{workspace, workspace_bytes_};
+  if (overlap(r, so) || overlap(r, ns) || overlap(so, ns) || overlap(ws, r) || overlap(ws, so) ||
+      overlap(ws, ns))
+    return COCODC_ERR_ALIAS;
+  Plan pl;
+  if (int rc = plan_segments(nullptr, 0, K, 0, nullptr, t_b, &pl)) return rc;
+  for (int32_t p = 0; p < K; ++p) pl.recs[static_cast<size_t>(pl.S) + 1 + p].length = frag_bytes[p];
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  WorkspaceView v = view(workspace, pl.S, K);
+  if (int rc = upload_table(pl.recs, v.table, s)) return rc;
+  hipLaunchKernelGGL(k_select_bytes, dim3(1), dim3(kThreads), 0, s, v.groups, K, R, t_g, static_cast<int64_t>(H),
+                     static_cast<unsigned long long>(byte_budget), sel_out, n_sel_out);
   HIP_TRY(hipGetLastError());
   return COCODC_OK;
 }

@@ -320,6 +320,30 @@ def test_selection_only_large_k_ties_inf_nan(B, ref):
             assert torch.all(sel[n:] == -7)
 
 
+def test_selection_under_byte_budget(B, ref):
+    rng = np.random.default_rng(1)
+    for K in (1, 3, 24, 65, 1024):
+        vals = np.array([0.0, 0.5, 1.0, 2.0, math.inf, math.nan])
+        R = vals[rng.integers(0, vals.size, K)]
+        if K > 8:
+            R[: K // 2] = rng.random(K // 2)
+        t_g, H = 10_000, 100
+        t_b = (t_g - rng.integers(1, 150, K)).tolist()
+        sizes = rng.integers(0, 1 << 30, K).tolist()
+        ws = B.new_workspace(K, 0)
+        for budget in (0, 1 << 29, 1 << 31, (1 << 30) * (K // 2), 1 << 62):
+            Rd = torch.from_numpy(R).cuda()
+            sel = torch.full((K,), -7, dtype=torch.int32, device="cuda")
+            n_sel = torch.zeros(1, dtype=torch.int32, device="cuda")
+            assert B.cocodc_select_fragments_bytes(K, Rd, t_b, t_g, H, sizes, budget, sel, n_sel, ws) == 0
+            torch.cuda.synchronize()
+            rc, want = ref.select_fragments_bytes(R, t_b, t_g, H, sizes, budget)
+            n = int(n_sel.item())
+            assert sel[:n].cpu().tolist() == want.tolist(), (K, budget)
+            assert torch.all(sel[n:] == -7)
+    assert B.cocodc_select_fragments_bytes(2, Rd, t_b[:2], t_g, H, None, 5, sel, n_sel, ws) == B.COCODC_ERR_NULL
+
+
 # ------------------------------------------------------------------ determinism
 def test_bitwise_reproducible_and_independent_of_launch_shape(B, ref):
     wl = synth.MINI_WORKLOADS["1.3B-mini"]
