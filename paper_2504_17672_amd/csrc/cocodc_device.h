@@ -1,0 +1,729 @@
+// cocodc_device.h -- device code of the CoCoDC outer-synchronisation library (gfx950):
+// stream access helpers, the per-element arithmetic, the streaming operations, the workgroup
+// reductions and the kernels.  Included by cocodc.hip only.
+#pragma once
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kWaves = kThreads / 64;
+// Tile size: 2^14 elements for large buffers; 2^11 for small ones (below 2^24 elements), so
+// that even a 1M-element call spreads over more workgroups than there are compute units.  It
+// depends on n_total alone, so the workspace size and the summation order are functions of
+// the arguments and not of the machine.
+constexpr int kTileShiftLarge = 14, kTileShiftSmall = 11;
+constexpr uint64_t kSmallBufferElements = 1ull << 24;
+static_assert((1u << kTileShiftLarge) == COCODC_TILE, "COCODC_TILE must match the large tile");
+inline int tile_shift_for(uint64_t n_total) {
+  return n_total < kSmallBufferElements ? kTileShiftSmall : kTileShiftLarge;
+}
+constexpr int kDepth = COCODC_DEPTH;  // independent 128-bit loads per stream kept in flight per lane
+constexpr int kTableChunk = 64;       // fragment records carried by one table-upload launch
+constexpr int kSums = 4;              // doubles per partial-sum slot
+
+static_assert((1u << kTileShiftSmall) % (4 * kThreads) == 0, "a tile must be a whole number of workgroup-wide vector rows");
+
+// Device-side description of one fragment.
+struct FragRec {
+  uint64_t offset;      // first element
+  uint64_t length;      // elements
+  uint64_t slot_begin;  // index of this fragment's first tile in the global tile list
+  uint64_t tile0;       // absolute window index (offset >> tile_shift) of that first tile
+  int64_t I_p;          // steps between the fragment's last two completed syncs (Eq. 11)
+  int64_t t_b;          // step of its last completed sync (Algorithm 2)
+};
+static_assert(sizeof(FragRec) == 48, "FragRec layout");
+
+struct TableChunk {
+  FragRec rec[kTableChunk];
+};
+
+// Hyper-parameters in the form the kernels consume.
+struct DevHP {
+  double mu, eta, sign;
+  double lambda, tauH;  // tauH = tau*H as a double; lambda is forced to 0 when tau == 0
+  double coef;          // lambda / (tau*H), 0 when tau == 0 (used when COCODC_EXACT_DIV == 0)
+  double alpha, one_minus_alpha;
+};
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+template <int V>
+struct Vec;
+template <>
+struct Vec<1> {
+  using type = float;
+};
+template <>
+struct Vec<4> {
+  using type = f32x4;
+};
+
+template <int V>
+__device__ __forceinline__ typename Vec<V>::type load_stream(const float* p) {
+  using T = typename Vec<V>::type;
+#if COCODC_NT_LOAD
+  return __builtin_nontemporal_load(reinterpret_cast<const T*>(p));
+#else
+  return *reinterpret_cast<const T*>(p);
+#endif
+}
+
+template <int V>
+__device__ __forceinline__ void store_stream(float* p, typename Vec<V>::type v) {
+  using T = typename Vec<V>::type;
+#if COCODC_NT_STORE
+  __builtin_nontemporal_store(v, reinterpret_cast<T*>(p));
+#else
+  *reinterpret_cast<T*>(p) = v;
+#endif
+}
+
+__device__ __forceinline__ float lane_get(float v, int) { return v; }
+__device__ __forceinline__ float lane_get(const f32x4& v, int k) { return v[k]; }
+__device__ __forceinline__ void lane_set(float& v, int, float x) { v = x; }
+__device__ __forceinline__ void lane_set(f32x4& v, int k, float x) { v[k] = x; }
+
+// ---- 16-bit streams of the bf16 variant: four bf16 = one 64-bit access per lane.
+template <int V>
+struct VecU16;
+template <>
+struct VecU16<1> {
+  using type = unsigned short;
+};
+typedef unsigned short u16x4 __attribute__((ext_vector_type(4)));
+template <>
+struct VecU16<4> {
+  using type = u16x4;
+};
+
+template <int V>
+__device__ __forceinline__ typename VecU16<V>::type load_stream_u16(const unsigned short* p) {
+  using T = typename VecU16<V>::type;
+#if COCODC_NT_LOAD
+  return __builtin_nontemporal_load(reinterpret_cast<const T*>(p));
+#else
+  return *reinterpret_cast<const T*>(p);
+#endif
+}
+template <int V>
+__device__ __forceinline__ void store_stream_u16(unsigned short* p, typename VecU16<V>::type v) {
+  using T = typename VecU16<V>::type;
+#if COCODC_NT_STORE
+  __builtin_nontemporal_store(v, reinterpret_cast<T*>(p));
+#else
+  *reinterpret_cast<T*>(p) = v;
+#endif
+}
+__device__ __forceinline__ unsigned short lane_get(unsigned short v, int) { return v; }
+__device__ __forceinline__ unsigned short lane_get(const u16x4& v, int k) { return v[k]; }
+__device__ __forceinline__ void lane_set(u16x4& v, int k, unsigned short x) { v[k] = x; }
+__device__ __forceinline__ void lane_set(unsigned short& v, int, unsigned short x) { v = x; }
+
+// bfloat16 = upper half of a binary32.  Widening is exact.
+__device__ __forceinline__ float widen_bf16(unsigned short b) {
+  return __uint_as_float(static_cast<unsigned>(b) << 16);
+}
+
+// Nearest bfloat16 to an fp64 value in ONE rounding, ties to even; subnormals (spacing
+// 2^-133) kept, overflow to infinity, any NaN -> 0x7FC0.
+// The value is first rounded to binary32 by the hardware conversion, then to bf16 on the bit
+// pattern.  Rounding twice differs from rounding once only when the binary32 value sits
+// exactly half way between two bf16 values although the fp64 value did not: in that (rare)
+// case the pattern is nudged one step towards the fp64 value before the second rounding.
+__device__ __forceinline__ unsigned short round_bf16(double x) {
+  const float f = static_cast<float>(x);
+  unsigned u = __float_as_uint(f);
+  if ((u & 0xFFFFu) == 0x8000u) {
+    const double back = static_cast<double>(f);
+    if (back != x) u += (fabs(x) > fabs(back)) ? 1u : 0xFFFFFFFFu;
+  }
+  const unsigned r = (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+  return static_cast<unsigned short>(x != x ? 0x7FC0u : r);
+}
+
+// ------------------------------------------------------------------ per-element arithmetic
+// Eq. 2 with OuterOptim = SGD with momentum: m' = mu*m + dg ; step = dg + mu*m' (Nesterov)
+// or m' (heavy ball) ; G = theta_g - eta*step.  Returns G rounded to fp32 (the value that is
+// stored and that the merge below starts from).
+// Every product and sum is rounded separately (no fused multiply-add): with decimal
+// constants such as 0.9 and 0.7 and fp32 inputs, about one result in 10^4 lies exactly half
+// way between two fp32 values before the final rounding, and a fused operation would break
+// those ties differently from the plain sequence.
+template <bool NESTEROV>
+__device__ __forceinline__ float outer_update(float theta_g, float m, float dg, const DevHP& hp,
+                                              float* m_new) {
+  const double dgd = static_cast<double>(dg);
+  const double m1 = hp.mu * static_cast<double>(m) + dgd;
+  const double step = NESTEROV ? (dgd + hp.mu * m1) : m1;
+  *m_new = static_cast<float>(m1);
+  return static_cast<float>(static_cast<double>(theta_g) - hp.eta * step);
+}
+
+// d = tau * g with g the change rate of Eq. 4 (send-time minus current local parameters).
+__device__ __forceinline__ double drift(float theta_send, float theta_m, const DevHP& hp) {
+  return hp.sign * (static_cast<double>(theta_send) - static_cast<double>(theta_m));
+}
+
+// MERGE 0: Algorithm 1.  Eq. 7 put into Eq. 8 and multiplied out by tau:
+//   theta_m <- G + d + (lambda/(tau*H)) * d*d*Delta,  Delta = G - theta_send.
+// MERGE 3: the same with tau == 0 (no overlap): the last term is an exact zero.
+// MERGE 1: Eq. 3 blend.  MERGE 2: adopt G.
+template <int MERGE>
+__device__ __forceinline__ double merge_local_f64(float G, float theta_send, float theta_m, double d,
+                                                  const DevHP& hp, float theta_g_prev = 0.0f) {
+  const double Gd = static_cast<double>(G);
+  if (MERGE == 1) return hp.one_minus_alpha * static_cast<double>(theta_m) + hp.alpha * Gd;
+  if (MERGE == 2) return Gd;
+  if (MERGE == 3) return Gd + d + 0.0;
+  // MERGE 4: the divergence term is the change accumulated before the send,
+  // theta^m_{p,t_p} - theta^g_{p,t_p-H} (text after Eq. 6), instead of G - theta^m_{p,t_p}.
+  const double Delta = (MERGE == 4) ? static_cast<double>(theta_send) - static_cast<double>(theta_g_prev)
+                                    : Gd - static_cast<double>(theta_send);
+#if COCODC_EXACT_DIV
+  const double corr = hp.lambda * d * d * Delta / hp.tauH;
+#else
+  const double corr = hp.coef * d * d * Delta;
+#endif
+  return Gd + d + corr;
+}
+
+template <int MERGE>
+__device__ __forceinline__ float merge_local(float G, float theta_send, float theta_m, double d,
+                                             const DevHP& hp) {
+  return static_cast<float>(merge_local_f64<MERGE>(G, theta_send, theta_m, d, hp));
+}
+
+// ------------------------------------------------------------------ streaming operations
+// Each operation provides, for V = 1 (scalar) and V = 4 (128-bit):
+//   Regs<V>           the values loaded for V consecutive elements,
+//   load<V>(i)        issues the loads of elements [i, i+V),
+//   apply<V>(i, r, a) computes, stores, and accumulates into a[kAcc].
+
+// HAS_SEND false: no send-time record (merge modes 1 and 2 only): the drift and its sums are 0.
+template <bool NESTEROV, int MERGE, bool HAS_PG, bool HAS_SEND = true>
+struct FusedOp {
+  static constexpr int kAcc = 4;
+  static constexpr int kVec = 4;       // elements per lane per access (128-bit fp32)
+  static constexpr int kLoads = kDepth;  // accesses per stream in flight per lane
+  float* theta_m;
+  const float* theta_send;
+  float* theta_g;
+  float* momentum;
+  const float* delta_g;
+  float* pg;  // may alias delta_g
+  DevHP hp;
+
+  template <int V>
+  struct Regs {
+    typename Vec<V>::type tm, ts, tg, m, dg;
+  };
+
+  template <int V>
+  __device__ __forceinline__ Regs<V> load(uint64_t i) const {
+    Regs<V> r;
+    r.tm = load_stream<V>(theta_m + i);
+    if (HAS_SEND) r.ts = load_stream<V>(theta_send + i);
+    r.tg = load_stream<V>(theta_g + i);
+    r.m = load_stream<V>(momentum + i);
+    r.dg = load_stream<V>(delta_g + i);
+    return r;
+  }
+
+  template <int V>
+  __device__ __forceinline__ void apply(uint64_t i, const Regs<V>& r, double* a) const {
+    typename Vec<V>::type o_tm, o_tg, o_m, o_pg;
+#pragma unroll
+    for (int k = 0; k < V; ++k) {
+      const float tm = lane_get(r.tm, k), tg = lane_get(r.tg, k);
+      const float ts = HAS_SEND ? lane_get(r.ts, k) : tm;
+      const float m = lane_get(r.m, k), dg = lane_get(r.dg, k);
+      float m1;
+      const float G = outer_update<NESTEROV>(tg, m, dg, hp, &m1);
+      const double d = HAS_SEND ? drift(ts, tm, hp) : 0.0;
+      const float tm1 = static_cast<float>(merge_local_f64<MERGE>(G, ts, tm, d, hp, tg));
+      const double dgd = static_cast<double>(dg);
+      a[0] = fma(dgd, dgd, a[0]);  // exact product: same as a plain multiply-then-add
+      a[1] += fabs(dgd);
+      if (HAS_SEND) {
+        a[2] += d * d;
+        a[3] += fabs(d);
+      }
+      lane_set(o_tm, k, tm1);
+      lane_set(o_tg, k, G);
+      lane_set(o_m, k, m1);
+      if (HAS_PG) lane_set(o_pg, k, tg - tm);  // pseudo-gradient, global minus local
+    }
+    store_stream<V>(theta_m + i, o_tm);
+    store_stream<V>(theta_g + i, o_tg);
+    store_stream<V>(momentum + i, o_m);
+    if (HAS_PG) store_stream<V>(pg + i, o_pg);
+  }
+};
+
+template <bool HAS_SEND>
+struct PseudoGradOp {
+  static constexpr int kAcc = 0;
+  static constexpr int kVec = 4;       // elements per lane per access (128-bit fp32)
+  static constexpr int kLoads = kDepth;  // accesses per stream in flight per lane
+  const float* theta_g;
+  const float* theta_m;
+  float* pg;
+  float* send_out;
+
+  template <int V>
+  struct Regs {
+    typename Vec<V>::type tg, tm;
+  };
+  template <int V>
+  __device__ __forceinline__ Regs<V> load(uint64_t i) const {
+    Regs<V> r;
+    r.tg = load_stream<V>(theta_g + i);
+    r.tm = load_stream<V>(theta_m + i);
+    return r;
+  }
+  template <int V>
+  __device__ __forceinline__ void apply(uint64_t i, const Regs<V>& r, double*) const {
+    typename Vec<V>::type o;
+#pragma unroll
+    for (int k = 0; k < V; ++k) lane_set(o, k, lane_get(r.tg, k) - lane_get(r.tm, k));
+    store_stream<V>(pg + i, o);
+    if (HAS_SEND) store_stream<V>(send_out + i, r.tm);
+  }
+};
+
+template <bool NESTEROV>
+struct OuterOp {
+  static constexpr int kAcc = 0;
+  static constexpr int kVec = 4;       // elements per lane per access (128-bit fp32)
+  static constexpr int kLoads = kDepth;  // accesses per stream in flight per lane
+  float* theta_g;
+  float* momentum;
+  const float* delta_g;
+  DevHP hp;
+
+  template <int V>
+  struct Regs {
+    typename Vec<V>::type tg, m, dg;
+  };
+  template <int V>
+  __device__ __forceinline__ Regs<V> load(uint64_t i) const {
+    Regs<V> r;
+    r.tg = load_stream<V>(theta_g + i);
+    r.m = load_stream<V>(momentum + i);
+    r.dg = load_stream<V>(delta_g + i);
+    return r;
+  }
+  template <int V>
+  __device__ __forceinline__ void apply(uint64_t i, const Regs<V>& r, double*) const {
+    typename Vec<V>::type o_tg, o_m;
+#pragma unroll
+    for (int k = 0; k < V; ++k) {
+      float m1;
+      const float G =
+          outer_update<NESTEROV>(lane_get(r.tg, k), lane_get(r.m, k), lane_get(r.dg, k), hp, &m1);
+      lane_set(o_tg, k, G);
+      lane_set(o_m, k, m1);
+    }
+    store_stream<V>(theta_g + i, o_tg);
+    store_stream<V>(momentum + i, o_m);
+  }
+};
+
+template <int MERGE, bool HAS_SEND = true>
+struct MergeOp {
+  static constexpr int kAcc = 0;
+  static constexpr int kVec = 4;       // elements per lane per access (128-bit fp32)
+  static constexpr int kLoads = kDepth;  // accesses per stream in flight per lane
+  float* theta_m;
+  const float* theta_send;
+  const float* theta_g;
+  DevHP hp;
+
+  template <int V>
+  struct Regs {
+    typename Vec<V>::type tm, ts, tg;
+  };
+  template <int V>
+  __device__ __forceinline__ Regs<V> load(uint64_t i) const {
+    Regs<V> r;
+    r.tm = load_stream<V>(theta_m + i);
+    if (HAS_SEND) r.ts = load_stream<V>(theta_send + i);
+    r.tg = load_stream<V>(theta_g + i);
+    return r;
+  }
+  template <int V>
+  __device__ __forceinline__ void apply(uint64_t i, const Regs<V>& r, double*) const {
+    typename Vec<V>::type o;
+#pragma unroll
+    for (int k = 0; k < V; ++k) {
+      const float tm = lane_get(r.tm, k);
+      const float ts = HAS_SEND ? lane_get(r.ts, k) : tm;
+      const double d = HAS_SEND ? drift(ts, tm, hp) : 0.0;
+      lane_set(o, k, merge_local<MERGE>(lane_get(r.tg, k), ts, tm, d, hp));
+    }
+    store_stream<V>(theta_m + i, o);
+  }
+};
+
+// The fused step with bfloat16 local parameters: theta_m, theta_send and the outgoing
+// pseudo-gradient are bf16 (2 bytes), theta_g, momentum, delta_g stay fp32: 28 B/param.
+template <bool NESTEROV, int MERGE, bool HAS_PG, bool HAS_SEND = true>
+struct FusedBf16Op {
+  static constexpr int kAcc = 4;
+  static constexpr int kVec = 4;       // 128-bit fp32 accesses, 64-bit bf16 accesses (8-wide measured slower)
+  static constexpr int kLoads = kDepth;
+  unsigned short* theta_m;
+  const unsigned short* theta_send;
+  float* theta_g;
+  float* momentum;
+  const float* delta_g;
+  unsigned short* pg;
+  DevHP hp;
+
+  template <int V>
+  struct Regs {
+    typename VecU16<V>::type tm, ts;
+    typename Vec<V>::type tg, m, dg;
+  };
+
+  template <int V>
+  __device__ __forceinline__ Regs<V> load(uint64_t i) const {
+    Regs<V> r;
+    r.tm = load_stream_u16<V>(theta_m + i);
+    if (HAS_SEND) r.ts = load_stream_u16<V>(theta_send + i);
+    r.tg = load_stream<V>(theta_g + i);
+    r.m = load_stream<V>(momentum + i);
+    r.dg = load_stream<V>(delta_g + i);
+    return r;
+  }
+
+  template <int V>
+  __device__ __forceinline__ void apply(uint64_t i, const Regs<V>& r, double* a) const {
+    typename VecU16<V>::type o_tm, o_pg;
+    typename Vec<V>::type o_tg, o_m;
+#pragma unroll
+    for (int k = 0; k < V; ++k) {
+      const float tm = widen_bf16(lane_get(r.tm, k)), tg = lane_get(r.tg, k);
+      const float ts = HAS_SEND ? widen_bf16(lane_get(r.ts, k)) : tm;
+      const float m = lane_get(r.m, k), dg = lane_get(r.dg, k);
+      float m1;
+      const float G = outer_update<NESTEROV>(tg, m, dg, hp, &m1);
+      const double d = HAS_SEND ? drift(ts, tm, hp) : 0.0;
+      const double tm1 = merge_local_f64<MERGE>(G, ts, tm, d, hp, tg);
+      const double dgd = static_cast<double>(dg);
+      a[0] = fma(dgd, dgd, a[0]);
+      a[1] += fabs(dgd);
+      if (HAS_SEND) {
+        a[2] += d * d;
+        a[3] += fabs(d);
+      }
+      lane_set(o_tm, k, round_bf16(tm1));
+      lane_set(o_tg, k, G);
+      lane_set(o_m, k, m1);
+      if (HAS_PG) lane_set(o_pg, k, round_bf16(static_cast<double>(tg) - static_cast<double>(tm)));
+    }
+    store_stream_u16<V>(theta_m + i, o_tm);
+    store_stream<V>(theta_g + i, o_tg);
+    store_stream<V>(momentum + i, o_m);
+    if (HAS_PG) store_stream_u16<V>(pg + i, o_pg);
+  }
+};
+
+template <bool HAS_SEND>
+struct PseudoGradBf16Op {
+  static constexpr int kAcc = 0;
+  static constexpr int kVec = 4;
+  static constexpr int kLoads = kDepth;
+  const float* theta_g;
+  const unsigned short* theta_m;
+  unsigned short* pg;
+  unsigned short* send_out;
+
+  template <int V>
+  struct Regs {
+    typename Vec<V>::type tg;
+    typename VecU16<V>::type tm;
+  };
+  template <int V>
+  __device__ __forceinline__ Regs<V> load(uint64_t i) const {
+    Regs<V> r;
+    r.tg = load_stream<V>(theta_g + i);
+    r.tm = load_stream_u16<V>(theta_m + i);
+    return r;
+  }
+  template <int V>
+  __device__ __forceinline__ void apply(uint64_t i, const Regs<V>& r, double*) const {
+    typename VecU16<V>::type o;
+#pragma unroll
+    for (int k = 0; k < V; ++k) {
+      lane_set(o, k, round_bf16(static_cast<double>(lane_get(r.tg, k)) -
+                                static_cast<double>(widen_bf16(lane_get(r.tm, k)))));
+    }
+    store_stream_u16<V>(pg + i, o);
+    if (HAS_SEND) store_stream_u16<V>(send_out + i, r.tm);
+  }
+};
+
+// Sum of squares (NORM 2) or of magnitudes (NORM 1) of any buffer: numerator of Eq. 11.
+template <int NORM>
+struct ScoreOp {
+  static constexpr int kAcc = 1;
+  static constexpr int kVec = 4;       // elements per lane per access (128-bit fp32)
+  static constexpr int kLoads = kDepth;  // accesses per stream in flight per lane
+  const float* x;
+
+  template <int V>
+  struct Regs {
+    typename Vec<V>::type x;
+  };
+  template <int V>
+  __device__ __forceinline__ Regs<V> load(uint64_t i) const {
+    Regs<V> r;
+    r.x = load_stream<V>(x + i);
+    return r;
+  }
+  template <int V>
+  __device__ __forceinline__ void apply(uint64_t, const Regs<V>& r, double* a) const {
+#pragma unroll
+    for (int k = 0; k < V; ++k) {
+      const double v = static_cast<double>(lane_get(r.x, k));
+      if (NORM == 2) {
+        a[0] = fma(v, v, a[0]);
+      } else {
+        a[0] += fabs(v);
+      }
+    }
+  }
+};
+
+// ------------------------------------------------------------------ reductions
+// Sum over the 64 lanes of a wavefront; the result is valid in lane 0.  Fixed tree.
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
+  return v;
+}
+
+// Sum of NA values over the workgroup in a fixed order; thread 0 returns the totals in a[].
+template <int NA>
+__device__ __forceinline__ void block_sum(double* a, double (*lds)[kSums]) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+  for (int k = 0; k < NA; ++k) {
+    const double s = wave_sum(a[k]);
+    if (lane == 0) lds[wave][k] = s;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+#pragma unroll
+    for (int k = 0; k < NA; ++k) {
+      double s = lds[0][k];
+#pragma unroll
+      for (int w = 1; w < kWaves; ++w) s += lds[w][k];
+      a[k] = s;
+    }
+  }
+  __syncthreads();
+}
+
+// ------------------------------------------------------------------ kernels
+__global__ void k_write_table(TableChunk chunk, FragRec* dst, int base, int count) {
+  const int i = threadIdx.x;
+  if (i < count) dst[base + i] = chunk.rec[i];
+}
+
+// Walks the tile list with stride gridDim.x.  tbl has K+1 records; tbl[K].slot_begin == T.
+#if COCODC_WAVES_PER_EU > 0
+#define COCODC_OCCUPANCY __attribute__((amdgpu_waves_per_eu(COCODC_WAVES_PER_EU)))
+#else
+#define COCODC_OCCUPANCY
+#endif
+template <class Op, bool VEC>
+__global__ __launch_bounds__(kThreads) COCODC_OCCUPANCY void k_walk(const FragRec* __restrict__ tbl, uint64_t T,
+                                                    int tile_shift, Op op, double* __restrict__ partials) {
+  __shared__ double lds[kWaves][kSums];
+  const uint64_t tid = threadIdx.x;
+  int p = 0;
+  for (uint64_t w = blockIdx.x; w < T; w += gridDim.x) {
+    while (w >= tbl[p + 1].slot_begin) ++p;  // uniform; skips empty fragments
+    const uint64_t f_off = tbl[p].offset, f_end = f_off + tbl[p].length;
+    const uint64_t win = (tbl[p].tile0 + (w - tbl[p].slot_begin)) << tile_shift;
+    const uint64_t win_end = win + (uint64_t(1) << tile_shift);
+    const uint64_t lo = f_off > win ? f_off : win;
+    const uint64_t hi = f_end < win_end ? f_end : win_end;
+
+    double acc[Op::kAcc > 0 ? Op::kAcc : 1];
+#pragma unroll
+    for (int k = 0; k < (Op::kAcc > 0 ? Op::kAcc : 1); ++k) acc[k] = 0.0;
+
+    if (VEC) {
+      constexpr int W = Op::kVec;      // elements per vector access
+      constexpr int D = Op::kLoads;    // vector accesses per stream in flight
+      uint64_t lo4 = (lo + (W - 1)) & ~uint64_t(W - 1);
+      if (lo4 > hi) lo4 = hi;
+      uint64_t hi4 = hi & ~uint64_t(W - 1);
+      if (hi4 < lo4) hi4 = lo4;
+      if (tid < lo4 - lo) {  // unaligned head of the fragment (at most W-1 elements)
+        const auto r = op.template load<1>(lo + tid);
+        op.template apply<1>(lo + tid, r, acc);
+      }
+      const uint64_t nvec = (hi4 - lo4) / W;
+      for (uint64_t v = tid; v < nvec; v += uint64_t(kThreads) * D) {
+        typename Op::template Regs<W> r[D];
+#pragma unroll
+        for (int k = 0; k < D; ++k) {
+          const uint64_t vk = v + uint64_t(k) * kThreads;
+          if (vk < nvec) r[k] = op.template load<W>(lo4 + vk * W);
+        }
+#pragma unroll
+        for (int k = 0; k < D; ++k) {
+          const uint64_t vk = v + uint64_t(k) * kThreads;
+          if (vk < nvec) op.template apply<W>(lo4 + vk * W, r[k], acc);
+        }
+      }
+      if (tid < hi - hi4) {  // unaligned tail (at most W-1 elements)
+        const auto r = op.template load<1>(hi4 + tid);
+        op.template apply<1>(hi4 + tid, r, acc);
+      }
+    } else {
+      for (uint64_t i = lo + tid; i < hi; i += kThreads) {
+        const auto r = op.template load<1>(i);
+        op.template apply<1>(i, r, acc);
+      }
+    }
+
+    if (Op::kAcc > 0) {
+      block_sum<(Op::kAcc > 0 ? Op::kAcc : 1)>(acc, lds);
+      if (tid == 0) {
+#pragma unroll
+        for (int k = 0; k < Op::kAcc; ++k) partials[w * kSums + k] = acc[k];
+      }
+    }
+  }
+}
+
+// One workgroup per fragment: adds that fragment's tile partials (thread t takes slots
+// t, t+256, ... in ascending order, then the fixed workgroup tree) and evaluates Eq. 11.
+//   which: index (0..3) of the sum that feeds R;  l2: take the square root of it.
+__global__ __launch_bounds__(kThreads) void k_finalize(const FragRec* __restrict__ tbl,
+                                                        const double* __restrict__ partials, int n_acc,
+                                                        int which, int l2, double* __restrict__ R_out,
+                                                        double* __restrict__ sums_out, int sums_stride) {
+  __shared__ double lds[kWaves][kSums];
+  const int p = blockIdx.x;
+  const uint64_t s0 = tbl[p].slot_begin, s1 = tbl[p + 1].slot_begin;
+  double acc[kSums] = {0.0, 0.0, 0.0, 0.0};
+  for (uint64_t s = s0 + threadIdx.x; s < s1; s += kThreads) {
+#pragma unroll
+    for (int k = 0; k < kSums; ++k) {
+      if (k < n_acc) acc[k] += partials[s * kSums + k];
+    }
+  }
+  block_sum<kSums>(acc, lds);
+  if (threadIdx.x == 0) {
+    const int64_t I_p = tbl[p].I_p;
+    const double s = acc[which];
+    const double norm = l2 ? sqrt(s) : s;
+    R_out[p] = (I_p <= 0) ? __builtin_huge_val() : norm / static_cast<double>(I_p);
+    if (sums_out) {
+      for (int k = 0; k < sums_stride; ++k) sums_out[p * sums_stride + k] = acc[k];
+    }
+  }
+}
+
+// Algorithm 2 applied `n` times without replacement == the first n entries of the order
+// (class, -R, p) with class 0 = not synchronised for >= H steps, 1 = has a number as
+// score, 2 = NaN score.  Every fragment counts how many fragments precede it.
+__global__ __launch_bounds__(kThreads) void k_select(const FragRec* __restrict__ tbl, int K,
+                                                      const double* __restrict__ R, int64_t t_g,
+                                                      int64_t H, int n, int* __restrict__ sel,
+                                                      int* __restrict__ n_sel) {
+  __shared__ double sR[COCODC_MAX_FRAGMENTS];
+  __shared__ unsigned char sC[COCODC_MAX_FRAGMENTS];
+  for (int p = threadIdx.x; p < K; p += kThreads) {
+    const double r = R[p];
+    const bool overdue = (t_g - tbl[p].t_b) >= H;
+    sR[p] = r;
+    sC[p] = overdue ? 0 : (r != r ? 2 : 1);
+  }
+  __syncthreads();
+  for (int p = threadIdx.x; p < K; p += kThreads) {
+    const int cp = sC[p];
+    const double rp = sR[p];
+    int rank = 0;
+    for (int q = 0; q < K; ++q) {
+      const int cq = sC[q];
+      bool before;
+      if (cq != cp) {
+        before = cq < cp;
+      } else if (cp == 1) {
+        const double rq = sR[q];
+        before = (rq > rp) || (rq == rp && q < p);
+      } else {
+        before = q < p;
+      }
+      rank += before ? 1 : 0;
+    }
+    if (rank < n) sel[rank] = p;
+  }
+  if (threadIdx.x == 0) *n_sel = n;
+}
+
+// Same priority order, cut by a byte budget: fragments are taken in rank order while their sizes
+// (FragRec::length of the group records, in bytes) still fit; the first that does not fit ends
+// the selection.
+__global__ __launch_bounds__(kThreads) void k_select_bytes(const FragRec* __restrict__ tbl, int K,
+                                                            const double* __restrict__ R, int64_t t_g,
+                                                            int64_t H, unsigned long long byte_budget,
+                                                            int* __restrict__ sel, int* __restrict__ n_sel) {
+  __shared__ double sR[COCODC_MAX_FRAGMENTS];
+  __shared__ unsigned char sC[COCODC_MAX_FRAGMENTS];
+  __shared__ int sOrder[COCODC_MAX_FRAGMENTS];
+  for (int p = threadIdx.x; p < K; p += kThreads) {
+    const double r = R[p];
+    const bool overdue = (t_g - tbl[p].t_b) >= H;
+    sR[p] = r;
+    sC[p] = overdue ? 0 : (r != r ? 2 : 1);
+  }
+  __syncthreads();
+  for (int p = threadIdx.x; p < K; p += kThreads) {
+    const int cp = sC[p];
+    const double rp = sR[p];
+    int rank = 0;
+    for (int q = 0; q < K; ++q) {
+      const int cq = sC[q];
+      bool before;
+      if (cq != cp) {
+        before = cq < cp;
+      } else if (cp == 1) {
+        const double rq = sR[q];
+        before = (rq > rp) || (rq == rp && q < p);
+      } else {
+        before = q < p;
+      }
+      rank += before ? 1 : 0;
+    }
+    sOrder[rank] = p;  // ranks are a permutation of 0..K-1
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    unsigned long long left = byte_budget;
+    int n = 0;
+    for (int r = 0; r < K; ++r) {
+      const int p = sOrder[r];
+      const unsigned long long need = tbl[p].length;
+      if (need > left) break;
+      left -= need;
+      sel[n++] = p;
+    }
+    *n_sel = n;
+  }
+}
+
+__global__ void k_fill_inf(double* R, int K) {
+  const int p = blockIdx.x * blockDim.x + threadIdx.x;
+  if (p < K) R[p] = __builtin_huge_val();
+}
+
+}  // namespace

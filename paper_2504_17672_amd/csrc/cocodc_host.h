@@ -1,0 +1,315 @@
+// cocodc_host.h -- host side of the library: error bookkeeping, workspace layout, validation of
+// fragment / segment tables and their tile plan, launch helpers, kernel timer.
+// Included by cocodc.hip only, after cocodc_device.h.
+#pragma once
+
+namespace {
+
+// ------------------------------------------------------------------ host side
+thread_local int g_last_hip_error = 0;
+int g_blocks_per_cu = 0;
+
+int hip_fail(hipError_t e) {
+  g_last_hip_error = static_cast<int>(e);
+  return COCODC_ERR_HIP;
+}
+
+#define HIP_TRY(expr)                          \
+  do {                                         \
+    hipError_t e_ = (expr);                    \
+    if (e_ != hipSuccess) return hip_fail(e_); \
+  } while (0)
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+uint64_t max_tiles(int32_t S, uint64_t n_total) {
+  // a segment of length L overlaps at most (L >> tile_shift) + 2 windows
+  return (n_total >> tile_shift_for(n_total)) + 2 * static_cast<uint64_t>(S) + 1;
+}
+
+// Device workspace: S+1 segment records (the tile walk), K+1 group records (one per fragment:
+// its range of tile slots, I_p, t_b), then one slot of kSums doubles per tile.
+struct WorkspaceView {
+  FragRec* table;    // S + 1 segment records; table[S].slot_begin == number of tiles
+  FragRec* groups;   // K + 1 fragment records; only slot_begin, I_p, t_b are meaningful
+  double* partials;  // max_tiles * kSums
+};
+
+size_t table_bytes(int32_t S, int32_t K) {
+  return align_up(sizeof(FragRec) * (static_cast<size_t>(S) + 1 + static_cast<size_t>(K) + 1), 256);
+}
+
+size_t workspace_bytes(int32_t S, int32_t K, uint64_t n_total) {
+  return table_bytes(S, K) + align_up(max_tiles(S, n_total) * kSums * sizeof(double), 256);
+}
+
+WorkspaceView view(void* ws, int32_t S, int32_t K) {
+  char* b = static_cast<char*>(ws);
+  FragRec* t = reinterpret_cast<FragRec*>(b);
+  return WorkspaceView{t, t + S + 1, reinterpret_cast<double*>(b + table_bytes(S, K))};
+}
+
+bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+struct Span {
+  const void* p;
+  size_t bytes;
+};
+bool overlap(const Span& a, const Span& b) {
+  if (!a.p || !b.p || a.bytes == 0 || b.bytes == 0) return false;
+  const uintptr_t a0 = reinterpret_cast<uintptr_t>(a.p), b0 = reinterpret_cast<uintptr_t>(b.p);
+  return a0 < b0 + b.bytes && b0 < a0 + a.bytes;
+}
+
+// Host-side plan of one call: the records to upload and the number of tiles.
+struct Plan {
+  std::vector<FragRec> recs;  // S+1 segment records followed by K+1 group records
+  int32_t S = 0, K = 0;
+  int tile_shift = kTileShiftLarge;
+  uint64_t T = 0;
+};
+
+// Validates a segment list (every segment inside n_total, no two overlapping, fragment ids in
+// [0, K)) and lays out the tile list: the segments of fragment 0 in the order given, then those
+// of fragment 1, ...  so that each fragment owns one contiguous range of tile slots.
+int plan_segments(const cocodc_segment_t* segs, int32_t S, int32_t K, uint64_t n_total, const int64_t* I_p,
+                  const int64_t* t_b, Plan* plan) {
+  if (!segs && S > 0) return COCODC_ERR_NULL;
+  if (K < 1 || K > COCODC_MAX_FRAGMENTS || S < 0 || S > COCODC_MAX_SEGMENTS) return COCODC_ERR_RANGE;
+  if (n_total > COCODC_MAX_ELEMENTS) return COCODC_ERR_RANGE;  // keeps every byte count far from overflow
+  std::vector<std::pair<uint64_t, uint64_t>> sorted;
+  sorted.reserve(S);
+  for (int32_t i = 0; i < S; ++i) {
+    if (segs[i].fragment < 0 || segs[i].fragment >= K) return COCODC_ERR_RANGE;
+    if (segs[i].offset > n_total || segs[i].length > n_total - segs[i].offset) return COCODC_ERR_RANGE;
+    if (segs[i].length) sorted.emplace_back(segs[i].offset, segs[i].offset + segs[i].length);
+  }
+  std::sort(sorted.begin(), sorted.end());
+  for (size_t i = 1; i < sorted.size(); ++i) {
+    if (sorted[i].first < sorted[i - 1].second) return COCODC_ERR_RANGE;  // segments overlap
+  }
+  std::vector<int32_t> order(static_cast<size_t>(S));
+  for (int32_t i = 0; i < S; ++i) order[i] = i;
+  std::stable_sort(order.begin(), order.end(),
+                   [&](int32_t a, int32_t b) { return segs[a].fragment < segs[b].fragment; });
+  plan->S = S;
+  plan->K = K;
+  plan->tile_shift = tile_shift_for(n_total);
+  const int sh = plan->tile_shift;
+  plan->recs.assign(static_cast<size_t>(S) + 1 + static_cast<size_t>(K) + 1, FragRec{});
+  FragRec* seg_rec = plan->recs.data();
+  FragRec* grp_rec = plan->recs.data() + S + 1;
+  uint64_t slot = 0;
+  int32_t next_group = 0;
+  for (int32_t j = 0; j < S; ++j) {
+    const cocodc_segment_t& sg = segs[order[j]];
+    while (next_group <= sg.fragment) grp_rec[next_group++].slot_begin = slot;
+    FragRec& r = seg_rec[j];
+    r.offset = sg.offset;
+    r.length = sg.length;
+    r.slot_begin = slot;
+    r.tile0 = r.offset >> sh;
+    if (r.length) slot += ((r.offset + r.length - 1) >> sh) - r.tile0 + 1;
+  }
+  while (next_group <= K) grp_rec[next_group++].slot_begin = slot;
+  seg_rec[S].slot_begin = slot;
+  for (int32_t p = 0; p < K; ++p) {
+    grp_rec[p].I_p = I_p ? I_p[p] : 0;
+    grp_rec[p].t_b = t_b ? t_b[p] : 0;
+  }
+  plan->T = slot;
+  return COCODC_OK;
+}
+
+// Contiguous fragments: fragment p is the single segment frags[p].
+int plan_table(const cocodc_fragment_t* frags, int32_t K, uint64_t n_total, const int64_t* I_p,
+               const int64_t* t_b, Plan* plan) {
+  if (!frags) return COCODC_ERR_NULL;
+  if (K < 1 || K > COCODC_MAX_FRAGMENTS) return COCODC_ERR_RANGE;
+  std::vector<cocodc_segment_t> segs(static_cast<size_t>(K));
+  for (int32_t p = 0; p < K; ++p) segs[p] = cocodc_segment_t{frags[p].offset, frags[p].length, p, 0};
+  return plan_segments(segs.data(), K, K, n_total, I_p, t_b, plan);
+}
+
+int upload_table(const std::vector<FragRec>& recs, FragRec* dst, hipStream_t s) {
+  const int n = static_cast<int>(recs.size());
+  for (int base = 0; base < n; base += kTableChunk) {
+    TableChunk c;
+    const int count = std::min(kTableChunk, n - base);
+    std::memset(&c, 0, sizeof(c));
+    std::memcpy(c.rec, recs.data() + base, sizeof(FragRec) * count);
+    hipLaunchKernelGGL(k_write_table, dim3(1), dim3(kTableChunk), 0, s, c, dst, base, count);
+    HIP_TRY(hipGetLastError());
+  }
+  return COCODC_OK;
+}
+
+int check_workspace(void* ws, size_t bytes, int32_t S, int32_t K, uint64_t n_total) {
+  if (!ws) return COCODC_ERR_NULL;
+  if (!aligned(ws, 256)) return COCODC_ERR_ALIGN;
+  if (bytes < workspace_bytes(S, K, n_total)) return COCODC_ERR_WORKSPACE;
+  return COCODC_OK;
+}
+
+int check_hparams(const cocodc_hparams_t* hp) {
+  if (!hp) return COCODC_ERR_NULL;
+  if (hp->tau < 0 || hp->H < 1) return COCODC_ERR_RANGE;
+  if (hp->nesterov != 0 && hp->nesterov != 1) return COCODC_ERR_RANGE;
+  if (hp->drift_sign != 1 && hp->drift_sign != -1) return COCODC_ERR_RANGE;
+  if (hp->score_src != 0 && hp->score_src != 1) return COCODC_ERR_RANGE;
+  if (hp->norm_kind != 1 && hp->norm_kind != 2) return COCODC_ERR_RANGE;
+  if (hp->merge_mode < 0 || hp->merge_mode > 2) return COCODC_ERR_RANGE;
+  if (hp->delta_src != 0 && hp->delta_src != 1) return COCODC_ERR_RANGE;
+  if (!std::isfinite(hp->lambda) || !std::isfinite(hp->eta) || !std::isfinite(hp->mu) ||
+      !std::isfinite(hp->alpha))
+    return COCODC_ERR_NONFINITE;
+  return COCODC_OK;
+}
+
+// Kernel variant of the merge: 0/1/2 as merge_mode, 3 = delay compensation with tau == 0,
+// 4 = delay compensation with the accumulated-change reading of the divergence term.
+int merge_variant(const cocodc_hparams_t& hp) {
+  if (hp.merge_mode != 0) return hp.merge_mode;
+  if (hp.tau < 1) return 3;
+  return hp.delta_src == 1 ? 4 : 0;
+}
+
+DevHP to_dev(const cocodc_hparams_t& hp) {
+  DevHP d;
+  d.mu = hp.mu;
+  d.eta = hp.eta;
+  d.sign = static_cast<double>(hp.drift_sign);
+  d.tauH = hp.tau >= 1 ? static_cast<double>(hp.tau) * static_cast<double>(hp.H) : 1.0;
+  d.lambda = hp.tau >= 1 ? hp.lambda : 0.0;
+  d.coef = d.lambda / d.tauH;
+  d.alpha = hp.alpha;
+  d.one_minus_alpha = 1.0 - hp.alpha;
+  return d;
+}
+
+int device_cus() {
+  static std::mutex mu;
+  static int cached[64] = {0};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+  std::lock_guard<std::mutex> lock(mu);
+  if (cached[dev] == 0) {
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+      n = 256;
+    cached[dev] = n;
+  }
+  return cached[dev];
+}
+
+unsigned grid_for(uint64_t T) {
+  uint64_t g = T;
+  if (g_blocks_per_cu > 0) g = std::min<uint64_t>(T, static_cast<uint64_t>(device_cus()) * g_blocks_per_cu);
+  return static_cast<unsigned>(std::min<uint64_t>(g, 0x7fffffffu));
+}
+
+template <class Op>
+int launch_walk(bool vec, const FragRec* tbl, uint64_t T, int tile_shift, const Op& op, double* partials,
+                hipStream_t s) {
+  if (T == 0) return COCODC_OK;
+  const dim3 grid(grid_for(T)), block(kThreads);
+  if (vec) {
+    hipLaunchKernelGGL((k_walk<Op, true>), grid, block, 0, s, tbl, T, tile_shift, op, partials);
+  } else {
+    hipLaunchKernelGGL((k_walk<Op, false>), grid, block, 0, s, tbl, T, tile_shift, op, partials);
+  }
+  HIP_TRY(hipGetLastError());
+  return COCODC_OK;
+}
+
+bool all_aligned16(std::initializer_list<const void*> ps) {
+  for (const void* p : ps) {
+    if (p && !aligned(p, 16)) return false;
+  }
+  return true;
+}
+bool all_aligned4(std::initializer_list<const void*> ps) {
+  for (const void* p : ps) {
+    if (p && !aligned(p, 4)) return false;
+  }
+  return true;
+}
+
+// ---- kernel timer (measurement aid) ----
+struct Profiler {
+  std::mutex mu;
+  std::vector<hipEvent_t> start, stop;
+  int used = 0;
+  bool on = false;
+} g_prof;
+
+template <bool NESTEROV, int MERGE>
+int launch_fused(bool vec, const FragRec* tbl, uint64_t T, int sh, float* tm, const float* ts, float* tg,
+                 float* m, const float* dg, float* pg, const DevHP& hp, double* partials, hipStream_t s) {
+  if (MERGE == 1 || MERGE == 2) {
+    if (!ts) {  // the blend and the plain replacement never look at the send-time record
+      if (pg) {
+        FusedOp<NESTEROV, (MERGE == 1 || MERGE == 2) ? MERGE : 1, true, false> op{tm, nullptr, tg, m, dg, pg, hp};
+        return launch_walk(vec, tbl, T, sh, op, partials, s);
+      }
+      FusedOp<NESTEROV, (MERGE == 1 || MERGE == 2) ? MERGE : 1, false, false> op{tm, nullptr, tg, m, dg, nullptr, hp};
+      return launch_walk(vec, tbl, T, sh, op, partials, s);
+    }
+  }
+  if (pg) {
+    FusedOp<NESTEROV, MERGE, true> op{tm, ts, tg, m, dg, pg, hp};
+    return launch_walk(vec, tbl, T, sh, op, partials, s);
+  }
+  FusedOp<NESTEROV, MERGE, false> op{tm, ts, tg, m, dg, nullptr, hp};
+  return launch_walk(vec, tbl, T, sh, op, partials, s);
+}
+
+template <bool NESTEROV>
+int launch_fused_m(int merge, bool vec, const FragRec* tbl, uint64_t T, int sh, float* tm, const float* ts,
+                   float* tg, float* m, const float* dg, float* pg, const DevHP& hp, double* partials,
+                   hipStream_t s) {
+  switch (merge) {
+    case 0: return launch_fused<NESTEROV, 0>(vec, tbl, T, sh, tm, ts, tg, m, dg, pg, hp, partials, s);
+    case 1: return launch_fused<NESTEROV, 1>(vec, tbl, T, sh, tm, ts, tg, m, dg, pg, hp, partials, s);
+    case 2: return launch_fused<NESTEROV, 2>(vec, tbl, T, sh, tm, ts, tg, m, dg, pg, hp, partials, s);
+    case 4: return launch_fused<NESTEROV, 4>(vec, tbl, T, sh, tm, ts, tg, m, dg, pg, hp, partials, s);
+    default: return launch_fused<NESTEROV, 3>(vec, tbl, T, sh, tm, ts, tg, m, dg, pg, hp, partials, s);
+  }
+}
+
+template <bool NESTEROV, int MERGE>
+int launch_fused_bf16(bool vec, const FragRec* tbl, uint64_t T, int sh, unsigned short* tm, const unsigned short* ts,
+                      float* tg, float* m, const float* dg, unsigned short* pg, const DevHP& hp, double* partials,
+                      hipStream_t s) {
+  if (MERGE == 1 || MERGE == 2) {
+    if (!ts) {
+      if (pg) {
+        FusedBf16Op<NESTEROV, (MERGE == 1 || MERGE == 2) ? MERGE : 1, true, false> op{tm, nullptr, tg, m, dg, pg, hp};
+        return launch_walk(vec, tbl, T, sh, op, partials, s);
+      }
+      FusedBf16Op<NESTEROV, (MERGE == 1 || MERGE == 2) ? MERGE : 1, false, false> op{tm, nullptr, tg, m, dg, nullptr, hp};
+      return launch_walk(vec, tbl, T, sh, op, partials, s);
+    }
+  }
+  if (pg) {
+    FusedBf16Op<NESTEROV, MERGE, true> op{tm, ts, tg, m, dg, pg, hp};
+    return launch_walk(vec, tbl, T, sh, op, partials, s);
+  }
+  FusedBf16Op<NESTEROV, MERGE, false> op{tm, ts, tg, m, dg, nullptr, hp};
+  return launch_walk(vec, tbl, T, sh, op, partials, s);
+}
+
+template <bool NESTEROV>
+int launch_fused_bf16_m(int merge, bool vec, const FragRec* tbl, uint64_t T, int sh, unsigned short* tm,
+                        const unsigned short* ts, float* tg, float* m, const float* dg, unsigned short* pg,
+                        const DevHP& hp, double* partials, hipStream_t s) {
+  switch (merge) {
+    case 0: return launch_fused_bf16<NESTEROV, 0>(vec, tbl, T, sh, tm, ts, tg, m, dg, pg, hp, partials, s);
+    case 1: return launch_fused_bf16<NESTEROV, 1>(vec, tbl, T, sh, tm, ts, tg, m, dg, pg, hp, partials, s);
+    case 2: return launch_fused_bf16<NESTEROV, 2>(vec, tbl, T, sh, tm, ts, tg, m, dg, pg, hp, partials, s);
+    case 4: return launch_fused_bf16<NESTEROV, 4>(vec, tbl, T, sh, tm, ts, tg, m, dg, pg, hp, partials, s);
+    default: return launch_fused_bf16<NESTEROV, 3>(vec, tbl, T, sh, tm, ts, tg, m, dg, pg, hp, partials, s);
+  }
+}
+
+}  // namespace
