@@ -97,6 +97,9 @@ def main():
                     help="instead of the fused-step benchmark, drive the Sec. 3.2 loop (cocodc_loop_step) for T "
                          "inner steps with one worker and the in-place send/receive buffer, and report the "
                          "time of its receive and send events")
+    ap.add_argument("--primitives", action="store_true",
+                    help="time the five single-step entry points (and their sum against the fused step) "
+                         "instead of the headline metric; prints its own JSON line")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
                     help="instead of the benchmark, run 5 plain device copies of MIB mebibytes (a kernel "
                          "of known traffic, to scale rocprofv3 FETCH_SIZE / WRITE_SIZE readings) and exit")
@@ -159,6 +162,69 @@ def main():
     if args.blocks_per_cu is not None:
         B.cocodc_set_blocks_per_cu(args.blocks_per_cu)
     torch.cuda.synchronize()
+
+    if args.primitives:
+        assert pg is not None and mode == 0, "--primitives times the default delay-compensation path with pg"
+        fr, th = wl.frags, st
+
+        def timed(fn, launches_per_call=1):
+            for _ in range(args.warmup):
+                fn()
+            B.check(B.cocodc_profiler_enable(args.steps * launches_per_call))
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(args.steps):
+                fn()
+            torch.cuda.synchronize()
+            wall = (time.perf_counter() - t0) / args.steps * 1e3
+            cnt, ms = B.cocodc_profiler_collect(args.steps * launches_per_call)
+            B.cocodc_profiler_disable()
+            assert cnt == args.steps * launches_per_call, cnt
+            return wall, sum(ms) / args.steps
+
+        calls = [
+            ("cocodc_pseudograd", "k_walk<PseudoGradOp>", 12,
+             lambda: B.check(B.cocodc_pseudograd(fr, n, th["theta_g"], th["theta_m"], pg, None, ws))),
+            ("cocodc_pseudograd + send-time record", "k_walk<PseudoGradOp>", 16,
+             lambda: B.check(B.cocodc_pseudograd(fr, n, th["theta_g"], th["theta_m"], pg, th["theta_m_send"], ws))),
+            ("cocodc_outer_nesterov", "k_walk<OuterOp>", 20,
+             lambda: B.check(B.cocodc_outer_nesterov(fr, n, th["theta_g"], th["momentum"], th["delta_g"], hp, ws))),
+            ("cocodc_delay_compensate", "k_walk<MergeOp>", 16,
+             lambda: B.check(B.cocodc_delay_compensate(fr, n, th["theta_m"], th["theta_m_send"], th["theta_g"], hp,
+                                                       ws))),
+            ("cocodc_fragment_scores", "k_walk<ScoreOp>", 4,
+             lambda: B.check(B.cocodc_fragment_scores(fr, n, th["delta_g"], bk.I_p, 2, R, None, ws))),
+        ]
+        rows = []
+        for name, kernel, bpp, fn in calls:
+            wall, k_ms = timed(fn)
+            rows.append({"entry": name, "kernel": kernel, "bytes_per_param": bpp, "ms_per_call": round(wall, 4),
+                         "kernel_ms_avg": round(k_ms, 4), "achieved_GBps": round(bpp * n / (k_ms * 1e-3) / 1e9, 1),
+                         "frac_of_peak": round(bpp * n / (k_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)})
+            print(f"[bench] {rows[-1]}", file=sys.stderr, flush=True)
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            B.check(B.cocodc_select_fragments(K, R, bk.t_b, bk.t_g, wl.H, wl.budget, sel, n_sel, ws))
+        torch.cuda.synchronize()
+        sel_ms = (time.perf_counter() - t0) / args.steps * 1e3
+
+        def five():
+            calls[0][3](); calls[2][3](); calls[3][3](); calls[4][3]()
+            B.check(B.cocodc_select_fragments(K, R, bk.t_b, bk.t_g, wl.H, wl.budget, sel, n_sel, ws))
+        seq_wall, seq_k = timed(five, 4)
+        fused_wall, fused_k = timed(lambda: B.check(B.cocodc_sync_step(
+            fr, n, th["theta_m"], th["theta_m_send"], th["theta_g"], th["momentum"], th["delta_g"], pg, bk.I_p,
+            bk.t_b, bk.t_g, wl.budget, hp, R, sel, n_sel, None, ws)))
+        assert bool(torch.isfinite(th["theta_m"][:1 << 20]).all().item())
+        print(json.dumps({"mode": "primitives", "workload": wl.name, "params": n, "steps": args.steps,
+                          "layout": layout, "stride_GiB": round(stride / (1 << 30), 2), "entries": rows,
+                          "select_ms_per_call": round(sel_ms, 4),
+                          "five_calls_in_sequence": {"bytes_per_param": 52, "ms": round(seq_wall, 4),
+                                                     "Gparams_per_s": round(n / seq_wall / 1e6, 2)},
+                          "fused": {"bytes_per_param": 36, "ms": round(fused_wall, 4),
+                                    "Gparams_per_s": round(n / fused_wall / 1e6, 2),
+                                    "speedup_over_sequence": round(seq_wall / fused_wall, 3)}}), flush=True)
+        return
 
     if args.loop_steps:
         rc, loop = B.cocodc_loop_create(wl.frags, n, hp, 1.0, 1.0, float(wl.tau))  # T_s = tau * T_c

@@ -328,7 +328,7 @@ uint64_t cocodc_layout_stride_bytes(uint64_t n_total);
 /* ---- diagnostics and measurement aids (no paper counterpart) ---- */
 
 /* Elements per tile (the aligned window of the flat buffers that one workgroup handles) for
- * buffers of n_total elements: 16384, or 2048 when n_total < 2^24 so that small calls still
+ * buffers of n_total elements: 4096, or 2048 when n_total < 2^24 so that small calls still
  * spread over the whole chip. */
 uint64_t cocodc_tile_elements(uint64_t n_total);
 
@@ -353,11 +353,13 @@ const char* cocodc_status_string(int status);
  * one workgroup per tile.  Results never depend on it.  Returns the previous value. */
 int cocodc_set_blocks_per_cu(int blocks_per_cu);
 
-/* Kernel timer for benchmarks.  After cocodc_profiler_enable(n) every cocodc_sync_step
- * call brackets its fused elementwise kernel with a pair of HIP events on the caller's
- * stream (up to n calls).  cocodc_profiler_collect synchronises those events, writes
- * up to `capacity` per-call durations in milliseconds to ms_out (host) and returns how
- * many it wrote; cocodc_profiler_disable releases the events.  Process-wide state:
+/* Kernel timer for benchmarks.  After cocodc_profiler_enable(n) every launch of a
+ * streaming kernel (one per call of cocodc_sync_step*, cocodc_pseudograd*,
+ * cocodc_outer_nesterov, cocodc_delay_compensate, cocodc_fragment_scores*) is bracketed
+ * by a pair of HIP events on the caller's stream (up to n launches; not under graph
+ * capture).  cocodc_profiler_collect synchronises those events, writes up to `capacity`
+ * per-launch durations in milliseconds to ms_out (host), in launch order, and returns
+ * how many it wrote; cocodc_profiler_disable releases the events.  Process-wide state:
  * not for concurrent use from several threads. */
 int cocodc_profiler_enable(int32_t max_records);
 int cocodc_profiler_collect(float* ms_out, int32_t capacity);

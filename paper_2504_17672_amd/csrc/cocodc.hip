@@ -29,10 +29,10 @@
 #include "cocodc.h"
 
 #ifndef COCODC_TILE
-#define COCODC_TILE 16384
+#define COCODC_TILE 4096
 #endif
 #ifndef COCODC_DEPTH
-#define COCODC_DEPTH 2
+#define COCODC_DEPTH 4
 #endif
 #ifndef COCODC_NT_LOAD
 #define COCODC_NT_LOAD 1
@@ -82,10 +82,10 @@ int cocodc_pseudograd(const cocodc_fragment_t* frags, int32_t K, uint64_t n_tota
   const bool vec = all_aligned16({theta_g_snap, theta_m, delta_m_out, theta_m_send_out});
   if (theta_m_send_out) {
     PseudoGradOp<true> op{theta_g_snap, theta_m, delta_m_out, theta_m_send_out};
-    return launch_walk(vec, v.table, pl.T, pl.tile_shift, op, v.partials, s);
+    return launch_walk(vec, walk_of(v, pl), op, v.partials, s);
   }
   PseudoGradOp<false> op{theta_g_snap, theta_m, delta_m_out, nullptr};
-  return launch_walk(vec, v.table, pl.T, pl.tile_shift, op, v.partials, s);
+  return launch_walk(vec, walk_of(v, pl), op, v.partials, s);
 }
 
 int cocodc_outer_nesterov(const cocodc_fragment_t* frags, int32_t K, uint64_t n_total, float* theta_g,
@@ -108,10 +108,10 @@ int cocodc_outer_nesterov(const cocodc_fragment_t* frags, int32_t K, uint64_t n_
   const DevHP d = to_dev(*hp);
   if (hp->nesterov) {
     OuterOp<true> op{theta_g, momentum, delta_g, d};
-    return launch_walk(vec, v.table, pl.T, pl.tile_shift, op, v.partials, s);
+    return launch_walk(vec, walk_of(v, pl), op, v.partials, s);
   }
   OuterOp<false> op{theta_g, momentum, delta_g, d};
-  return launch_walk(vec, v.table, pl.T, pl.tile_shift, op, v.partials, s);
+  return launch_walk(vec, walk_of(v, pl), op, v.partials, s);
 }
 
 int cocodc_delay_compensate(const cocodc_fragment_t* frags, int32_t K, uint64_t n_total, float* theta_m,
@@ -137,19 +137,19 @@ int cocodc_delay_compensate(const cocodc_fragment_t* frags, int32_t K, uint64_t 
   switch (merge_variant(*hp)) {
     case 0: {
       MergeOp<0> op{theta_m, theta_m_send, theta_g, d};
-      return launch_walk(vec, v.table, pl.T, pl.tile_shift, op, v.partials, s);
+      return launch_walk(vec, walk_of(v, pl), op, v.partials, s);
     }
     case 1: {
       MergeOp<1, false> op{theta_m, nullptr, theta_g, d};
-      return launch_walk(vec, v.table, pl.T, pl.tile_shift, op, v.partials, s);
+      return launch_walk(vec, walk_of(v, pl), op, v.partials, s);
     }
     case 2: {
       MergeOp<2, false> op{theta_m, nullptr, theta_g, d};
-      return launch_walk(vec, v.table, pl.T, pl.tile_shift, op, v.partials, s);
+      return launch_walk(vec, walk_of(v, pl), op, v.partials, s);
     }
     default: {
       MergeOp<3> op{theta_m, theta_m_send, theta_g, d};
-      return launch_walk(vec, v.table, pl.T, pl.tile_shift, op, v.partials, s);
+      return launch_walk(vec, walk_of(v, pl), op, v.partials, s);
     }
   }
 }
@@ -170,13 +170,13 @@ static int fragment_scores_impl(Plan& pl, int32_t K, uint64_t n_total, const flo
   int rc;
   if (norm_kind == 2) {
     ScoreOp<2> op{x};
-    rc = launch_walk(vec, v.table, pl.T, pl.tile_shift, op, v.partials, s);
+    rc = launch_walk(vec, walk_of(v, pl), op, v.partials, s);
   } else {
     ScoreOp<1> op{x};
-    rc = launch_walk(vec, v.table, pl.T, pl.tile_shift, op, v.partials, s);
+    rc = launch_walk(vec, walk_of(v, pl), op, v.partials, s);
   }
   if (rc) return rc;
-  hipLaunchKernelGGL(k_finalize, dim3(K), dim3(kThreads), 0, s, v.groups, v.partials, 1, 0,
+  hipLaunchKernelGGL(k_finalize, dim3(K), dim3(kFinalizeThreads), 0, s, v.groups, v.partials, 1, 0,
                      norm_kind == 2 ? 1 : 0, R_out, sum_out, 1);
   HIP_TRY(hipGetLastError());
   return COCODC_OK;
@@ -253,21 +253,14 @@ static int sync_step_impl(Plan& pl, int32_t K, uint64_t n_total, float* theta_m,
   const bool vec = all_aligned16({theta_m, theta_m_send, theta_g, momentum, delta_g, delta_m_out});
   const DevHP d = to_dev(*hp);
 
-  int slot = -1;
-  {
-    std::lock_guard<std::mutex> lock(g_prof.mu);
-    if (g_prof.on && g_prof.used < static_cast<int>(g_prof.start.size())) slot = g_prof.used++;
-  }
-  if (slot >= 0) HIP_TRY(hipEventRecord(g_prof.start[slot], s));
-  int rc = hp->nesterov ? launch_fused_m<true>(merge_variant(*hp), vec, v.table, pl.T, pl.tile_shift, theta_m, theta_m_send, theta_g,
+  int rc = hp->nesterov ? launch_fused_m<true>(merge_variant(*hp), vec, walk_of(v, pl), theta_m, theta_m_send, theta_g,
                                                momentum, delta_g, delta_m_out, d, v.partials, s)
-                        : launch_fused_m<false>(merge_variant(*hp), vec, v.table, pl.T, pl.tile_shift, theta_m, theta_m_send,
+                        : launch_fused_m<false>(merge_variant(*hp), vec, walk_of(v, pl), theta_m, theta_m_send,
                                                 theta_g, momentum, delta_g, delta_m_out, d, v.partials, s);
-  if (slot >= 0) HIP_TRY(hipEventRecord(g_prof.stop[slot], s));
   if (rc) return rc;
 
   const int which = (hp->score_src ? 2 : 0) + (hp->norm_kind == 2 ? 0 : 1);
-  hipLaunchKernelGGL(k_finalize, dim3(K), dim3(kThreads), 0, s, v.groups, v.partials, kSums, which,
+  hipLaunchKernelGGL(k_finalize, dim3(K), dim3(kFinalizeThreads), 0, s, v.groups, v.partials, kSums, which,
                      hp->norm_kind == 2 ? 1 : 0, R_out, sums_out, kSums);
   HIP_TRY(hipGetLastError());
   hipLaunchKernelGGL(k_select, dim3(1), dim3(kThreads), 0, s, v.groups, K, R_out, t_g,
@@ -341,10 +334,10 @@ int cocodc_pseudograd_bf16(const cocodc_fragment_t* frags, int32_t K, uint64_t n
   const bool vec = all_aligned16({theta_g_snap, theta_m, delta_m_out, theta_m_send_out});
   if (theta_m_send_out) {
     PseudoGradBf16Op<true> op{theta_g_snap, theta_m, delta_m_out, theta_m_send_out};
-    return launch_walk(vec, v.table, pl.T, pl.tile_shift, op, v.partials, s);
+    return launch_walk(vec, walk_of(v, pl), op, v.partials, s);
   }
   PseudoGradBf16Op<false> op{theta_g_snap, theta_m, delta_m_out, nullptr};
-  return launch_walk(vec, v.table, pl.T, pl.tile_shift, op, v.partials, s);
+  return launch_walk(vec, walk_of(v, pl), op, v.partials, s);
 }
 
 int cocodc_sync_step_bf16(const cocodc_fragment_t* frags, int32_t K, uint64_t n_total, uint16_t* theta_m,
@@ -380,20 +373,13 @@ int cocodc_sync_step_bf16(const cocodc_fragment_t* frags, int32_t K, uint64_t n_
   if (int rc = upload_table(pl.recs, v.table, s)) return rc;
   const bool vec = all_aligned16({theta_m, theta_m_send, theta_g, momentum, delta_g, delta_m_out});
   const DevHP d = to_dev(*hp);
-  int slot = -1;
-  {
-    std::lock_guard<std::mutex> lock(g_prof.mu);
-    if (g_prof.on && g_prof.used < static_cast<int>(g_prof.start.size())) slot = g_prof.used++;
-  }
-  if (slot >= 0) HIP_TRY(hipEventRecord(g_prof.start[slot], s));
-  int rc = hp->nesterov ? launch_fused_bf16_m<true>(merge_variant(*hp), vec, v.table, pl.T, pl.tile_shift, theta_m, theta_m_send,
+  int rc = hp->nesterov ? launch_fused_bf16_m<true>(merge_variant(*hp), vec, walk_of(v, pl), theta_m, theta_m_send,
                                                     theta_g, momentum, delta_g, delta_m_out, d, v.partials, s)
-                        : launch_fused_bf16_m<false>(merge_variant(*hp), vec, v.table, pl.T, pl.tile_shift, theta_m, theta_m_send,
+                        : launch_fused_bf16_m<false>(merge_variant(*hp), vec, walk_of(v, pl), theta_m, theta_m_send,
                                                      theta_g, momentum, delta_g, delta_m_out, d, v.partials, s);
-  if (slot >= 0) HIP_TRY(hipEventRecord(g_prof.stop[slot], s));
   if (rc) return rc;
   const int which = (hp->score_src ? 2 : 0) + (hp->norm_kind == 2 ? 0 : 1);
-  hipLaunchKernelGGL(k_finalize, dim3(K), dim3(kThreads), 0, s, v.groups, v.partials, kSums, which,
+  hipLaunchKernelGGL(k_finalize, dim3(K), dim3(kFinalizeThreads), 0, s, v.groups, v.partials, kSums, which,
                      hp->norm_kind == 2 ? 1 : 0, R_out, sums_out, kSums);
   HIP_TRY(hipGetLastError());
   hipLaunchKernelGGL(k_select, dim3(1), dim3(kThreads), 0, s, v.groups, K, R_out, t_g,

@@ -7,13 +7,16 @@ namespace {
 
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / 64;
-// Tile size: 2^14 elements for large buffers; 2^11 for small ones (below 2^24 elements), so
-// that even a 1M-element call spreads over more workgroups than there are compute units.  It
-// depends on n_total alone, so the workspace size and the summation order are functions of
-// the arguments and not of the machine.
-constexpr int kTileShiftLarge = 14, kTileShiftSmall = 11;
+// Tile size: 2^12 elements for large buffers -- kThreads lanes x one 128-bit access x kDepth, so
+// a workgroup loads its whole tile, computes, stores and ends (measured faster than workgroups
+// that loop over a larger tile) -- and 2^11 for small ones (below 2^24 elements), so that even a
+// 1M-element call spreads over more workgroups than there are compute units.  It depends on
+// n_total alone, so the workspace size and the summation order are functions of the
+// arguments and not of the machine.
+constexpr int ilog2(unsigned v) { return v <= 1 ? 0 : 1 + ilog2(v >> 1); }
+constexpr int kTileShiftLarge = ilog2(COCODC_TILE), kTileShiftSmall = kTileShiftLarge < 11 ? kTileShiftLarge : 11;
 constexpr uint64_t kSmallBufferElements = 1ull << 24;
-static_assert((1u << kTileShiftLarge) == COCODC_TILE, "COCODC_TILE must match the large tile");
+static_assert((1u << kTileShiftLarge) == COCODC_TILE && kTileShiftLarge >= 10, "COCODC_TILE: a power of two >= 1024");
 inline int tile_shift_for(uint64_t n_total) {
   return n_total < kSmallBufferElements ? kTileShiftSmall : kTileShiftLarge;
 }
@@ -21,7 +24,7 @@ constexpr int kDepth = COCODC_DEPTH;  // independent 128-bit loads per stream ke
 constexpr int kTableChunk = 64;       // fragment records carried by one table-upload launch
 constexpr int kSums = 4;              // doubles per partial-sum slot
 
-static_assert((1u << kTileShiftSmall) % (4 * kThreads) == 0, "a tile must be a whole number of workgroup-wide vector rows");
+static_assert((1u << kTileShiftSmall) % (4 * kThreads) == 0 && kTileShiftSmall >= 10, "a tile must be a whole number of workgroup-wide vector rows");
 
 // Device-side description of one fragment.
 struct FragRec {
@@ -33,6 +36,15 @@ struct FragRec {
   int64_t t_b;          // step of its last completed sync (Algorithm 2)
 };
 static_assert(sizeof(FragRec) == 48, "FragRec layout");
+
+// What a streaming kernel walks: the segment records, their number S, the number of tiles T
+// (== tbl[S].slot_begin) and the tile size.
+struct Walk {
+  const FragRec* tbl;
+  uint64_t T;
+  int32_t S;
+  int32_t tile_shift;
+};
 
 struct TableChunk {
   FragRec rec[kTableChunk];
@@ -505,8 +517,9 @@ __device__ __forceinline__ double wave_sum(double v) {
   return v;
 }
 
-// Sum of NA values over the workgroup in a fixed order; thread 0 returns the totals in a[].
-template <int NA>
+// Sum of NA values over a workgroup of NW wavefronts in a fixed order; thread 0 returns the
+// totals in a[].
+template <int NA, int NW = kWaves>
 __device__ __forceinline__ void block_sum(double* a, double (*lds)[kSums]) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 #pragma unroll
@@ -520,7 +533,7 @@ __device__ __forceinline__ void block_sum(double* a, double (*lds)[kSums]) {
     for (int k = 0; k < NA; ++k) {
       double s = lds[0][k];
 #pragma unroll
-      for (int w = 1; w < kWaves; ++w) s += lds[w][k];
+      for (int w = 1; w < NW; ++w) s += lds[w][k];
       a[k] = s;
     }
   }
@@ -540,13 +553,25 @@ __global__ void k_write_table(TableChunk chunk, FragRec* dst, int base, int coun
 #define COCODC_OCCUPANCY
 #endif
 template <class Op, bool VEC>
-__global__ __launch_bounds__(kThreads) COCODC_OCCUPANCY void k_walk(const FragRec* __restrict__ tbl, uint64_t T,
-                                                    int tile_shift, Op op, double* __restrict__ partials) {
+__global__ __launch_bounds__(kThreads) COCODC_OCCUPANCY void k_walk(Walk wk, Op op, double* __restrict__ partials) {
   __shared__ double lds[kWaves][kSums];
+  const FragRec* __restrict__ tbl = wk.tbl;
+  const uint64_t T = wk.T;
+  const int tile_shift = wk.tile_shift;
   const uint64_t tid = threadIdx.x;
+  // The segment of the first tile: the last record whose slot_begin is <= the tile index (records
+  // of empty segments share their successor's slot_begin, so they are never the last).  A
+  // workgroup lives for one tile of a few microseconds, so this is a bisection, not a scan.
   int p = 0;
+  if (blockIdx.x < T) {
+    int hi = wk.S;
+    while (hi - p > 1) {
+      const int mid = (p + hi) >> 1;
+      if (tbl[mid].slot_begin <= blockIdx.x) p = mid; else hi = mid;
+    }
+  }
   for (uint64_t w = blockIdx.x; w < T; w += gridDim.x) {
-    while (w >= tbl[p + 1].slot_begin) ++p;  // uniform; skips empty fragments
+    while (w >= tbl[p + 1].slot_begin) ++p;  // uniform; later tiles of a persistent grid
     const uint64_t f_off = tbl[p].offset, f_end = f_off + tbl[p].length;
     const uint64_t win = (tbl[p].tile0 + (w - tbl[p].slot_begin)) << tile_shift;
     const uint64_t win_end = win + (uint64_t(1) << tile_shift);
@@ -603,24 +628,45 @@ __global__ __launch_bounds__(kThreads) COCODC_OCCUPANCY void k_walk(const FragRe
   }
 }
 
-// One workgroup per fragment: adds that fragment's tile partials (thread t takes slots
-// t, t+256, ... in ascending order, then the fixed workgroup tree) and evaluates Eq. 11.
+// One workgroup of kFinalizeThreads per fragment: adds that fragment's tile partials (thread t
+// takes slots t, t+kFinalizeThreads, ... in ascending order, four slots in flight, then the
+// fixed workgroup tree) and evaluates Eq. 11.
 //   which: index (0..3) of the sum that feeds R;  l2: take the square root of it.
-__global__ __launch_bounds__(kThreads) void k_finalize(const FragRec* __restrict__ tbl,
-                                                        const double* __restrict__ partials, int n_acc,
-                                                        int which, int l2, double* __restrict__ R_out,
-                                                        double* __restrict__ sums_out, int sums_stride) {
-  __shared__ double lds[kWaves][kSums];
+constexpr int kFinalizeThreads = 1024;
+__global__ __launch_bounds__(kFinalizeThreads) void k_finalize(const FragRec* __restrict__ tbl,
+                                                                const double* __restrict__ partials, int n_acc,
+                                                                int which, int l2, double* __restrict__ R_out,
+                                                                double* __restrict__ sums_out, int sums_stride) {
+  typedef double f64x2 __attribute__((ext_vector_type(2)));
+  static_assert(kSums == 4, "a slot is read as two 16-byte halves");
+  constexpr int U = 4;
+  __shared__ double lds[kFinalizeThreads / 64][kSums];
   const int p = blockIdx.x;
   const uint64_t s0 = tbl[p].slot_begin, s1 = tbl[p + 1].slot_begin;
+  const f64x2* __restrict__ slots = reinterpret_cast<const f64x2*>(partials);
   double acc[kSums] = {0.0, 0.0, 0.0, 0.0};
-  for (uint64_t s = s0 + threadIdx.x; s < s1; s += kThreads) {
+  for (uint64_t s = s0 + threadIdx.x; s < s1; s += uint64_t(kFinalizeThreads) * U) {
+    f64x2 a[U], b[U];
 #pragma unroll
-    for (int k = 0; k < kSums; ++k) {
-      if (k < n_acc) acc[k] += partials[s * kSums + k];
+    for (int u = 0; u < U; ++u) {
+      const uint64_t su = s + uint64_t(u) * kFinalizeThreads;
+      a[u] = b[u] = f64x2{0.0, 0.0};
+      if (su < s1) {
+        a[u] = slots[su * 2];
+        if (n_acc > 2) b[u] = slots[su * 2 + 1];
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      if (s + uint64_t(u) * kFinalizeThreads < s1) {
+        acc[0] += a[u].x;
+        if (n_acc > 1) acc[1] += a[u].y;
+        if (n_acc > 2) acc[2] += b[u].x;
+        if (n_acc > 3) acc[3] += b[u].y;
+      }
     }
   }
-  block_sum<kSums>(acc, lds);
+  block_sum<kSums, kFinalizeThreads / 64>(acc, lds);
   if (threadIdx.x == 0) {
     const int64_t I_p = tbl[p].I_p;
     const double s = acc[which];

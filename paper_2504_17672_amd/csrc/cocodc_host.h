@@ -69,6 +69,8 @@ struct Plan {
   uint64_t T = 0;
 };
 
+Walk walk_of(const WorkspaceView& v, const Plan& pl) { return Walk{v.table, pl.T, pl.S, pl.tile_shift}; }
+
 // Validates a segment list (every segment inside n_total, no two overlapping, fragment ids in
 // [0, K)) and lays out the tile list: the segments of fragment 0 in the order given, then those
 // of fragment 1, ...  so that each fragment owns one contiguous range of tile slots.
@@ -208,17 +210,33 @@ unsigned grid_for(uint64_t T) {
   return static_cast<unsigned>(std::min<uint64_t>(g, 0x7fffffffu));
 }
 
+// ---- kernel timer (measurement aid) ----
+struct Profiler {
+  std::mutex mu;
+  std::vector<hipEvent_t> start, stop;
+  int used = 0;
+  bool on = false;
+} g_prof;
+
+// Every streaming kernel is launched here; while the timer is on, each launch is bracketed by a
+// pair of events on the launch stream.
 template <class Op>
-int launch_walk(bool vec, const FragRec* tbl, uint64_t T, int tile_shift, const Op& op, double* partials,
-                hipStream_t s) {
-  if (T == 0) return COCODC_OK;
-  const dim3 grid(grid_for(T)), block(kThreads);
+int launch_walk(bool vec, const Walk& wk, const Op& op, double* partials, hipStream_t s) {
+  if (wk.T == 0) return COCODC_OK;
+  int slot = -1;
+  {
+    std::lock_guard<std::mutex> lock(g_prof.mu);
+    if (g_prof.on && g_prof.used < static_cast<int>(g_prof.start.size())) slot = g_prof.used++;
+  }
+  if (slot >= 0) HIP_TRY(hipEventRecord(g_prof.start[slot], s));
+  const dim3 grid(grid_for(wk.T)), block(kThreads);
   if (vec) {
-    hipLaunchKernelGGL((k_walk<Op, true>), grid, block, 0, s, tbl, T, tile_shift, op, partials);
+    hipLaunchKernelGGL((k_walk<Op, true>), grid, block, 0, s, wk, op, partials);
   } else {
-    hipLaunchKernelGGL((k_walk<Op, false>), grid, block, 0, s, tbl, T, tile_shift, op, partials);
+    hipLaunchKernelGGL((k_walk<Op, false>), grid, block, 0, s, wk, op, partials);
   }
   HIP_TRY(hipGetLastError());
+  if (slot >= 0) HIP_TRY(hipEventRecord(g_prof.stop[slot], s));
   return COCODC_OK;
 }
 
@@ -235,80 +253,72 @@ bool all_aligned4(std::initializer_list<const void*> ps) {
   return true;
 }
 
-// ---- kernel timer (measurement aid) ----
-struct Profiler {
-  std::mutex mu;
-  std::vector<hipEvent_t> start, stop;
-  int used = 0;
-  bool on = false;
-} g_prof;
-
 template <bool NESTEROV, int MERGE>
-int launch_fused(bool vec, const FragRec* tbl, uint64_t T, int sh, float* tm, const float* ts, float* tg,
+int launch_fused(bool vec, const Walk& wk, float* tm, const float* ts, float* tg,
                  float* m, const float* dg, float* pg, const DevHP& hp, double* partials, hipStream_t s) {
   if (MERGE == 1 || MERGE == 2) {
     if (!ts) {  // the blend and the plain replacement never look at the send-time record
       if (pg) {
         FusedOp<NESTEROV, (MERGE == 1 || MERGE == 2) ? MERGE : 1, true, false> op{tm, nullptr, tg, m, dg, pg, hp};
-        return launch_walk(vec, tbl, T, sh, op, partials, s);
+        return launch_walk(vec, wk, op, partials, s);
       }
       FusedOp<NESTEROV, (MERGE == 1 || MERGE == 2) ? MERGE : 1, false, false> op{tm, nullptr, tg, m, dg, nullptr, hp};
-      return launch_walk(vec, tbl, T, sh, op, partials, s);
+      return launch_walk(vec, wk, op, partials, s);
     }
   }
   if (pg) {
     FusedOp<NESTEROV, MERGE, true> op{tm, ts, tg, m, dg, pg, hp};
-    return launch_walk(vec, tbl, T, sh, op, partials, s);
+    return launch_walk(vec, wk, op, partials, s);
   }
   FusedOp<NESTEROV, MERGE, false> op{tm, ts, tg, m, dg, nullptr, hp};
-  return launch_walk(vec, tbl, T, sh, op, partials, s);
+  return launch_walk(vec, wk, op, partials, s);
 }
 
 template <bool NESTEROV>
-int launch_fused_m(int merge, bool vec, const FragRec* tbl, uint64_t T, int sh, float* tm, const float* ts,
+int launch_fused_m(int merge, bool vec, const Walk& wk, float* tm, const float* ts,
                    float* tg, float* m, const float* dg, float* pg, const DevHP& hp, double* partials,
                    hipStream_t s) {
   switch (merge) {
-    case 0: return launch_fused<NESTEROV, 0>(vec, tbl, T, sh, tm, ts, tg, m, dg, pg, hp, partials, s);
-    case 1: return launch_fused<NESTEROV, 1>(vec, tbl, T, sh, tm, ts, tg, m, dg, pg, hp, partials, s);
-    case 2: return launch_fused<NESTEROV, 2>(vec, tbl, T, sh, tm, ts, tg, m, dg, pg, hp, partials, s);
-    case 4: return launch_fused<NESTEROV, 4>(vec, tbl, T, sh, tm, ts, tg, m, dg, pg, hp, partials, s);
-    default: return launch_fused<NESTEROV, 3>(vec, tbl, T, sh, tm, ts, tg, m, dg, pg, hp, partials, s);
+    case 0: return launch_fused<NESTEROV, 0>(vec, wk, tm, ts, tg, m, dg, pg, hp, partials, s);
+    case 1: return launch_fused<NESTEROV, 1>(vec, wk, tm, ts, tg, m, dg, pg, hp, partials, s);
+    case 2: return launch_fused<NESTEROV, 2>(vec, wk, tm, ts, tg, m, dg, pg, hp, partials, s);
+    case 4: return launch_fused<NESTEROV, 4>(vec, wk, tm, ts, tg, m, dg, pg, hp, partials, s);
+    default: return launch_fused<NESTEROV, 3>(vec, wk, tm, ts, tg, m, dg, pg, hp, partials, s);
   }
 }
 
 template <bool NESTEROV, int MERGE>
-int launch_fused_bf16(bool vec, const FragRec* tbl, uint64_t T, int sh, unsigned short* tm, const unsigned short* ts,
+int launch_fused_bf16(bool vec, const Walk& wk, unsigned short* tm, const unsigned short* ts,
                       float* tg, float* m, const float* dg, unsigned short* pg, const DevHP& hp, double* partials,
                       hipStream_t s) {
   if (MERGE == 1 || MERGE == 2) {
     if (!ts) {
       if (pg) {
         FusedBf16Op<NESTEROV, (MERGE == 1 || MERGE == 2) ? MERGE : 1, true, false> op{tm, nullptr, tg, m, dg, pg, hp};
-        return launch_walk(vec, tbl, T, sh, op, partials, s);
+        return launch_walk(vec, wk, op, partials, s);
       }
       FusedBf16Op<NESTEROV, (MERGE == 1 || MERGE == 2) ? MERGE : 1, false, false> op{tm, nullptr, tg, m, dg, nullptr, hp};
-      return launch_walk(vec, tbl, T, sh, op, partials, s);
+      return launch_walk(vec, wk, op, partials, s);
     }
   }
   if (pg) {
     FusedBf16Op<NESTEROV, MERGE, true> op{tm, ts, tg, m, dg, pg, hp};
-    return launch_walk(vec, tbl, T, sh, op, partials, s);
+    return launch_walk(vec, wk, op, partials, s);
   }
   FusedBf16Op<NESTEROV, MERGE, false> op{tm, ts, tg, m, dg, nullptr, hp};
-  return launch_walk(vec, tbl, T, sh, op, partials, s);
+  return launch_walk(vec, wk, op, partials, s);
 }
 
 template <bool NESTEROV>
-int launch_fused_bf16_m(int merge, bool vec, const FragRec* tbl, uint64_t T, int sh, unsigned short* tm,
+int launch_fused_bf16_m(int merge, bool vec, const Walk& wk, unsigned short* tm,
                         const unsigned short* ts, float* tg, float* m, const float* dg, unsigned short* pg,
                         const DevHP& hp, double* partials, hipStream_t s) {
   switch (merge) {
-    case 0: return launch_fused_bf16<NESTEROV, 0>(vec, tbl, T, sh, tm, ts, tg, m, dg, pg, hp, partials, s);
-    case 1: return launch_fused_bf16<NESTEROV, 1>(vec, tbl, T, sh, tm, ts, tg, m, dg, pg, hp, partials, s);
-    case 2: return launch_fused_bf16<NESTEROV, 2>(vec, tbl, T, sh, tm, ts, tg, m, dg, pg, hp, partials, s);
-    case 4: return launch_fused_bf16<NESTEROV, 4>(vec, tbl, T, sh, tm, ts, tg, m, dg, pg, hp, partials, s);
-    default: return launch_fused_bf16<NESTEROV, 3>(vec, tbl, T, sh, tm, ts, tg, m, dg, pg, hp, partials, s);
+    case 0: return launch_fused_bf16<NESTEROV, 0>(vec, wk, tm, ts, tg, m, dg, pg, hp, partials, s);
+    case 1: return launch_fused_bf16<NESTEROV, 1>(vec, wk, tm, ts, tg, m, dg, pg, hp, partials, s);
+    case 2: return launch_fused_bf16<NESTEROV, 2>(vec, wk, tm, ts, tg, m, dg, pg, hp, partials, s);
+    case 4: return launch_fused_bf16<NESTEROV, 4>(vec, wk, tm, ts, tg, m, dg, pg, hp, partials, s);
+    default: return launch_fused_bf16<NESTEROV, 3>(vec, wk, tm, ts, tg, m, dg, pg, hp, partials, s);
   }
 }
 

@@ -130,11 +130,11 @@ def test_edge_tables(B, ref, table):
 
 @pytest.mark.parametrize("view_off", [0, 1])
 def test_odd_tables_in_a_large_buffer(B, ref, view_off):
-    """Buffers of 2^24 elements or more are walked in 16384-element tiles (smaller ones in
+    """Buffers of 2^24 elements or more are walked in 4096-element tiles (smaller ones in
     2048-element tiles): unaligned fragments across those boundaries, both kernel variants."""
     n_total = (1 << 24) + 70001
     frags = [(5, 100000), (16384 * 7 - 1, 2), (16384 * 9 + 1, 16383), (16384 * 11, 16384), (16384 * 20 + 3, 3 * 16384 + 1),
-             ((1 << 24) + 1, 70000)]
+             (4096 * 93 - 1, 2), (4096 * 95 + 1, 4095), ((1 << 24) + 1, 70000)]
     base = synth.Workload("large-odd", (n_total,), tau=5, H=100)
     st = synth.make_state(base, "cuda", seed=4, pad=9)
     bk = synth.Bookkeeping(t_g=1000, t_b=[1000 - 7 * (1 + p % 3) for p in range(len(frags))],
@@ -143,7 +143,7 @@ def test_odd_tables_in_a_large_buffer(B, ref, view_off):
     s = {k: v[view_off:] for k, v in st.items()}
     fr = [(o - view_off, l) for o, l in frags]
     n_alloc = s["theta_m"].numel()
-    assert B.cocodc_tile_elements(n_alloc) == 16384
+    assert B.cocodc_tile_elements(n_alloc) == 4096
     host = U.host_copy(s)
     ws = B.new_workspace(len(fr), n_alloc)
     go = U.run_gpu_fused(B, fr, n_alloc, s, bk, 2, ghp, ws)

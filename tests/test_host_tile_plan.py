@@ -53,12 +53,12 @@ def check_plan(B, segs, K, n_total):
 @given(st.integers(0, 2 ** 32), st.integers(1, 400_000), st.integers(1, 40), st.integers(1, 9), st.booleans())
 def test_random_segment_tables(B, seed, n_used, S, K, large):
     rng = random.Random(seed)
-    n_total = n_used + ((1 << 24) if large else 0)  # large: the 16384-element tile applies
+    n_total = n_used + ((1 << 24) if large else 0)  # large: the 4096-element tile applies
     check_plan(B, random_table(rng, n_used, S, K), K, n_total)
 
 
 def test_boundary_tables(B):
-    assert B.cocodc_tile_elements(1 << 20) == 2048 and B.cocodc_tile_elements(1 << 24) == 16384
+    assert B.cocodc_tile_elements(1 << 20) == 2048 and B.cocodc_tile_elements(1 << 24) == 4096
     for n_big in (0, 1 << 24):  # both tile sizes
         tile = B.cocodc_tile_elements(3 * 16384 + n_big)
         check_plan(B, [(0, tile, 0)], 1, 3 * 16384 + n_big)
