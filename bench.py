@@ -26,7 +26,7 @@ BYTES_PER_PARAM = 36   # 5 fp32 reads + 4 fp32 writes (theta_m, theta_g, momentu
 # command, each scaled by what the same counter reads for a plain 4 GiB device copy (FETCH_SIZE
 # reads half the true bytes on this GPU, WRITE_SIZE reads them exactly).  The runs and their
 # commands are recorded in profiles/fused_sync_step_<workload>.txt.  None where no run exists.
-MEASURED_TRAFFIC_BYTES = {'7B': 237876453252, '1.3B': 46757912976}
+MEASURED_TRAFFIC_BYTES = {'7B': 237917636268, '1.3B': 46765973035}
 
 
 def cpu_baseline(wl, st, bk, sample_frag, repeats=2):

@@ -31,6 +31,9 @@
 #ifndef COCODC_TILE
 #define COCODC_TILE 4096
 #endif
+#ifndef COCODC_THREADS
+#define COCODC_THREADS 256
+#endif
 #ifndef COCODC_DEPTH
 #define COCODC_DEPTH 4
 #endif

@@ -5,7 +5,7 @@
 
 namespace {
 
-constexpr int kThreads = 256;
+constexpr int kThreads = COCODC_THREADS;
 constexpr int kWaves = kThreads / 64;
 // Tile size: 2^12 elements for large buffers -- kThreads lanes x one 128-bit access x kDepth, so
 // a workgroup loads its whole tile, computes, stores and ends (measured faster than workgroups
@@ -21,7 +21,7 @@ inline int tile_shift_for(uint64_t n_total) {
   return n_total < kSmallBufferElements ? kTileShiftSmall : kTileShiftLarge;
 }
 constexpr int kDepth = COCODC_DEPTH;  // independent 128-bit loads per stream kept in flight per lane
-constexpr int kTableChunk = 64;       // fragment records carried by one table-upload launch
+constexpr int kTableChunk = 80;       // fragment records carried by one table-upload launch
 constexpr int kSums = 4;              // doubles per partial-sum slot
 
 static_assert((1u << kTileShiftSmall) % (4 * kThreads) == 0 && kTileShiftSmall >= 10, "a tile must be a whole number of workgroup-wide vector rows");
