@@ -207,7 +207,8 @@ int device_cus() {
 unsigned grid_for(uint64_t T) {
   uint64_t g = T;
   if (g_blocks_per_cu > 0) g = std::min<uint64_t>(T, static_cast<uint64_t>(device_cus()) * g_blocks_per_cu);
-  return static_cast<unsigned>(std::min<uint64_t>(g, 0x7fffffffu));
+  // a launch may not exceed 2^32 - 1 threads per dimension; the kernels stride over what is left
+  return static_cast<unsigned>(std::min<uint64_t>(g, 0xffffffffu / kThreads));
 }
 
 // ---- kernel timer (measurement aid) ----

@@ -82,6 +82,31 @@ def test_adversarial_segment_tables(B, ref, view_off):
     _case(B, ref, segs, 5, n, [7, 14, 21, 7, 0], [990, 980, 970, 100, 990], 1000, 3, view_off=view_off)
 
 
+@pytest.mark.parametrize("n_total_pad", [0, 1 << 24])
+def test_maximum_number_of_segments(B, ref, n_total_pad):
+    """4096 segments (the most a table may hold) in shuffled order over 300 fragments, every fifth one
+    empty, lengths from 1 element to several tiles: every workgroup has to find its segment among
+    thousands of records, runs of records without tiles included.  With both tile sizes."""
+    import random
+    rng = random.Random(11)
+    S, K = 4096, 300
+    segs, off = [], 3
+    for j in range(S):
+        if j % 5 == 4:
+            ln = 0
+        else:
+            ln = rng.choice([1, 2, 3, 5, 64, 700, 2047, 2048, 2049, 4095, 4096, 4097, rng.randrange(1, 13000)])
+        segs.append((off, ln, rng.randrange(K)))
+        off += ln + rng.choice([0, 0, 1, 3, 4096])
+    n_used = off + 5
+    rng.shuffle(segs)
+    I_p = [1 + p % 7 for p in range(K)]
+    t_b = [1000 - (p * 37) % 150 for p in range(K)]
+    n = n_used + n_total_pad
+    assert B.cocodc_tile_elements(n) == (4096 if n_total_pad else 2048)
+    _case(B, ref, segs, K, n, I_p, t_b, 1000, 17, seed=5)
+
+
 def test_segmented_equals_contiguous_on_gpu(B, ref):
     wl = synth.MINI_WORKLOADS["125M-mini"]
     bk = synth.bookkeeping(wl)
