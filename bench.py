@@ -25,8 +25,9 @@ BYTES_PER_PARAM = 36   # 5 fp32 reads + 4 fp32 writes (theta_m, theta_g, momentu
 # HBM bytes per launch of the fused kernel: rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE runs of this
 # command, each scaled by what the same counter reads for a plain 4 GiB device copy (FETCH_SIZE
 # reads half the true bytes on this GPU, WRITE_SIZE reads them exactly).  The runs and their
-# commands are recorded in profiles/fused_sync_step_<workload>.txt.  None where no run exists.
-MEASURED_TRAFFIC_BYTES = {'7B': 237917636268, '1.3B': 46765973035}
+# commands are recorded in profiles/fused_sync_step_<workload>.txt (fused_sync_step_bf16_<workload>.txt for
+# the 28 B/param bf16 variant).  Keyed by (workload, bytes per parameter); None where no run exists.
+MEASURED_TRAFFIC_BYTES = {('7B', 36): 237917636268, ('1.3B', 36): 46765973035, ('7B', 28): 185056695176}
 
 
 def cpu_baseline(wl, st, bk, sample_frag, repeats=2):
@@ -363,7 +364,7 @@ def main():
                    "selected": sel[:int(n_sel.item())].cpu().tolist()},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4),
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name) if bpp == BYTES_PER_PARAM else None,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((wl.name, bpp)) if mode == 0 and not args.no_pg else None,
                      "kernel": "k_walk<FusedBf16Op>" if args.bf16 else "k_walk<FusedOp>", "kernel_ms_avg": round(k1_avg, 4),
                      "kernel_ms_min": round(min(k1_ms), 4), "algorithmic_bytes": bpp * n},
         "cpu_baseline": cpu,

@@ -1,20 +1,23 @@
-// cocodc.hip -- gfx950 (MI355X) kernels and C ABI of the CoCoDC outer-synchronisation path.
+// cocodc.hip -- gfx950 (MI355X) C ABI of the CoCoDC outer-synchronisation path: the one
+// translation unit of the library.  cocodc_device.h holds the device code, cocodc_host.h the
+// validation, tile planning and launch helpers, cocodc_loop.h the Sec. 3.2 loop; this file holds
+// the build switches and the entry points declared in cocodc.h.
 //
 // One streaming pass per call.  Every kernel walks the same list of TILES: a tile is the
-// part of one fragment that falls into one aligned window of 2^tile_shift elements of the flat
-// buffers, so a tile never straddles two fragments and, inside a tile, element indices that
-// are multiples of 4 are 16-byte aligned whenever the buffer bases are.  A workgroup of
-// 256 threads (4 wavefronts of 64) handles a tile with 128-bit loads and stores, several
-// independent loads in flight per lane, fp64 arithmetic in registers and one rounding per
-// stored fp32 value.  Per-fragment sums (paper Eq. 11) are produced as one fp64 partial per
-// tile (lane -> wavefront shuffle -> LDS -> tile slot) and combined by a second kernel in a
-// fixed order, so scores are bit-reproducible and independent of the launch shape.
+// part of one segment of a fragment that falls into one aligned window of 2^tile_shift elements
+// of the flat buffers, so a tile never straddles two fragments and, inside a tile, element
+// indices that are multiples of 4 are 16-byte aligned whenever the buffer bases are.  A
+// workgroup of 256 threads (4 wavefronts of 64) loads its whole tile with 128-bit accesses
+// (COCODC_DEPTH per stream and lane in flight), computes in fp64 registers with one rounding
+// per stored value, stores and ends.  Per-fragment sums (paper Eq. 11) are produced as one fp64
+// partial per tile (lane -> wavefront shuffle -> LDS -> tile slot) and combined by a second
+// kernel in a fixed order, so scores are bit-reproducible and independent of the launch shape.
 //
 // No MFMA: nothing on this path is a contraction; the bound is HBM bandwidth
 // (20 B read + 16 B written per parameter in the fused step).
 //
-// Compile with -ffp-contract=off: the few fused multiply-adds used are written explicitly
-// so that the fused kernel and the single-step kernels round identically.
+// Compile with -ffp-contract=off: no multiply-add may be contracted, so that the fused kernel,
+// the single-step kernels and a plain fp64 evaluation of the same expressions round identically.
 
 #include <hip/hip_runtime.h>
 
