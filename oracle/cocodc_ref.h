@@ -15,10 +15,12 @@
  * The new global state is rounded to fp32 BEFORE it enters the delay-compensation
  * step, because in the unfused sequence that step reads it back from an fp32 buffer.
  *
- * Pinned by tests/test_oracle_*.py (hand-computed scalars, closed forms, textbook /
- * library special cases, brute force, exhaustive enumeration).  The composition of all
- * steps on random data has no value printed in the paper: end-to-end parity unpinned
- * by the paper, pinned only through its parts.
+ * Pinned by tests/test_oracle_*.py: hand-computed scalars (each step, and one element
+ * through the whole fused step in exact binary fractions), closed forms, textbook /
+ * library special cases (torch's SGD with Nesterov momentum, torch's vector norms),
+ * brute force, exhaustive enumeration, the identity "fused step == the five steps in
+ * sequence", and the one worked example the paper prints (the planner's N = 8, h = 12).
+ * The paper prints no numerical example of the update itself.
  *
  * Return value of every function: 0 on success, negative on invalid arguments
  * (-1 null pointer, -3 out-of-range scalar or fragment table).

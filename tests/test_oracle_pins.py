@@ -516,6 +516,43 @@ def test_fused_equals_sequence_of_primitives(ref, amplified):
     assert fo["sel"].tolist()[0] == (0 if amplified else wl.K - 1)
 
 
+def test_fused_step_hand_computed_in_binary_fractions(ref):
+    """One element through the whole step with operands that are exact binary fractions, so that
+    every intermediate value is exact and was written down by hand (Eq. 2, then Eq. 4, 7, 8, Eq. 11):
+      eta = mu = 1/2, theta_g = 1, m = 1/4, delta_g = 1/2, theta_m = 1, theta_send = 3/2,
+      tau = 4, H = 8, lambda = 1/2, I_p = 4
+      m'    = 1/8 + 1/2                      = 5/8
+      step  = 1/2 + (1/2)(5/8)               = 13/16
+      G     = 1 - (1/2)(13/16)               = 19/32
+      d     = 3/2 - 1                        = 1/2          (= g * tau, g = 1/8)
+      Delta = 19/32 - 3/2                    = -29/32
+      corr  = (1/2)(1/2)(1/2)(-29/32)/(4*8)  = -29/8192
+      theta_m' = 19/32 + 1/2 - 29/8192       = 8931/8192
+      pg    = theta_g - theta_m              = 0
+      sums  = (delta_g^2, |delta_g|, d^2, |d|) = (1/4, 1/2, 1/4, 1/2);  R = sqrt(1/4)/4 = 1/8.
+    A second element with the paper's change-rate form: theta_m' must equal G + tau*(g + lambda*g*g*Delta/H)."""
+    from fractions import Fraction as F
+    hp = ref.hparams(4, 8, lam=0.5, eta=0.5, mu=0.5)
+    tm = np.array([1.0], np.float32)
+    ts = np.array([1.5], np.float32)
+    tg = np.array([1.0], np.float32)
+    m = np.array([0.25], np.float32)
+    dg = np.array([0.5], np.float32)
+    pg = np.array([7.0], np.float32)
+    out = ref.sync_step([(0, 1)], tm, ts, tg, m, dg, pg, [4], [96], 100, 1, hp, shadow=True)
+    assert out["rc"] == 0
+    assert F(float(m[0])) == F(5, 8)
+    assert F(float(tg[0])) == F(19, 32)
+    assert F(float(tm[0])) == F(8931, 8192)
+    assert F(float(out["theta_m64"][0])) == F(8931, 8192)
+    assert pg[0] == 0.0
+    assert [F(float(v)) for v in out["sums"][0]] == [F(1, 4), F(1, 2), F(1, 4), F(1, 2)]
+    assert F(float(out["R"][0])) == F(1, 8)
+    assert out["sel"].tolist() == [0]
+    g, Delta, tau, H, lam = F(1, 8), F(-29, 32), 4, 8, F(1, 2)
+    assert F(19, 32) + tau * (g + lam * g * g * Delta / H) == F(8931, 8192)
+
+
 def test_fused_in_place_pseudograd_alias_and_untouched_padding(ref):
     wl = synth.Workload("t", (513, 255), tau=5, H=100, budget=1)
     bk = synth.bookkeeping(wl)
