@@ -128,6 +128,32 @@ def test_edge_tables(B, ref, table):
         U.compare_selection(go, ro, bk, 100)
 
 
+def test_maximum_number_of_fragments(B, ref):
+    """1024 fragments (the most a table may hold): lengths from 0 to a few tiles, gaps, budget 100,
+    some fragments overdue and some never synchronised; scores, ranks and every element."""
+    import random
+    rng = random.Random(7)
+    frags, off = [], 2
+    for p in range(1024):
+        ln = rng.choice([0, 1, 3, 4, 257, 2047, 2048, 2049, 4097, rng.randrange(1, 9000)])
+        frags.append((off, ln))
+        off += ln + rng.choice([0, 0, 1, 5])
+    n_total = off + 3
+    base = synth.Workload("k1024", (n_total,), tau=5, H=100)
+    st = synth.make_state(base, "cuda", seed=8)
+    bk = synth.Bookkeeping(t_g=1000, t_b=[1000 - (p * 13) % 120 for p in range(1024)],
+                           I_p=[(p * 7) % 11 for p in range(1024)])   # every 11th: never synchronised
+    ghp, rhp = B.hparams(5, 100), ref.hparams(5, 100)
+    host = U.host_copy(st)
+    ws = B.new_workspace(1024, n_total)
+    print(f"case k1024 n={n_total}", flush=True)
+    go = U.run_gpu_fused(B, frags, n_total, st, bk, 100, ghp, ws)
+    ro = U.run_ref_fused(ref, frags, host, bk, 100, rhp)
+    U.compare_fused(st, go, host, ro, frags)
+    U.compare_selection(go, ro, bk, 100)
+    assert len(go["sel_list"]) == 100
+
+
 @pytest.mark.parametrize("view_off", [0, 1])
 def test_odd_tables_in_a_large_buffer(B, ref, view_off):
     """Buffers of 2^24 elements or more are walked in 4096-element tiles (smaller ones in
