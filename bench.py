@@ -213,6 +213,10 @@ def main():
             calls[0][3](); calls[2][3](); calls[3][3](); calls[4][3]()
             B.check(B.cocodc_select_fragments(K, R, bk.t_b, bk.t_g, wl.H, wl.budget, sel, n_sel, ws))
         seq_wall, seq_k = timed(five, 4)
+        mix_wall, mix_k = timed(lambda: B.check(B.cocodc_debug_stream_mix(
+            fr, n, th["theta_m"], th["theta_m_send"], th["theta_g"], th["momentum"], th["delta_g"], pg, ws)), 1)
+        for name in ("theta_m", "theta_g", "momentum"):   # the additions above grew them; back to model scale
+            th[name].normal_(0.0, 0.02)
         fused_wall, fused_k = timed(lambda: B.check(B.cocodc_sync_step(
             fr, n, th["theta_m"], th["theta_m_send"], th["theta_g"], th["momentum"], th["delta_g"], pg, bk.I_p,
             bk.t_b, bk.t_g, wl.budget, hp, R, sel, n_sel, None, ws)))
@@ -222,6 +226,11 @@ def main():
                           "select_ms_per_call": round(sel_ms, 4),
                           "five_calls_in_sequence": {"bytes_per_param": 52, "ms": round(seq_wall, 4),
                                                      "Gparams_per_s": round(n / seq_wall / 1e6, 2)},
+                          "same_streams_no_arithmetic": {
+                              "entry": "cocodc_debug_stream_mix", "bytes_per_param": 36, "kernel_ms_avg": round(mix_k, 4),
+                              "achieved_GBps": round(36 * n / (mix_k * 1e-3) / 1e9, 1),
+                              "fused_kernel_ms_avg": round(fused_k, 4),
+                              "fused_kernel_over_this": round(fused_k / mix_k, 4)},
                           "fused": {"bytes_per_param": 36, "ms": round(fused_wall, 4),
                                     "Gparams_per_s": round(n / fused_wall / 1e6, 2),
                                     "speedup_over_sequence": round(seq_wall / fused_wall, 3)}}), flush=True)

@@ -342,6 +342,16 @@ int cocodc_debug_tile_plan(const cocodc_segment_t* segs, int32_t S, int32_t K, u
                            uint64_t* seg_offset_out, uint64_t* seg_slot_begin_out,
                            uint64_t* frag_slot_begin_out, uint64_t* tile_capacity_out);
 
+/* Measurement aid (no paper counterpart): streams the six device buffers exactly as the fused
+ * step does -- a, c, d read and rewritten in place, b and e read, f written, 36 bytes per
+ * element of every fragment -- with one fp32 addition per stored value (a += b, c += e, d += e,
+ * f = b + c).  Its duration is what the memory system gives this access pattern when the
+ * arithmetic is free; bench.py reports it beside the fused step.  Same table, workspace,
+ * alignment and overlap rules as cocodc_sync_step (no two buffers may overlap). */
+int cocodc_debug_stream_mix(const cocodc_fragment_t* frags, int32_t K, uint64_t n_total, float* a,
+                            const float* b, float* c, float* d, const float* e, float* f,
+                            void* workspace, size_t workspace_bytes, void* stream);
+
 /* hipError_t of the most recent failing HIP call on this thread (0 if none). */
 int cocodc_last_hip_error(void);
 

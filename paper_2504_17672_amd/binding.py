@@ -42,7 +42,7 @@ EXPORTS = (
     "cocodc_pseudograd_bf16", "cocodc_sync_step_bf16", "cocodc_select_fragments_bytes",
     "cocodc_loop_create", "cocodc_loop_destroy", "cocodc_loop_reset_scores", "cocodc_loop_observe",
     "cocodc_loop_plan", "cocodc_loop_due", "cocodc_loop_step", "cocodc_loop_state",
-    "cocodc_tile_elements", "cocodc_debug_tile_plan",
+    "cocodc_tile_elements", "cocodc_debug_tile_plan", "cocodc_debug_stream_mix",
     "cocodc_layout_stride_bytes", "cocodc_last_hip_error", "cocodc_status_string", "cocodc_set_blocks_per_cu",
     "cocodc_profiler_enable", "cocodc_profiler_collect", "cocodc_profiler_disable",
 )
@@ -116,6 +116,8 @@ _lib.cocodc_loop_step.argtypes = [_P, C.c_int64, C.POINTER(cocodc_loop_buffers_t
 _lib.cocodc_loop_state.argtypes = [_P, _i64_p, _i64_p, _i64_p]
 _lib.cocodc_tile_elements.restype = C.c_uint64
 _lib.cocodc_tile_elements.argtypes = [C.c_uint64]
+_lib.cocodc_debug_stream_mix.argtypes = [_frag_p, C.c_int32, C.c_uint64, _P, _P, _P, _P, _P, _P, _P, C.c_size_t, _P]
+_lib.cocodc_debug_stream_mix.restype = C.c_int
 _lib.cocodc_debug_tile_plan.argtypes = [_seg_p, C.c_int32, C.c_int32, C.c_uint64, _P, _P, _P, _P]
 _lib.cocodc_layout_stride_bytes.restype = C.c_uint64
 _lib.cocodc_layout_stride_bytes.argtypes = [C.c_uint64]
@@ -489,6 +491,13 @@ def cocodc_sync_step_bf16(frags, n_total, theta_m, theta_m_send, theta_g, moment
 
 def cocodc_tile_elements(n_total):
     return int(_lib.cocodc_tile_elements(int(n_total)))
+
+
+def cocodc_debug_stream_mix(frags, n_total, a, b, c, d, e, f, workspace, workspace_bytes=None, stream=None, K=None):
+    fa, k = _frags(frags)
+    wp, wb = _ws(workspace, workspace_bytes)
+    return _lib.cocodc_debug_stream_mix(fa, k if K is None else K, int(n_total), _ptr(a), _ptr(b), _ptr(c), _ptr(d),
+                                        _ptr(e), _ptr(f), wp, wb, _stream(stream))
 
 
 def cocodc_debug_tile_plan(segs, K, n_total, S=None):

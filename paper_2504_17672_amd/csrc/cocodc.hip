@@ -448,6 +448,28 @@ uint64_t cocodc_layout_stride_bytes(uint64_t n_total) {
   return stride;
 }
 
+int cocodc_debug_stream_mix(const cocodc_fragment_t* frags, int32_t K, uint64_t n_total, float* a, const float* b,
+                            float* c, float* d, const float* e, float* f, void* workspace,
+                            size_t workspace_bytes_, void* stream) {
+  if (!a || !b || !c || !d || !e || !f) return COCODC_ERR_NULL;
+  if (!all_aligned4({a, b, c, d, e, f})) return COCODC_ERR_ALIGN;
+  Plan pl;
+  if (int rc = plan_table(frags, K, n_total, nullptr, nullptr, &pl)) return rc;
+  if (int rc = check_workspace(workspace, workspace_bytes_, pl.S, K, n_total)) return rc;
+  const size_t nb = n_total * sizeof(float);
+  const Span sp[] = {{a, nb}, {b, nb}, {c, nb}, {d, nb}, {e, nb}, {f, nb}, {workspace, workspace_bytes_}};
+  for (int i = 0; i < 7; ++i) {
+    for (int j = i + 1; j < 7; ++j) {
+      if (overlap(sp[i], sp[j])) return COCODC_ERR_ALIAS;
+    }
+  }
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  WorkspaceView v = view(workspace, pl.S, K);
+  if (int rc = upload_table(pl.recs, v.table, s)) return rc;
+  StreamMixOp op{a, b, c, d, e, f};
+  return launch_walk(all_aligned16({a, b, c, d, e, f}), walk_of(v, pl), op, v.partials, s);
+}
+
 uint64_t cocodc_tile_elements(uint64_t n_total) { return uint64_t(1) << tile_shift_for(n_total); }
 
 int cocodc_debug_tile_plan(const cocodc_segment_t* segs, int32_t S, int32_t K, uint64_t n_total,

@@ -304,6 +304,51 @@ struct PseudoGradOp {
   }
 };
 
+// Measurement aid: the nine streams of the fused step (five read, four written, three of them in
+// place) with one fp32 addition per stored value and no sums -- what the memory system gives this
+// access pattern when the arithmetic costs nothing.
+struct StreamMixOp {
+  static constexpr int kAcc = 0;
+  static constexpr int kVec = 4;
+  static constexpr int kLoads = kDepth;
+  float* a;        // read and written
+  const float* b;  // read
+  float* c;        // read and written
+  float* d;        // read and written
+  const float* e;  // read
+  float* f;        // written
+
+  template <int V>
+  struct Regs {
+    typename Vec<V>::type a, b, c, d, e;
+  };
+  template <int V>
+  __device__ __forceinline__ Regs<V> load(uint64_t i) const {
+    Regs<V> r;
+    r.a = load_stream<V>(a + i);
+    r.b = load_stream<V>(b + i);
+    r.c = load_stream<V>(c + i);
+    r.d = load_stream<V>(d + i);
+    r.e = load_stream<V>(e + i);
+    return r;
+  }
+  template <int V>
+  __device__ __forceinline__ void apply(uint64_t i, const Regs<V>& r, double*) const {
+    typename Vec<V>::type oa, oc, od, of;
+#pragma unroll
+    for (int k = 0; k < V; ++k) {
+      lane_set(oa, k, lane_get(r.a, k) + lane_get(r.b, k));
+      lane_set(oc, k, lane_get(r.c, k) + lane_get(r.e, k));
+      lane_set(od, k, lane_get(r.d, k) + lane_get(r.e, k));
+      lane_set(of, k, lane_get(r.b, k) + lane_get(r.c, k));
+    }
+    store_stream<V>(a + i, oa);
+    store_stream<V>(c + i, oc);
+    store_stream<V>(d + i, od);
+    store_stream<V>(f + i, of);
+  }
+};
+
 template <bool NESTEROV>
 struct OuterOp {
   static constexpr int kAcc = 0;

@@ -128,6 +128,28 @@ def test_edge_tables(B, ref, table):
         U.compare_selection(go, ro, bk, 100)
 
 
+def test_stream_mix_measurement_aid(B):
+    """The measurement kernel's output is defined (a += b, c += e, d += e, f = b + c on the elements
+    of the fragments, nothing elsewhere), so that what bench.py times is known to have run."""
+    n = (1 << 24) + 5000
+    frags = [(3, 70001), (80000, 4096 * 3), ((1 << 24) + 1, 4000)]
+    g = torch.Generator(device="cuda").manual_seed(5)
+    a, b, c, d, e, f = (torch.randn(n, device="cuda", generator=g) for _ in range(6))
+    want = [a.clone(), c.clone(), d.clone(), f.clone()]
+    for o, l in frags:
+        sl = slice(o, o + l)
+        want[0][sl] = a[sl] + b[sl]
+        want[1][sl] = c[sl] + e[sl]
+        want[2][sl] = d[sl] + e[sl]
+        want[3][sl] = b[sl] + c[sl]
+    ws = B.new_workspace(len(frags), n)
+    assert B.cocodc_debug_stream_mix(frags, n, a, b, c, d, e, f, ws) == 0
+    torch.cuda.synchronize()
+    for got, w in zip((a, c, d, f), want):
+        assert torch.equal(got, w)
+    assert B.cocodc_debug_stream_mix(frags, n, a, a, c, d, e, f, ws) == -7   # overlapping buffers
+
+
 def test_maximum_number_of_fragments(B, ref):
     """1024 fragments (the most a table may hold): lengths from 0 to a few tiles, gaps, budget 100,
     some fragments overdue and some never synchronised; scores, ranks and every element."""
