@@ -417,6 +417,54 @@ def test_bitwise_reproducible_and_independent_of_launch_shape(B, ref):
         assert o["sel_list"] == o0["sel_list"]
 
 
+def test_concurrent_calls_from_threads_on_their_own_streams(B, ref):
+    """Calls that use different workspaces may run at the same time: four host threads, each on a
+    stream of its own with its own buffers and workspace, 20 steps each; every thread's final state
+    equals the one the same 20 steps give when run alone."""
+    import threading
+    wl = synth.MINI_WORKLOADS["1.3B-mini"]
+    bk = synth.bookkeeping(wl)
+    ghp = B.hparams(wl.tau, wl.H)
+    n_threads, n_steps = 4, 20
+
+    def run(seed, stream, box):
+        st = synth.make_state(wl, "cuda", seed=seed)
+        ws = B.new_workspace(wl.K, wl.n_total)
+        out = U.gpu_outputs(wl.K)
+        pg = torch.empty_like(st["delta_g"])
+        torch.cuda.synchronize()
+        with torch.cuda.stream(stream):
+            for _ in range(n_steps):
+                rc = B.cocodc_sync_step(wl.frags, wl.n_total, st["theta_m"], st["theta_m_send"], st["theta_g"],
+                                        st["momentum"], st["delta_g"], pg, bk.I_p, bk.t_b, bk.t_g, wl.budget, ghp,
+                                        out["R"], out["sel"], out["n_sel"], out["sums"], ws, stream=stream)
+                if rc != 0:
+                    box["rc"] = rc
+                    return
+            stream.synchronize()
+        box.update(rc=0, st=st, out=out, pg=pg)
+
+    alone = []
+    for t in range(n_threads):
+        box = {}
+        run(100 + t, torch.cuda.Stream(), box)
+        assert box["rc"] == 0
+        alone.append(box)
+    together = [{} for _ in range(n_threads)]
+    threads = [threading.Thread(target=run, args=(100 + t, torch.cuda.Stream(), together[t])) for t in range(n_threads)]
+    for th in threads:
+        th.start()
+    for th in threads:
+        th.join()
+    torch.cuda.synchronize()
+    for a, b in zip(alone, together):
+        assert b.get("rc") == 0
+        for k in ("theta_m", "theta_g", "momentum"):
+            assert torch.equal(a["st"][k], b["st"][k]), k
+        assert torch.equal(a["pg"], b["pg"])
+        assert torch.equal(a["out"]["R"], b["out"]["R"]) and torch.equal(a["out"]["sel"], b["out"]["sel"])
+
+
 # ------------------------------------------------------------------ consecutive syncs
 def test_hundred_consecutive_syncs_heavy_tailed_drift(B, ref):
     """1.3B-shaped run (reduced width): both sides evolve their own state in lock-step."""
