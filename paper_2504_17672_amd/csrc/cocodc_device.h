@@ -591,7 +591,8 @@ __global__ void k_write_table(TableChunk chunk, FragRec* dst, int base, int coun
   if (i < count) dst[base + i] = chunk.rec[i];
 }
 
-// Walks the tile list with stride gridDim.x.  tbl has K+1 records; tbl[K].slot_begin == T.
+// One workgroup per tile (or, with a persistent grid, a walk over the tile list with stride
+// gridDim.x).  wk.tbl has S+1 segment records; wk.tbl[S].slot_begin == wk.T, the number of tiles.
 #if COCODC_WAVES_PER_EU > 0
 #define COCODC_OCCUPANCY __attribute__((amdgpu_waves_per_eu(COCODC_WAVES_PER_EU)))
 #else
