@@ -128,6 +128,31 @@ def test_edge_tables(B, ref, table):
         U.compare_selection(go, ro, bk, 100)
 
 
+def test_hand_computed_element_in_binary_fractions(B):
+    """The element worked out by hand in tests/test_oracle_pins.py (every operand and intermediate
+    an exact binary fraction), through the GPU library alone:
+      eta = mu = 1/2, theta_g = 1, m = 1/4, delta_g = 1/2, theta_m = 1, theta_send = 3/2, tau = 4,
+      H = 8, lambda = 1/2, I_p = 4  ->  m' = 5/8, G = 19/32, theta_m' = 8931/8192, pg = 0, R = 1/8."""
+    from fractions import Fraction as F
+    hp = B.hparams(4, 8, lam=0.5, eta=0.5, mu=0.5)
+    n = 8   # the element sits at index 5 of a small buffer; the rest must stay untouched
+    mk = lambda v: torch.full((n,), 9.0, device="cuda").index_fill_(0, torch.tensor([5], device="cuda"), v)
+    tm, ts, tg, m, dg = mk(1.0), mk(1.5), mk(1.0), mk(0.25), mk(0.5)
+    pg = torch.full((n,), 7.0, device="cuda")
+    out = U.gpu_outputs(1)
+    ws = B.new_workspace(1, n)
+    assert B.cocodc_sync_step([(5, 1)], n, tm, ts, tg, m, dg, pg, [4], [96], 100, 1, hp, out["R"], out["sel"],
+                              out["n_sel"], out["sums"], ws) == 0
+    torch.cuda.synchronize()
+    assert F(m[5].item()) == F(5, 8) and F(tg[5].item()) == F(19, 32) and F(tm[5].item()) == F(8931, 8192)
+    assert pg[5].item() == 0.0 and F(out["R"][0].item()) == F(1, 8)
+    assert [F(v) for v in out["sums"][0].tolist()] == [F(1, 4), F(1, 2), F(1, 4), F(1, 2)]
+    assert out["n_sel"].item() == 1 and out["sel"][0].item() == 0
+    keep = [i for i in range(n) if i != 5]
+    for t, v in ((tm, 9.0), (tg, 9.0), (m, 9.0), (pg, 7.0)):
+        assert (t[keep] == v).all()
+
+
 def test_stream_mix_measurement_aid(B):
     """The measurement kernel's output is defined (a += b, c += e, d += e, f = b + c on the elements
     of the fragments, nothing elsewhere), so that what bench.py times is known to have run."""
