@@ -356,7 +356,7 @@ def main():
         bpp = (2 + 4 + 4 + 4 + (2 if mode == 0 else 0)) + (2 + 4 + 4 + (0 if args.no_pg else 2))
     achieved = bpp * n / (k1_avg * 1e-3) / 1e9
     out = {
-        "metric": "fused sync-step Gparams/s and achieved HBM GB/s (% of peak), 1xMI355X",
+        "metric": "fused sync-step Gparams/s and achieved HBM GB/s (% of peak), 1\u00d7MI355X",
         "value": round(n / (elapsed / args.steps) / 1e9, 3),
         "unit": "Gparams/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
