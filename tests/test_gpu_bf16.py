@@ -148,3 +148,27 @@ def test_bf16_pseudograd_entry_point(B, ref):
     assert B.cocodc_pseudograd_bf16(frags, n, st["theta_g"], tm, pg, None, ws) == 0
     assert B.cocodc_pseudograd_bf16(frags, n, st["theta_g"], tm, tm, None, ws) == B.COCODC_ERR_ALIAS
     assert B.cocodc_pseudograd_bf16(frags, n, st["theta_g"], tm.data_ptr() + 1, pg, None, ws) == B.COCODC_ERR_ALIGN
+
+
+@pytest.mark.parametrize("seed", range(2))
+def test_bf16_random_cases(B, ref, seed):
+    """Seeded random fragment sizes, base alignments and hyper-parameter switches."""
+    import random
+    rng = random.Random(3000 + seed)
+    for case in range(20):
+        K = rng.choice([1, 2, 3, 7, 20])
+        sizes = tuple(rng.choice([0, 1, 3, 4, 5, 1000, 2047, 2048, 2049, 4096, 4101, rng.randrange(1, 25000)])
+                      for _ in range(K))
+        if sum(sizes) == 0:
+            sizes = sizes + (17,)
+        merge_mode = rng.choice([0, 0, 0, 1, 2])
+        score_src = rng.choice([0, 0, 1])
+        wl = synth.Workload(f"bf16-rnd-{seed}-{case}", sizes, tau=rng.choice([0, 1, 2, 5, 50]),
+                            H=rng.choice([1, 3, 100, 1000]), budget=rng.randrange(0, len(sizes) + 1))
+        _case(B, ref, wl, seed=seed * 100 + case, amplified=rng.random() < 0.4, view_off=rng.choice([0, 1, 2, 3, 4]),
+              pg=rng.random() < 0.8, send=(merge_mode == 0 or score_src == 1 or rng.random() < 0.5),
+              variant=rng.choice(["regular", "mixed"]) if len(sizes) > 1 else "regular",
+              lam=rng.choice([0.0, 0.5, 1.0, 3.0]), eta=rng.choice([0.7, 1.0]), mu=rng.choice([0.9, 0.0]),
+              nesterov=rng.choice([1, 0]), drift_sign=rng.choice([1, -1]), score_src=score_src,
+              norm_kind=rng.choice([2, 1]), merge_mode=merge_mode, alpha=rng.choice([1.0, 0.5]),
+              delta_src=rng.choice([0, 1]) if merge_mode == 0 else 0)
