@@ -28,10 +28,13 @@
  *   bytes, 256-byte aligned, holds the device copy of the fragment table and the
  *   partial sums; it carries no state between calls, but two calls that are in flight
  *   at the same time (different streams) must use different workspaces.
- * Alignment.  fp32 buffers must be 4-byte aligned.  When all of them are 16-byte
- *   aligned the kernels use 128-bit accesses (fragment offsets may still be odd: the
- *   unaligned head and tail of a fragment are handled element-wise); otherwise a
- *   slower element-wise variant of the same kernel runs.  Results are identical.
+ * Alignment.  fp32 buffers must be 4-byte aligned (bf16 buffers 2-byte).  The kernels
+ *   make 128-bit accesses at element indices that are multiples of 4 (a fragment's head
+ *   and tail up to such an index are handled element by element, so fragment offsets may
+ *   be odd).  They are fastest when every buffer base is a multiple of 128 bytes, as
+ *   hipMalloc's are: bases 16 bytes or 4 bytes off a 128-byte boundary cost about 11 %
+ *   (every wavefront access then straddles cache lines).  Results, scores included, do
+ *   not depend on the alignment of the buffers.
  * Aliasing.  Distinct arguments must not overlap, with one exception: delta_m_out may
  *   be exactly delta_g (the all-reduce buffer is reused in place).
  * Streams.  `stream` is a hipStream_t passed as void* (NULL = the default stream).
@@ -43,7 +46,8 @@
  *   dictates, and a NaN score ranks last in the selection.
  * Arithmetic.  Every fp32 input is widened to fp64, the update is evaluated in fp64
  *   registers and each stored fp32 value is rounded once.  Per-fragment sums are
- *   accumulated in fp64 in a fixed order that depends only on the fragment table, so
+ *   accumulated in fp64 in a fixed order that depends only on the fragment table and
+ *   n_total (not on buffer addresses, launch shape or device), so
  *   repeated calls on the same bytes give bit-identical scores and selections (the
  *   property Sec. 3.2 relies on for coordination-free selection).
  * Limits.  1 <= K <= COCODC_MAX_FRAGMENTS, n_total <= COCODC_MAX_ELEMENTS.

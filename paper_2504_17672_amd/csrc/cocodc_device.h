@@ -71,9 +71,22 @@ struct Vec<4> {
   using type = f32x4;
 };
 
-template <int V>
+// A = true: the address is a multiple of the access size (128-bit accesses on 16-byte
+// boundaries).  A = false: only the element alignment is known; the same access is then made
+// through a type of that alignment, which the compiler may split into narrower accesses.
+typedef f32x4 f32x4_unaligned __attribute__((aligned(4)));
+template <int V, bool A>
+struct VecAccess {
+  using type = typename Vec<V>::type;
+};
+template <>
+struct VecAccess<4, false> {
+  using type = f32x4_unaligned;
+};
+
+template <int V, bool A = true>
 __device__ __forceinline__ typename Vec<V>::type load_stream(const float* p) {
-  using T = typename Vec<V>::type;
+  using T = typename VecAccess<V, A>::type;
 #if COCODC_NT_LOAD
   return __builtin_nontemporal_load(reinterpret_cast<const T*>(p));
 #else
@@ -81,9 +94,9 @@ __device__ __forceinline__ typename Vec<V>::type load_stream(const float* p) {
 #endif
 }
 
-template <int V>
+template <int V, bool A = true>
 __device__ __forceinline__ void store_stream(float* p, typename Vec<V>::type v) {
-  using T = typename Vec<V>::type;
+  using T = typename VecAccess<V, A>::type;
 #if COCODC_NT_STORE
   __builtin_nontemporal_store(v, reinterpret_cast<T*>(p));
 #else
@@ -109,18 +122,28 @@ struct VecU16<4> {
   using type = u16x4;
 };
 
-template <int V>
+typedef u16x4 u16x4_unaligned __attribute__((aligned(2)));
+template <int V, bool A>
+struct VecU16Access {
+  using type = typename VecU16<V>::type;
+};
+template <>
+struct VecU16Access<4, false> {
+  using type = u16x4_unaligned;
+};
+
+template <int V, bool A = true>
 __device__ __forceinline__ typename VecU16<V>::type load_stream_u16(const unsigned short* p) {
-  using T = typename VecU16<V>::type;
+  using T = typename VecU16Access<V, A>::type;
 #if COCODC_NT_LOAD
   return __builtin_nontemporal_load(reinterpret_cast<const T*>(p));
 #else
   return *reinterpret_cast<const T*>(p);
 #endif
 }
-template <int V>
+template <int V, bool A = true>
 __device__ __forceinline__ void store_stream_u16(unsigned short* p, typename VecU16<V>::type v) {
-  using T = typename VecU16<V>::type;
+  using T = typename VecU16Access<V, A>::type;
 #if COCODC_NT_STORE
   __builtin_nontemporal_store(v, reinterpret_cast<T*>(p));
 #else
@@ -231,18 +254,18 @@ struct FusedOp {
     typename Vec<V>::type tm, ts, tg, m, dg;
   };
 
-  template <int V>
+  template <int V, bool A = true>
   __device__ __forceinline__ Regs<V> load(uint64_t i) const {
     Regs<V> r;
-    r.tm = load_stream<V>(theta_m + i);
-    if (HAS_SEND) r.ts = load_stream<V>(theta_send + i);
-    r.tg = load_stream<V>(theta_g + i);
-    r.m = load_stream<V>(momentum + i);
-    r.dg = load_stream<V>(delta_g + i);
+    r.tm = load_stream<V, A>(theta_m + i);
+    if (HAS_SEND) r.ts = load_stream<V, A>(theta_send + i);
+    r.tg = load_stream<V, A>(theta_g + i);
+    r.m = load_stream<V, A>(momentum + i);
+    r.dg = load_stream<V, A>(delta_g + i);
     return r;
   }
 
-  template <int V>
+  template <int V, bool A = true>
   __device__ __forceinline__ void apply(uint64_t i, const Regs<V>& r, double* a) const {
     typename Vec<V>::type o_tm, o_tg, o_m, o_pg;
 #pragma unroll
@@ -266,10 +289,10 @@ struct FusedOp {
       lane_set(o_m, k, m1);
       if (HAS_PG) lane_set(o_pg, k, tg - tm);  // pseudo-gradient, global minus local
     }
-    store_stream<V>(theta_m + i, o_tm);
-    store_stream<V>(theta_g + i, o_tg);
-    store_stream<V>(momentum + i, o_m);
-    if (HAS_PG) store_stream<V>(pg + i, o_pg);
+    store_stream<V, A>(theta_m + i, o_tm);
+    store_stream<V, A>(theta_g + i, o_tg);
+    store_stream<V, A>(momentum + i, o_m);
+    if (HAS_PG) store_stream<V, A>(pg + i, o_pg);
   }
 };
 
@@ -287,20 +310,20 @@ struct PseudoGradOp {
   struct Regs {
     typename Vec<V>::type tg, tm;
   };
-  template <int V>
+  template <int V, bool A = true>
   __device__ __forceinline__ Regs<V> load(uint64_t i) const {
     Regs<V> r;
-    r.tg = load_stream<V>(theta_g + i);
-    r.tm = load_stream<V>(theta_m + i);
+    r.tg = load_stream<V, A>(theta_g + i);
+    r.tm = load_stream<V, A>(theta_m + i);
     return r;
   }
-  template <int V>
+  template <int V, bool A = true>
   __device__ __forceinline__ void apply(uint64_t i, const Regs<V>& r, double*) const {
     typename Vec<V>::type o;
 #pragma unroll
     for (int k = 0; k < V; ++k) lane_set(o, k, lane_get(r.tg, k) - lane_get(r.tm, k));
-    store_stream<V>(pg + i, o);
-    if (HAS_SEND) store_stream<V>(send_out + i, r.tm);
+    store_stream<V, A>(pg + i, o);
+    if (HAS_SEND) store_stream<V, A>(send_out + i, r.tm);
   }
 };
 
@@ -322,17 +345,17 @@ struct StreamMixOp {
   struct Regs {
     typename Vec<V>::type a, b, c, d, e;
   };
-  template <int V>
+  template <int V, bool A = true>
   __device__ __forceinline__ Regs<V> load(uint64_t i) const {
     Regs<V> r;
-    r.a = load_stream<V>(a + i);
-    r.b = load_stream<V>(b + i);
-    r.c = load_stream<V>(c + i);
-    r.d = load_stream<V>(d + i);
-    r.e = load_stream<V>(e + i);
+    r.a = load_stream<V, A>(a + i);
+    r.b = load_stream<V, A>(b + i);
+    r.c = load_stream<V, A>(c + i);
+    r.d = load_stream<V, A>(d + i);
+    r.e = load_stream<V, A>(e + i);
     return r;
   }
-  template <int V>
+  template <int V, bool A = true>
   __device__ __forceinline__ void apply(uint64_t i, const Regs<V>& r, double*) const {
     typename Vec<V>::type oa, oc, od, of;
 #pragma unroll
@@ -342,10 +365,10 @@ struct StreamMixOp {
       lane_set(od, k, lane_get(r.d, k) + lane_get(r.e, k));
       lane_set(of, k, lane_get(r.b, k) + lane_get(r.c, k));
     }
-    store_stream<V>(a + i, oa);
-    store_stream<V>(c + i, oc);
-    store_stream<V>(d + i, od);
-    store_stream<V>(f + i, of);
+    store_stream<V, A>(a + i, oa);
+    store_stream<V, A>(c + i, oc);
+    store_stream<V, A>(d + i, od);
+    store_stream<V, A>(f + i, of);
   }
 };
 
@@ -363,15 +386,15 @@ struct OuterOp {
   struct Regs {
     typename Vec<V>::type tg, m, dg;
   };
-  template <int V>
+  template <int V, bool A = true>
   __device__ __forceinline__ Regs<V> load(uint64_t i) const {
     Regs<V> r;
-    r.tg = load_stream<V>(theta_g + i);
-    r.m = load_stream<V>(momentum + i);
-    r.dg = load_stream<V>(delta_g + i);
+    r.tg = load_stream<V, A>(theta_g + i);
+    r.m = load_stream<V, A>(momentum + i);
+    r.dg = load_stream<V, A>(delta_g + i);
     return r;
   }
-  template <int V>
+  template <int V, bool A = true>
   __device__ __forceinline__ void apply(uint64_t i, const Regs<V>& r, double*) const {
     typename Vec<V>::type o_tg, o_m;
 #pragma unroll
@@ -382,8 +405,8 @@ struct OuterOp {
       lane_set(o_tg, k, G);
       lane_set(o_m, k, m1);
     }
-    store_stream<V>(theta_g + i, o_tg);
-    store_stream<V>(momentum + i, o_m);
+    store_stream<V, A>(theta_g + i, o_tg);
+    store_stream<V, A>(momentum + i, o_m);
   }
 };
 
@@ -401,15 +424,15 @@ struct MergeOp {
   struct Regs {
     typename Vec<V>::type tm, ts, tg;
   };
-  template <int V>
+  template <int V, bool A = true>
   __device__ __forceinline__ Regs<V> load(uint64_t i) const {
     Regs<V> r;
-    r.tm = load_stream<V>(theta_m + i);
-    if (HAS_SEND) r.ts = load_stream<V>(theta_send + i);
-    r.tg = load_stream<V>(theta_g + i);
+    r.tm = load_stream<V, A>(theta_m + i);
+    if (HAS_SEND) r.ts = load_stream<V, A>(theta_send + i);
+    r.tg = load_stream<V, A>(theta_g + i);
     return r;
   }
-  template <int V>
+  template <int V, bool A = true>
   __device__ __forceinline__ void apply(uint64_t i, const Regs<V>& r, double*) const {
     typename Vec<V>::type o;
 #pragma unroll
@@ -419,7 +442,7 @@ struct MergeOp {
       const double d = HAS_SEND ? drift(ts, tm, hp) : 0.0;
       lane_set(o, k, merge_local<MERGE>(lane_get(r.tg, k), ts, tm, d, hp));
     }
-    store_stream<V>(theta_m + i, o);
+    store_stream<V, A>(theta_m + i, o);
   }
 };
 
@@ -444,18 +467,18 @@ struct FusedBf16Op {
     typename Vec<V>::type tg, m, dg;
   };
 
-  template <int V>
+  template <int V, bool A = true>
   __device__ __forceinline__ Regs<V> load(uint64_t i) const {
     Regs<V> r;
-    r.tm = load_stream_u16<V>(theta_m + i);
-    if (HAS_SEND) r.ts = load_stream_u16<V>(theta_send + i);
-    r.tg = load_stream<V>(theta_g + i);
-    r.m = load_stream<V>(momentum + i);
-    r.dg = load_stream<V>(delta_g + i);
+    r.tm = load_stream_u16<V, A>(theta_m + i);
+    if (HAS_SEND) r.ts = load_stream_u16<V, A>(theta_send + i);
+    r.tg = load_stream<V, A>(theta_g + i);
+    r.m = load_stream<V, A>(momentum + i);
+    r.dg = load_stream<V, A>(delta_g + i);
     return r;
   }
 
-  template <int V>
+  template <int V, bool A = true>
   __device__ __forceinline__ void apply(uint64_t i, const Regs<V>& r, double* a) const {
     typename VecU16<V>::type o_tm, o_pg;
     typename Vec<V>::type o_tg, o_m;
@@ -480,10 +503,10 @@ struct FusedBf16Op {
       lane_set(o_m, k, m1);
       if (HAS_PG) lane_set(o_pg, k, round_bf16(static_cast<double>(tg) - static_cast<double>(tm)));
     }
-    store_stream_u16<V>(theta_m + i, o_tm);
-    store_stream<V>(theta_g + i, o_tg);
-    store_stream<V>(momentum + i, o_m);
-    if (HAS_PG) store_stream_u16<V>(pg + i, o_pg);
+    store_stream_u16<V, A>(theta_m + i, o_tm);
+    store_stream<V, A>(theta_g + i, o_tg);
+    store_stream<V, A>(momentum + i, o_m);
+    if (HAS_PG) store_stream_u16<V, A>(pg + i, o_pg);
   }
 };
 
@@ -502,14 +525,14 @@ struct PseudoGradBf16Op {
     typename Vec<V>::type tg;
     typename VecU16<V>::type tm;
   };
-  template <int V>
+  template <int V, bool A = true>
   __device__ __forceinline__ Regs<V> load(uint64_t i) const {
     Regs<V> r;
-    r.tg = load_stream<V>(theta_g + i);
-    r.tm = load_stream_u16<V>(theta_m + i);
+    r.tg = load_stream<V, A>(theta_g + i);
+    r.tm = load_stream_u16<V, A>(theta_m + i);
     return r;
   }
-  template <int V>
+  template <int V, bool A = true>
   __device__ __forceinline__ void apply(uint64_t i, const Regs<V>& r, double*) const {
     typename VecU16<V>::type o;
 #pragma unroll
@@ -517,8 +540,8 @@ struct PseudoGradBf16Op {
       lane_set(o, k, round_bf16(static_cast<double>(lane_get(r.tg, k)) -
                                 static_cast<double>(widen_bf16(lane_get(r.tm, k)))));
     }
-    store_stream_u16<V>(pg + i, o);
-    if (HAS_SEND) store_stream_u16<V>(send_out + i, r.tm);
+    store_stream_u16<V, A>(pg + i, o);
+    if (HAS_SEND) store_stream_u16<V, A>(send_out + i, r.tm);
   }
 };
 
@@ -534,13 +557,13 @@ struct ScoreOp {
   struct Regs {
     typename Vec<V>::type x;
   };
-  template <int V>
+  template <int V, bool A = true>
   __device__ __forceinline__ Regs<V> load(uint64_t i) const {
     Regs<V> r;
-    r.x = load_stream<V>(x + i);
+    r.x = load_stream<V, A>(x + i);
     return r;
   }
-  template <int V>
+  template <int V, bool A = true>
   __device__ __forceinline__ void apply(uint64_t, const Regs<V>& r, double* a) const {
 #pragma unroll
     for (int k = 0; k < V; ++k) {
@@ -628,14 +651,18 @@ __global__ __launch_bounds__(kThreads) COCODC_OCCUPANCY void k_walk(Walk wk, Op 
 #pragma unroll
     for (int k = 0; k < (Op::kAcc > 0 ? Op::kAcc : 1); ++k) acc[k] = 0.0;
 
-    if (VEC) {
+    // VEC: every buffer base is 16-byte aligned, so are the element indices that are multiples
+    // of W, and the accesses below are single 128-bit ones.  Otherwise the same accesses are made
+    // through element-aligned types.  Either way lane t handles the same elements in the same
+    // order, so the sums do not depend on the alignment of the buffers.
+    {
       constexpr int W = Op::kVec;      // elements per vector access
       constexpr int D = Op::kLoads;    // vector accesses per stream in flight
       uint64_t lo4 = (lo + (W - 1)) & ~uint64_t(W - 1);
       if (lo4 > hi) lo4 = hi;
       uint64_t hi4 = hi & ~uint64_t(W - 1);
       if (hi4 < lo4) hi4 = lo4;
-      if (tid < lo4 - lo) {  // unaligned head of the fragment (at most W-1 elements)
+      if (tid < lo4 - lo) {  // head of the fragment up to a multiple of W (at most W-1 elements)
         const auto r = op.template load<1>(lo + tid);
         op.template apply<1>(lo + tid, r, acc);
       }
@@ -645,22 +672,17 @@ __global__ __launch_bounds__(kThreads) COCODC_OCCUPANCY void k_walk(Walk wk, Op 
 #pragma unroll
         for (int k = 0; k < D; ++k) {
           const uint64_t vk = v + uint64_t(k) * kThreads;
-          if (vk < nvec) r[k] = op.template load<W>(lo4 + vk * W);
+          if (vk < nvec) r[k] = op.template load<W, VEC>(lo4 + vk * W);
         }
 #pragma unroll
         for (int k = 0; k < D; ++k) {
           const uint64_t vk = v + uint64_t(k) * kThreads;
-          if (vk < nvec) op.template apply<W>(lo4 + vk * W, r[k], acc);
+          if (vk < nvec) op.template apply<W, VEC>(lo4 + vk * W, r[k], acc);
         }
       }
-      if (tid < hi - hi4) {  // unaligned tail (at most W-1 elements)
+      if (tid < hi - hi4) {  // tail (at most W-1 elements)
         const auto r = op.template load<1>(hi4 + tid);
         op.template apply<1>(hi4 + tid, r, acc);
-      }
-    } else {
-      for (uint64_t i = lo + tid; i < hi; i += kThreads) {
-        const auto r = op.template load<1>(i);
-        op.template apply<1>(i, r, acc);
       }
     }
 

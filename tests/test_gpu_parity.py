@@ -442,6 +442,33 @@ def test_bitwise_reproducible_and_independent_of_launch_shape(B, ref):
         assert o["sel_list"] == o0["sel_list"]
 
 
+def test_scores_do_not_depend_on_buffer_alignment(B):
+    """The same fragment table over the same values at bases that are 16-byte aligned, 4 bytes off
+    and 8 bytes off: stored values, raw sums, scores and selection are bit-identical."""
+    wl = synth.MINI_WORKLOADS["125M-mini"]
+    bk = synth.bookkeeping(wl)
+    ghp = B.hparams(wl.tau, wl.H)
+    st = synth.make_state(wl, "cuda", seed=6)
+    ws = B.new_workspace(wl.K, wl.n_total)
+    results = []
+    for shift in (0, 1, 2, 3, 4):
+        s = {}
+        for k, v in st.items():
+            buf = torch.empty(wl.n_total + 8, device="cuda")
+            buf[shift:shift + wl.n_total].copy_(v)
+            s[k] = buf[shift:shift + wl.n_total]
+            assert s[k].data_ptr() % 16 == (4 * shift) % 16
+        o = U.run_gpu_fused(B, wl.frags, wl.n_total, s, bk, wl.budget, ghp, ws)
+        results.append((s, o))
+    s0, o0 = results[0]
+    for s, o in results[1:]:
+        for k in ("theta_m", "theta_g", "momentum"):
+            assert torch.equal(s[k], s0[k])
+        assert torch.equal(o["pg"], o0["pg"])
+        assert torch.equal(o["R"], o0["R"]) and torch.equal(o["sums"], o0["sums"])
+        assert o["sel_list"] == o0["sel_list"]
+
+
 def test_concurrent_calls_from_threads_on_their_own_streams(B, ref):
     """Calls that use different workspaces may run at the same time: four host threads, each on a
     stream of its own with its own buffers and workspace, 20 steps each; every thread's final state
