@@ -32,6 +32,43 @@ def test_library_exports_every_declared_symbol(B):
     assert sorted(B.EXPORTS) == names
 
 
+def test_header_is_plain_c():
+    """The boundary is a C ABI: the header compiles as C99 without warnings, and a C program that
+    uses its types links against the library."""
+    import subprocess, tempfile
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    inc = os.path.join(root, "include")
+    r = subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-x", "c",
+                        os.path.join(inc, "cocodc.h")], capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+    src = r"""
+#include "cocodc.h"
+#include <stdio.h>
+int main(void) {
+  cocodc_fragment_t f = {0, 16};
+  cocodc_hparams_t hp = {5, 100, 0.5, 0.7, 0.9, 1, 1, 0, 2, 0, 1.0, 0, 0};
+  int64_t N = 0, h = 0;
+  (void)f; (void)hp;
+  if (cocodc_sync_plan(4, 100, 0.4, 1.0, 5.0, &N, &h) != COCODC_OK) return 2;
+  printf("%lld %lld %zu %s\n", (long long)N, (long long)h, cocodc_workspace_bytes(4, 1u << 20),
+         cocodc_status_string(COCODC_ERR_ALIAS));
+  return 0;
+}
+"""
+    lib = os.path.join(root, "paper_2504_17672_amd", "libcocodc.so")
+    with tempfile.TemporaryDirectory() as d:
+        c = os.path.join(d, "t.c")
+        open(c, "w").write(src)
+        exe = os.path.join(d, "t")
+        r = subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-I", inc, c, lib, "-Wl,-rpath," + os.path.dirname(lib),
+                            "-Wl,-rpath,/opt/rocm/lib", "-o", exe], capture_output=True, text=True)
+        assert r.returncode == 0, r.stderr
+        r = subprocess.run([exe], capture_output=True, text=True)
+        assert r.returncode == 0, (r.stdout, r.stderr)
+        N, h, ws, name = r.stdout.split()
+        assert (int(N), int(h)) == (8, 12) and int(ws) > 0 and name == "COCODC_ERR_ALIAS"
+
+
 def test_workspace_size(B):
     assert B.cocodc_workspace_bytes(0, 100) == 0
     assert B.cocodc_workspace_bytes(B.COCODC_MAX_FRAGMENTS + 1, 100) == 0
