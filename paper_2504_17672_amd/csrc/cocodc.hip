@@ -31,6 +31,16 @@
 
 #include "cocodc.h"
 
+// Build switches.  The defaults are the fastest measured; the others exist so that the
+// alternatives can be built and timed again (-DNAME=value on the hipcc line).
+//   COCODC_TILE          elements per tile of large buffers (power of two >= 1024)
+//   COCODC_THREADS       threads per workgroup of the streaming kernels
+//   COCODC_DEPTH         128-bit accesses per stream and lane in flight
+//                        (TILE == THREADS * 4 * DEPTH: a workgroup handles its tile in one step)
+//   COCODC_NT_LOAD/STORE nontemporal loads / stores (1) or plain ones (0)
+//   COCODC_EXACT_DIV     fp64 division as the oracle does it (1: bit-identical results) or a
+//                        multiplication by a precomputed reciprocal (0: last-bit differences)
+//   COCODC_WAVES_PER_EU  occupancy hint for the streaming kernels (0: none)
 #ifndef COCODC_TILE
 #define COCODC_TILE 4096
 #endif
