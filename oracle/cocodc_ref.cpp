@@ -303,6 +303,39 @@ int cocodc_ref_sync_step(const cocodc_ref_fragment_t* frags, int32_t K, uint64_t
   return cocodc_ref_select_fragments(K, R_out, t_b, t_g, hp->H, budget, sel_out, n_sel_out);
 }
 
+/* One event of the loop of Sec. 3.2: the fragments q with recv_mask[q] != 0 have just arrived
+ * (Alg. 1 and Eq. 2 for them, their scores R_q of Eq. 11 replace the old ones); the others keep
+ * their buffers and their scores; then Alg. 2 looks at all K scores. */
+int cocodc_ref_sync_event(const cocodc_ref_fragment_t* frags, int32_t K, uint64_t n_total,
+                          const uint8_t* recv_mask, float* theta_m, const float* theta_m_send,
+                          float* theta_g, float* momentum, const float* delta_g, float* delta_m_out,
+                          const int64_t* I_p, const int64_t* t_b, int64_t t_g, int32_t budget,
+                          const cocodc_ref_hparams_t* hp, double* R, int32_t* sel_out,
+                          int32_t* n_sel_out, double* sums_out) {
+  if (!recv_mask || !theta_m || !theta_g || !momentum || !delta_g) return kErrNull;
+  if (!I_p || !t_b || !R || !sel_out || !n_sel_out) return kErrNull;
+  if (int rc = check_table(frags, K, n_total)) return rc;
+  if (int rc = check_hparams(hp)) return rc;
+  if (!theta_m_send && (hp->merge_mode == 0 || hp->score_src == 1)) return kErrNull;
+  if (budget < 0) return kErrRange;
+  for (int32_t q = 0; q < K; ++q) {
+    if (!recv_mask[q]) continue;
+    Sums s;
+    for (uint64_t i = frags[q].offset; i < frags[q].offset + frags[q].length; ++i) {
+      sync_element(i, theta_m, theta_m_send, theta_g, momentum, delta_g, delta_m_out, *hp, &s,
+                   nullptr);
+    }
+    R[q] = score_from_sums(s, I_p[q], *hp);
+    if (sums_out) {
+      sums_out[4 * q + 0] = s.g2;
+      sums_out[4 * q + 1] = s.g1;
+      sums_out[4 * q + 2] = s.d2;
+      sums_out[4 * q + 3] = s.d1;
+    }
+  }
+  return cocodc_ref_select_fragments(K, R, t_b, t_g, hp->H, budget, sel_out, n_sel_out);
+}
+
 int cocodc_ref_sync_step_mt(const cocodc_ref_fragment_t* frags, int32_t K, uint64_t n_total,
                             float* theta_m, const float* theta_m_send, float* theta_g,
                             float* momentum, const float* delta_g, float* delta_m_out,

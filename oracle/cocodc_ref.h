@@ -113,6 +113,20 @@ int cocodc_ref_sync_step(const cocodc_ref_fragment_t* frags, int32_t K, uint64_t
                          int32_t* n_sel_out, double* sums_out /* nullable */,
                          const cocodc_ref_shadow_t* shadow /* nullable */);
 
+/* One event of the loop of Sec. 3.2 in one call.  recv_mask[q] != 0 marks the fragments whose
+ * averaged pseudo-gradient has just arrived: they get the fused step (Eq. 2, Alg. 1, next
+ * pseudo-gradient) and a fresh score R[q] (Eq. 11, from I_p[q]); every other fragment keeps its
+ * buffers, its R[p] and its row of sums_out.  R is therefore read and written: it holds the
+ * scores of earlier events (+inf before a fragment's first synchronisation).  Then Alg. 2 runs
+ * over all K scores with t_b as passed (the caller has already set t_b of the arrived
+ * fragments to the current step). */
+int cocodc_ref_sync_event(const cocodc_ref_fragment_t* frags, int32_t K, uint64_t n_total,
+                          const uint8_t* recv_mask, float* theta_m, const float* theta_m_send,
+                          float* theta_g, float* momentum, const float* delta_g, float* delta_m_out,
+                          const int64_t* I_p, const int64_t* t_b, int64_t t_g, int32_t budget,
+                          const cocodc_ref_hparams_t* hp, double* R, int32_t* sel_out,
+                          int32_t* n_sel_out, double* sums_out);
+
 /* Same per-element arithmetic as cocodc_ref_sync_step, spread over host threads in
  * fixed 65536-element chunks whose partial sums are added in chunk order (so the
  * result does not depend on n_threads).  Exists only so the CPU baseline can be timed

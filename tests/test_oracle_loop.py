@@ -5,6 +5,7 @@ staleness it is there to guarantee.  CPU only."""
 import math
 
 import numpy as np
+import pytest
 import torch
 
 from paper_2504_17672_amd import synth
@@ -122,3 +123,107 @@ def test_moving_average_replans(ref):
     assert abs(loop.T_s - 5.0) < 1e-15 and (loop.N, loop.h) == (8, 12)
     loop.observe(1.0, 1000.0, 1.0)   # no capacity: N falls back to K (Eq. 9)
     assert (loop.N, loop.h) == (4, 25)
+
+
+# ------------------------------------------------------------------ one loop event in one call
+def _event_state(seed, n):
+    rng = np.random.default_rng(seed)
+    return {k: rng.normal(0, 0.5, n).astype(np.float32)
+            for k in ("theta_m", "theta_m_send", "theta_g", "momentum", "delta_g")}
+
+
+@pytest.mark.parametrize("mask", [(1, 1, 1, 1, 1), (0, 1, 0, 0, 1), (0, 0, 0, 0, 0), (1, 0, 0, 0, 0)])
+def test_event_equals_step_on_the_arrived_fragments_then_selection_over_all(ref, mask):
+    """sync_event == (sync_step restricted to the arrived fragments, which leaves everything else as it
+    was) followed by Alg. 2 over the K scores old and new.  The right-hand side is put together here
+    from the already pinned single functions."""
+    frags = [(3, 700), (703, 0), (710, 1), (800, 4100), (5000, 333)]
+    K, n = len(frags), 5400
+    hp = ref.hparams(2, 3, lam=0.5)
+    I_p = [4, 9, 2, 6, 3]
+    t_b = [90, 99, 40, 95, 97]
+    R_old = np.array([0.25, np.inf, 7.0, 0.5, 0.125])
+    a = _event_state(1, n)
+    b = {k: v.copy() for k, v in a.items()}
+    pg_a = np.full(n, 555.0, np.float32)
+    pg_b = pg_a.copy()
+    sums_a = np.full((K, 4), -3.0)
+
+    R_a = R_old.copy()
+    out = ref.sync_event(frags, mask, a["theta_m"], a["theta_m_send"], a["theta_g"], a["momentum"], a["delta_g"],
+                         pg_a, I_p, t_b, 100, 2, hp, R_a, sums=sums_a)
+    assert out["rc"] == 0
+
+    arrived = [q for q in range(K) if mask[q]]
+    R_b = R_old.copy()
+    sums_b = np.full((K, 4), -3.0)
+    if arrived:
+        sub = ref.sync_step([frags[q] for q in arrived], b["theta_m"], b["theta_m_send"], b["theta_g"], b["momentum"],
+                            b["delta_g"], pg_b, [I_p[q] for q in arrived], [t_b[q] for q in arrived], 100, 0, hp)
+        assert sub["rc"] == 0
+        for j, q in enumerate(arrived):
+            R_b[q] = sub["R"][j]
+            sums_b[q] = sub["sums"][j]
+    rc, sel = ref.select_fragments(R_b, t_b, 100, hp.H, 2)
+    assert rc == 0
+    for k in a:
+        assert np.array_equal(a[k], b[k]), k
+    assert np.array_equal(pg_a, pg_b)
+    assert np.array_equal(R_a, R_b) and np.array_equal(sums_a, sums_b)
+    assert out["sel"].tolist() == sel.tolist()
+    if not arrived:   # nothing arrived: nothing but the selection happens
+        for k, v in _event_state(1, n).items():
+            assert np.array_equal(a[k], v)
+        assert np.array_equal(R_a, R_old)
+
+
+def test_event_by_event_equals_the_loop(ref):
+    """Driving sync_event from the schedule of Sec. 3.2 (receive at t_p + tau, decide every h steps)
+    reproduces the reference loop: same sends, same final buffers."""
+    from oracle.loop import RefLoop
+    frags = [(0, 300), (300, 500), (800, 200), (1000, 24)]
+    K, n, tau, H = 4, 1024, 5, 100
+    hp = ref.hparams(tau, H)
+    st_a, st_b = _event_state(2, n), None
+    st_b = {k: v.copy() for k, v in st_a.items()}
+    loop = RefLoop(frags, hp, gamma=0.4, T_c=1.0, T_s=5.0)
+    pg_a = np.zeros(n, np.float32)
+    log_a = []
+    for t in range(1, 131):
+        rec, sent = loop.step(t, st_a["theta_m"], st_a["theta_m_send"], st_a["theta_g"], st_a["momentum"],
+                              st_a["delta_g"], pg_a)
+        if rec or sent >= 0:
+            log_a.append((t, tuple(rec), sent))
+    # the same schedule driven by hand through sync_event
+    R = np.full(K, np.inf)
+    t_b, I_p, flying = [0] * K, [0] * K, [-1] * K
+    pg_b = np.zeros(n, np.float32)
+    log_b = []
+    h = loop.h
+    for t in range(1, 131):
+        mask = [1 if flying[p] >= 0 and flying[p] + tau == t else 0 for p in range(K)]
+        for p in range(K):
+            if mask[p]:
+                I_p[p] = flying[p] - t_b[p]
+                t_b[p] = t
+                flying[p] = -1
+        decide = t % h == 0 and sum(f >= 0 for f in flying) < K
+        sent = -1
+        if any(mask) or decide:
+            want = sum(f >= 0 for f in flying) + 1 if decide else 0
+            out = ref.sync_event(frags, mask, st_b["theta_m"], st_b["theta_m_send"], st_b["theta_g"],
+                                 st_b["momentum"], st_b["delta_g"], None, I_p, t_b, t, want, hp, R)
+            assert out["rc"] == 0
+            if decide:
+                for q in out["sel"].tolist():
+                    if flying[q] < 0:
+                        sent = q
+                        break
+        if sent >= 0:
+            assert ref.pseudograd([frags[sent]], st_b["theta_g"], st_b["theta_m"], pg_b, st_b["theta_m_send"]) == 0
+            flying[sent] = t
+        if any(mask) or sent >= 0:
+            log_b.append((t, tuple(p for p in range(K) if mask[p]), sent))
+    assert log_a == log_b and len(log_a) > 10
+    for k in st_a:
+        assert np.array_equal(st_a[k], st_b[k]), k

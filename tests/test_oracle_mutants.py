@@ -9,6 +9,7 @@ import subprocess
 import pytest
 
 import oracle
+import test_oracle_loop as loop_pins
 import test_oracle_pins as pins
 
 SRC = os.path.join(os.path.dirname(oracle.__file__), "cocodc_ref.cpp")
@@ -59,6 +60,10 @@ MUTANTS = [
     ("planner_min_instead_of_max", "if (cap > static_cast<double>(N))", "if (cap < static_cast<double>(N))"),
     ("planner_ignores_gamma", "std::floor(gamma * ((static_cast<double>(H) * T_c) / T_s))", "std::floor((static_cast<double>(H) * T_c) / T_s)"),
     ("planner_interval_inverted", "static_cast<int64_t>(H) / N;", "N / static_cast<int64_t>(H);"),
+    ("event_mask_inverted", "if (!recv_mask[q]) continue;", "if (recv_mask[q]) continue;"),
+    ("event_mask_ignored", "if (!recv_mask[q]) continue;", ""),
+    ("event_selects_from_arrived_only", "return cocodc_ref_select_fragments(K, R, t_b, t_g, hp->H, budget, sel_out, n_sel_out);\n}",
+     "for (int32_t q = 0; q < K; ++q) if (!recv_mask[q]) R[q] = -1.0;\n  return cocodc_ref_select_fragments(K, R, t_b, t_g, hp->H, budget, sel_out, n_sel_out);\n}"),
 ]
 
 BATTERY = [
@@ -90,6 +95,7 @@ BATTERY = [
     lambda ref: pins.test_fused_equals_sequence_of_primitives(ref, True),
     pins.test_score_source_and_norm_switches,
     pins.test_selection_exhaustive_small,
+    lambda ref: loop_pins.test_event_equals_step_on_the_arrived_fragments_then_selection_over_all(ref, (0, 1, 0, 0, 1)),
 ]
 
 
@@ -101,7 +107,7 @@ def _compile(text, path):
                     "-I", os.path.dirname(SRC), "-o", path, src], check=True)
     lib = C.CDLL(path)
     for name in ("pseudograd", "outer_nesterov", "delay_compensate", "fragment_scores", "select_fragments",
-                 "sync_step", "sync_step_mt", "sync_plan"):
+                 "sync_step", "sync_step_mt", "sync_plan", "sync_event"):
         getattr(lib, "cocodc_ref_" + name).restype = C.c_int
     return lib
 
