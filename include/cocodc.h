@@ -207,6 +207,25 @@ int cocodc_sync_step(const cocodc_fragment_t* frags, int32_t K, uint64_t n_total
                      double* sums_out /* nullable */, void* workspace, size_t workspace_bytes,
                      void* stream);
 
+/* One event of the loop of Sec. 3.2 in one call: "the fragments q with recv_mask[q] != 0 have
+ * just arrived; which fragment is sent next?".  recv_mask: host, K entries.  The marked
+ * fragments get exactly what cocodc_sync_step does for them (Eq. 2, Algorithm 1, next
+ * pseudo-gradient) and a fresh score R[q] (Eq. 11, from I_p[q]); every other fragment keeps
+ * its buffers, its R[p] and its row of sums_out, whatever I_p[p] says.  R (device, K) is
+ * therefore read AND written: it must hold the scores of earlier events, +inf for fragments
+ * that were never synchronised (cocodc_loop_reset_scores).  Algorithm 2 then runs over all K
+ * scores with t_b as passed: the caller has already set t_b[q] of the arrived fragments to
+ * the current step.  A mask without any mark reduces the call to the selection.  Everything
+ * else (ownership, alignment, aliasing, errors) as for cocodc_sync_step. */
+int cocodc_sync_event(const cocodc_fragment_t* frags, int32_t K, uint64_t n_total,
+                      const uint8_t* recv_mask, float* theta_m,
+                      const float* theta_m_send /* nullable as in cocodc_sync_step */, float* theta_g,
+                      float* momentum, const float* delta_g, float* delta_m_out /* nullable */,
+                      const int64_t* I_p, const int64_t* t_b, int64_t t_g, int32_t budget,
+                      const cocodc_hparams_t* hp, double* R /* in and out */, int32_t* sel_out,
+                      int32_t* n_sel_out, double* sums_out /* nullable */, void* workspace,
+                      size_t workspace_bytes, void* stream);
+
 /* The same two calls for fragments made of several segments (Sec. 4.1: strided shards).
  * segs: host, S entries in any order; the segments of one fragment are summed in the order
  * listed.  Segments must not overlap; a fragment may have none.  I_p, t_b, R_out, sel_out,

@@ -37,7 +37,7 @@ COCODC_ERR_ALIAS = -7
 
 EXPORTS = (
     "cocodc_workspace_bytes", "cocodc_pseudograd", "cocodc_outer_nesterov", "cocodc_delay_compensate",
-    "cocodc_fragment_scores", "cocodc_select_fragments", "cocodc_sync_step", "cocodc_sync_plan",
+    "cocodc_fragment_scores", "cocodc_select_fragments", "cocodc_sync_step", "cocodc_sync_event", "cocodc_sync_plan",
     "cocodc_workspace_bytes_segmented", "cocodc_fragment_scores_segmented", "cocodc_sync_step_segmented",
     "cocodc_pseudograd_bf16", "cocodc_sync_step_bf16", "cocodc_select_fragments_bytes",
     "cocodc_loop_create", "cocodc_loop_destroy", "cocodc_loop_reset_scores", "cocodc_loop_observe",
@@ -90,6 +90,9 @@ _lib.cocodc_select_fragments.argtypes = [C.c_int32, _P, _i64_p, C.c_int64, C.c_i
                                          C.c_size_t, _P]
 _lib.cocodc_sync_step.argtypes = [_frag_p, C.c_int32, C.c_uint64, _P, _P, _P, _P, _P, _P, _i64_p, _i64_p,
                                   C.c_int64, C.c_int32, _hp_p, _P, _P, _P, _P, _P, C.c_size_t, _P]
+_lib.cocodc_sync_event.argtypes = [_frag_p, C.c_int32, C.c_uint64, _P, _P, _P, _P, _P, _P, _P, _i64_p, _i64_p,
+                                   C.c_int64, C.c_int32, _hp_p, _P, _P, _P, _P, _P, C.c_size_t, _P]
+_lib.cocodc_sync_event.restype = C.c_int
 _lib.cocodc_sync_plan.argtypes = [C.c_int32, C.c_int32, C.c_double, C.c_double, C.c_double, _i64_p, _i64_p]
 _seg_p = C.POINTER(cocodc_segment_t)
 _lib.cocodc_workspace_bytes_segmented.restype = C.c_size_t
@@ -330,6 +333,21 @@ def cocodc_sync_step(frags, n_total, theta_m, theta_m_send, theta_g, momentum, d
                                  _i64(t_b), int(t_g), int(budget), C.byref(hp) if hp is not None else None,
                                  _ptr(R_out), _ptr(sel_out), _ptr(n_sel_out), _ptr(sums_out), wp, wb,
                                  _stream(stream))
+
+
+def cocodc_sync_event(frags, n_total, recv_mask, theta_m, theta_m_send, theta_g, momentum, delta_g, delta_m_out,
+                      I_p, t_b, t_g, budget, hp, R, sel_out, n_sel_out, sums_out, workspace, workspace_bytes=None,
+                      stream=None, K=None):
+    """recv_mask: a sequence of K truth values (host).  R: device, read and written."""
+    fa, k = _frags(frags)
+    wp, wb = _ws(workspace, workspace_bytes)
+    mask = None
+    if recv_mask is not None:
+        mask = (C.c_uint8 * len(recv_mask))(*[1 if m else 0 for m in recv_mask])
+    return _lib.cocodc_sync_event(fa, k if K is None else K, int(n_total), mask, _ptr(theta_m), _ptr(theta_m_send),
+                                  _ptr(theta_g), _ptr(momentum), _ptr(delta_g), _ptr(delta_m_out), _i64(I_p),
+                                  _i64(t_b), int(t_g), int(budget), C.byref(hp) if hp is not None else None,
+                                  _ptr(R), _ptr(sel_out), _ptr(n_sel_out), _ptr(sums_out), wp, wb, _stream(stream))
 
 
 def cocodc_sync_plan(K, H, gamma, T_c, T_s):

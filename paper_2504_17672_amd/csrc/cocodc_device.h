@@ -710,6 +710,7 @@ __global__ __launch_bounds__(kFinalizeThreads) void k_finalize(const FragRec* __
   constexpr int U = 4;
   __shared__ double lds[kFinalizeThreads / 64][kSums];
   const int p = blockIdx.x;
+  if (tbl[p].length == 0) return;  // the fragment takes no part in this call: its score stays
   const uint64_t s0 = tbl[p].slot_begin, s1 = tbl[p + 1].slot_begin;
   const f64x2* __restrict__ slots = reinterpret_cast<const f64x2*>(partials);
   double acc[kSums] = {0.0, 0.0, 0.0, 0.0};

@@ -31,7 +31,7 @@ uint64_t max_tiles(int32_t S, uint64_t n_total) {
 // its range of tile slots, I_p, t_b), then one slot of kSums doubles per tile.
 struct WorkspaceView {
   FragRec* table;    // S + 1 segment records; table[S].slot_begin == number of tiles
-  FragRec* groups;   // K + 1 fragment records; only slot_begin, I_p, t_b are meaningful
+  FragRec* groups;   // K + 1 fragment records; slot_begin, I_p, t_b and length (1: takes part, 0: not)
   double* partials;  // max_tiles * kSums
 };
 
@@ -74,8 +74,11 @@ Walk walk_of(const WorkspaceView& v, const Plan& pl) { return Walk{v.table, pl.T
 // Validates a segment list (every segment inside n_total, no two overlapping, fragment ids in
 // [0, K)) and lays out the tile list: the segments of fragment 0 in the order given, then those
 // of fragment 1, ...  so that each fragment owns one contiguous range of tile slots.
+// recv_mask (nullable, K entries): fragments whose entry is 0 take no part in the call -- their
+// segments get no tiles and their group record says so (length 0), so that the reduction leaves
+// their score alone.  Group records of fragments that do take part carry length 1.
 int plan_segments(const cocodc_segment_t* segs, int32_t S, int32_t K, uint64_t n_total, const int64_t* I_p,
-                  const int64_t* t_b, Plan* plan) {
+                  const int64_t* t_b, Plan* plan, const uint8_t* recv_mask = nullptr) {
   if (!segs && S > 0) return COCODC_ERR_NULL;
   if (K < 1 || K > COCODC_MAX_FRAGMENTS || S < 0 || S > COCODC_MAX_SEGMENTS) return COCODC_ERR_RANGE;
   if (n_total > COCODC_MAX_ELEMENTS) return COCODC_ERR_RANGE;  // keeps every byte count far from overflow
@@ -108,7 +111,7 @@ int plan_segments(const cocodc_segment_t* segs, int32_t S, int32_t K, uint64_t n
     while (next_group <= sg.fragment) grp_rec[next_group++].slot_begin = slot;
     FragRec& r = seg_rec[j];
     r.offset = sg.offset;
-    r.length = sg.length;
+    r.length = (!recv_mask || recv_mask[sg.fragment]) ? sg.length : 0;
     r.slot_begin = slot;
     r.tile0 = r.offset >> sh;
     if (r.length) slot += ((r.offset + r.length - 1) >> sh) - r.tile0 + 1;
@@ -118,6 +121,7 @@ int plan_segments(const cocodc_segment_t* segs, int32_t S, int32_t K, uint64_t n
   for (int32_t p = 0; p < K; ++p) {
     grp_rec[p].I_p = I_p ? I_p[p] : 0;
     grp_rec[p].t_b = t_b ? t_b[p] : 0;
+    grp_rec[p].length = (!recv_mask || recv_mask[p]) ? 1 : 0;
   }
   plan->T = slot;
   return COCODC_OK;
@@ -125,12 +129,12 @@ int plan_segments(const cocodc_segment_t* segs, int32_t S, int32_t K, uint64_t n
 
 // Contiguous fragments: fragment p is the single segment frags[p].
 int plan_table(const cocodc_fragment_t* frags, int32_t K, uint64_t n_total, const int64_t* I_p,
-               const int64_t* t_b, Plan* plan) {
+               const int64_t* t_b, Plan* plan, const uint8_t* recv_mask = nullptr) {
   if (!frags) return COCODC_ERR_NULL;
   if (K < 1 || K > COCODC_MAX_FRAGMENTS) return COCODC_ERR_RANGE;
   std::vector<cocodc_segment_t> segs(static_cast<size_t>(K));
   for (int32_t p = 0; p < K; ++p) segs[p] = cocodc_segment_t{frags[p].offset, frags[p].length, p, 0};
-  return plan_segments(segs.data(), K, K, n_total, I_p, t_b, plan);
+  return plan_segments(segs.data(), K, K, n_total, I_p, t_b, plan, recv_mask);
 }
 
 int upload_table(const std::vector<FragRec>& recs, FragRec* dst, hipStream_t s) {

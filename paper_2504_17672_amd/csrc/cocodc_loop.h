@@ -109,31 +109,40 @@ int cocodc_loop_step(cocodc_loop_t* loop, int64_t t, const cocodc_loop_buffers_t
   *sent_out = -1;
   hipStream_t s = static_cast<hipStream_t>(stream);
 
-  // 1. fragments whose all-reduce completes now
+  // 1. fragments whose all-reduce completes now; 2. is it time to start the next one?  Both are
+  //    one event: a single call updates the arrived fragments and ranks all K for the decision.
+  std::vector<uint8_t> arrived(static_cast<size_t>(K), 0);
+  std::vector<int64_t> I_new(loop->I_p), tb_new(loop->t_b), fly_new(loop->in_flight);
+  int32_t n_rec = 0;
   for (int32_t p = 0; p < K; ++p) {
     if (loop->in_flight[p] < 0 || loop->in_flight[p] + loop->hp.tau != t) continue;
-    const int64_t I = loop->in_flight[p] - loop->t_b[p];  // Eq. 11: I_p = t_p - t_{p,b}
-    const int64_t tb = loop->t_b[p];
-    if (int rc = cocodc_sync_step(&loop->frags[p], 1, loop->n_total, buf->theta_m, buf->theta_m_send,
-                                  buf->theta_g, buf->momentum, buf->delta_g, nullptr, &I, &tb, t, 0, &loop->hp,
-                                  buf->R + p, buf->sel, buf->n_sel, nullptr, buf->workspace,
-                                  buf->workspace_bytes, stream))
-      return rc;
-    loop->I_p[p] = I;
-    loop->t_b[p] = t;
-    loop->in_flight[p] = -1;
-    received_out[(*n_received_out)++] = p;
+    I_new[p] = loop->in_flight[p] - loop->t_b[p];  // Eq. 11: I_p = t_p - t_{p,b}
+    tb_new[p] = t;
+    fly_new[p] = -1;
+    arrived[p] = 1;
+    received_out[n_rec++] = p;
   }
-
-  // 2. time to start the next fragment synchronisation?
-  if (t % loop->h != 0) return COCODC_OK;
   int32_t n_flying = 0;
-  for (int32_t p = 0; p < K; ++p) n_flying += loop->in_flight[p] >= 0 ? 1 : 0;
-  if (n_flying >= K) return COCODC_OK;
-  const int32_t want = n_flying + 1;  // the first fragment of the priority order that is not in flight
-  if (int rc = cocodc_select_fragments(K, buf->R, loop->t_b.data(), t, loop->hp.H, want, buf->sel, buf->n_sel,
-                                       buf->workspace, buf->workspace_bytes, stream))
-    return rc;
+  for (int32_t p = 0; p < K; ++p) n_flying += fly_new[p] >= 0 ? 1 : 0;
+  const bool decide = (t % loop->h == 0) && n_flying < K;
+  // the first fragment of the priority order that is not in flight is among the first n_flying + 1
+  const int32_t want = decide ? n_flying + 1 : 0;
+  if (n_rec > 0) {
+    if (int rc = cocodc_sync_event(loop->frags.data(), K, loop->n_total, arrived.data(), buf->theta_m,
+                                   buf->theta_m_send, buf->theta_g, buf->momentum, buf->delta_g, nullptr,
+                                   I_new.data(), tb_new.data(), t, want, &loop->hp, buf->R, buf->sel, buf->n_sel,
+                                   nullptr, buf->workspace, buf->workspace_bytes, stream))
+      return rc;
+    loop->I_p.swap(I_new);
+    loop->t_b.swap(tb_new);
+    loop->in_flight.swap(fly_new);
+    *n_received_out = n_rec;
+  } else if (decide) {
+    if (int rc = cocodc_select_fragments(K, buf->R, loop->t_b.data(), t, loop->hp.H, want, buf->sel, buf->n_sel,
+                                         buf->workspace, buf->workspace_bytes, stream))
+      return rc;
+  }
+  if (!decide) return COCODC_OK;
   std::vector<int32_t> order(static_cast<size_t>(want));
   HIP_TRY(hipMemcpyAsync(order.data(), buf->sel, sizeof(int32_t) * want, hipMemcpyDeviceToHost, s));
   HIP_TRY(hipStreamSynchronize(s));

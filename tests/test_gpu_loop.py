@@ -117,3 +117,70 @@ def test_loop_rejects_bad_arguments(B):
     assert B.cocodc_loop_observe(loop, 1.0, 1.0, 1.5) == B.COCODC_ERR_RANGE
     assert B.cocodc_loop_observe(loop, float("nan"), 1.0, 0.5) == B.COCODC_ERR_NONFINITE
     B.cocodc_loop_destroy(loop)
+
+
+# ------------------------------------------------------------------ one loop event in one call
+def test_sync_event_random_masks(B, ref):
+    """cocodc_sync_event against the oracle's event function: random arrival masks (none, some, all),
+    old scores that must survive for the fragments that did not arrive (infinities and a NaN among
+    them), every merge mode; stored values, scores, untouched rows and the selection identical."""
+    import random
+    rng = random.Random(77)
+    for case in range(40):
+        K = rng.choice([1, 2, 4, 9, 24])
+        sizes = tuple(rng.choice([0, 1, 5, 2048, 4097, rng.randrange(1, 20000)]) for _ in range(K))
+        wl = synth.Workload(f"event-{case}", sizes, tau=rng.choice([0, 2, 5]), H=rng.choice([1, 3, 100]))
+        n = max(wl.n_total, 1)
+        pad_big = rng.random() < 0.2
+        n_alloc = n + 16 + ((1 << 24) if pad_big else 0)
+        mask = [rng.random() < rng.choice([0.0, 0.3, 1.0]) for _ in range(K)]
+        merge_mode = rng.choice([0, 0, 1, 2])
+        hpk = dict(lam=rng.choice([0.0, 0.5, 3.0]), nesterov=rng.choice([0, 1]), drift_sign=rng.choice([1, -1]),
+                   score_src=rng.choice([0, 1]), norm_kind=rng.choice([1, 2]), merge_mode=merge_mode, alpha=0.5,
+                   delta_src=rng.choice([0, 1]) if merge_mode == 0 else 0)
+        print(f"case event #{case} K={K} n={n_alloc} mask={[int(m) for m in mask]} tau={wl.tau} H={wl.H} hp={hpk}",
+              flush=True)
+        base = synth.Workload("e", (n_alloc,), tau=wl.tau, H=wl.H)
+        st = synth.make_state(base, "cuda", seed=case, amplified=rng.random() < 0.5)
+        host = U.host_copy(st)
+        ghp, rhp = B.hparams(wl.tau, wl.H, **hpk), ref.hparams(wl.tau, wl.H, **hpk)
+        I_p = [rng.choice([0, 1, 7, 30]) for _ in range(K)]
+        t_b = [1000 - rng.choice([0, 1, 2, 3, 99, 100, 500]) for _ in range(K)]
+        budget = rng.randrange(0, K + 2)
+        R0 = np.array([rng.choice([np.inf, 0.0, 0.5, 2.0, rng.random(), np.nan if K > 3 and rng.random() < 0.1 else 1.5])
+                       for _ in range(K)])
+        R_dev = torch.from_numpy(R0.copy()).cuda()
+        sums_dev = torch.full((K, 4), -3.0, dtype=torch.float64, device="cuda")
+        out = U.gpu_outputs(K)
+        pg = torch.full((n_alloc,), 555.0, device="cuda")
+        ws = B.new_workspace(K, n_alloc)
+        rc = B.cocodc_sync_event(wl.frags, n_alloc, mask, st["theta_m"], st["theta_m_send"], st["theta_g"],
+                                 st["momentum"], st["delta_g"], pg, I_p, t_b, 1000, budget, ghp, R_dev, out["sel"],
+                                 out["n_sel"], sums_dev, ws)
+        assert rc == 0, B.cocodc_status_string(rc)
+        torch.cuda.synchronize()
+        R_ref = R0.copy()
+        sums_ref = np.full((K, 4), -3.0)
+        h_pg = np.full(n_alloc, 555.0, np.float32)
+        ro = ref.sync_event(wl.frags, mask, host["theta_m"], host["theta_m_send"], host["theta_g"], host["momentum"],
+                            host["delta_g"], h_pg, I_p, t_b, 1000, budget, rhp, R_ref, sums=sums_ref)
+        assert ro["rc"] == 0
+        for k in ("theta_m", "theta_g", "momentum", "theta_m_send", "delta_g"):
+            assert np.array_equal(st[k].cpu().numpy(), host[k]), k
+        assert np.array_equal(pg.cpu().numpy().view(np.uint32), h_pg.view(np.uint32))
+        Rg = R_dev.cpu().numpy()
+        arrived = np.array(mask, bool)
+        # scores of fragments that did not arrive: the very same bits as before
+        assert np.array_equal(Rg[~arrived].view(np.uint64), R0[~arrived].view(np.uint64))
+        fin = arrived & np.isfinite(R_ref)
+        assert np.array_equal(np.isposinf(Rg[arrived]), np.isposinf(R_ref[arrived]))
+        assert U.rel_err(Rg[fin], R_ref[fin]) <= U.SCORE_TOL_TIGHT
+        sg = sums_dev.cpu().numpy()
+        assert np.array_equal(sg[~arrived], sums_ref[~arrived])
+        assert U.rel_err(sg[arrived], sums_ref[arrived]) <= U.SCORE_TOL_TIGHT
+        n_sel = int(out["n_sel"].item())
+        assert n_sel == min(budget, K)
+        got = out["sel"][:n_sel].cpu().tolist()
+        if got != ro["sel"].tolist():   # only if two deciding scores are closer than the summation error
+            bk = synth.Bookkeeping(t_g=1000, t_b=t_b, I_p=I_p)
+            assert not np.isnan(R_ref).any() and U.selection_margin(R_ref, bk, wl.H, n_sel) < 1e-9
