@@ -151,6 +151,17 @@ def test_invalid_arguments_are_rejected_before_any_device_work(B):
     assert step(tm=tg) == B.COCODC_ERR_ALIAS
     assert step(pg=dg + nb // 2) == B.COCODC_ERR_ALIAS
     assert step(sums=R) == B.COCODC_ERR_ALIAS
+
+    def event(mask, **kw):
+        a = dict(tm=tm, R=R, ws=ws, wsb=wsb, frags=frags)
+        a.update(kw)
+        return B.cocodc_sync_event(a["frags"], n, mask, a["tm"], ts, tg, m, dg, pg, I_p, t_b, 10, 1, hp, a["R"], sel,
+                                   nsel, sums, a["ws"], a["wsb"], stream=0)
+    assert event(None) == B.COCODC_ERR_NULL
+    assert event([1, 0], tm=None) == B.COCODC_ERR_NULL
+    assert event([1, 0], R=R + 4) == B.COCODC_ERR_ALIGN
+    assert event([0, 0], frags=[(0, 2048), (2047, 2049)]) == B.COCODC_ERR_RANGE   # checked whatever the mask says
+    assert event([1, 1], wsb=wsb - 1) == B.COCODC_ERR_WORKSPACE
     assert step(ws=tm) == B.COCODC_ERR_ALIAS
 
     assert B.cocodc_pseudograd(frags, n, tg, tm, None, None, ws, wsb, stream=0) == B.COCODC_ERR_NULL
