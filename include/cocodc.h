@@ -207,6 +207,28 @@ int cocodc_sync_step(const cocodc_fragment_t* frags, int32_t K, uint64_t n_total
                      double* sums_out /* nullable */, void* workspace, size_t workspace_bytes,
                      void* stream);
 
+/* cocodc_sync_step for callers that cannot allocate device memory: code that runs under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, checks and
+ * results (bit for bit) as cocodc_sync_step, without the workspace: the device-side fragment
+ * table and the per-tile partial sums live in a fixed array of COCODC_NOALLOC_SCRATCH_BYTES inside
+ * the library (one per GPU, held until the process ends).  The call itself allocates nothing on
+ * the device and frees nothing.
+ *   Limit: cocodc_workspace_bytes(K, n_total) <= COCODC_NOALLOC_SCRATCH_BYTES, i.e. about
+ *   8.5e9 elements (the 7B fragment set needs 52 MB); larger calls return COCODC_ERR_WORKSPACE
+ *   and launch nothing.
+ *   The GPU that `stream` belongs to must be the current device.  The first call on a GPU looks up
+ *   the array's address there (make it outside a graph capture).
+ *   All calls on one GPU share the array: two of them must not be in flight at the same time
+ *   (issue them on one stream, or order the streams); they would race on the partial sums.
+ *   Nothing in the array needs clearing between calls. */
+#define COCODC_NOALLOC_SCRATCH_BYTES (64u << 20)
+int cocodc_sync_step_noalloc(const cocodc_fragment_t* frags, int32_t K, uint64_t n_total, float* theta_m,
+                             const float* theta_m_send, float* theta_g, float* momentum,
+                             const float* delta_g, float* delta_m_out /* nullable */, const int64_t* I_p,
+                             const int64_t* t_b, int64_t t_g, int32_t budget, const cocodc_hparams_t* hp,
+                             double* R_out, int32_t* sel_out, int32_t* n_sel_out,
+                             double* sums_out /* nullable */, void* stream);
+
 /* One event of the loop of Sec. 3.2 in one call: "the fragments q with recv_mask[q] != 0 have
  * just arrived; which fragment is sent next?".  recv_mask: host, K entries.  The marked
  * fragments get exactly what cocodc_sync_step does for them (Eq. 2, Algorithm 1, next

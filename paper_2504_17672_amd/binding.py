@@ -37,7 +37,8 @@ COCODC_ERR_ALIAS = -7
 
 EXPORTS = (
     "cocodc_workspace_bytes", "cocodc_pseudograd", "cocodc_outer_nesterov", "cocodc_delay_compensate",
-    "cocodc_fragment_scores", "cocodc_select_fragments", "cocodc_sync_step", "cocodc_sync_event", "cocodc_sync_plan",
+    "cocodc_fragment_scores", "cocodc_select_fragments", "cocodc_sync_step", "cocodc_sync_step_noalloc",
+    "cocodc_sync_event", "cocodc_sync_plan",
     "cocodc_workspace_bytes_segmented", "cocodc_fragment_scores_segmented", "cocodc_sync_step_segmented",
     "cocodc_pseudograd_bf16", "cocodc_sync_step_bf16", "cocodc_select_fragments_bytes",
     "cocodc_loop_create", "cocodc_loop_destroy", "cocodc_loop_reset_scores", "cocodc_loop_observe",
@@ -90,6 +91,8 @@ _lib.cocodc_select_fragments.argtypes = [C.c_int32, _P, _i64_p, C.c_int64, C.c_i
                                          C.c_size_t, _P]
 _lib.cocodc_sync_step.argtypes = [_frag_p, C.c_int32, C.c_uint64, _P, _P, _P, _P, _P, _P, _i64_p, _i64_p,
                                   C.c_int64, C.c_int32, _hp_p, _P, _P, _P, _P, _P, C.c_size_t, _P]
+_lib.cocodc_sync_step_noalloc.argtypes = [_frag_p, C.c_int32, C.c_uint64, _P, _P, _P, _P, _P, _P, _i64_p, _i64_p,
+                                          C.c_int64, C.c_int32, _hp_p, _P, _P, _P, _P, _P]
 _lib.cocodc_sync_event.argtypes = [_frag_p, C.c_int32, C.c_uint64, _P, _P, _P, _P, _P, _P, _P, _i64_p, _i64_p,
                                    C.c_int64, C.c_int32, _hp_p, _P, _P, _P, _P, _P, C.c_size_t, _P]
 _lib.cocodc_sync_event.restype = C.c_int
@@ -333,6 +336,19 @@ def cocodc_sync_step(frags, n_total, theta_m, theta_m_send, theta_g, momentum, d
                                  _i64(t_b), int(t_g), int(budget), C.byref(hp) if hp is not None else None,
                                  _ptr(R_out), _ptr(sel_out), _ptr(n_sel_out), _ptr(sums_out), wp, wb,
                                  _stream(stream))
+
+
+COCODC_NOALLOC_SCRATCH_BYTES = 64 << 20
+
+
+def cocodc_sync_step_noalloc(frags, n_total, theta_m, theta_m_send, theta_g, momentum, delta_g, delta_m_out, I_p,
+                             t_b, t_g, budget, hp, R_out, sel_out, n_sel_out, sums_out, stream=None, K=None):
+    fa, k = _frags(frags)
+    return _lib.cocodc_sync_step_noalloc(fa, k if K is None else K, int(n_total), _ptr(theta_m),
+                                         _ptr(theta_m_send), _ptr(theta_g), _ptr(momentum), _ptr(delta_g),
+                                         _ptr(delta_m_out), _i64(I_p), _i64(t_b), int(t_g), int(budget),
+                                         C.byref(hp) if hp is not None else None, _ptr(R_out), _ptr(sel_out),
+                                         _ptr(n_sel_out), _ptr(sums_out), _stream(stream))
 
 
 def cocodc_sync_event(frags, n_total, recv_mask, theta_m, theta_m_send, theta_g, momentum, delta_g, delta_m_out,

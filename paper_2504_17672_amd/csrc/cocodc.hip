@@ -244,17 +244,17 @@ int cocodc_select_fragments(int32_t K, const double* R, const int64_t* t_b, int6
   return COCODC_OK;
 }
 
-static int sync_step_impl(Plan& pl, int32_t K, uint64_t n_total, float* theta_m, const float* theta_m_send,
-                          float* theta_g, float* momentum, const float* delta_g, float* delta_m_out, int64_t t_g,
-                          int32_t budget, const cocodc_hparams_t* hp, double* R_out, int32_t* sel_out,
-                          int32_t* n_sel_out, double* sums_out, void* workspace, size_t workspace_bytes_,
-                          void* stream) {
-  if (int rc = check_workspace(workspace, workspace_bytes_, pl.S, K, n_total)) return rc;
-  const int n = budget < K ? budget : K;
+// The buffers of the fused step may not overlap, except that the pseudo-gradient may be written
+// over delta_g.  A NULL entry (an optional buffer, or no workspace to check yet) overlaps nothing.
+static int sync_step_overlaps(int32_t K, uint64_t n_total, const float* theta_m, const float* theta_m_send,
+                              const float* theta_g, const float* momentum, const float* delta_g,
+                              const float* delta_m_out, int n_sel_max, const double* R_out, const int32_t* sel_out,
+                              const int32_t* n_sel_out, const double* sums_out, const void* workspace,
+                              size_t workspace_bytes_) {
   const size_t nb = n_total * sizeof(float);
   const Span sp[] = {{theta_m, nb},     {theta_m_send, nb},           {theta_g, nb},
                      {momentum, nb},    {delta_g, nb},                {delta_m_out, nb},
-                     {R_out, sizeof(double) * K}, {sel_out, sizeof(int32_t) * n}, {n_sel_out, sizeof(int32_t)},
+                     {R_out, sizeof(double) * K}, {sel_out, sizeof(int32_t) * n_sel_max}, {n_sel_out, sizeof(int32_t)},
                      {sums_out, sizeof(double) * 4 * K}, {workspace, workspace_bytes_}};
   const int ns = static_cast<int>(sizeof(sp) / sizeof(sp[0]));
   for (int i = 0; i < ns; ++i) {
@@ -263,6 +263,19 @@ static int sync_step_impl(Plan& pl, int32_t K, uint64_t n_total, float* theta_m,
       if (overlap(sp[i], sp[j])) return COCODC_ERR_ALIAS;
     }
   }
+  return COCODC_OK;
+}
+
+static int sync_step_impl(Plan& pl, int32_t K, uint64_t n_total, float* theta_m, const float* theta_m_send,
+                          float* theta_g, float* momentum, const float* delta_g, float* delta_m_out, int64_t t_g,
+                          int32_t budget, const cocodc_hparams_t* hp, double* R_out, int32_t* sel_out,
+                          int32_t* n_sel_out, double* sums_out, void* workspace, size_t workspace_bytes_,
+                          void* stream) {
+  if (int rc = check_workspace(workspace, workspace_bytes_, pl.S, K, n_total)) return rc;
+  const int n = budget < K ? budget : K;
+  if (int rc = sync_step_overlaps(K, n_total, theta_m, theta_m_send, theta_g, momentum, delta_g, delta_m_out, n, R_out,
+                                  sel_out, n_sel_out, sums_out, workspace, workspace_bytes_))
+    return rc;
   hipStream_t s = static_cast<hipStream_t>(stream);
   WorkspaceView v = view(workspace, pl.S, K);
   if (int rc = upload_table(pl.recs, v.table, s)) return rc;
@@ -313,6 +326,58 @@ int cocodc_sync_step(const cocodc_fragment_t* frags, int32_t K, uint64_t n_total
   if (int rc = plan_table(frags, K, n_total, I_p, t_b, &pl)) return rc;
   return sync_step_impl(pl, K, n_total, theta_m, theta_m_send, theta_g, momentum, delta_g, delta_m_out, t_g, budget,
                         hp, R_out, sel_out, n_sel_out, sums_out, workspace, workspace_bytes_, stream);
+}
+
+// ---- the fused step for callers that cannot allocate device memory --------------------------
+// The device-side table and the per-tile partial sums, which the other entry points keep in the
+// caller's workspace, live in this file-scope array instead: one copy per GPU, held from the
+// moment the library's code is loaded on that GPU until the process ends.  `scratch` is only the
+// host-side name of the symbol; its device address on each GPU is looked up once, with that GPU
+// current, and kept in g_scratch_ptr.  Host code uses that pointer, never the name.
+static __device__ __align__(256) unsigned char scratch[COCODC_NOALLOC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+int scratch_of_current_device(void** out) {
+  int dev = -1;
+  HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return COCODC_ERR_RANGE;
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) return hip_fail(hipErrorInvalidSymbol);
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return COCODC_OK;
+}
+}  // namespace
+
+int cocodc_sync_step_noalloc(const cocodc_fragment_t* frags, int32_t K, uint64_t n_total, float* theta_m,
+                             const float* theta_m_send, float* theta_g, float* momentum, const float* delta_g,
+                             float* delta_m_out, const int64_t* I_p, const int64_t* t_b, int64_t t_g,
+                             int32_t budget, const cocodc_hparams_t* hp, double* R_out, int32_t* sel_out,
+                             int32_t* n_sel_out, double* sums_out, void* stream) {
+  if (int rc = sync_step_check(theta_m, theta_m_send, theta_g, momentum, delta_g, delta_m_out, I_p, t_b, budget, hp,
+                               R_out, sel_out, n_sel_out, sums_out))
+    return rc;
+  Plan pl;
+  if (int rc = plan_table(frags, K, n_total, I_p, t_b, &pl)) return rc;
+  // the fixed array must hold what cocodc_workspace_bytes(K, n_total) asks for
+  if (workspace_bytes(pl.S, K, n_total) > static_cast<size_t>(COCODC_NOALLOC_SCRATCH_BYTES)) return COCODC_ERR_WORKSPACE;
+  if (int rc = sync_step_overlaps(K, n_total, theta_m, theta_m_send, theta_g, momentum, delta_g, delta_m_out,
+                                  budget < K ? budget : K, R_out, sel_out, n_sel_out, sums_out, nullptr, 0))
+    return rc;
+  void* ws = nullptr;  // every check that needs no device is done: only now is the GPU touched
+  if (int rc = scratch_of_current_device(&ws)) return rc;
+  // Nothing in the array has to start at zero: the table is rewritten by every call and every
+  // partial-sum slot that the reduction reads was written by this call's streaming kernel.
+  return sync_step_impl(pl, K, n_total, theta_m, theta_m_send, theta_g, momentum, delta_g, delta_m_out, t_g, budget,
+                        hp, R_out, sel_out, n_sel_out, sums_out, ws, COCODC_NOALLOC_SCRATCH_BYTES, stream);
 }
 
 int cocodc_sync_event(const cocodc_fragment_t* frags, int32_t K, uint64_t n_total, const uint8_t* recv_mask,

@@ -152,6 +152,26 @@ def test_invalid_arguments_are_rejected_before_any_device_work(B):
     assert step(pg=dg + nb // 2) == B.COCODC_ERR_ALIAS
     assert step(sums=R) == B.COCODC_ERR_ALIAS
 
+    # the entry point without a workspace: same checks, and a size limit instead of a workspace size
+    def noalloc(**kw):
+        a = dict(frags=frags, n=n, tm=tm, budget=1, hp=hp, R=R, K=None)
+        a.update(kw)
+        return B.cocodc_sync_step_noalloc(a["frags"], a["n"], a["tm"], ts, tg, m, dg, pg, I_p, t_b, 10, a["budget"],
+                                          a["hp"], a["R"], sel, nsel, sums, stream=0, K=a["K"])
+    assert noalloc(tm=None) == B.COCODC_ERR_NULL
+    assert noalloc(R=R + 4) == B.COCODC_ERR_ALIGN
+    assert noalloc(budget=-1) == B.COCODC_ERR_RANGE
+    assert noalloc(hp=B.hparams(5, 0)) == B.COCODC_ERR_RANGE
+    assert noalloc(frags=[(0, 2048), (2047, 2049)]) == B.COCODC_ERR_RANGE
+    assert noalloc(tm=tg) == B.COCODC_ERR_ALIAS
+    big = 1 << 34
+    assert B.cocodc_workspace_bytes(2, big) > B.COCODC_NOALLOC_SCRATCH_BYTES
+    assert noalloc(frags=[(0, big // 2), (big // 2, big // 2)], n=big) in (B.COCODC_ERR_WORKSPACE, B.COCODC_ERR_ALIAS)
+    assert B.cocodc_sync_step_noalloc([(0, big)], big, base, base + (1 << 40), base + (2 << 40), base + (3 << 40),
+                                      base + (4 << 40), None, [1], [0], 10, 1, hp, base + (5 << 40),
+                                      base + (5 << 40) + 4096, base + (5 << 40) + 8192, None, stream=0) \
+        == B.COCODC_ERR_WORKSPACE
+
     def event(mask, **kw):
         a = dict(tm=tm, R=R, ws=ws, wsb=wsb, frags=frags)
         a.update(kw)
