@@ -229,16 +229,22 @@ int cocodc_sync_step_noalloc(const cocodc_fragment_t* frags, int32_t K, uint64_t
                              double* R_out, int32_t* sel_out, int32_t* n_sel_out,
                              double* sums_out /* nullable */, void* stream);
 
-/* One event of the loop of Sec. 3.2 in one call: "the fragments q with recv_mask[q] != 0 have
- * just arrived; which fragment is sent next?".  recv_mask: host, K entries.  The marked
- * fragments get exactly what cocodc_sync_step does for them (Eq. 2, Algorithm 1, next
- * pseudo-gradient) and a fresh score R[q] (Eq. 11, from I_p[q]); every other fragment keeps
+/* One event of the loop of Sec. 3.2 in one call: "these fragments have just arrived, those are
+ * still in flight; which fragment is sent next?".  recv_mask: host, K entries, each a combination
+ * of COCODC_MASK_ARRIVED and COCODC_MASK_IN_FLIGHT (any other bit: COCODC_ERR_RANGE).
+ * Fragments marked ARRIVED get exactly what cocodc_sync_step does for them (Eq. 2, Algorithm 1,
+ * next pseudo-gradient) and a fresh score R[q] (Eq. 11, from I_p[q]); every other fragment keeps
  * its buffers, its R[p] and its row of sums_out, whatever I_p[p] says.  R (device, K) is
  * therefore read AND written: it must hold the scores of earlier events, +inf for fragments
- * that were never synchronised (cocodc_loop_reset_scores).  Algorithm 2 then runs over all K
- * scores with t_b as passed: the caller has already set t_b[q] of the arrived fragments to
- * the current step.  A mask without any mark reduces the call to the selection.  Everything
- * else (ownership, alignment, aliasing, errors) as for cocodc_sync_step. */
+ * that were never synchronised (cocodc_loop_reset_scores).  Algorithm 2 then runs over the
+ * scores of the fragments NOT marked IN_FLIGHT (the send-time record of a fragment whose
+ * all-reduce is still under way must not be overwritten), with t_b as passed: the caller has
+ * already set t_b[q] of the arrived fragments to the current step.  It writes
+ * min(budget, number of fragments not in flight) indices.  A mask without any mark reduces the
+ * call to the selection.  Everything else (ownership, alignment, aliasing, errors) as for
+ * cocodc_sync_step. */
+#define COCODC_MASK_ARRIVED 1u
+#define COCODC_MASK_IN_FLIGHT 2u
 int cocodc_sync_event(const cocodc_fragment_t* frags, int32_t K, uint64_t n_total,
                       const uint8_t* recv_mask, float* theta_m,
                       const float* theta_m_send /* nullable as in cocodc_sync_step */, float* theta_g,
@@ -298,7 +304,8 @@ int cocodc_sync_plan(int32_t K, int32_t H, double gamma, double T_c, double T_s,
 
 /* Host-side schedule state of one worker: which fragment was sent when, t_{p,b}, I_p, the
  * moving averages of T_c and T_s and the resulting N and h (Eq. 9, Eq. 10).  Opaque; lives in
- * host memory only. */
+ * host memory only (from the first send decision on it also owns four bytes of pinned host
+ * memory and one HIP event).  One loop object is for one thread at a time. */
 typedef struct cocodc_loop cocodc_loop_t;
 
 /* Device buffers the loop works on (all caller-owned; see the conventions above). */
@@ -336,25 +343,44 @@ int cocodc_loop_observe(cocodc_loop_t* loop, double T_c_sample, double T_s_sampl
 /* Current plan: N (Eq. 9) and h (Eq. 10, at least 1). */
 int cocodc_loop_plan(const cocodc_loop_t* loop, int64_t* N_out, int64_t* h_out);
 
-/* Fragments whose all-reduce, launched at step t - tau, completes at step t (ascending).
- * Lets the caller put their averaged pseudo-gradients into delta_g before cocodc_loop_step. */
-int cocodc_loop_due(const cocodc_loop_t* loop, int64_t t, int32_t* due_out, int32_t* n_due_out);
+/* Fragments whose all-reduce, launched at step t - tau or earlier, is complete at step t and has
+ * not been received yet (ascending).  Lets the caller put their averaged pseudo-gradients into
+ * delta_g before cocodc_loop_step.  Reads back a send decision that is still pending if that
+ * fragment could be among them. */
+int cocodc_loop_due(cocodc_loop_t* loop, int64_t t, int32_t* due_out, int32_t* n_due_out);
 
-/* One inner step t = 1, 2, ... of the worker, called after its local optimiser step:
+/* One inner step t of the worker, called after its local optimiser step; t >= 1 and larger than
+ * the t of the previous call (COCODC_ERR_RANGE otherwise; steps without an event may be skipped):
  *  1. every fragment due at t is received, in ascending index: the fused step
- *     (cocodc_sync_step) on that fragment alone with I_p = t_p - t_{p,b} (Eq. 11), which
- *     updates R_p; then t_{p,b} <- t.
+ *     (cocodc_sync_step) on that fragment alone with I_p = max(1, t_p - t_{p,b}) (Eq. 11; the
+ *     interval of a fragment sent again at the very step its previous synchronisation completed
+ *     counts as one step, so that R_p = +infinity remains the mark of a fragment that was never
+ *     synchronised), which updates R_p; then t_{p,b} <- t.
  *  2. if t is a multiple of h: Algorithm 2 picks p* among the fragments that are not in flight
  *     (t_g = t); its pseudo-gradient goes to delta_m_out and theta_m_send records the
- *     send-time parameters (cocodc_pseudograd); it will be due at t + tau.
- * received_out (host, K int32), n_received_out, sent_out (host; -1 if nothing was sent).
- * Synchronises the stream when it has to read the selection back (once per send). */
+ *     send-time parameters; it will be due at t + tau.
+ * Both happen on the device and the call never waits for the stream: p* is chosen by the
+ * selection kernel and the pseudo-gradient kernel reads it from device memory.
+ * received_out (host, K int32), n_received_out.  sent_out (host): -1 if this step took no send
+ * decision, COCODC_LOOP_SENT_PENDING if it took one; which fragment it was is copied to the host
+ * asynchronously, and cocodc_loop_last_sent tells (it waits for that copy and for nothing else).
+ * The schedule itself reads the copy back when it next needs it: at the next send decision or
+ * when the fragment could be due, whichever comes first.
+ * Every pointer of `buf` is checked before anything is enqueued (delta_m_out and theta_m_send are
+ * required): a rejected step changes neither the buffers nor the schedule. */
+#define COCODC_LOOP_SENT_PENDING (-2)
 int cocodc_loop_step(cocodc_loop_t* loop, int64_t t, const cocodc_loop_buffers_t* buf, void* stream,
                      int32_t* received_out, int32_t* n_received_out, int32_t* sent_out);
 
+/* The most recent send decision: the step it was taken at and the fragment (-1, -1 before the
+ * first; fragment -1 if nothing was eligible).  Waits until that decision has been copied to the
+ * host.  A caller that launches the all-reduce from the host calls this right after the step. */
+int cocodc_loop_last_sent(cocodc_loop_t* loop, int64_t* t_sent_out, int32_t* sent_out);
+
 /* Copies the bookkeeping out (host arrays of K): t_{p,b}, the I_p used at the last receive
- * (0 = never), and the send step of a fragment in flight (-1 = not in flight). */
-int cocodc_loop_state(const cocodc_loop_t* loop, int64_t* t_b_out, int64_t* I_p_out, int64_t* in_flight_out);
+ * (0 = never), and the send step of a fragment in flight (-1 = not in flight).  Reads back a
+ * pending send decision first. */
+int cocodc_loop_state(cocodc_loop_t* loop, int64_t* t_b_out, int64_t* I_p_out, int64_t* in_flight_out);
 
 /* ---- data layout in HBM (no paper counterpart) ---- */
 

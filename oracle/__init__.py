@@ -211,8 +211,9 @@ def fragment_scores_segmented(segs, K, x, I_p, norm_kind=2):
 
 def sync_event(frags, recv_mask, theta_m, theta_m_send, theta_g, momentum, delta_g, delta_m_out, I_p, t_b, t_g,
                budget, hp, R, sums=None):
-    """One loop event: fused step on the fragments marked in recv_mask, R (numpy float64, K) updated in
-    place for them, selection over all K.  Returns dict rc, sel."""
+    """One loop event: fused step on the fragments whose recv_mask entry has bit 0 set (True counts as 1),
+    R (numpy float64, K) updated in place for them, selection over the fragments whose entry does not have
+    bit 1 (in flight) set.  Returns dict rc, sel."""
     K = len(frags)
     n = theta_m.size
     assert R.dtype == np.float64 and R.size == K

@@ -219,16 +219,20 @@ int cocodc_ref_fragment_scores(const cocodc_ref_fragment_t* frags, int32_t K, ui
   return kOk;
 }
 
-// Algorithm 2, run `budget` times; a fragment already chosen in this call is skipped.
+// Algorithm 2, run `budget` times; a fragment already chosen in this call is skipped, and so
+// is one whose all-reduce is still in flight (in_flight, nullable: nobody is).
 // Each run: the first fragment (lowest index) not synchronised for at least H steps
 // wins; otherwise the fragment with the largest R_p, the first one on ties.  A NaN
 // score never beats a number (it can only be chosen when nothing else is left).
-int cocodc_ref_select_fragments(int32_t K, const double* R, const int64_t* t_b, int64_t t_g,
-                                int32_t H, int32_t budget, int32_t* sel_out, int32_t* n_sel_out) {
-  if (!R || !t_b || !sel_out || !n_sel_out) return kErrNull;
-  if (K < 1 || H < 1 || budget < 0) return kErrRange;
+namespace {
+int select_among(int32_t K, const double* R, const int64_t* t_b, int64_t t_g, int32_t H,
+                 int32_t budget, const uint8_t* in_flight, int32_t* sel_out, int32_t* n_sel_out) {
   std::vector<char> taken(static_cast<size_t>(K), 0);
-  const int32_t n_sel = budget < K ? budget : K;
+  int32_t candidates = 0;
+  for (int32_t p = 0; p < K; ++p) {
+    if (in_flight && in_flight[p]) taken[p] = 1; else ++candidates;
+  }
+  const int32_t n_sel = budget < candidates ? budget : candidates;
   for (int32_t b = 0; b < n_sel; ++b) {
     int32_t p_star = -1;
     for (int32_t p = 0; p < K; ++p) {
@@ -253,6 +257,14 @@ int cocodc_ref_select_fragments(int32_t K, const double* R, const int64_t* t_b, 
   }
   *n_sel_out = n_sel;
   return kOk;
+}
+}  // namespace
+
+int cocodc_ref_select_fragments(int32_t K, const double* R, const int64_t* t_b, int64_t t_g,
+                                int32_t H, int32_t budget, int32_t* sel_out, int32_t* n_sel_out) {
+  if (!R || !t_b || !sel_out || !n_sel_out) return kErrNull;
+  if (K < 1 || H < 1 || budget < 0) return kErrRange;
+  return select_among(K, R, t_b, t_g, H, budget, nullptr, sel_out, n_sel_out);
 }
 
 int cocodc_ref_select_fragments_bytes(int32_t K, const double* R, const int64_t* t_b, int64_t t_g,
@@ -303,9 +315,10 @@ int cocodc_ref_sync_step(const cocodc_ref_fragment_t* frags, int32_t K, uint64_t
   return cocodc_ref_select_fragments(K, R_out, t_b, t_g, hp->H, budget, sel_out, n_sel_out);
 }
 
-/* One event of the loop of Sec. 3.2: the fragments q with recv_mask[q] != 0 have just arrived
- * (Alg. 1 and Eq. 2 for them, their scores R_q of Eq. 11 replace the old ones); the others keep
- * their buffers and their scores; then Alg. 2 looks at all K scores. */
+/* One event of the loop of Sec. 3.2.  recv_mask[q] bit 0: fragment q has just arrived (Alg. 1 and
+ * Eq. 2 for it, its score R_q of Eq. 11 replaces the old one); the others keep their buffers and
+ * their scores.  Bit 1: fragment q is in flight and cannot be chosen.  Then Alg. 2 looks at the
+ * scores of all fragments that are not in flight. */
 int cocodc_ref_sync_event(const cocodc_ref_fragment_t* frags, int32_t K, uint64_t n_total,
                           const uint8_t* recv_mask, float* theta_m, const float* theta_m_send,
                           float* theta_g, float* momentum, const float* delta_g, float* delta_m_out,
@@ -318,8 +331,13 @@ int cocodc_ref_sync_event(const cocodc_ref_fragment_t* frags, int32_t K, uint64_
   if (int rc = check_hparams(hp)) return rc;
   if (!theta_m_send && (hp->merge_mode == 0 || hp->score_src == 1)) return kErrNull;
   if (budget < 0) return kErrRange;
+  std::vector<uint8_t> in_flight(static_cast<size_t>(K), 0);
   for (int32_t q = 0; q < K; ++q) {
-    if (!recv_mask[q]) continue;
+    if (recv_mask[q] > 3) return kErrRange;
+    in_flight[q] = (recv_mask[q] & 2) ? 1 : 0;
+  }
+  for (int32_t q = 0; q < K; ++q) {
+    if (!(recv_mask[q] & 1)) continue;
     Sums s;
     for (uint64_t i = frags[q].offset; i < frags[q].offset + frags[q].length; ++i) {
       sync_element(i, theta_m, theta_m_send, theta_g, momentum, delta_g, delta_m_out, *hp, &s,
@@ -333,7 +351,7 @@ int cocodc_ref_sync_event(const cocodc_ref_fragment_t* frags, int32_t K, uint64_
       sums_out[4 * q + 3] = s.d1;
     }
   }
-  return cocodc_ref_select_fragments(K, R, t_b, t_g, hp->H, budget, sel_out, n_sel_out);
+  return select_among(K, R, t_b, t_g, hp->H, budget, in_flight.data(), sel_out, n_sel_out);
 }
 
 int cocodc_ref_sync_step_mt(const cocodc_ref_fragment_t* frags, int32_t K, uint64_t n_total,

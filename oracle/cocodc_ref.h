@@ -113,13 +113,14 @@ int cocodc_ref_sync_step(const cocodc_ref_fragment_t* frags, int32_t K, uint64_t
                          int32_t* n_sel_out, double* sums_out /* nullable */,
                          const cocodc_ref_shadow_t* shadow /* nullable */);
 
-/* One event of the loop of Sec. 3.2 in one call.  recv_mask[q] != 0 marks the fragments whose
+/* One event of the loop of Sec. 3.2 in one call.  Bit 0 of recv_mask[q] marks the fragments whose
  * averaged pseudo-gradient has just arrived: they get the fused step (Eq. 2, Alg. 1, next
  * pseudo-gradient) and a fresh score R[q] (Eq. 11, from I_p[q]); every other fragment keeps its
  * buffers, its R[p] and its row of sums_out.  R is therefore read and written: it holds the
- * scores of earlier events (+inf before a fragment's first synchronisation).  Then Alg. 2 runs
- * over all K scores with t_b as passed (the caller has already set t_b of the arrived
- * fragments to the current step). */
+ * scores of earlier events (+inf before a fragment's first synchronisation).  Bit 1 marks the
+ * fragments whose all-reduce is still in flight.  Then Alg. 2 runs `budget` times over the scores
+ * of the fragments that are not in flight, with t_b as passed (the caller has already set t_b of
+ * the arrived fragments to the current step). */
 int cocodc_ref_sync_event(const cocodc_ref_fragment_t* frags, int32_t K, uint64_t n_total,
                           const uint8_t* recv_mask, float* theta_m, const float* theta_m_send,
                           float* theta_g, float* momentum, const float* delta_g, float* delta_m_out,

@@ -3,15 +3,20 @@ single steps.  TEST INFRASTRUCTURE ONLY (see oracle/cocodc_ref.h).
 
 One worker, inner steps t = 1, 2, ...; all buffers are host numpy arrays.  Per step, after the
 worker's local update:
-  1. every fragment whose all-reduce was launched tau steps ago completes: the fused oracle
-     step on that fragment alone, with I_p = t_p - t_{p,b} (Eq. 11); then t_{p,b} <- t
-     ("the step at which the previous synchronisation was completed");
+  1. every fragment whose all-reduce was launched tau (or more) steps ago completes: the fused
+     oracle step on that fragment alone, with I_p = t_p - t_{p,b} (Eq. 11), taken as 1 when it
+     would be 0; then t_{p,b} <- t ("the step at which the previous synchronisation was
+     completed");
   2. every h steps (Eq. 10; h = floor(H/N), at least 1, N from Eq. 9) the next fragment is
      chosen by Algorithm 2 with t_g = t among the fragments that are not in flight; its
      pseudo-gradient is written to the send buffer and its parameters are recorded.
 All t_{p,b} start at 0 and all R_p at +infinity (never-synchronised fragments go first).
 Readings where the paper is silent: a fragment in flight is not eligible; h = 0 is taken as 1;
 receives happen before the send decision of the same step, in ascending fragment index.
+When a fragment is sent again at the very step its previous synchronisation completed (possible
+when a decision step coincides with an arrival), Eq. 11 as printed has I_p = t_p - t_{p,b} = 0.
+Sec. 3.2 keeps R_p = infinity for fragments that have not yet completed a synchronisation, so a
+fragment that has completed one must get a finite score: the interval is taken as one step.
 """
 import numpy as np
 
@@ -19,6 +24,9 @@ from . import pseudograd, select_fragments, sync_plan, sync_step
 
 
 class RefLoop:
+    # The interval of Eq. 11 never counts as less than this many steps (see the module text).
+    min_interval = 1
+
     def __init__(self, frags, hp, gamma, T_c, T_s):
         self.frags = [(int(o), int(l)) for o, l in frags]
         self.K = len(self.frags)
@@ -41,12 +49,12 @@ class RefLoop:
         self._replan()
 
     def due(self, t):
-        return [p for p in range(self.K) if self.in_flight[p] >= 0 and self.in_flight[p] + self.hp.tau == t]
+        return [p for p in range(self.K) if self.in_flight[p] >= 0 and self.in_flight[p] + self.hp.tau <= t]
 
     def step(self, t, theta_m, theta_m_send, theta_g, momentum, delta_g, delta_m_out):
         received = []
         for p in self.due(t):
-            I = self.in_flight[p] - self.t_b[p]
+            I = max(self.min_interval, self.in_flight[p] - self.t_b[p])
             out = sync_step([self.frags[p]], theta_m, theta_m_send, theta_g, momentum, delta_g, None,
                             [I], [self.t_b[p]], t, 0, self.hp)
             assert out["rc"] == 0

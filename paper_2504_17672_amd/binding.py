@@ -42,7 +42,7 @@ EXPORTS = (
     "cocodc_workspace_bytes_segmented", "cocodc_fragment_scores_segmented", "cocodc_sync_step_segmented",
     "cocodc_pseudograd_bf16", "cocodc_sync_step_bf16", "cocodc_select_fragments_bytes",
     "cocodc_loop_create", "cocodc_loop_destroy", "cocodc_loop_reset_scores", "cocodc_loop_observe",
-    "cocodc_loop_plan", "cocodc_loop_due", "cocodc_loop_step", "cocodc_loop_state",
+    "cocodc_loop_plan", "cocodc_loop_due", "cocodc_loop_step", "cocodc_loop_state", "cocodc_loop_last_sent",
     "cocodc_tile_elements", "cocodc_debug_tile_plan", "cocodc_debug_stream_mix",
     "cocodc_layout_stride_bytes", "cocodc_last_hip_error", "cocodc_status_string", "cocodc_set_blocks_per_cu",
     "cocodc_profiler_enable", "cocodc_profiler_collect", "cocodc_profiler_disable",
@@ -120,6 +120,7 @@ _lib.cocodc_loop_plan.argtypes = [_P, _i64_p, _i64_p]
 _lib.cocodc_loop_due.argtypes = [_P, C.c_int64, _i32_p, _i32_p]
 _lib.cocodc_loop_step.argtypes = [_P, C.c_int64, C.POINTER(cocodc_loop_buffers_t), _P, _i32_p, _i32_p, _i32_p]
 _lib.cocodc_loop_state.argtypes = [_P, _i64_p, _i64_p, _i64_p]
+_lib.cocodc_loop_last_sent.argtypes = [_P, _i64_p, _i32_p]
 _lib.cocodc_tile_elements.restype = C.c_uint64
 _lib.cocodc_tile_elements.argtypes = [C.c_uint64]
 _lib.cocodc_debug_stream_mix.argtypes = [_frag_p, C.c_int32, C.c_uint64, _P, _P, _P, _P, _P, _P, _P, C.c_size_t, _P]
@@ -354,12 +355,13 @@ def cocodc_sync_step_noalloc(frags, n_total, theta_m, theta_m_send, theta_g, mom
 def cocodc_sync_event(frags, n_total, recv_mask, theta_m, theta_m_send, theta_g, momentum, delta_g, delta_m_out,
                       I_p, t_b, t_g, budget, hp, R, sel_out, n_sel_out, sums_out, workspace, workspace_bytes=None,
                       stream=None, K=None):
-    """recv_mask: a sequence of K truth values (host).  R: device, read and written."""
+    """recv_mask: a sequence of K entries (host): bools (arrived or not) or combinations of
+    COCODC_MASK_ARRIVED / COCODC_MASK_IN_FLIGHT.  R: device, read and written."""
     fa, k = _frags(frags)
     wp, wb = _ws(workspace, workspace_bytes)
     mask = None
     if recv_mask is not None:
-        mask = (C.c_uint8 * len(recv_mask))(*[1 if m else 0 for m in recv_mask])
+        mask = (C.c_uint8 * max(len(recv_mask), 1))(*[int(m) & 0xFF for m in recv_mask])
     return _lib.cocodc_sync_event(fa, k if K is None else K, int(n_total), mask, _ptr(theta_m), _ptr(theta_m_send),
                                   _ptr(theta_g), _ptr(momentum), _ptr(delta_g), _ptr(delta_m_out), _i64(I_p),
                                   _i64(t_b), int(t_g), int(budget), C.byref(hp) if hp is not None else None,
@@ -444,8 +446,19 @@ def loop_buffers(theta_m, theta_m_send, theta_g, momentum, delta_g, delta_m_out,
                                  v(R), v(sel), v(n_sel), workspace.data_ptr(), wb)
 
 
+COCODC_LOOP_SENT_PENDING = -2
+COCODC_MASK_ARRIVED, COCODC_MASK_IN_FLIGHT = 1, 2
+
+
+def cocodc_loop_last_sent(handle):
+    """Returns (status, step of the most recent send decision, fragment sent); waits for its read-back."""
+    t, p = C.c_int64(-1), C.c_int32(-1)
+    rc = _lib.cocodc_loop_last_sent(handle[0], C.byref(t), C.byref(p))
+    return rc, t.value, p.value
+
+
 def cocodc_loop_step(handle, t, buffers, stream=None):
-    """Returns (status, [received fragments], sent fragment or -1)."""
+    """Returns (status, [received fragments], -1 or COCODC_LOOP_SENT_PENDING)."""
     rec = (C.c_int32 * max(handle[1], 1))()
     n, sent = C.c_int32(0), C.c_int32(-1)
     rc = _lib.cocodc_loop_step(handle[0], int(t), C.byref(buffers), _stream(stream), rec, C.byref(n), C.byref(sent))

@@ -22,6 +22,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <atomic>
 #include <cmath>
 #include <cstdint>
 #include <cstring>
@@ -94,7 +95,7 @@ int cocodc_pseudograd(const cocodc_fragment_t* frags, int32_t K, uint64_t n_tota
     return COCODC_ERR_ALIAS;
   hipStream_t s = static_cast<hipStream_t>(stream);
   WorkspaceView v = view(workspace, pl.S, K);
-  if (int rc = upload_table(pl.recs, v.table, s)) return rc;
+  if (int rc = upload_table(pl, v, s)) return rc;
   const bool vec = all_aligned16({theta_g_snap, theta_m, delta_m_out, theta_m_send_out});
   if (theta_m_send_out) {
     PseudoGradOp<true> op{theta_g_snap, theta_m, delta_m_out, theta_m_send_out};
@@ -119,7 +120,7 @@ int cocodc_outer_nesterov(const cocodc_fragment_t* frags, int32_t K, uint64_t n_
     return COCODC_ERR_ALIAS;
   hipStream_t s = static_cast<hipStream_t>(stream);
   WorkspaceView v = view(workspace, pl.S, K);
-  if (int rc = upload_table(pl.recs, v.table, s)) return rc;
+  if (int rc = upload_table(pl, v, s)) return rc;
   const bool vec = all_aligned16({theta_g, momentum, delta_g});
   const DevHP d = to_dev(*hp);
   if (hp->nesterov) {
@@ -147,7 +148,7 @@ int cocodc_delay_compensate(const cocodc_fragment_t* frags, int32_t K, uint64_t 
     return COCODC_ERR_ALIAS;
   hipStream_t s = static_cast<hipStream_t>(stream);
   WorkspaceView v = view(workspace, pl.S, K);
-  if (int rc = upload_table(pl.recs, v.table, s)) return rc;
+  if (int rc = upload_table(pl, v, s)) return rc;
   const bool vec = all_aligned16({theta_m, theta_m_send, theta_g});
   const DevHP d = to_dev(*hp);
   switch (merge_variant(*hp)) {
@@ -181,7 +182,7 @@ static int fragment_scores_impl(Plan& pl, int32_t K, uint64_t n_total, const flo
     return COCODC_ERR_ALIAS;
   hipStream_t s = static_cast<hipStream_t>(stream);
   WorkspaceView v = view(workspace, pl.S, K);
-  if (int rc = upload_table(pl.recs, v.table, s)) return rc;
+  if (int rc = upload_table(pl, v, s)) return rc;
   const bool vec = aligned(x, 16);
   int rc;
   if (norm_kind == 2) {
@@ -237,7 +238,7 @@ int cocodc_select_fragments(int32_t K, const double* R, const int64_t* t_b, int6
   if (int rc = plan_segments(nullptr, 0, K, 0, nullptr, t_b, &pl)) return rc;
   hipStream_t s = static_cast<hipStream_t>(stream);
   WorkspaceView v = view(workspace, pl.S, K);
-  if (int rc = upload_table(pl.recs, v.table, s)) return rc;
+  if (int rc = upload_table(pl, v, s)) return rc;
   hipLaunchKernelGGL(k_select, dim3(1), dim3(kThreads), 0, s, v.groups, K, R, t_g, static_cast<int64_t>(H),
                      n, sel_out, n_sel_out);
   HIP_TRY(hipGetLastError());
@@ -272,26 +273,31 @@ static int sync_step_impl(Plan& pl, int32_t K, uint64_t n_total, float* theta_m,
                           int32_t* n_sel_out, double* sums_out, void* workspace, size_t workspace_bytes_,
                           void* stream) {
   if (int rc = check_workspace(workspace, workspace_bytes_, pl.S, K, n_total)) return rc;
-  const int n = budget < K ? budget : K;
+  int candidates = 0, taking_part = 0;  // fragments Algorithm 2 may choose; fragments this call updates
+  for (int32_t p = 0; p < K; ++p) {
+    candidates += pl.groups[p].in_flight ? 0 : 1;
+    taking_part += pl.groups[p].takes_part ? 1 : 0;
+  }
+  const int n = budget < candidates ? budget : candidates;
   if (int rc = sync_step_overlaps(K, n_total, theta_m, theta_m_send, theta_g, momentum, delta_g, delta_m_out, n, R_out,
                                   sel_out, n_sel_out, sums_out, workspace, workspace_bytes_))
     return rc;
   hipStream_t s = static_cast<hipStream_t>(stream);
   WorkspaceView v = view(workspace, pl.S, K);
-  if (int rc = upload_table(pl.recs, v.table, s)) return rc;
-  const bool vec = all_aligned16({theta_m, theta_m_send, theta_g, momentum, delta_g, delta_m_out});
-  const DevHP d = to_dev(*hp);
-
-  int rc = hp->nesterov ? launch_fused_m<true>(merge_variant(*hp), vec, walk_of(v, pl), theta_m, theta_m_send, theta_g,
-                                               momentum, delta_g, delta_m_out, d, v.partials, s)
-                        : launch_fused_m<false>(merge_variant(*hp), vec, walk_of(v, pl), theta_m, theta_m_send,
-                                                theta_g, momentum, delta_g, delta_m_out, d, v.partials, s);
-  if (rc) return rc;
-
-  const int which = (hp->score_src ? 2 : 0) + (hp->norm_kind == 2 ? 0 : 1);
-  hipLaunchKernelGGL(k_finalize, dim3(K), dim3(kFinalizeThreads), 0, s, v.groups, v.partials, kSums, which,
-                     hp->norm_kind == 2 ? 1 : 0, R_out, sums_out, kSums);
-  HIP_TRY(hipGetLastError());
+  if (int rc = upload_table(pl, v, s)) return rc;
+  if (taking_part > 0) {
+    const bool vec = all_aligned16({theta_m, theta_m_send, theta_g, momentum, delta_g, delta_m_out});
+    const DevHP d = to_dev(*hp);
+    int rc = hp->nesterov ? launch_fused_m<true>(merge_variant(*hp), vec, walk_of(v, pl), theta_m, theta_m_send,
+                                                 theta_g, momentum, delta_g, delta_m_out, d, v.partials, s)
+                          : launch_fused_m<false>(merge_variant(*hp), vec, walk_of(v, pl), theta_m, theta_m_send,
+                                                  theta_g, momentum, delta_g, delta_m_out, d, v.partials, s);
+    if (rc) return rc;
+    const int which = (hp->score_src ? 2 : 0) + (hp->norm_kind == 2 ? 0 : 1);
+    hipLaunchKernelGGL(k_finalize, dim3(K), dim3(kFinalizeThreads), 0, s, v.groups, v.partials, kSums, which,
+                       hp->norm_kind == 2 ? 1 : 0, R_out, sums_out, kSums);
+    HIP_TRY(hipGetLastError());
+  }
   hipLaunchKernelGGL(k_select, dim3(1), dim3(kThreads), 0, s, v.groups, K, R_out, t_g,
                      static_cast<int64_t>(hp->H), n, sel_out, n_sel_out);
   HIP_TRY(hipGetLastError());
@@ -426,7 +432,7 @@ int cocodc_pseudograd_bf16(const cocodc_fragment_t* frags, int32_t K, uint64_t n
     return COCODC_ERR_ALIAS;
   hipStream_t s = static_cast<hipStream_t>(stream);
   WorkspaceView v = view(workspace, pl.S, K);
-  if (int rc = upload_table(pl.recs, v.table, s)) return rc;
+  if (int rc = upload_table(pl, v, s)) return rc;
   const bool vec = all_aligned16({theta_g_snap, theta_m, delta_m_out, theta_m_send_out});
   if (theta_m_send_out) {
     PseudoGradBf16Op<true> op{theta_g_snap, theta_m, delta_m_out, theta_m_send_out};
@@ -466,7 +472,7 @@ int cocodc_sync_step_bf16(const cocodc_fragment_t* frags, int32_t K, uint64_t n_
   }
   hipStream_t s = static_cast<hipStream_t>(stream);
   WorkspaceView v = view(workspace, pl.S, K);
-  if (int rc = upload_table(pl.recs, v.table, s)) return rc;
+  if (int rc = upload_table(pl, v, s)) return rc;
   const bool vec = all_aligned16({theta_m, theta_m_send, theta_g, momentum, delta_g, delta_m_out});
   const DevHP d = to_dev(*hp);
   int rc = hp->nesterov ? launch_fused_bf16_m<true>(merge_variant(*hp), vec, walk_of(v, pl), theta_m, theta_m_send,
@@ -498,10 +504,10 @@ int cocodc_select_fragments_bytes(int32_t K, const double* R, const int64_t* t_b
     return COCODC_ERR_ALIAS;
   Plan pl;
   if (int rc = plan_segments(nullptr, 0, K, 0, nullptr, t_b, &pl)) return rc;
-  for (int32_t p = 0; p < K; ++p) pl.recs[static_cast<size_t>(pl.S) + 1 + p].length = frag_bytes[p];
+  for (int32_t p = 0; p < K; ++p) pl.groups[p].bytes = frag_bytes[p];
   hipStream_t s = static_cast<hipStream_t>(stream);
   WorkspaceView v = view(workspace, pl.S, K);
-  if (int rc = upload_table(pl.recs, v.table, s)) return rc;
+  if (int rc = upload_table(pl, v, s)) return rc;
   hipLaunchKernelGGL(k_select_bytes, dim3(1), dim3(kThreads), 0, s, v.groups, K, R, t_g, static_cast<int64_t>(H),
                      static_cast<unsigned long long>(byte_budget), sel_out, n_sel_out);
   HIP_TRY(hipGetLastError());
@@ -555,7 +561,7 @@ int cocodc_debug_stream_mix(const cocodc_fragment_t* frags, int32_t K, uint64_t 
   }
   hipStream_t s = static_cast<hipStream_t>(stream);
   WorkspaceView v = view(workspace, pl.S, K);
-  if (int rc = upload_table(pl.recs, v.table, s)) return rc;
+  if (int rc = upload_table(pl, v, s)) return rc;
   StreamMixOp op{a, b, c, d, e, f};
   return launch_walk(all_aligned16({a, b, c, d, e, f}), walk_of(v, pl), op, v.partials, s);
 }
@@ -569,10 +575,10 @@ int cocodc_debug_tile_plan(const cocodc_segment_t* segs, int32_t S, int32_t K, u
   Plan pl;
   if (int rc = plan_segments(segs, S, K, n_total, nullptr, nullptr, &pl)) return rc;
   for (int32_t j = 0; j <= S; ++j) {
-    seg_offset_out[j] = pl.recs[j].offset;
-    seg_slot_begin_out[j] = pl.recs[j].slot_begin;
+    seg_offset_out[j] = pl.segs[j].offset;
+    seg_slot_begin_out[j] = pl.segs[j].slot_begin;
   }
-  for (int32_t p = 0; p <= K; ++p) frag_slot_begin_out[p] = pl.recs[static_cast<size_t>(S) + 1 + p].slot_begin;
+  for (int32_t p = 0; p <= K; ++p) frag_slot_begin_out[p] = pl.groups[p].slot_begin;
   *tile_capacity_out = max_tiles(S, n_total);
   return COCODC_OK;
 }
@@ -594,15 +600,13 @@ const char* cocodc_status_string(int status) {
 }
 
 int cocodc_set_blocks_per_cu(int blocks_per_cu) {
-  const int old = g_blocks_per_cu;
-  g_blocks_per_cu = blocks_per_cu < 0 ? 0 : blocks_per_cu;
-  return old;
+  return g_blocks_per_cu.exchange(blocks_per_cu < 0 ? 0 : blocks_per_cu);
 }
 
 int cocodc_profiler_enable(int32_t max_records) {
   if (max_records < 1 || max_records > 65536) return COCODC_ERR_RANGE;
   std::lock_guard<std::mutex> lock(g_prof.mu);
-  if (g_prof.on) return COCODC_ERR_RANGE;
+  if (g_prof.on.load()) return COCODC_ERR_RANGE;
   g_prof.start.resize(max_records);
   g_prof.stop.resize(max_records);
   for (int i = 0; i < max_records; ++i) {
@@ -610,14 +614,14 @@ int cocodc_profiler_enable(int32_t max_records) {
     HIP_TRY(hipEventCreate(&g_prof.stop[i]));
   }
   g_prof.used = 0;
-  g_prof.on = true;
+  g_prof.on.store(true, std::memory_order_release);
   return COCODC_OK;
 }
 
 int cocodc_profiler_collect(float* ms_out, int32_t capacity) {
   if (!ms_out) return COCODC_ERR_NULL;
   std::lock_guard<std::mutex> lock(g_prof.mu);
-  if (!g_prof.on) return COCODC_ERR_RANGE;
+  if (!g_prof.on.load()) return COCODC_ERR_RANGE;
   const int n = std::min<int>(g_prof.used, capacity);
   for (int i = 0; i < n; ++i) {
     HIP_TRY(hipEventSynchronize(g_prof.stop[i]));
@@ -629,7 +633,8 @@ int cocodc_profiler_collect(float* ms_out, int32_t capacity) {
 
 int cocodc_profiler_disable(void) {
   std::lock_guard<std::mutex> lock(g_prof.mu);
-  if (!g_prof.on) return COCODC_OK;
+  if (!g_prof.on.load()) return COCODC_OK;
+  g_prof.on.store(false, std::memory_order_release);
   for (size_t i = 0; i < g_prof.start.size(); ++i) {
     (void)hipEventDestroy(g_prof.start[i]);
     (void)hipEventDestroy(g_prof.stop[i]);
@@ -637,7 +642,6 @@ int cocodc_profiler_disable(void) {
   g_prof.start.clear();
   g_prof.stop.clear();
   g_prof.used = 0;
-  g_prof.on = false;
   return COCODC_OK;
 }
 

@@ -21,33 +21,47 @@ inline int tile_shift_for(uint64_t n_total) {
   return n_total < kSmallBufferElements ? kTileShiftSmall : kTileShiftLarge;
 }
 constexpr int kDepth = COCODC_DEPTH;  // independent 128-bit loads per stream kept in flight per lane
-constexpr int kTableChunk = 80;       // fragment records carried by one table-upload launch
+constexpr int kTableChunkWords = 240;  // 16-byte words of table carried by one upload launch
 constexpr int kSums = 4;              // doubles per partial-sum slot
 
 static_assert((1u << kTileShiftSmall) % (4 * kThreads) == 0 && kTileShiftSmall >= 10, "a tile must be a whole number of workgroup-wide vector rows");
 
-// Device-side description of one fragment.
-struct FragRec {
+// Device-side description of one segment (a contiguous piece of a fragment).
+struct SegRec {
   uint64_t offset;      // first element
-  uint64_t length;      // elements
-  uint64_t slot_begin;  // index of this fragment's first tile in the global tile list
+  uint64_t length;      // elements (0: the segment takes no part in this call)
+  uint64_t slot_begin;  // index of this segment's first tile in the global tile list
   uint64_t tile0;       // absolute window index (offset >> tile_shift) of that first tile
-  int64_t I_p;          // steps between the fragment's last two completed syncs (Eq. 11)
-  int64_t t_b;          // step of its last completed sync (Algorithm 2)
 };
-static_assert(sizeof(FragRec) == 48, "FragRec layout");
+static_assert(sizeof(SegRec) == 32, "SegRec layout");
+
+// Device-side description of one fragment as a whole (one record per fragment, K + 1 of them;
+// record K only closes the last fragment's range of tile slots).
+struct GroupRec {
+  uint64_t slot_begin;   // index of the fragment's first tile in the global tile list
+  uint64_t bytes;        // its size, for the selection under a byte budget
+  uint64_t f_offset;     // the fragment's own element range when it is one contiguous piece
+  uint64_t f_length;     //   (what the send-time walk over a fragment chosen on the device needs)
+  int64_t I_p;           // steps between the fragment's last two completed syncs (Eq. 11)
+  int64_t t_b;           // step of its last completed sync (Algorithm 2)
+  uint32_t takes_part;   // 1: this call updates the fragment and its score; 0: it leaves both alone
+  uint32_t in_flight;    // 1: an all-reduce of the fragment is under way: Algorithm 2 passes it over
+  uint64_t reserved;
+};
+static_assert(sizeof(GroupRec) == 64, "GroupRec layout");
 
 // What a streaming kernel walks: the segment records, their number S, the number of tiles T
 // (== tbl[S].slot_begin) and the tile size.
 struct Walk {
-  const FragRec* tbl;
+  const SegRec* tbl;
   uint64_t T;
   int32_t S;
   int32_t tile_shift;
 };
 
+// The tables travel to the device as kernel arguments, kTableChunkWords 16-byte words per launch.
 struct TableChunk {
-  FragRec rec[kTableChunk];
+  uint4 w[kTableChunkWords];
 };
 
 // Hyper-parameters in the form the kernels consume.
@@ -609,9 +623,48 @@ __device__ __forceinline__ void block_sum(double* a, double (*lds)[kSums]) {
 }
 
 // ------------------------------------------------------------------ kernels
-__global__ void k_write_table(TableChunk chunk, FragRec* dst, int base, int count) {
+__global__ void k_write_table(TableChunk chunk, uint4* dst, int base, int count) {
   const int i = threadIdx.x;
-  if (i < count) dst[base + i] = chunk.rec[i];
+  if (i < count) dst[base + i] = chunk.w[i];
+}
+
+// The elements [lo, hi) of one tile (hi - lo <= 2^tile_shift, the tile's window is aligned to
+// that size): a head up to a multiple of the vector width, whole vector rows, a tail.
+// VEC: every buffer base is 16-byte aligned, so are the element indices that are multiples of W,
+// and the accesses below are single 128-bit ones.  Otherwise the same accesses are made through
+// element-aligned types.  Either way lane t handles the same elements in the same order, so the
+// sums do not depend on the alignment of the buffers.
+template <class Op, bool VEC>
+__device__ __forceinline__ void walk_tile(const Op& op, uint64_t lo, uint64_t hi, double* acc) {
+  const uint64_t tid = threadIdx.x;
+  constexpr int W = Op::kVec;      // elements per vector access
+  constexpr int D = Op::kLoads;    // vector accesses per stream in flight
+  uint64_t lo4 = (lo + (W - 1)) & ~uint64_t(W - 1);
+  if (lo4 > hi) lo4 = hi;
+  uint64_t hi4 = hi & ~uint64_t(W - 1);
+  if (hi4 < lo4) hi4 = lo4;
+  if (tid < lo4 - lo) {  // head of the fragment up to a multiple of W (at most W-1 elements)
+    const auto r = op.template load<1>(lo + tid);
+    op.template apply<1>(lo + tid, r, acc);
+  }
+  const uint64_t nvec = (hi4 - lo4) / W;
+  for (uint64_t v = tid; v < nvec; v += uint64_t(kThreads) * D) {
+    typename Op::template Regs<W> r[D];
+#pragma unroll
+    for (int k = 0; k < D; ++k) {
+      const uint64_t vk = v + uint64_t(k) * kThreads;
+      if (vk < nvec) r[k] = op.template load<W, VEC>(lo4 + vk * W);
+    }
+#pragma unroll
+    for (int k = 0; k < D; ++k) {
+      const uint64_t vk = v + uint64_t(k) * kThreads;
+      if (vk < nvec) op.template apply<W, VEC>(lo4 + vk * W, r[k], acc);
+    }
+  }
+  if (tid < hi - hi4) {  // tail (at most W-1 elements)
+    const auto r = op.template load<1>(hi4 + tid);
+    op.template apply<1>(hi4 + tid, r, acc);
+  }
 }
 
 // One workgroup per tile (or, with a persistent grid, a walk over the tile list with stride
@@ -624,10 +677,9 @@ __global__ void k_write_table(TableChunk chunk, FragRec* dst, int base, int coun
 template <class Op, bool VEC>
 __global__ __launch_bounds__(kThreads) COCODC_OCCUPANCY void k_walk(Walk wk, Op op, double* __restrict__ partials) {
   __shared__ double lds[kWaves][kSums];
-  const FragRec* __restrict__ tbl = wk.tbl;
+  const SegRec* __restrict__ tbl = wk.tbl;
   const uint64_t T = wk.T;
   const int tile_shift = wk.tile_shift;
-  const uint64_t tid = threadIdx.x;
   // The segment of the first tile: the last record whose slot_begin is <= the tile index (records
   // of empty segments share their successor's slot_begin, so they are never the last).  A
   // workgroup lives for one tile of a few microseconds, so this is a bisection, not a scan.
@@ -651,48 +703,43 @@ __global__ __launch_bounds__(kThreads) COCODC_OCCUPANCY void k_walk(Walk wk, Op 
 #pragma unroll
     for (int k = 0; k < (Op::kAcc > 0 ? Op::kAcc : 1); ++k) acc[k] = 0.0;
 
-    // VEC: every buffer base is 16-byte aligned, so are the element indices that are multiples
-    // of W, and the accesses below are single 128-bit ones.  Otherwise the same accesses are made
-    // through element-aligned types.  Either way lane t handles the same elements in the same
-    // order, so the sums do not depend on the alignment of the buffers.
-    {
-      constexpr int W = Op::kVec;      // elements per vector access
-      constexpr int D = Op::kLoads;    // vector accesses per stream in flight
-      uint64_t lo4 = (lo + (W - 1)) & ~uint64_t(W - 1);
-      if (lo4 > hi) lo4 = hi;
-      uint64_t hi4 = hi & ~uint64_t(W - 1);
-      if (hi4 < lo4) hi4 = lo4;
-      if (tid < lo4 - lo) {  // head of the fragment up to a multiple of W (at most W-1 elements)
-        const auto r = op.template load<1>(lo + tid);
-        op.template apply<1>(lo + tid, r, acc);
-      }
-      const uint64_t nvec = (hi4 - lo4) / W;
-      for (uint64_t v = tid; v < nvec; v += uint64_t(kThreads) * D) {
-        typename Op::template Regs<W> r[D];
-#pragma unroll
-        for (int k = 0; k < D; ++k) {
-          const uint64_t vk = v + uint64_t(k) * kThreads;
-          if (vk < nvec) r[k] = op.template load<W, VEC>(lo4 + vk * W);
-        }
-#pragma unroll
-        for (int k = 0; k < D; ++k) {
-          const uint64_t vk = v + uint64_t(k) * kThreads;
-          if (vk < nvec) op.template apply<W, VEC>(lo4 + vk * W, r[k], acc);
-        }
-      }
-      if (tid < hi - hi4) {  // tail (at most W-1 elements)
-        const auto r = op.template load<1>(hi4 + tid);
-        op.template apply<1>(hi4 + tid, r, acc);
-      }
-    }
+    walk_tile<Op, VEC>(op, lo, hi, acc);
 
     if (Op::kAcc > 0) {
       block_sum<(Op::kAcc > 0 ? Op::kAcc : 1)>(acc, lds);
-      if (tid == 0) {
+      if (threadIdx.x == 0) {
 #pragma unroll
         for (int k = 0; k < Op::kAcc; ++k) partials[w * kSums + k] = acc[k];
       }
     }
+  }
+}
+
+// The same walk over ONE fragment that is named in device memory: *chosen is the index of a
+// contiguous fragment picked by an earlier kernel on the same stream (Algorithm 2), so the host
+// does not have to know it to launch the work.  groups[p] carries the fragment's range.  The
+// grid is sized by the host for the largest fragment that could have been chosen; workgroups
+// beyond the chosen fragment's tiles return at once, and all of them do when *chosen is negative
+// (nothing was eligible).  Element-wise operations only (no per-fragment sums).
+template <class Op, bool VEC>
+__global__ __launch_bounds__(kThreads) COCODC_OCCUPANCY void k_walk_chosen(const GroupRec* __restrict__ groups, int K,
+                                                                          const int* __restrict__ chosen,
+                                                                          int tile_shift, Op op) {
+  static_assert(Op::kAcc == 0, "the walk over a chosen fragment keeps no sums");
+  const int p = *chosen;
+  if (p < 0 || p >= K) return;
+  const uint64_t f_off = groups[p].f_offset, f_len = groups[p].f_length;
+  if (f_len == 0) return;
+  const uint64_t f_end = f_off + f_len;
+  const uint64_t tile0 = f_off >> tile_shift;
+  const uint64_t n_tiles = ((f_end - 1) >> tile_shift) - tile0 + 1;
+  for (uint64_t w = blockIdx.x; w < n_tiles; w += gridDim.x) {
+    const uint64_t win = (tile0 + w) << tile_shift;
+    const uint64_t win_end = win + (uint64_t(1) << tile_shift);
+    const uint64_t lo = f_off > win ? f_off : win;
+    const uint64_t hi = f_end < win_end ? f_end : win_end;
+    double acc[1] = {0.0};
+    walk_tile<Op, VEC>(op, lo, hi, acc);
   }
 }
 
@@ -701,7 +748,7 @@ __global__ __launch_bounds__(kThreads) COCODC_OCCUPANCY void k_walk(Walk wk, Op 
 // fixed workgroup tree) and evaluates Eq. 11.
 //   which: index (0..3) of the sum that feeds R;  l2: take the square root of it.
 constexpr int kFinalizeThreads = 1024;
-__global__ __launch_bounds__(kFinalizeThreads) void k_finalize(const FragRec* __restrict__ tbl,
+__global__ __launch_bounds__(kFinalizeThreads) void k_finalize(const GroupRec* __restrict__ tbl,
                                                                 const double* __restrict__ partials, int n_acc,
                                                                 int which, int l2, double* __restrict__ R_out,
                                                                 double* __restrict__ sums_out, int sums_stride) {
@@ -710,7 +757,7 @@ __global__ __launch_bounds__(kFinalizeThreads) void k_finalize(const FragRec* __
   constexpr int U = 4;
   __shared__ double lds[kFinalizeThreads / 64][kSums];
   const int p = blockIdx.x;
-  if (tbl[p].length == 0) return;  // the fragment takes no part in this call: its score stays
+  if (tbl[p].takes_part == 0) return;  // the fragment takes no part in this call: its score stays
   const uint64_t s0 = tbl[p].slot_begin, s1 = tbl[p + 1].slot_begin;
   const f64x2* __restrict__ slots = reinterpret_cast<const f64x2*>(partials);
   double acc[kSums] = {0.0, 0.0, 0.0, 0.0};
@@ -748,86 +795,74 @@ __global__ __launch_bounds__(kFinalizeThreads) void k_finalize(const FragRec* __
 }
 
 // Algorithm 2 applied `n` times without replacement == the first n entries of the order
-// (class, -R, p) with class 0 = not synchronised for >= H steps, 1 = has a number as
-// score, 2 = NaN score.  Every fragment counts how many fragments precede it.
-__global__ __launch_bounds__(kThreads) void k_select(const FragRec* __restrict__ tbl, int K,
+// (class, -R, p) with class 0 = not synchronised for >= H steps, 1 = has a number as score,
+// 2 = NaN score, 3 = in flight (never a candidate; the host keeps n within the number of
+// candidates).  Every fragment counts how many fragments precede it.
+__device__ __forceinline__ void load_priorities(const GroupRec* __restrict__ tbl, int K,
+                                                const double* __restrict__ R, int64_t t_g, int64_t H,
+                                                double* sR, unsigned char* sC) {
+  for (int p = threadIdx.x; p < K; p += kThreads) {
+    const double r = R[p];
+    const bool overdue = (t_g - tbl[p].t_b) >= H;
+    sR[p] = r;
+    sC[p] = tbl[p].in_flight ? 3 : (overdue ? 0 : (r != r ? 2 : 1));
+  }
+  __syncthreads();
+}
+
+__device__ __forceinline__ int priority_rank(int p, int K, const double* sR, const unsigned char* sC) {
+  const int cp = sC[p];
+  const double rp = sR[p];
+  int rank = 0;
+  for (int q = 0; q < K; ++q) {
+    const int cq = sC[q];
+    bool before;
+    if (cq != cp) {
+      before = cq < cp;
+    } else if (cp == 1) {
+      const double rq = sR[q];
+      before = (rq > rp) || (rq == rp && q < p);
+    } else {
+      before = q < p;
+    }
+    rank += before ? 1 : 0;
+  }
+  return rank;
+}
+
+__global__ __launch_bounds__(kThreads) void k_select(const GroupRec* __restrict__ tbl, int K,
                                                       const double* __restrict__ R, int64_t t_g,
                                                       int64_t H, int n, int* __restrict__ sel,
                                                       int* __restrict__ n_sel) {
   __shared__ double sR[COCODC_MAX_FRAGMENTS];
   __shared__ unsigned char sC[COCODC_MAX_FRAGMENTS];
+  load_priorities(tbl, K, R, t_g, H, sR, sC);
   for (int p = threadIdx.x; p < K; p += kThreads) {
-    const double r = R[p];
-    const bool overdue = (t_g - tbl[p].t_b) >= H;
-    sR[p] = r;
-    sC[p] = overdue ? 0 : (r != r ? 2 : 1);
-  }
-  __syncthreads();
-  for (int p = threadIdx.x; p < K; p += kThreads) {
-    const int cp = sC[p];
-    const double rp = sR[p];
-    int rank = 0;
-    for (int q = 0; q < K; ++q) {
-      const int cq = sC[q];
-      bool before;
-      if (cq != cp) {
-        before = cq < cp;
-      } else if (cp == 1) {
-        const double rq = sR[q];
-        before = (rq > rp) || (rq == rp && q < p);
-      } else {
-        before = q < p;
-      }
-      rank += before ? 1 : 0;
-    }
+    const int rank = priority_rank(p, K, sR, sC);
     if (rank < n) sel[rank] = p;
   }
   if (threadIdx.x == 0) *n_sel = n;
 }
 
 // Same priority order, cut by a byte budget: fragments are taken in rank order while their sizes
-// (FragRec::length of the group records, in bytes) still fit; the first that does not fit ends
-// the selection.
-__global__ __launch_bounds__(kThreads) void k_select_bytes(const FragRec* __restrict__ tbl, int K,
+// (GroupRec::bytes) still fit; the first that does not fit ends the selection.
+__global__ __launch_bounds__(kThreads) void k_select_bytes(const GroupRec* __restrict__ tbl, int K,
                                                             const double* __restrict__ R, int64_t t_g,
                                                             int64_t H, unsigned long long byte_budget,
                                                             int* __restrict__ sel, int* __restrict__ n_sel) {
   __shared__ double sR[COCODC_MAX_FRAGMENTS];
   __shared__ unsigned char sC[COCODC_MAX_FRAGMENTS];
   __shared__ int sOrder[COCODC_MAX_FRAGMENTS];
-  for (int p = threadIdx.x; p < K; p += kThreads) {
-    const double r = R[p];
-    const bool overdue = (t_g - tbl[p].t_b) >= H;
-    sR[p] = r;
-    sC[p] = overdue ? 0 : (r != r ? 2 : 1);
-  }
-  __syncthreads();
-  for (int p = threadIdx.x; p < K; p += kThreads) {
-    const int cp = sC[p];
-    const double rp = sR[p];
-    int rank = 0;
-    for (int q = 0; q < K; ++q) {
-      const int cq = sC[q];
-      bool before;
-      if (cq != cp) {
-        before = cq < cp;
-      } else if (cp == 1) {
-        const double rq = sR[q];
-        before = (rq > rp) || (rq == rp && q < p);
-      } else {
-        before = q < p;
-      }
-      rank += before ? 1 : 0;
-    }
-    sOrder[rank] = p;  // ranks are a permutation of 0..K-1
-  }
+  load_priorities(tbl, K, R, t_g, H, sR, sC);
+  for (int p = threadIdx.x; p < K; p += kThreads) sOrder[priority_rank(p, K, sR, sC)] = p;  // a permutation
   __syncthreads();
   if (threadIdx.x == 0) {
     unsigned long long left = byte_budget;
     int n = 0;
     for (int r = 0; r < K; ++r) {
       const int p = sOrder[r];
-      const unsigned long long need = tbl[p].length;
+      if (sC[p] == 3) break;  // only fragments in flight are left
+      const unsigned long long need = tbl[p].bytes;
       if (need > left) break;
       left -= need;
       sel[n++] = p;

@@ -7,7 +7,7 @@ namespace {
 
 // ------------------------------------------------------------------ host side
 thread_local int g_last_hip_error = 0;
-int g_blocks_per_cu = 0;
+std::atomic<int> g_blocks_per_cu{0};
 
 int hip_fail(hipError_t e) {
   g_last_hip_error = static_cast<int>(e);
@@ -27,16 +27,16 @@ uint64_t max_tiles(int32_t S, uint64_t n_total) {
   return (n_total >> tile_shift_for(n_total)) + 2 * static_cast<uint64_t>(S) + 1;
 }
 
-// Device workspace: S+1 segment records (the tile walk), K+1 group records (one per fragment:
-// its range of tile slots, I_p, t_b), then one slot of kSums doubles per tile.
+// Device workspace: S+1 segment records (the tile walk), K+1 fragment records (one per fragment:
+// its range of tile slots, I_p, t_b, flags), then one slot of kSums doubles per tile.
 struct WorkspaceView {
-  FragRec* table;    // S + 1 segment records; table[S].slot_begin == number of tiles
-  FragRec* groups;   // K + 1 fragment records; slot_begin, I_p, t_b and length (1: takes part, 0: not)
+  SegRec* table;     // S + 1 segment records; table[S].slot_begin == number of tiles
+  GroupRec* groups;  // K + 1 fragment records
   double* partials;  // max_tiles * kSums
 };
 
 size_t table_bytes(int32_t S, int32_t K) {
-  return align_up(sizeof(FragRec) * (static_cast<size_t>(S) + 1 + static_cast<size_t>(K) + 1), 256);
+  return align_up(sizeof(SegRec) * (static_cast<size_t>(S) + 1) + sizeof(GroupRec) * (static_cast<size_t>(K) + 1), 256);
 }
 
 size_t workspace_bytes(int32_t S, int32_t K, uint64_t n_total) {
@@ -45,8 +45,8 @@ size_t workspace_bytes(int32_t S, int32_t K, uint64_t n_total) {
 
 WorkspaceView view(void* ws, int32_t S, int32_t K) {
   char* b = static_cast<char*>(ws);
-  FragRec* t = reinterpret_cast<FragRec*>(b);
-  return WorkspaceView{t, t + S + 1, reinterpret_cast<double*>(b + table_bytes(S, K))};
+  SegRec* t = reinterpret_cast<SegRec*>(b);
+  return WorkspaceView{t, reinterpret_cast<GroupRec*>(t + S + 1), reinterpret_cast<double*>(b + table_bytes(S, K))};
 }
 
 bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
@@ -63,7 +63,8 @@ bool overlap(const Span& a, const Span& b) {
 
 // Host-side plan of one call: the records to upload and the number of tiles.
 struct Plan {
-  std::vector<FragRec> recs;  // S+1 segment records followed by K+1 group records
+  std::vector<SegRec> segs;      // S + 1 segment records
+  std::vector<GroupRec> groups;  // K + 1 fragment records
   int32_t S = 0, K = 0;
   int tile_shift = kTileShiftLarge;
   uint64_t T = 0;
@@ -71,17 +72,26 @@ struct Plan {
 
 Walk walk_of(const WorkspaceView& v, const Plan& pl) { return Walk{v.table, pl.T, pl.S, pl.tile_shift}; }
 
+// What a caller's event mask says about fragment p (no mask: every fragment takes part).
+constexpr uint8_t kMaskArrived = 1, kMaskInFlight = 2;
+
 // Validates a segment list (every segment inside n_total, no two overlapping, fragment ids in
 // [0, K)) and lays out the tile list: the segments of fragment 0 in the order given, then those
 // of fragment 1, ...  so that each fragment owns one contiguous range of tile slots.
-// recv_mask (nullable, K entries): fragments whose entry is 0 take no part in the call -- their
-// segments get no tiles and their group record says so (length 0), so that the reduction leaves
-// their score alone.  Group records of fragments that do take part carry length 1.
+// mask (nullable, K entries, bits kMaskArrived | kMaskInFlight): fragments without the arrived
+// bit take no part in the call -- their segments get no tiles and their fragment record says so,
+// so that the reduction leaves their score alone; fragments with the in-flight bit are passed
+// over by the selection.
 int plan_segments(const cocodc_segment_t* segs, int32_t S, int32_t K, uint64_t n_total, const int64_t* I_p,
-                  const int64_t* t_b, Plan* plan, const uint8_t* recv_mask = nullptr) {
+                  const int64_t* t_b, Plan* plan, const uint8_t* mask = nullptr) {
   if (!segs && S > 0) return COCODC_ERR_NULL;
   if (K < 1 || K > COCODC_MAX_FRAGMENTS || S < 0 || S > COCODC_MAX_SEGMENTS) return COCODC_ERR_RANGE;
   if (n_total > COCODC_MAX_ELEMENTS) return COCODC_ERR_RANGE;  // keeps every byte count far from overflow
+  if (mask) {
+    for (int32_t p = 0; p < K; ++p) {
+      if (mask[p] & ~(kMaskArrived | kMaskInFlight)) return COCODC_ERR_RANGE;
+    }
+  }
   std::vector<std::pair<uint64_t, uint64_t>> sorted;
   sorted.reserve(S);
   for (int32_t i = 0; i < S; ++i) {
@@ -101,17 +111,18 @@ int plan_segments(const cocodc_segment_t* segs, int32_t S, int32_t K, uint64_t n
   plan->K = K;
   plan->tile_shift = tile_shift_for(n_total);
   const int sh = plan->tile_shift;
-  plan->recs.assign(static_cast<size_t>(S) + 1 + static_cast<size_t>(K) + 1, FragRec{});
-  FragRec* seg_rec = plan->recs.data();
-  FragRec* grp_rec = plan->recs.data() + S + 1;
+  plan->segs.assign(static_cast<size_t>(S) + 1, SegRec{});
+  plan->groups.assign(static_cast<size_t>(K) + 1, GroupRec{});
+  SegRec* seg_rec = plan->segs.data();
+  GroupRec* grp_rec = plan->groups.data();
   uint64_t slot = 0;
   int32_t next_group = 0;
   for (int32_t j = 0; j < S; ++j) {
     const cocodc_segment_t& sg = segs[order[j]];
     while (next_group <= sg.fragment) grp_rec[next_group++].slot_begin = slot;
-    FragRec& r = seg_rec[j];
+    SegRec& r = seg_rec[j];
     r.offset = sg.offset;
-    r.length = (!recv_mask || recv_mask[sg.fragment]) ? sg.length : 0;
+    r.length = (!mask || (mask[sg.fragment] & kMaskArrived)) ? sg.length : 0;
     r.slot_begin = slot;
     r.tile0 = r.offset >> sh;
     if (r.length) slot += ((r.offset + r.length - 1) >> sh) - r.tile0 + 1;
@@ -121,30 +132,45 @@ int plan_segments(const cocodc_segment_t* segs, int32_t S, int32_t K, uint64_t n
   for (int32_t p = 0; p < K; ++p) {
     grp_rec[p].I_p = I_p ? I_p[p] : 0;
     grp_rec[p].t_b = t_b ? t_b[p] : 0;
-    grp_rec[p].length = (!recv_mask || recv_mask[p]) ? 1 : 0;
+    grp_rec[p].takes_part = (!mask || (mask[p] & kMaskArrived)) ? 1 : 0;
+    grp_rec[p].in_flight = (mask && (mask[p] & kMaskInFlight)) ? 1 : 0;
   }
   plan->T = slot;
   return COCODC_OK;
 }
 
-// Contiguous fragments: fragment p is the single segment frags[p].
+// Contiguous fragments: fragment p is the single segment frags[p]; its fragment record also
+// carries that range (whatever the mask says) for a walk over a fragment chosen on the device.
 int plan_table(const cocodc_fragment_t* frags, int32_t K, uint64_t n_total, const int64_t* I_p,
-               const int64_t* t_b, Plan* plan, const uint8_t* recv_mask = nullptr) {
+               const int64_t* t_b, Plan* plan, const uint8_t* mask = nullptr) {
   if (!frags) return COCODC_ERR_NULL;
   if (K < 1 || K > COCODC_MAX_FRAGMENTS) return COCODC_ERR_RANGE;
   std::vector<cocodc_segment_t> segs(static_cast<size_t>(K));
   for (int32_t p = 0; p < K; ++p) segs[p] = cocodc_segment_t{frags[p].offset, frags[p].length, p, 0};
-  return plan_segments(segs.data(), K, K, n_total, I_p, t_b, plan, recv_mask);
+  if (int rc = plan_segments(segs.data(), K, K, n_total, I_p, t_b, plan, mask)) return rc;
+  for (int32_t p = 0; p < K; ++p) {
+    plan->groups[p].f_offset = frags[p].offset;
+    plan->groups[p].f_length = frags[p].length;
+  }
+  return COCODC_OK;
 }
 
-int upload_table(const std::vector<FragRec>& recs, FragRec* dst, hipStream_t s) {
-  const int n = static_cast<int>(recs.size());
-  for (int base = 0; base < n; base += kTableChunk) {
+// Both tables go to the head of the workspace (segment records, then fragment records) as kernel
+// arguments of a few small launches: no memcpy node, so a call records into a HIP graph.
+int upload_table(const Plan& pl, const WorkspaceView& v, hipStream_t s) {
+  static_assert(sizeof(SegRec) % 16 == 0 && sizeof(GroupRec) % 16 == 0, "tables are moved in 16-byte words");
+  const size_t seg_bytes = sizeof(SegRec) * pl.segs.size(), grp_bytes = sizeof(GroupRec) * pl.groups.size();
+  std::vector<unsigned char> blob(seg_bytes + grp_bytes);
+  std::memcpy(blob.data(), pl.segs.data(), seg_bytes);
+  std::memcpy(blob.data() + seg_bytes, pl.groups.data(), grp_bytes);
+  const int n = static_cast<int>(blob.size() / 16);
+  for (int base = 0; base < n; base += kTableChunkWords) {
     TableChunk c;
-    const int count = std::min(kTableChunk, n - base);
+    const int count = std::min(kTableChunkWords, n - base);
     std::memset(&c, 0, sizeof(c));
-    std::memcpy(c.rec, recs.data() + base, sizeof(FragRec) * count);
-    hipLaunchKernelGGL(k_write_table, dim3(1), dim3(kTableChunk), 0, s, c, dst, base, count);
+    std::memcpy(c.w, blob.data() + static_cast<size_t>(base) * 16, static_cast<size_t>(count) * 16);
+    hipLaunchKernelGGL(k_write_table, dim3(1), dim3(kTableChunkWords), 0, s, c, reinterpret_cast<uint4*>(v.table), base,
+                       count);
     HIP_TRY(hipGetLastError());
   }
   return COCODC_OK;
@@ -210,7 +236,8 @@ int device_cus() {
 
 unsigned grid_for(uint64_t T) {
   uint64_t g = T;
-  if (g_blocks_per_cu > 0) g = std::min<uint64_t>(T, static_cast<uint64_t>(device_cus()) * g_blocks_per_cu);
+  const int per_cu = g_blocks_per_cu.load(std::memory_order_relaxed);
+  if (per_cu > 0) g = std::min<uint64_t>(T, static_cast<uint64_t>(device_cus()) * per_cu);
   // a launch may not exceed 2^32 - 1 threads per dimension; the kernels stride over what is left
   return static_cast<unsigned>(std::min<uint64_t>(g, 0xffffffffu / kThreads));
 }
@@ -220,20 +247,33 @@ struct Profiler {
   std::mutex mu;
   std::vector<hipEvent_t> start, stop;
   int used = 0;
-  bool on = false;
+  std::atomic<bool> on{false};  // read without the lock on every launch: the timer is normally off
 } g_prof;
+
+// A slot of the timer for the launch that follows, or -1 (timer off or full).
+int prof_begin(hipStream_t s) {
+  if (!g_prof.on.load(std::memory_order_acquire)) return -1;
+  int slot = -1;
+  {
+    std::lock_guard<std::mutex> lock(g_prof.mu);
+    if (g_prof.on.load(std::memory_order_relaxed) && g_prof.used < static_cast<int>(g_prof.start.size()))
+      slot = g_prof.used++;
+  }
+  if (slot >= 0 && hipEventRecord(g_prof.start[slot], s) != hipSuccess) return -1;
+  return slot;
+}
+
+int prof_end(int slot, hipStream_t s) {
+  if (slot >= 0) HIP_TRY(hipEventRecord(g_prof.stop[slot], s));
+  return COCODC_OK;
+}
 
 // Every streaming kernel is launched here; while the timer is on, each launch is bracketed by a
 // pair of events on the launch stream.
 template <class Op>
 int launch_walk(bool vec, const Walk& wk, const Op& op, double* partials, hipStream_t s) {
   if (wk.T == 0) return COCODC_OK;
-  int slot = -1;
-  {
-    std::lock_guard<std::mutex> lock(g_prof.mu);
-    if (g_prof.on && g_prof.used < static_cast<int>(g_prof.start.size())) slot = g_prof.used++;
-  }
-  if (slot >= 0) HIP_TRY(hipEventRecord(g_prof.start[slot], s));
+  const int slot = prof_begin(s);
   const dim3 grid(grid_for(wk.T)), block(kThreads);
   if (vec) {
     hipLaunchKernelGGL((k_walk<Op, true>), grid, block, 0, s, wk, op, partials);
@@ -241,8 +281,24 @@ int launch_walk(bool vec, const Walk& wk, const Op& op, double* partials, hipStr
     hipLaunchKernelGGL((k_walk<Op, false>), grid, block, 0, s, wk, op, partials);
   }
   HIP_TRY(hipGetLastError());
-  if (slot >= 0) HIP_TRY(hipEventRecord(g_prof.stop[slot], s));
-  return COCODC_OK;
+  return prof_end(slot, s);
+}
+
+// The walk over the one fragment that *chosen (device memory) names; max_tiles = the number of
+// tiles of the largest fragment it could name.
+template <class Op>
+int launch_walk_chosen(bool vec, const GroupRec* groups, int32_t K, const int32_t* chosen, int tile_shift,
+                       uint64_t max_tiles_, const Op& op, hipStream_t s) {
+  if (max_tiles_ == 0) return COCODC_OK;
+  const int slot = prof_begin(s);
+  const dim3 grid(grid_for(max_tiles_)), block(kThreads);
+  if (vec) {
+    hipLaunchKernelGGL((k_walk_chosen<Op, true>), grid, block, 0, s, groups, K, chosen, tile_shift, op);
+  } else {
+    hipLaunchKernelGGL((k_walk_chosen<Op, false>), grid, block, 0, s, groups, K, chosen, tile_shift, op);
+  }
+  HIP_TRY(hipGetLastError());
+  return prof_end(slot, s);
 }
 
 bool all_aligned16(std::initializer_list<const void*> ps) {

@@ -1,5 +1,12 @@
 // cocodc_loop.h -- the adaptive-transmission loop of the paper's Sec. 3.2 around the kernels:
 // host-side schedule state and the cocodc_loop_* entry points.  Included by cocodc.hip only.
+//
+// A loop step never waits for the stream.  The send decision (Algorithm 2 among the fragments
+// that are not in flight) is taken by the selection kernel, and the pseudo-gradient of the chosen
+// fragment is produced by a kernel that reads the choice from device memory, so the host does not
+// need to know p* to enqueue the work.  The choice is copied to a pinned host slot behind an
+// event; the schedule reads it (waiting on that event only) when it next needs it: at the next
+// send decision or when the fragment could be due, i.e. at least min(h, tau) steps later.
 #pragma once
 
 struct cocodc_loop {
@@ -9,6 +16,14 @@ struct cocodc_loop {
   double gamma = 1.0, T_c = 1.0, T_s = 1.0;
   int64_t N = 1, h = 1;
   std::vector<int64_t> t_b, I_p, in_flight;
+  int64_t last_t = 0;  // the step of the previous cocodc_loop_step call; steps must increase
+  // a send decision taken on the device whose outcome the host has not read yet
+  bool pending = false;
+  int64_t pending_t = 0;
+  int32_t* chosen_host = nullptr;  // pinned host memory the chosen index is copied to
+  hipEvent_t chosen_ready = nullptr;
+  int64_t last_sent_t = -1;  // the most recent send decision that has been read back
+  int32_t last_sent = -1;
 };
 
 namespace {
@@ -19,6 +34,25 @@ int replan(cocodc_loop* L) {
   L->N = N;
   L->h = h < 1 ? 1 : h;  // more syncs than steps: at most one send per step
   return COCODC_OK;
+}
+
+// Folds a pending send decision into the bookkeeping (waits for its read-back, nothing else).
+int resolve_pending(cocodc_loop* L) {
+  if (!L->pending) return COCODC_OK;
+  HIP_TRY(hipEventSynchronize(L->chosen_ready));
+  L->pending = false;
+  const int32_t p = *L->chosen_host;
+  L->last_sent_t = L->pending_t;
+  L->last_sent = -1;
+  if (p >= 0 && p < static_cast<int32_t>(L->frags.size()) && L->in_flight[p] < 0) {
+    L->in_flight[p] = L->pending_t;
+    L->last_sent = p;
+  }
+  return COCODC_OK;
+}
+
+bool due_at(const cocodc_loop* L, size_t p, int64_t t) {
+  return L->in_flight[p] >= 0 && L->in_flight[p] + L->hp.tau <= t;
 }
 }  // namespace
 
@@ -50,7 +84,13 @@ int cocodc_loop_create(const cocodc_fragment_t* frags, int32_t K, uint64_t n_tot
   return COCODC_OK;
 }
 
-void cocodc_loop_destroy(cocodc_loop_t* loop) { delete loop; }
+void cocodc_loop_destroy(cocodc_loop_t* loop) {
+  if (!loop) return;
+  if (loop->pending) (void)hipEventSynchronize(loop->chosen_ready);
+  if (loop->chosen_ready) (void)hipEventDestroy(loop->chosen_ready);
+  if (loop->chosen_host) (void)hipHostFree(loop->chosen_host);
+  delete loop;
+}
 
 int cocodc_loop_reset_scores(cocodc_loop_t* loop, double* R, void* stream) {
   if (!loop || !R) return COCODC_ERR_NULL;
@@ -79,18 +119,22 @@ int cocodc_loop_plan(const cocodc_loop_t* loop, int64_t* N_out, int64_t* h_out) 
   return COCODC_OK;
 }
 
-int cocodc_loop_due(const cocodc_loop_t* loop, int64_t t, int32_t* due_out, int32_t* n_due_out) {
+int cocodc_loop_due(cocodc_loop_t* loop, int64_t t, int32_t* due_out, int32_t* n_due_out) {
   if (!loop || !due_out || !n_due_out) return COCODC_ERR_NULL;
+  if (loop->pending && loop->pending_t + loop->hp.tau <= t) {
+    if (int rc = resolve_pending(loop)) return rc;
+  }
   int32_t n = 0;
   for (size_t p = 0; p < loop->frags.size(); ++p) {
-    if (loop->in_flight[p] >= 0 && loop->in_flight[p] + loop->hp.tau == t) due_out[n++] = static_cast<int32_t>(p);
+    if (due_at(loop, p, t)) due_out[n++] = static_cast<int32_t>(p);
   }
   *n_due_out = n;
   return COCODC_OK;
 }
 
-int cocodc_loop_state(const cocodc_loop_t* loop, int64_t* t_b_out, int64_t* I_p_out, int64_t* in_flight_out) {
+int cocodc_loop_state(cocodc_loop_t* loop, int64_t* t_b_out, int64_t* I_p_out, int64_t* in_flight_out) {
   if (!loop || !t_b_out || !I_p_out || !in_flight_out) return COCODC_ERR_NULL;
+  if (int rc = resolve_pending(loop)) return rc;
   for (size_t p = 0; p < loop->frags.size(); ++p) {
     t_b_out[p] = loop->t_b[p];
     I_p_out[p] = loop->I_p[p];
@@ -99,66 +143,103 @@ int cocodc_loop_state(const cocodc_loop_t* loop, int64_t* t_b_out, int64_t* I_p_
   return COCODC_OK;
 }
 
+int cocodc_loop_last_sent(cocodc_loop_t* loop, int64_t* t_sent_out, int32_t* sent_out) {
+  if (!loop || !t_sent_out || !sent_out) return COCODC_ERR_NULL;
+  if (int rc = resolve_pending(loop)) return rc;
+  *t_sent_out = loop->last_sent_t;
+  *sent_out = loop->last_sent;
+  return COCODC_OK;
+}
+
 int cocodc_loop_step(cocodc_loop_t* loop, int64_t t, const cocodc_loop_buffers_t* buf, void* stream,
                      int32_t* received_out, int32_t* n_received_out, int32_t* sent_out) {
   if (!loop || !buf || !received_out || !n_received_out || !sent_out) return COCODC_ERR_NULL;
-  if (t < 1) return COCODC_ERR_RANGE;
-  if (!buf->R || !buf->sel || !buf->n_sel || !buf->theta_m_send) return COCODC_ERR_NULL;
+  if (t < 1 || t <= loop->last_t) return COCODC_ERR_RANGE;  // steps are numbered 1, 2, ... and never go back
   const int32_t K = static_cast<int32_t>(loop->frags.size());
+  // Everything either kind of event could need is checked before anything is enqueued, so that a
+  // rejected step leaves the buffers and the schedule as they were.
+  if (!buf->delta_m_out || !buf->theta_m_send) return COCODC_ERR_NULL;
+  static const int64_t kOne = 1;
+  if (int rc = sync_step_check(buf->theta_m, buf->theta_m_send, buf->theta_g, buf->momentum, buf->delta_g,
+                               buf->delta_m_out, &kOne, &kOne, 1, &loop->hp, buf->R, buf->sel, buf->n_sel, nullptr))
+    return rc;
+  if (int rc = check_workspace(buf->workspace, buf->workspace_bytes, K, K, loop->n_total)) return rc;
+  if (int rc = sync_step_overlaps(K, loop->n_total, buf->theta_m, buf->theta_m_send, buf->theta_g, buf->momentum,
+                                  buf->delta_g, buf->delta_m_out, 1, buf->R, buf->sel, buf->n_sel, nullptr,
+                                  buf->workspace, buf->workspace_bytes))
+    return rc;
   *n_received_out = 0;
   *sent_out = -1;
   hipStream_t s = static_cast<hipStream_t>(stream);
 
+  const bool decision_step = (t % loop->h == 0);
+  if (loop->pending && (decision_step || loop->pending_t + loop->hp.tau <= t)) {
+    if (int rc = resolve_pending(loop)) return rc;
+  }
+
   // 1. fragments whose all-reduce completes now; 2. is it time to start the next one?  Both are
-  //    one event: a single call updates the arrived fragments and ranks all K for the decision.
-  std::vector<uint8_t> arrived(static_cast<size_t>(K), 0);
+  //    one event: the arrived fragments are updated and all K are ranked for the decision.
+  std::vector<uint8_t> mask(static_cast<size_t>(K), 0);
   std::vector<int64_t> I_new(loop->I_p), tb_new(loop->t_b), fly_new(loop->in_flight);
   int32_t n_rec = 0;
   for (int32_t p = 0; p < K; ++p) {
-    if (loop->in_flight[p] < 0 || loop->in_flight[p] + loop->hp.tau != t) continue;
-    I_new[p] = loop->in_flight[p] - loop->t_b[p];  // Eq. 11: I_p = t_p - t_{p,b}
+    if (!due_at(loop, static_cast<size_t>(p), t)) continue;
+    // Eq. 11: I_p = t_p - t_{p,b}; a fragment sent again at the very step its previous
+    // synchronisation completed has t_p = t_{p,b}: the interval is taken as one step, so that
+    // R_p = +infinity stays what Sec. 3.2 reserves it for, fragments never synchronised.
+    I_new[p] = std::max<int64_t>(1, loop->in_flight[p] - loop->t_b[p]);
     tb_new[p] = t;
     fly_new[p] = -1;
-    arrived[p] = 1;
+    mask[p] = kMaskArrived;
     received_out[n_rec++] = p;
   }
   int32_t n_flying = 0;
-  for (int32_t p = 0; p < K; ++p) n_flying += fly_new[p] >= 0 ? 1 : 0;
-  const bool decide = (t % loop->h == 0) && n_flying < K;
-  // the first fragment of the priority order that is not in flight is among the first n_flying + 1
-  const int32_t want = decide ? n_flying + 1 : 0;
-  if (n_rec > 0) {
-    if (int rc = cocodc_sync_event(loop->frags.data(), K, loop->n_total, arrived.data(), buf->theta_m,
-                                   buf->theta_m_send, buf->theta_g, buf->momentum, buf->delta_g, nullptr,
-                                   I_new.data(), tb_new.data(), t, want, &loop->hp, buf->R, buf->sel, buf->n_sel,
-                                   nullptr, buf->workspace, buf->workspace_bytes, stream))
-      return rc;
-    loop->I_p.swap(I_new);
-    loop->t_b.swap(tb_new);
-    loop->in_flight.swap(fly_new);
-    *n_received_out = n_rec;
-  } else if (decide) {
-    if (int rc = cocodc_select_fragments(K, buf->R, loop->t_b.data(), t, loop->hp.H, want, buf->sel, buf->n_sel,
-                                         buf->workspace, buf->workspace_bytes, stream))
-      return rc;
-  }
-  if (!decide) return COCODC_OK;
-  std::vector<int32_t> order(static_cast<size_t>(want));
-  HIP_TRY(hipMemcpyAsync(order.data(), buf->sel, sizeof(int32_t) * want, hipMemcpyDeviceToHost, s));
-  HIP_TRY(hipStreamSynchronize(s));
-  int32_t p_star = -1;
-  for (int32_t q : order) {
-    if (q >= 0 && q < K && loop->in_flight[q] < 0) {
-      p_star = q;
-      break;
+  uint64_t widest = 0;  // tiles of the largest fragment Algorithm 2 could choose
+  const int sh = tile_shift_for(loop->n_total);
+  for (int32_t p = 0; p < K; ++p) {
+    if (fly_new[p] >= 0) {
+      mask[p] |= kMaskInFlight;
+      ++n_flying;
+    } else if (loop->frags[p].length) {
+      const uint64_t o = loop->frags[p].offset, e = o + loop->frags[p].length;
+      widest = std::max<uint64_t>(widest, ((e - 1) >> sh) - (o >> sh) + 1);
     }
   }
-  if (p_star < 0) return COCODC_OK;
-  if (int rc = cocodc_pseudograd(&loop->frags[p_star], 1, loop->n_total, buf->theta_g, buf->theta_m,
-                                 buf->delta_m_out, buf->theta_m_send, buf->workspace, buf->workspace_bytes, stream))
+  const bool decide = decision_step && n_flying < K;  // (a pending decision was read back above)
+  if (n_rec == 0 && !decide) {
+    loop->last_t = t;
+    return COCODC_OK;
+  }
+
+  Plan pl;
+  if (int rc = plan_table(loop->frags.data(), K, loop->n_total, I_new.data(), tb_new.data(), &pl, mask.data()))
     return rc;
-  loop->in_flight[p_star] = t;
-  *sent_out = p_star;
+  if (int rc = sync_step_impl(pl, K, loop->n_total, buf->theta_m, buf->theta_m_send, buf->theta_g, buf->momentum,
+                              buf->delta_g, nullptr, t, decide ? 1 : 0, &loop->hp, buf->R, buf->sel, buf->n_sel,
+                              nullptr, buf->workspace, buf->workspace_bytes, stream))
+    return rc;
+  loop->I_p.swap(I_new);
+  loop->t_b.swap(tb_new);
+  loop->in_flight.swap(fly_new);
+  loop->last_t = t;
+  *n_received_out = n_rec;
+  if (!decide) return COCODC_OK;
+
+  // The chosen fragment's pseudo-gradient and send-time record, for whichever fragment sel[0] names.
+  WorkspaceView v = view(buf->workspace, pl.S, K);
+  const bool vec = all_aligned16({buf->theta_g, buf->theta_m, buf->delta_m_out, buf->theta_m_send});
+  PseudoGradOp<true> op{buf->theta_g, buf->theta_m, buf->delta_m_out, buf->theta_m_send};
+  if (int rc = launch_walk_chosen(vec, v.groups, K, buf->sel, sh, widest, op, s)) return rc;
+  if (!loop->chosen_host) {
+    HIP_TRY(hipHostMalloc(reinterpret_cast<void**>(&loop->chosen_host), sizeof(int32_t), hipHostMallocDefault));
+    HIP_TRY(hipEventCreateWithFlags(&loop->chosen_ready, hipEventDisableTiming));
+  }
+  *loop->chosen_host = -1;
+  HIP_TRY(hipMemcpyAsync(loop->chosen_host, buf->sel, sizeof(int32_t), hipMemcpyDeviceToHost, s));
+  HIP_TRY(hipEventRecord(loop->chosen_ready, s));
+  loop->pending = true;
+  loop->pending_t = t;
+  *sent_out = COCODC_LOOP_SENT_PENDING;
   return COCODC_OK;
 }
 

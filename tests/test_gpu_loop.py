@@ -19,9 +19,12 @@ def B():
     return binding
 
 
-def _run_both(B, ref, wl, gamma, T_c, T_s, steps, closed, seed=0, observe_at=None):
+def _run_both(B, ref, wl, gamma, T_c, T_s, steps, closed, seed=0, observe_at=None, lazy=False):
+    """lazy=False: the test asks after every step which fragment was sent (cocodc_loop_last_sent) and
+    compares the bookkeeping; lazy=True: it never asks, so the schedule reads each decision back only
+    when it needs it itself, and the logs of received fragments and the final state are compared."""
     from oracle.loop import RefLoop
-    print(f"case loop {wl.name} K={wl.K} n={wl.n_total} steps={steps} closed={closed}", flush=True)
+    print(f"case loop {wl.name} K={wl.K} n={wl.n_total} steps={steps} closed={closed} lazy={lazy}", flush=True)
     st = synth.make_state(wl, "cuda", seed=seed)
     host = U.host_copy(st)
     n, K = wl.n_total, wl.K
@@ -65,11 +68,22 @@ def _run_both(B, ref, wl, gamma, T_c, T_s, steps, closed, seed=0, observe_at=Non
             assert rc == 0, B.cocodc_status_string(rc)
             rrec, rsent = rloop.step(t, host["theta_m"], host["theta_m_send"], host["theta_g"], host["momentum"],
                                      host["delta_g"], send_host)
-            assert (rec, sent) == (rrec, rsent), (t, rec, sent, rrec, rsent)
-            n_sent += sent >= 0
+            assert rec == rrec, (t, rec, rrec)
+            # a decision step reports "pending" unless every fragment is in flight (then nothing is decided)
+            assert sent in (-1, B.COCODC_LOOP_SENT_PENDING)
+            if rsent >= 0:
+                assert sent == B.COCODC_LOOP_SENT_PENDING, (t, sent, rsent)
+            if not lazy:
+                if sent == B.COCODC_LOOP_SENT_PENDING:
+                    assert B.cocodc_loop_last_sent(loop) == (0, t, rsent), (t, rsent)
+                else:
+                    assert rsent == -1
+                rc, t_b, I_p, fl = B.cocodc_loop_state(loop)
+                assert (t_b, I_p, fl) == (rloop.t_b, rloop.I_p, rloop.in_flight)
+            n_sent += rsent >= 0
             n_received += len(rec)
-            rc, t_b, I_p, fl = B.cocodc_loop_state(loop)
-            assert (t_b, I_p, fl) == (rloop.t_b, rloop.I_p, rloop.in_flight)
+        rc, t_b, I_p, fl = B.cocodc_loop_state(loop)
+        assert (t_b, I_p, fl) == (rloop.t_b, rloop.I_p, rloop.in_flight)
         torch.cuda.synchronize()
         for k in ("theta_m", "theta_m_send", "theta_g", "momentum", "delta_g"):
             gk = st[k].cpu().numpy()
@@ -106,6 +120,64 @@ def test_loop_deep_overlap(B, ref):
     _run_both(B, ref, wl, 1.0, 1.0, 5.0, 200, closed=True)
 
 
+@pytest.mark.parametrize("closed", [True, False])
+def test_loop_without_asking_who_was_sent(B, ref, closed):
+    """Nobody reads the send decisions back: the schedule does so itself when the fragment could be
+    due or at the next decision.  Sizes chosen so that the chosen fragment spans several tiles, a
+    single element, or nothing at all."""
+    wl = synth.Workload("loop-lazy", (70001, 1, 0, 33000, 4097), tau=3, H=40)
+    n_sent, n_rec = _run_both(B, ref, wl, 1.0, 1.0, 4.0, 260, closed=closed, lazy=True)
+    assert n_sent >= 260 // 4 - 1
+
+
+def test_loop_send_interval_equal_to_overlap(B, ref):
+    """h == tau: arrivals and decisions coincide, a fragment can be sent again at the step it arrived;
+    its interval counts as one step and its score stays finite (as in the loop oracle)."""
+    wl = synth.Workload("loop-h-eq-tau", (30000, 25000, 20001, 15000), tau=5, H=100)
+    _run_both(B, ref, wl, 1.0, 1.0, 5.0, 300, closed=True)
+    _run_both(B, ref, wl, 1.0, 1.0, 5.0, 300, closed=True, lazy=True)
+
+
+def test_loop_step_rejections_change_nothing(B):
+    wl = synth.Workload("loop-rej", (5000, 3000), tau=2, H=10)
+    st = synth.make_state(wl, "cuda", seed=3)
+    keep = {k: v.clone() for k, v in st.items()}
+    n, K = wl.n_total, wl.K
+    rc, loop = B.cocodc_loop_create(wl.frags, n, B.hparams(2, 10), 1.0, 1.0, 5.0)   # N = 2, h = 5
+    assert rc == 0
+    R = torch.zeros(K, dtype=torch.float64, device="cuda")
+    sel = torch.zeros(K, dtype=torch.int32, device="cuda")
+    n_sel = torch.zeros(1, dtype=torch.int32, device="cuda")
+    ws = B.new_workspace(K, n)
+    out = torch.zeros(n, device="cuda")
+    assert B.cocodc_loop_reset_scores(loop, R) == 0
+    good = (st["theta_m"], st["theta_m_send"], st["theta_g"], st["momentum"], st["delta_g"], out, R, sel, n_sel, ws)
+    try:
+        for i in (0, 1, 2, 3, 4, 5, 6, 7, 8):          # each required pointer missing in turn
+            args = list(good)
+            args[i] = None
+            assert B.cocodc_loop_step(loop, 5, B.loop_buffers(*args))[0] == B.COCODC_ERR_NULL, i
+        args = list(good)
+        args[5] = st["theta_g"]                          # the pseudo-gradient over the global state
+        assert B.cocodc_loop_step(loop, 5, B.loop_buffers(*args))[0] == B.COCODC_ERR_ALIAS
+        assert B.cocodc_loop_step(loop, 0, B.loop_buffers(*good))[0] == B.COCODC_ERR_RANGE
+        torch.cuda.synchronize()
+        for k in keep:
+            assert torch.equal(keep[k], st[k]), k
+        assert B.cocodc_loop_state(loop) == (0, [0, 0], [0, 0], [-1, -1])
+        assert B.cocodc_loop_last_sent(loop) == (0, -1, -1)
+        assert B.cocodc_loop_step(loop, 5, B.loop_buffers(*good)) == (0, [], B.COCODC_LOOP_SENT_PENDING)
+        assert B.cocodc_loop_last_sent(loop) == (0, 5, 0)
+        assert B.cocodc_loop_step(loop, 5, B.loop_buffers(*good))[0] == B.COCODC_ERR_RANGE   # steps never go back
+        assert B.cocodc_loop_step(loop, 4, B.loop_buffers(*good))[0] == B.COCODC_ERR_RANGE
+        # a skipped arrival step: the fragment sent at 5 (tau = 2) is still received at 9
+        assert B.cocodc_loop_due(loop, 6) == (0, []) and B.cocodc_loop_due(loop, 9) == (0, [0])
+        assert B.cocodc_loop_step(loop, 9, B.loop_buffers(*good)) == (0, [0], -1)
+        assert B.cocodc_loop_state(loop) == (0, [9, 0], [5, 0], [-1, -1])
+    finally:
+        B.cocodc_loop_destroy(loop)
+
+
 def test_loop_rejects_bad_arguments(B):
     hp = B.hparams(5, 100)
     assert B.cocodc_loop_create([(0, 10), (5, 10)], 20, hp, 0.4, 1.0, 5.0)[0] == B.COCODC_ERR_RANGE
@@ -133,7 +205,9 @@ def test_sync_event_random_masks(B, ref):
         n = max(wl.n_total, 1)
         pad_big = rng.random() < 0.2
         n_alloc = n + 16 + ((1 << 24) if pad_big else 0)
-        mask = [rng.random() < rng.choice([0.0, 0.3, 1.0]) for _ in range(K)]
+        mask = [int(rng.random() < rng.choice([0.0, 0.3, 1.0])) for _ in range(K)]
+        if case % 2:   # some fragments are still in flight: Algorithm 2 passes them over
+            mask = [m | (2 if rng.random() < 0.4 else 0) for m in mask]
         merge_mode = rng.choice([0, 0, 1, 2])
         hpk = dict(lam=rng.choice([0.0, 0.5, 3.0]), nesterov=rng.choice([0, 1]), drift_sign=rng.choice([1, -1]),
                    score_src=rng.choice([0, 1]), norm_kind=rng.choice([1, 2]), merge_mode=merge_mode, alpha=0.5,
@@ -169,7 +243,7 @@ def test_sync_event_random_masks(B, ref):
             assert np.array_equal(st[k].cpu().numpy(), host[k]), k
         assert np.array_equal(pg.cpu().numpy().view(np.uint32), h_pg.view(np.uint32))
         Rg = R_dev.cpu().numpy()
-        arrived = np.array(mask, bool)
+        arrived = np.array([m & 1 for m in mask], bool)
         # scores of fragments that did not arrive: the very same bits as before
         assert np.array_equal(Rg[~arrived].view(np.uint64), R0[~arrived].view(np.uint64))
         fin = arrived & np.isfinite(R_ref)
@@ -179,8 +253,9 @@ def test_sync_event_random_masks(B, ref):
         assert np.array_equal(sg[~arrived], sums_ref[~arrived])
         assert U.rel_err(sg[arrived], sums_ref[arrived]) <= U.SCORE_TOL_TIGHT
         n_sel = int(out["n_sel"].item())
-        assert n_sel == min(budget, K)
+        assert n_sel == min(budget, sum(1 for m in mask if not m & 2))
         got = out["sel"][:n_sel].cpu().tolist()
+        assert all(not mask[q] & 2 for q in got)
         if got != ro["sel"].tolist():   # only if two deciding scores are closer than the summation error
             bk = synth.Bookkeeping(t_g=1000, t_b=t_b, I_p=I_p)
             assert not np.isnan(R_ref).any() and U.selection_margin(R_ref, bk, wl.H, n_sel) < 1e-9

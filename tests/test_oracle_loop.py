@@ -45,12 +45,12 @@ def test_paper_setup_gives_eight_syncs_per_period(ref):
     assert [e["t"] for e in log if e["sent"] >= 0][:8] == [12, 24, 36, 48, 60, 72, 84, 96]
     # never-synchronised fragments have R = infinity: the first K sends are 0, 1, 2, 3
     assert [e["sent"] for e in log if e["sent"] >= 0][:4] == [0, 1, 2, 3]
-    # every send arrives exactly tau steps later, with I_p = t_p - t_{p,b}
+    # every send arrives exactly tau steps later, with I_p = t_p - t_{p,b} (never 0 here: h > tau)
     sent_at = {}
     for e in log:
         for p in e["received"]:
             assert sent_at[p] + 5 == e["t"]
-            assert e["I_p"][p] == sent_at[p] - e["t_b_before"][p]
+            assert e["I_p"][p] == sent_at[p] - e["t_b_before"][p] >= 1
             assert e["t_b"][p] == e["t"] and math.isfinite(e["R"][p]) and e["R"][p] > 0
             del sent_at[p]
         if e["sent"] >= 0:
@@ -201,24 +201,36 @@ def test_event_by_event_equals_the_loop(ref):
     log_b = []
     h = loop.h
     for t in range(1, 131):
-        mask = [1 if flying[p] >= 0 and flying[p] + tau == t else 0 for p in range(K)]
+        mask = [1 if flying[p] >= 0 and flying[p] + tau <= t else 0 for p in range(K)]
         for p in range(K):
             if mask[p]:
-                I_p[p] = flying[p] - t_b[p]
+                I_p[p] = max(1, flying[p] - t_b[p])
                 t_b[p] = t
                 flying[p] = -1
         decide = t % h == 0 and sum(f >= 0 for f in flying) < K
         sent = -1
         if any(mask) or decide:
+            # (a) the whole priority order, then the first fragment of it that is not in flight
             want = sum(f >= 0 for f in flying) + 1 if decide else 0
-            out = ref.sync_event(frags, mask, st_b["theta_m"], st_b["theta_m_send"], st_b["theta_g"],
-                                 st_b["momentum"], st_b["delta_g"], None, I_p, t_b, t, want, hp, R)
+            shadow = {k: v.copy() for k, v in st_b.items()}
+            R_shadow = R.copy()
+            out = ref.sync_event(frags, mask, shadow["theta_m"], shadow["theta_m_send"], shadow["theta_g"],
+                                 shadow["momentum"], shadow["delta_g"], None, I_p, t_b, t, want, hp, R_shadow)
             assert out["rc"] == 0
             if decide:
                 for q in out["sel"].tolist():
                     if flying[q] < 0:
                         sent = q
                         break
+            # (b) the event told who is in flight, budget 1: the same fragment, the same buffers and scores
+            full = [m | (2 if flying[p] >= 0 else 0) for p, m in enumerate(mask)]
+            out2 = ref.sync_event(frags, full, st_b["theta_m"], st_b["theta_m_send"], st_b["theta_g"],
+                                  st_b["momentum"], st_b["delta_g"], None, I_p, t_b, t, 1 if decide else 0, hp, R)
+            assert out2["rc"] == 0
+            assert out2["sel"].tolist() == ([sent] if decide else [])
+            assert np.array_equal(R, R_shadow)
+            for k in st_b:
+                assert np.array_equal(st_b[k], shadow[k]), k
         if sent >= 0:
             assert ref.pseudograd([frags[sent]], st_b["theta_g"], st_b["theta_m"], pg_b, st_b["theta_m_send"]) == 0
             flying[sent] = t
@@ -227,3 +239,89 @@ def test_event_by_event_equals_the_loop(ref):
     assert log_a == log_b and len(log_a) > 10
     for k in st_a:
         assert np.array_equal(st_a[k], st_b[k]), k
+
+
+def test_selection_passes_over_fragments_in_flight(ref):
+    """Alg. 2 among the fragments that are not in flight == the whole priority order (pinned by
+    enumeration elsewhere) with the fragments in flight struck out: every subset in flight, scores with
+    ties / infinities / NaN, some fragments overdue, every budget."""
+    import itertools
+    K, n = 4, 8
+    frags = [(0, 2), (2, 2), (4, 2), (6, 2)]
+    hp = ref.hparams(1, 10)
+    z = {k: np.zeros(n, np.float32) for k in ("theta_m", "theta_m_send", "theta_g", "momentum", "delta_g")}
+    n_cases = 0
+    for scores in itertools.product([0.5, 2.0, np.inf, np.nan], repeat=K):
+        for ages in ((1, 1, 1, 1), (1, 10, 1, 12), (10, 1, 1, 1)):
+            t_b = [100 - a for a in ages]
+            R = np.array(scores)
+            rc, order = ref.select_fragments(R, t_b, 100, 10, K)
+            assert rc == 0
+            for flying in itertools.product([0, 1], repeat=K):
+                for budget in (0, 1, 2, K + 1):
+                    mask = [2 * f for f in flying]
+                    R_ev = R.copy()
+                    out = ref.sync_event(frags, mask, z["theta_m"], z["theta_m_send"], z["theta_g"], z["momentum"],
+                                         z["delta_g"], None, [1] * K, t_b, 100, budget, hp, R_ev)
+                    assert out["rc"] == 0
+                    want = [q for q in order.tolist() if not flying[q]][:budget]
+                    assert out["sel"].tolist() == want, (scores, ages, flying, budget)
+                    assert np.array_equal(R_ev.view(np.uint64), R.view(np.uint64))   # no arrival: scores untouched
+                    n_cases += 1
+    assert n_cases == 4 ** 4 * 3 * 16 * 4
+    assert ref.sync_event(frags, [4, 0, 0, 0], z["theta_m"], z["theta_m_send"], z["theta_g"], z["momentum"],
+                          z["delta_g"], None, [1] * K, [0] * K, 100, 1, hp, np.zeros(K))["rc"] < 0
+
+
+def test_send_interval_equal_to_overlap_keeps_scores_finite(ref):
+    """h == tau: every arrival coincides with a send decision, so a fragment can be sent again at the very
+    step its previous synchronisation completed (t_p == t_{p,b}).  Its next score must be a number: Sec. 3.2
+    keeps R_p = infinity for fragments that never completed a synchronisation.  The interval then counts
+    as one step; everywhere else I_p = t_p - t_{p,b} as Eq. 11 prints it."""
+    wl = synth.Workload("h-eq-tau", (3000, 2500, 2000, 1500), tau=5, H=100)
+    loop, st, log = make_run(ref, wl, 1.0, 1.0, 5.0, 400)   # N = 20, h = 5 = tau
+    assert (loop.N, loop.h) == (20, 5)
+    completed = set()
+    sent_at, n_same_step = {}, 0
+    for e in log:
+        for p in e["received"]:
+            t_p = sent_at.pop(p)
+            assert e["I_p"][p] == max(1, t_p - e["t_b_before"][p]) and e["I_p"][p] >= 1
+            n_same_step += t_p == e["t_b_before"][p]
+            completed.add(p)
+        for p in completed:
+            assert math.isfinite(e["R"][p]) and e["R"][p] > 0, (e["t"], p)
+        for p in set(range(4)) - completed:
+            assert e["R"][p] == math.inf
+        if e["sent"] >= 0:
+            sent_at[e["sent"]] = e["t"]
+    assert n_same_step > 10                 # the case did occur
+    assert completed == {0, 1, 2, 3}
+    # the overdue rule of Alg. 2 still bounds every fragment's staleness
+    assert max(e["t"] - tb for e in log for tb in e["t_b"]) <= 100 + 4 * 5 + 5
+    sends = [e["sent"] for e in log if e["sent"] >= 0]
+    assert all(sends.count(p) >= 400 // (100 + 4 * 5 + 5) for p in range(4))
+
+
+def test_arrivals_are_not_lost_when_steps_are_skipped(ref):
+    """A fragment is due once tau steps have passed since it was sent, also when the caller did not call
+    the loop at exactly that step."""
+    from oracle.loop import RefLoop
+    frags = [(0, 8), (8, 8)]
+    st = _event_state(3, 16)
+    loop = RefLoop(frags, ref.hparams(5, 100), gamma=1.0, T_c=1.0, T_s=50.0)   # N = 2, h = 50
+    pg = np.zeros(16, np.float32)
+    rec, sent = loop.step(50, st["theta_m"], st["theta_m_send"], st["theta_g"], st["momentum"], st["delta_g"], pg)
+    assert (rec, sent) == ([], 0)
+    assert loop.due(54) == [] and loop.due(55) == [0] and loop.due(58) == [0]
+    rec, sent = loop.step(58, st["theta_m"], st["theta_m_send"], st["theta_g"], st["momentum"], st["delta_g"], pg)
+    assert (rec, sent) == ([0], -1) and loop.t_b == [58, 0] and loop.I_p == [50, 0] and loop.in_flight == [-1, -1]
+
+
+def test_the_interval_pin_sees_the_reading_it_guards(ref, monkeypatch):
+    """Planted mistake (on the CPU, in the oracle): with the interval taken literally as t_p - t_{p,b}, a
+    fragment sent again at the step its synchronisation completed gets R_p = infinity; the pin above must fail."""
+    from oracle.loop import RefLoop
+    monkeypatch.setattr(RefLoop, "min_interval", 0)
+    with pytest.raises(AssertionError):
+        test_send_interval_equal_to_overlap_keeps_scores_finite(ref)

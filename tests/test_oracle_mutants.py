@@ -60,10 +60,14 @@ MUTANTS = [
     ("planner_min_instead_of_max", "if (cap > static_cast<double>(N))", "if (cap < static_cast<double>(N))"),
     ("planner_ignores_gamma", "std::floor(gamma * ((static_cast<double>(H) * T_c) / T_s))", "std::floor((static_cast<double>(H) * T_c) / T_s)"),
     ("planner_interval_inverted", "static_cast<int64_t>(H) / N;", "N / static_cast<int64_t>(H);"),
-    ("event_mask_inverted", "if (!recv_mask[q]) continue;", "if (recv_mask[q]) continue;"),
-    ("event_mask_ignored", "if (!recv_mask[q]) continue;", ""),
-    ("event_selects_from_arrived_only", "return cocodc_ref_select_fragments(K, R, t_b, t_g, hp->H, budget, sel_out, n_sel_out);\n}",
-     "for (int32_t q = 0; q < K; ++q) if (!recv_mask[q]) R[q] = -1.0;\n  return cocodc_ref_select_fragments(K, R, t_b, t_g, hp->H, budget, sel_out, n_sel_out);\n}"),
+    ("event_mask_inverted", "if (!(recv_mask[q] & 1)) continue;", "if (recv_mask[q] & 1) continue;"),
+    ("event_mask_ignored", "if (!(recv_mask[q] & 1)) continue;", ""),
+    ("event_selects_from_arrived_only", "return select_among(K, R, t_b, t_g, hp->H, budget, in_flight.data(), sel_out, n_sel_out);\n}",
+     "for (int32_t q = 0; q < K; ++q) if (!(recv_mask[q] & 1)) R[q] = -1.0;\n  return select_among(K, R, t_b, t_g, hp->H, budget, in_flight.data(), sel_out, n_sel_out);\n}"),
+    ("event_ignores_in_flight", "in_flight[q] = (recv_mask[q] & 2) ? 1 : 0;", "in_flight[q] = 0;"),
+    ("event_in_flight_bit_confused_with_arrived", "in_flight[q] = (recv_mask[q] & 2) ? 1 : 0;", "in_flight[q] = (recv_mask[q] & 1) ? 1 : 0;"),
+    ("in_flight_counts_against_the_budget", "const int32_t n_sel = budget < candidates ? budget : candidates;",
+     "const int32_t n_sel = (budget < K ? budget : K) - (K - candidates) > 0 ? (budget < K ? budget : K) - (K - candidates) : 0;"),
 ]
 
 BATTERY = [
@@ -96,6 +100,7 @@ BATTERY = [
     pins.test_score_source_and_norm_switches,
     pins.test_selection_exhaustive_small,
     lambda ref: loop_pins.test_event_equals_step_on_the_arrived_fragments_then_selection_over_all(ref, (0, 1, 0, 0, 1)),
+    loop_pins.test_selection_passes_over_fragments_in_flight,
 ]
 
 
