@@ -122,40 +122,66 @@ def _gen(device, seed: int, buffer: str, sync_index: int) -> torch.Generator:
     return g
 
 
-def fill_normal(out: torch.Tensor, sigma: float, gen: torch.Generator, chunk: int = 1 << 28):
-    """In-place N(0, sigma) fill, in chunks so no full-size temporary is needed."""
+def fill_normal(out: torch.Tensor, sigma: float, gen: torch.Generator, chunk: int = 1 << 28, states=None):
+    """In-place N(0, sigma) fill, in chunks so no full-size temporary is needed.  `states` (a list,
+    optional) receives (first element, number of elements, generator state) of every chunk, from which
+    refill_chunk can draw the same chunk again later."""
     flat = out.view(-1)
     for lo in range(0, flat.numel(), chunk):
-        flat[lo:lo + chunk].normal_(0.0, sigma, generator=gen)
+        sl = flat[lo:lo + chunk]
+        if states is not None:
+            states.append((lo, sl.numel(), gen.get_state()))
+        sl.normal_(0.0, sigma, generator=gen)
     return out
 
 
-def fill_student_t3(out: torch.Tensor, scale: float, gen: torch.Generator, chunk: int = 1 << 26):
+def _student_t3_chunk(sl: torch.Tensor, scale: float, gen: torch.Generator):
+    n = sl.numel()
+    z = torch.empty(n, dtype=torch.float32, device=sl.device).normal_(generator=gen)
+    chi = torch.zeros(n, dtype=torch.float32, device=sl.device)
+    tmp = torch.empty(n, dtype=torch.float32, device=sl.device)
+    for _ in range(3):
+        tmp.normal_(generator=gen)
+        chi.addcmul_(tmp, tmp)
+    chi.div_(3.0).sqrt_()
+    sl.copy_(z.div_(chi).mul_(scale))
+
+
+def fill_student_t3(out: torch.Tensor, scale: float, gen: torch.Generator, chunk: int = 1 << 26, states=None):
     """In-place Student-t(nu=3) * scale: z / sqrt((a^2 + b^2 + c^2) / 3) from four normals."""
     flat = out.view(-1)
     for lo in range(0, flat.numel(), chunk):
         sl = flat[lo:lo + chunk]
-        n = sl.numel()
-        z = torch.empty(n, dtype=torch.float32, device=out.device).normal_(generator=gen)
-        chi = torch.zeros(n, dtype=torch.float32, device=out.device)
-        tmp = torch.empty(n, dtype=torch.float32, device=out.device)
-        for _ in range(3):
-            tmp.normal_(generator=gen)
-            chi.addcmul_(tmp, tmp)
-        chi.div_(3.0).sqrt_()
-        sl.copy_(z.div_(chi).mul_(scale))
+        if states is not None:
+            states.append((lo, sl.numel(), gen.get_state()))
+        _student_t3_chunk(sl, scale, gen)
     return out
 
 
-def fill_drift(out: torch.Tensor, kind: str, gen: torch.Generator, sigma: float = SIGMA["drift"]):
+def refill_chunk(out: torch.Tensor, kind: str, sigma: float, state) -> torch.Tensor:
+    """Draws one recorded chunk again (same generator state, same number of elements, hence the same
+    values) into `out`, a tensor of exactly that chunk's length.  kind: "normal" | "student_t3"."""
+    gen = torch.Generator(device=out.device)
+    gen.set_state(state)
     if kind == "normal":
-        return fill_normal(out, sigma, gen)
+        out.normal_(0.0, sigma, generator=gen)
+    elif kind == "student_t3":
+        _student_t3_chunk(out, sigma, gen)
+    else:
+        raise ValueError(kind)
+    return out
+
+
+def fill_drift(out: torch.Tensor, kind: str, gen: torch.Generator, sigma: float = SIGMA["drift"], states=None):
+    if kind == "normal":
+        return fill_normal(out, sigma, gen, states=states)
     if kind == "student_t3":
-        return fill_student_t3(out, sigma, gen)
+        return fill_student_t3(out, sigma, gen, states=states)
     raise ValueError(kind)
 
 
-def make_state(wl: Workload, device, seed: int = 0, pad: int = 0, amplified: bool = False, buffers=None):
+def make_state(wl: Workload, device, seed: int = 0, pad: int = 0, amplified: bool = False, buffers=None,
+               record=None):
     """The five resident buffers of one worker just before a sync is applied.
 
     theta_m_send is derived so that "drift since send" = theta_m - theta_m_send:
@@ -165,6 +191,9 @@ def make_state(wl: Workload, device, seed: int = 0, pad: int = 0, amplified: boo
     with a sentinel) after the last fragment so tests can verify nothing outside the
     fragment table is written.  `buffers` (optional) maps each of the five names to a
     preallocated fp32 tensor of n_total + pad elements to fill instead of allocating.
+    `record` (a dict, optional) receives, per buffer that the sync step overwrites ("theta_m",
+    "theta_g", "momentum"), the (kind, sigma, chunk states) from which original_slice can draw any
+    part of that buffer's initial contents again.
     """
     n = wl.n_total
 
@@ -178,7 +207,11 @@ def make_state(wl: Workload, device, seed: int = 0, pad: int = 0, amplified: boo
     st = {}
     for name in ("theta_m", "theta_g", "momentum", "delta_g"):
         t = alloc(name)
-        fill_normal(t[:n], 0.5 if amplified else SIGMA[name], _gen(device, seed, name, 0))
+        sigma = 0.5 if amplified else SIGMA[name]
+        states = [] if record is not None else None
+        fill_normal(t[:n], sigma, _gen(device, seed, name, 0), states=states)
+        if record is not None:
+            record[name] = ("normal", sigma, states)
         if pad:
             t[n:] = 777.0
         st[name] = t
@@ -193,6 +226,32 @@ def make_state(wl: Workload, device, seed: int = 0, pad: int = 0, amplified: boo
         send[n:] = 777.0
     st["theta_m_send"] = send
     return st
+
+
+def original_slice(record, name: str, lo: int, hi: int, device, scratch=None) -> torch.Tensor:
+    """Elements [lo, hi) of buffer `name` as make_state(record=...) first filled it, drawn again chunk
+    by chunk (for checks at sizes where no copy of the initial state can be kept)."""
+    kind, sigma, states = record[name]
+    out = torch.empty(hi - lo, dtype=torch.float32, device=device)
+    for c_lo, c_n, state in states:
+        a, b = max(lo, c_lo), min(hi, c_lo + c_n)
+        if a >= b:
+            continue
+        tmp = scratch[:c_n] if scratch is not None and scratch.numel() >= c_n else \
+            torch.empty(c_n, dtype=torch.float32, device=device)
+        refill_chunk(tmp, kind, sigma, state)
+        out[a - lo:b - lo].copy_(tmp[a - c_lo:b - c_lo])
+    return out
+
+
+def draw_sync_inputs(wl: Workload, device, seed: int, sync_index: int, drift_out: torch.Tensor,
+                     delta_g_out: torch.Tensor):
+    """The fresh inputs of sync `sync_index` >= 1 of a consecutive-sync run, into caller-provided
+    buffers: the local drift since the previous sync and the newly arrived global pseudo-gradient
+    (the same values next_sync_inputs draws)."""
+    n = wl.n_total
+    fill_drift(drift_out[:n], wl.drift, _gen(device, seed, "drift", sync_index))
+    fill_normal(delta_g_out[:n], SIGMA["delta_g"], _gen(device, seed, "delta_g", sync_index))
 
 
 def next_sync_inputs(wl: Workload, st, seed: int, sync_index: int):

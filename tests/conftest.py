@@ -18,3 +18,10 @@ def ref():
     import oracle
     oracle.lib()
     return oracle
+
+
+def pytest_terminal_summary(terminalreporter):
+    """How close the GPU-vs-oracle fragment selections of this session came to a tie."""
+    util = sys.modules.get("parity_util")
+    if util is not None and util.SESSION_LOG.compared:
+        terminalreporter.write_line(f"[selection parity] {util.SESSION_LOG}")

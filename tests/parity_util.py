@@ -111,11 +111,125 @@ def compare_fused(gpu_state, gpu_out, ref_host, ref_out, frags, tight=True, chec
     return obs
 
 
-def compare_selection(gpu_out, ref_out, bk, H):
-    """Selected indices must be identical unless two oracle scores that decide the order are
-    closer than the summation-order error of the oracle itself."""
+def summation_bound(n_elements):
+    """Worst-case relative error of the oracle's index-order fp64 sum of n non-negative terms:
+    n * 2^-53 (each of the n additions is off by at most half an ulp of a running sum that never
+    exceeds the total).  The kernel's tree sums carry far less.  Two oracle scores that differ by
+    less than this cannot be ranked by the oracle itself."""
+    return float(max(int(n_elements), 1)) * 2.0 ** -53
+
+
+class SelectionLog:
+    """Smallest deciding margin seen and how often the oracle's own order was within its
+    summation error (the tests that expect that never to happen assert ambiguous == 0)."""
+
+    def __init__(self):
+        self.min_margin = float("inf")
+        self.ambiguous = 0
+        self.compared = 0
+
+    def __repr__(self):
+        return f"selections compared {self.compared}, smallest margin {self.min_margin:.3g}, ambiguous {self.ambiguous}"
+
+
+SESSION_LOG = SelectionLog()   # every comparison of a test session; printed in the terminal summary
+
+
+def compare_selection(gpu_out, ref_out, bk, H, frag_lengths=None, log=None, in_flight=None, allow_ambiguous=False):
+    """The selection is integer work on fp64 scores, so it is checked in two steps.
+    (1) Always: the GPU's indices are exactly what the pinned Algorithm 2 of the oracle gives when it
+        is fed the GPU's OWN scores (same doubles in, same indices out: bit-exact).
+    (2) Against the oracle's selection from ITS scores: identical, unless two oracle scores that
+        decide the order are closer than the oracle's own summation error (summation_bound of the
+        largest fragment; 1e-12 if no lengths are given) -- then either order is correct and (1) has
+        already shown that the GPU's order is the priority order of scores that agree with the
+        oracle's to that precision.  That escape is open only to callers that pass
+        allow_ambiguous=True (they count it in log.ambiguous and bound the count); everywhere else a
+        differing selection fails.
+    Returns the smallest relative gap between deciding oracle scores."""
+    import oracle as ref
     margin = selection_margin(ref_out["R"], bk, H, len(ref_out["sel"]))
+    Rg = gpu_out["R"].cpu().numpy() if hasattr(gpu_out["R"], "cpu") else np.asarray(gpu_out["R"])
+    n_sel = len(gpu_out["sel_list"])
+    if in_flight is None:
+        rc, own = ref.select_fragments(Rg, bk.t_b, bk.t_g, H, n_sel)
+        assert rc == 0
+        own = own.tolist()
+    else:
+        rc, order = ref.select_fragments(Rg, bk.t_b, bk.t_g, H, len(Rg))
+        assert rc == 0
+        own = [q for q in order.tolist() if not in_flight[q]][:n_sel]
+    assert gpu_out["sel_list"] == own, ("selection is not Algorithm 2 on the GPU's own scores", gpu_out["sel_list"], own)
+    assert n_sel == len(ref_out["sel"])
+    for lg in {id(l): l for l in (log, SESSION_LOG) if l is not None}.values():
+        lg.compared += 1
+        lg.min_margin = min(lg.min_margin, margin)
     if gpu_out["sel_list"] != ref_out["sel"].tolist():
-        assert margin < 1e-9, (gpu_out["sel_list"], ref_out["sel"].tolist(), margin)
-        assert sorted(gpu_out["sel_list"]) == sorted(set(gpu_out["sel_list"]))
+        bound = summation_bound(max(frag_lengths)) if frag_lengths else 1e-12
+        assert allow_ambiguous and margin < bound, (gpu_out["sel_list"], ref_out["sel"].tolist(), margin, bound)
+        for lg in {id(l): l for l in (log, SESSION_LOG) if l is not None}.values():
+            lg.ambiguous += 1
     return margin
+
+
+# ---------------------------------------------------------------------------------------------
+# Full-width comparisons: the oracle's chunk-parallel variant (the same per-element code as the
+# definitional loop; only the order of the per-fragment sums differs, by chunks of 65536) run on
+# pinned host staging buffers, the stored values compared bit for bit on the GPU.
+def pinned(n, dtype=torch.float32):
+    return torch.empty(n, dtype=dtype, pin_memory=True)
+
+
+def pinned_block(n_buffers, n):
+    """n_buffers fp32 host buffers of n elements carved out of ONE pinned allocation (torch rounds
+    every pinned allocation up to a power of two, so large buffers are cheaper in one piece)."""
+    block = torch.empty(n_buffers * n, dtype=torch.float32, pin_memory=True)
+    return [block[i * n:(i + 1) * n] for i in range(n_buffers)]
+
+
+class DeviceComparer:
+    """Compares a device tensor with a host tensor (pinned or pageable) bit for bit, on the device,
+    moving the host data through two pinned staging chunks so that pageable memory is not slow."""
+
+    def __init__(self, chunk=1 << 27):
+        self.chunk = chunk
+        self.stage = [pinned(chunk), pinned(chunk)]
+        self.dev = [torch.empty(chunk, dtype=torch.float32, device="cuda") for _ in range(2)]
+        self.done = [torch.cuda.Event(), torch.cuda.Event()]
+
+    def mismatches(self, gpu_tensor, host_tensor):
+        """Number of elements whose bit patterns differ."""
+        n = gpu_tensor.numel()
+        assert host_tensor.numel() == n
+        bad = torch.zeros((), dtype=torch.int64, device="cuda")
+        for i, lo in enumerate(range(0, n, self.chunk)):
+            j = i & 1
+            m = min(self.chunk, n - lo)
+            self.done[j].synchronize()                       # the staging chunk is free again
+            self.stage[j][:m].copy_(host_tensor[lo:lo + m])  # host to pinned (threads of the CPU copy)
+            self.dev[j][:m].copy_(self.stage[j][:m], non_blocking=True)
+            bad += (gpu_tensor[lo:lo + m].view(torch.int32) != self.dev[j][:m].view(torch.int32)).sum()
+            self.done[j].record()
+        return int(bad.item())
+
+
+def bits_equal(gpu_tensor, host_tensor, scratch):
+    """True when the device tensor holds exactly the bits of the (pinned) host tensor."""
+    n = gpu_tensor.numel()
+    if n == 0:
+        return True
+    dst = scratch[:n]
+    dst.copy_(host_tensor[:n], non_blocking=False)
+    return bool(torch.equal(gpu_tensor.view(torch.int32), dst.view(torch.int32)))
+
+
+def mismatch_report(gpu_tensor, host_tensor, scratch):
+    """How a failed bits_equal looks: count, first index, worst relative deviation."""
+    n = gpu_tensor.numel()
+    dst = scratch[:n]
+    dst.copy_(host_tensor[:n])
+    bad = (gpu_tensor.view(torch.int32) != dst.view(torch.int32))
+    cnt = int(bad.sum().item())
+    first = int(bad.nonzero()[0].item()) if cnt else -1
+    rel = ((gpu_tensor.double() - dst.double()).abs() / dst.double().abs().clamp_min(1e-30)).max().item()
+    return dict(mismatching=cnt, first=first, max_rel=rel)

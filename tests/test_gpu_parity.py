@@ -527,7 +527,7 @@ def test_hundred_consecutive_syncs_heavy_tailed_drift(B, ref):
         host = U.host_copy(st)
         bk = synth.bookkeeping(wl)
         ws = B.new_workspace(wl.K, wl.n_total)
-        n_ambiguous = 0
+        log = U.SelectionLog()
         for k in range(wl.n_syncs):
             if k > 0:
                 synth.next_sync_inputs(wl, st, 0, k)
@@ -538,15 +538,15 @@ def test_hundred_consecutive_syncs_heavy_tailed_drift(B, ref):
                 host["delta_g"][:] = st["delta_g"].cpu().numpy()
             go = U.run_gpu_fused(B, wl.frags, wl.n_total, st, bk, wl.budget, ghp, ws, pg=None)
             ro = U.run_ref_fused(ref, wl.frags, host, bk, wl.budget, rhp, pg=False, shadow=(k in (0, 9, 99)))
-            margin = U.compare_selection(go, ro, bk, wl.H)
-            n_ambiguous += go["sel_list"] != ro["sel"].tolist()
+            margin = U.compare_selection(go, ro, bk, wl.H, frag_lengths=wl.frag_lengths, log=log)
             if k in (0, 9, 99):
                 obs = U.compare_fused(st, go, host, ro, wl.frags, tight=False, check_pg=False)
                 print(f"   sync {k + 1} score_src={score_src} observed",
                       {a: (f"{b:.3g}" if isinstance(b, float) else b) for a, b in obs.items()},
                       f"margin {margin:.3g}", flush=True)
             bk = synth.advance_bookkeeping(wl, bk, ro["sel"].tolist())
-        assert n_ambiguous == 0
+        print(f"   score_src={score_src}: {log}", flush=True)
+        assert log.ambiguous == 0 and log.compared == wl.n_syncs
 
 
 # ------------------------------------------------------------------ error paths that need a device
