@@ -22,12 +22,39 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published peak
 BYTES_PER_PARAM = 36   # 5 fp32 reads + 4 fp32 writes (theta_m, theta_g, momentum, pseudo-gradient)
 
-# HBM bytes per launch of the fused kernel: rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE runs of this
-# command, each scaled by what the same counter reads for a plain 4 GiB device copy (FETCH_SIZE
-# reads half the true bytes on this GPU, WRITE_SIZE reads them exactly).  The runs and their
-# commands are recorded in profiles/fused_sync_step_<workload>.txt (fused_sync_step_bf16_<workload>.txt for
-# the 28 B/param bf16 variant).  Keyed by (workload, bytes per parameter); None where no run exists.
-MEASURED_TRAFFIC_BYTES = {('7B', 36): 237917636268, ('1.3B', 36): 46765973035, ('7B', 28): 185056695176}
+PROFILE_DIR = os.path.join(ROOT, "profiles")
+KERNEL_SOURCES = ("paper_2504_17672_amd/csrc/cocodc_device.h", "paper_2504_17672_amd/csrc/cocodc.hip")
+
+
+def kernel_source_sha256():
+    """Fingerprint of the files that define the streaming kernels and their build switches."""
+    import hashlib
+    h = hashlib.sha256()
+    for rel in KERNEL_SOURCES:
+        with open(os.path.join(ROOT, rel), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()
+
+
+def profiled_traffic(workload, bf16):
+    """HBM bytes per launch of the fused kernel as the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs recorded in
+    profiles/fused_sync_step[_bf16]_<workload>.txt measured them (each counter scaled by what it reads for a plain
+    device copy of known size; the summary names the commands).  The number belongs to the kernel sources it
+    was measured on: the summary carries their fingerprint, and when the sources have changed since (or no
+    summary exists for the workload) there is nothing to report: (None, reason)."""
+    import re
+    name = f"fused_sync_step_{'bf16_' if bf16 else ''}{workload}.txt"
+    path = os.path.join(PROFILE_DIR, name)
+    if not os.path.exists(path):
+        return None, f"no profile summary profiles/{name}"
+    text = open(path).read()
+    m_hash = re.search(r"kernel_source_sha256:\s*([0-9a-f]{64})", text)
+    m_traffic = re.search(r"traffic_bytes_per_launch:\s*(\d+)", text)
+    if not m_hash or not m_traffic:
+        return None, f"profiles/{name} carries no traffic figure"
+    if m_hash.group(1) != kernel_source_sha256():
+        return None, f"profiles/{name} was measured on other kernel sources"
+    return int(m_traffic.group(1)), f"profiles/{name}"
 
 
 def cpu_baseline(wl, st, bk, sample_frag, repeats=2):
@@ -77,6 +104,8 @@ def main():
     ap.add_argument("--blocks-per-cu", type=int, default=None, help="launch-shape override (tuning)")
     ap.add_argument("--no-pg", action="store_true", help="skip the pseudo-gradient output (32 B/param)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
+    ap.add_argument("--no-packed-pass", action="store_true",
+                    help="skip the second timed pass with the buffers back to back (the 'packed_layout' object)")
     ap.add_argument("--merge-mode", default="dc", choices=["dc", "blend", "replace"],
                     help="dc: delay compensation (Eq. 8, default); blend: Streaming-DiLoCo merge (Eq. 3, "
                          "alpha 0.5, no send-time record: 32 B/param); replace: blocking-DiLoCo merge")
@@ -131,7 +160,7 @@ def main():
     wl = synth.WORKLOADS[args.workload]
     K, n = wl.K, wl.n_total
     print(f"[bench] workload {wl.name}: K={K} n={n} resident {5 * 4 * n / 1e9:.1f} GB", file=sys.stderr, flush=True)
-    layout, arena, bufs = args.layout, None, None
+    layout, arena, bufs, probe = args.layout, None, None, {}
     stride = B.cocodc_layout_stride_bytes(n) if args.stride_gib is None else int(args.stride_gib * (1 << 30))
     if layout in ("spaced", "tuned"):
         try:
@@ -359,6 +388,60 @@ def main():
     if args.bf16:  # theta_m read+written, theta_m_send read, pseudo-gradient written: 2 bytes each
         bpp = (2 + 4 + 4 + 4 + (2 if mode == 0 else 0)) + (2 + 4 + 4 + (0 if args.no_pg else 2))
     achieved = bpp * n / (k1_avg * 1e-3) / 1e9
+    selected = sel[:int(n_sel.item())].cpu().tolist()
+
+    # What the placement is worth.  (a) The set-up probe timed the fused step at every candidate
+    # stride: which is the smallest arena that still reaches 80 % of the HBM peak?  (b) The same
+    # timed region once more with the six buffers back to back in the same allocation, which is
+    # where separate hipMalloc calls put them.
+    GiB = 1 << 30
+    nbytes = 4 * n
+    layout_detail = {"kind": layout}
+    if arena is not None:
+        layout_detail.update(stride_GiB=round(stride / GiB, 2), arena_GiB=round(arena.numel() / GiB, 1),
+                             used_span_GiB=round((5 * stride + nbytes) / GiB, 1))
+    if probe:
+        gbps = {g: 36 * n / (ms * 1e-3) / 1e9 for g, ms in probe.items()}
+        layout_detail["probe_GBps_by_stride_GiB"] = {f"{g:g}": round(v, 0) for g, v in sorted(gbps.items())}
+        ok = [g for g, v in sorted(gbps.items()) if v >= 0.8 * HBM_PEAK_GBS]
+        layout_detail["smallest_stride_GiB_with_80pct"] = ok[0] if ok else None
+        layout_detail["span_GiB_at_that_stride"] = round((5 * ok[0] * GiB + nbytes) / GiB, 1) if ok else None
+    packed = None
+    plain = (arena is not None and not args.graph and not args.bf16 and segs is None and mode == 0 and pg is not None)
+    if plain and not args.no_packed_pass:
+        pstride = (nbytes + 255) // 256 * 256
+        pviews = [arena[k * pstride:k * pstride + nbytes].view(torch.float32) for k in range(6)]
+        pbufs = dict(zip(("theta_m", "theta_m_send", "theta_g", "momentum", "delta_g", "pg"), pviews))
+        del st
+        pst = synth.make_state(wl, dev, seed=0, buffers=pbufs)   # overwrites the tuned buffers: they are done
+        ppg = pbufs["pg"]
+
+        def pstep():
+            B.check(B.cocodc_sync_step(wl.frags, n, pst["theta_m"], pst["theta_m_send"], pst["theta_g"],
+                                       pst["momentum"], pst["delta_g"], ppg, bk.I_p, bk.t_b, bk.t_g, wl.budget, hp, R,
+                                       sel, n_sel, None, ws))
+        for _ in range(args.warmup):
+            pstep()
+        B.check(B.cocodc_profiler_enable(args.steps))
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            pstep()
+        torch.cuda.synchronize()
+        p_elapsed = time.perf_counter() - t0
+        cnt, p_ms = B.cocodc_profiler_collect(args.steps)
+        B.cocodc_profiler_disable()
+        assert cnt == args.steps
+        p_avg = sum(p_ms) / len(p_ms)
+        p_ach = bpp * n / (p_avg * 1e-3) / 1e9
+        packed = {"layout": "the six buffers back to back in one allocation (what separate allocations give)",
+                  "span_GiB": round(6 * pstride / GiB, 1), "value": round(n / (p_elapsed / args.steps) / 1e9, 3),
+                  "unit": "Gparams/s", "ms_per_step": round(p_elapsed / args.steps * 1e3, 4),
+                  "kernel_ms_avg": round(p_avg, 4), "achieved": round(p_ach, 1),
+                  "frac": round(p_ach / HBM_PEAK_GBS, 4)}
+    traffic, traffic_source = (None, "not the profiled configuration")
+    if mode == 0 and not args.no_pg and segs is None and not args.graph:
+        traffic, traffic_source = profiled_traffic(wl.name, args.bf16)
     out = {
         "metric": "fused sync-step Gparams/s and achieved HBM GB/s (% of peak), 1\u00d7MI355X",
         "value": round(n / (elapsed / args.steps) / 1e9, 3),
@@ -369,17 +452,21 @@ def main():
         "dtype": "f64", "data": "synthetic",
         "config": {"workload": wl.name, "K": K, "params": n, "tau": wl.tau, "H": wl.H, "budget": wl.budget,
                    "bytes_per_param": bpp, "merge_mode": args.merge_mode,
-                   "local_dtype": "bf16" if args.bf16 else "f32", "launch": "hip graph replay" if args.graph else "eager",
+                   "arithmetic": "fp64 in registers, each stored value rounded once",
+                   "storage_dtype": "bf16 local parameters, f32 global state" if args.bf16 else "f32",
+                   "launch": "hip graph replay" if args.graph else "eager",
                    "fragments": (f"{args.strided_shards} strided shards of {len(segs)} segments" if segs
                                  else "contiguous"),
                    "layout": (f"{layout}: one allocation, buffer bases {stride / (1 << 30):.2f} GiB apart"
                               if layout != "packed" else "packed: separate allocations"),
-                   "selected": sel[:int(n_sel.item())].cpu().tolist()},
+                   "layout_detail": layout_detail,
+                   "selected": selected},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4),
-                     "traffic": MEASURED_TRAFFIC_BYTES.get((wl.name, bpp)) if mode == 0 and not args.no_pg else None,
+                     "traffic": traffic, "traffic_source": traffic_source,
                      "kernel": "k_walk<FusedBf16Op>" if args.bf16 else "k_walk<FusedOp>", "kernel_ms_avg": round(k1_avg, 4),
                      "kernel_ms_min": round(min(k1_ms), 4), "algorithmic_bytes": bpp * n},
+        "packed_layout": packed,
         "cpu_baseline": cpu,
     }
     print(json.dumps(out), flush=True)

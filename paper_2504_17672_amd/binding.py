@@ -248,13 +248,17 @@ def tuned_spaced_buffers(n_total, frags, device="cuda", count=6, max_arena_bytes
     if max_arena_bytes is None:
         free, _ = torch.cuda.mem_get_info(device)
         max_arena_bytes = int(free * 0.92)
-    lo = max(13 * GiB, (nbytes + GiB - 1) // GiB * GiB)
+    back_to_back = (nbytes + GiB - 1) // GiB * GiB   # the smallest stride on the 1 GiB grid
+    lo = max(13 * GiB, back_to_back)
     hi = (max_arena_bytes - nbytes) // (count - 1) // GiB * GiB
     base = cocodc_layout_stride_bytes(n_total)
     if hi < lo:
         arena, bufs = spaced_buffers(n_total, count, device)
         return arena, bufs, base, {}
-    cands = sorted(set(range(lo, hi + 1, 2 * GiB)) | ({base} if lo <= base <= hi else set()))
+    # every 2 GiB from 13 GiB on (where the fast placements start), and below that every 1 GiB from
+    # back-to-back on, so that the probe also tells how small an arena still runs fast
+    cands = sorted(set(range(lo, hi + 1, 2 * GiB)) | set(range(back_to_back, lo, GiB)) |
+                   ({base} if lo <= base <= hi else set()))
     arena = torch.empty((count - 1) * cands[-1] + nbytes, dtype=torch.uint8, device=device)
     for off in range(0, arena.numel(), 8 * GiB):
         arena[off:off + 8 * GiB].zero_()
