@@ -238,6 +238,28 @@ def main():
         torch.cuda.synchronize()
         sel_ms = (time.perf_counter() - t0) / args.steps * 1e3
 
+        # For scale: the same two reads and one write per element through torch's own element-wise
+        # kernel on the same three buffers (what a plain 2-read-1-write stream gets on this GPU).
+        def torch_ms(fn):
+            for _ in range(args.warmup):
+                fn()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(args.steps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / args.steps
+        ref_rows = []
+        for name, bpp, fn in (
+                ("torch.sub(theta_g, theta_m, out=pg)", 12, lambda: torch.sub(th["theta_g"], th["theta_m"], out=pg)),
+                ("pg.copy_(theta_g)", 8, lambda: pg.copy_(th["theta_g"])),
+                ("pg.fill_(0)", 4, lambda: pg.fill_(0.0))):
+            ms = torch_ms(fn)
+            ref_rows.append({"reference": name, "bytes_per_param": bpp, "ms": round(ms, 4),
+                             "achieved_GBps": round(bpp * n / (ms * 1e-3) / 1e9, 1)})
+            print(f"[bench] {ref_rows[-1]}", file=sys.stderr, flush=True)
+
         def five():
             calls[0][3](); calls[2][3](); calls[3][3](); calls[4][3]()
             B.check(B.cocodc_select_fragments(K, R, bk.t_b, bk.t_g, wl.H, wl.budget, sel, n_sel, ws))
@@ -252,7 +274,7 @@ def main():
         assert bool(torch.isfinite(th["theta_m"][:1 << 20]).all().item())
         print(json.dumps({"mode": "primitives", "workload": wl.name, "params": n, "steps": args.steps,
                           "layout": layout, "stride_GiB": round(stride / (1 << 30), 2), "entries": rows,
-                          "select_ms_per_call": round(sel_ms, 4),
+                          "select_ms_per_call": round(sel_ms, 4), "torch_references": ref_rows,
                           "five_calls_in_sequence": {"bytes_per_param": 52, "ms": round(seq_wall, 4),
                                                      "Gparams_per_s": round(n / seq_wall / 1e6, 2)},
                           "same_streams_no_arithmetic": {

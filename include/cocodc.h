@@ -434,6 +434,13 @@ const char* cocodc_status_string(int status);
  * one workgroup per tile.  Results never depend on it.  Returns the previous value. */
 int cocodc_set_blocks_per_cu(int blocks_per_cu);
 
+/* Where the kernels read the fragment table from.  Tables of at most 32 segments and 32 fragments
+ * normally travel inside the arguments of every kernel of a call, which saves the small upload
+ * launch in front of them; larger tables are written to the head of the workspace first.
+ * enabled = 0 makes every call upload (to compare the two paths; results never depend on it).
+ * Returns the previous setting.  Process-wide. */
+int cocodc_set_tables_in_args(int enabled);
+
 /* Kernel timer for benchmarks.  After cocodc_profiler_enable(n) every launch of a
  * streaming kernel (one per call of cocodc_sync_step*, cocodc_pseudograd*,
  * cocodc_outer_nesterov, cocodc_delay_compensate, cocodc_fragment_scores*) is bracketed

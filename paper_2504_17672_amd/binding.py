@@ -45,6 +45,7 @@ EXPORTS = (
     "cocodc_loop_plan", "cocodc_loop_due", "cocodc_loop_step", "cocodc_loop_state", "cocodc_loop_last_sent",
     "cocodc_tile_elements", "cocodc_debug_tile_plan", "cocodc_debug_stream_mix",
     "cocodc_layout_stride_bytes", "cocodc_last_hip_error", "cocodc_status_string", "cocodc_set_blocks_per_cu",
+    "cocodc_set_tables_in_args",
     "cocodc_profiler_enable", "cocodc_profiler_collect", "cocodc_profiler_disable",
 )
 
@@ -131,6 +132,7 @@ _lib.cocodc_layout_stride_bytes.argtypes = [C.c_uint64]
 _lib.cocodc_status_string.restype = C.c_char_p
 _lib.cocodc_status_string.argtypes = [C.c_int]
 _lib.cocodc_set_blocks_per_cu.argtypes = [C.c_int]
+_lib.cocodc_set_tables_in_args.argtypes = [C.c_int]
 _lib.cocodc_profiler_enable.argtypes = [C.c_int32]
 _lib.cocodc_profiler_collect.argtypes = [C.POINTER(C.c_float), C.c_int32]
 for _name in EXPORTS:
@@ -389,6 +391,10 @@ def cocodc_status_string(status):
 
 def cocodc_set_blocks_per_cu(n):
     return int(_lib.cocodc_set_blocks_per_cu(int(n)))
+
+
+def cocodc_set_tables_in_args(enabled):
+    return int(_lib.cocodc_set_tables_in_args(1 if enabled else 0))
 
 
 def cocodc_profiler_enable(max_records):

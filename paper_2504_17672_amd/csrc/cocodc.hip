@@ -193,10 +193,7 @@ static int fragment_scores_impl(Plan& pl, int32_t K, uint64_t n_total, const flo
     rc = launch_walk(vec, walk_of(v, pl), op, v.partials, s);
   }
   if (rc) return rc;
-  hipLaunchKernelGGL(k_finalize, dim3(K), dim3(kFinalizeThreads), 0, s, v.groups, v.partials, 1, 0,
-                     norm_kind == 2 ? 1 : 0, R_out, sum_out, 1);
-  HIP_TRY(hipGetLastError());
-  return COCODC_OK;
+  return launch_finalize(pl, v, 1, 0, norm_kind == 2 ? 1 : 0, R_out, sum_out, 1, s);
 }
 
 int cocodc_fragment_scores(const cocodc_fragment_t* frags, int32_t K, uint64_t n_total, const float* x,
@@ -239,10 +236,7 @@ int cocodc_select_fragments(int32_t K, const double* R, const int64_t* t_b, int6
   hipStream_t s = static_cast<hipStream_t>(stream);
   WorkspaceView v = view(workspace, pl.S, K);
   if (int rc = upload_table(pl, v, s)) return rc;
-  hipLaunchKernelGGL(k_select, dim3(1), dim3(kThreads), 0, s, v.groups, K, R, t_g, static_cast<int64_t>(H),
-                     n, sel_out, n_sel_out);
-  HIP_TRY(hipGetLastError());
-  return COCODC_OK;
+  return launch_select(pl, v, R, t_g, static_cast<int64_t>(H), n, sel_out, n_sel_out, s);
 }
 
 // The buffers of the fused step may not overlap, except that the pseudo-gradient may be written
@@ -294,14 +288,9 @@ static int sync_step_impl(Plan& pl, int32_t K, uint64_t n_total, float* theta_m,
                                                   theta_g, momentum, delta_g, delta_m_out, d, v.partials, s);
     if (rc) return rc;
     const int which = (hp->score_src ? 2 : 0) + (hp->norm_kind == 2 ? 0 : 1);
-    hipLaunchKernelGGL(k_finalize, dim3(K), dim3(kFinalizeThreads), 0, s, v.groups, v.partials, kSums, which,
-                       hp->norm_kind == 2 ? 1 : 0, R_out, sums_out, kSums);
-    HIP_TRY(hipGetLastError());
+    if (int rc2 = launch_finalize(pl, v, kSums, which, hp->norm_kind == 2 ? 1 : 0, R_out, sums_out, kSums, s)) return rc2;
   }
-  hipLaunchKernelGGL(k_select, dim3(1), dim3(kThreads), 0, s, v.groups, K, R_out, t_g,
-                     static_cast<int64_t>(hp->H), n, sel_out, n_sel_out);
-  HIP_TRY(hipGetLastError());
-  return COCODC_OK;
+  return launch_select(pl, v, R_out, t_g, static_cast<int64_t>(hp->H), n, sel_out, n_sel_out, s);
 }
 
 static int sync_step_check(float* theta_m, const float* theta_m_send, float* theta_g, float* momentum,
@@ -481,13 +470,8 @@ int cocodc_sync_step_bf16(const cocodc_fragment_t* frags, int32_t K, uint64_t n_
                                                      theta_g, momentum, delta_g, delta_m_out, d, v.partials, s);
   if (rc) return rc;
   const int which = (hp->score_src ? 2 : 0) + (hp->norm_kind == 2 ? 0 : 1);
-  hipLaunchKernelGGL(k_finalize, dim3(K), dim3(kFinalizeThreads), 0, s, v.groups, v.partials, kSums, which,
-                     hp->norm_kind == 2 ? 1 : 0, R_out, sums_out, kSums);
-  HIP_TRY(hipGetLastError());
-  hipLaunchKernelGGL(k_select, dim3(1), dim3(kThreads), 0, s, v.groups, K, R_out, t_g,
-                     static_cast<int64_t>(hp->H), n, sel_out, n_sel_out);
-  HIP_TRY(hipGetLastError());
-  return COCODC_OK;
+  if (int rc2 = launch_finalize(pl, v, kSums, which, hp->norm_kind == 2 ? 1 : 0, R_out, sums_out, kSums, s)) return rc2;
+  return launch_select(pl, v, R_out, t_g, static_cast<int64_t>(hp->H), n, sel_out, n_sel_out, s);
 }
 
 int cocodc_select_fragments_bytes(int32_t K, const double* R, const int64_t* t_b, int64_t t_g, int32_t H,
@@ -505,11 +489,12 @@ int cocodc_select_fragments_bytes(int32_t K, const double* R, const int64_t* t_b
   Plan pl;
   if (int rc = plan_segments(nullptr, 0, K, 0, nullptr, t_b, &pl)) return rc;
   for (int32_t p = 0; p < K; ++p) pl.groups[p].bytes = frag_bytes[p];
+  pl.in_args = false;  // this kernel reads the records from the workspace, whatever their number
   hipStream_t s = static_cast<hipStream_t>(stream);
   WorkspaceView v = view(workspace, pl.S, K);
   if (int rc = upload_table(pl, v, s)) return rc;
-  hipLaunchKernelGGL(k_select_bytes, dim3(1), dim3(kThreads), 0, s, v.groups, K, R, t_g, static_cast<int64_t>(H),
-                     static_cast<unsigned long long>(byte_budget), sel_out, n_sel_out);
+  hipLaunchKernelGGL(k_select_bytes<GroupTable>, dim3(1), dim3(kThreads), 0, s, GroupTable{v.groups}, K, R, t_g,
+                     static_cast<int64_t>(H), static_cast<unsigned long long>(byte_budget), sel_out, n_sel_out);
   HIP_TRY(hipGetLastError());
   return COCODC_OK;
 }
@@ -602,6 +587,8 @@ const char* cocodc_status_string(int status) {
 int cocodc_set_blocks_per_cu(int blocks_per_cu) {
   return g_blocks_per_cu.exchange(blocks_per_cu < 0 ? 0 : blocks_per_cu);
 }
+
+int cocodc_set_tables_in_args(int enabled) { return g_tables_in_args.exchange(enabled ? 1 : 0); }
 
 int cocodc_profiler_enable(int32_t max_records) {
   if (max_records < 1 || max_records > 65536) return COCODC_ERR_RANGE;

@@ -50,13 +50,32 @@ struct GroupRec {
 };
 static_assert(sizeof(GroupRec) == 64, "GroupRec layout");
 
-// What a streaming kernel walks: the segment records, their number S, the number of tiles T
-// (== tbl[S].slot_begin) and the tile size.
+// What a streaming kernel walks: S segment records (plus a closing one whose slot_begin is the
+// number of tiles T) and the tile size.  The records themselves come either from the workspace
+// (SegTable / GroupTable: a pointer) or, for tables of at most kInlineRecs segments and fragments,
+// inside the kernel arguments (SegInline / GroupInline: no upload launch before the kernel).
 struct Walk {
-  const SegRec* tbl;
   uint64_t T;
   int32_t S;
   int32_t tile_shift;
+};
+
+constexpr int kInlineRecs = 32;
+struct SegTable {
+  const SegRec* p;
+  __device__ __forceinline__ const SegRec& operator[](int i) const { return p[i]; }
+};
+struct SegInline {
+  SegRec r[kInlineRecs + 1];
+  __device__ __forceinline__ const SegRec& operator[](int i) const { return r[i]; }
+};
+struct GroupTable {
+  const GroupRec* p;
+  __device__ __forceinline__ const GroupRec& operator[](int i) const { return p[i]; }
+};
+struct GroupInline {
+  GroupRec r[kInlineRecs + 1];
+  __device__ __forceinline__ const GroupRec& operator[](int i) const { return r[i]; }
 };
 
 // The tables travel to the device as kernel arguments, kTableChunkWords 16-byte words per launch.
@@ -674,10 +693,9 @@ __device__ __forceinline__ void walk_tile(const Op& op, uint64_t lo, uint64_t hi
 #else
 #define COCODC_OCCUPANCY
 #endif
-template <class Op, bool VEC>
-__global__ __launch_bounds__(kThreads) COCODC_OCCUPANCY void k_walk(Walk wk, Op op, double* __restrict__ partials) {
+template <class Op, bool VEC, class Segs>
+__global__ __launch_bounds__(kThreads) COCODC_OCCUPANCY void k_walk(Segs tbl, Walk wk, Op op, double* __restrict__ partials) {
   __shared__ double lds[kWaves][kSums];
-  const SegRec* __restrict__ tbl = wk.tbl;
   const uint64_t T = wk.T;
   const int tile_shift = wk.tile_shift;
   // The segment of the first tile: the last record whose slot_begin is <= the tile index (records
@@ -748,7 +766,8 @@ __global__ __launch_bounds__(kThreads) COCODC_OCCUPANCY void k_walk_chosen(const
 // fixed workgroup tree) and evaluates Eq. 11.
 //   which: index (0..3) of the sum that feeds R;  l2: take the square root of it.
 constexpr int kFinalizeThreads = 1024;
-__global__ __launch_bounds__(kFinalizeThreads) void k_finalize(const GroupRec* __restrict__ tbl,
+template <class Groups>
+__global__ __launch_bounds__(kFinalizeThreads) void k_finalize(Groups tbl,
                                                                 const double* __restrict__ partials, int n_acc,
                                                                 int which, int l2, double* __restrict__ R_out,
                                                                 double* __restrict__ sums_out, int sums_stride) {
@@ -798,7 +817,8 @@ __global__ __launch_bounds__(kFinalizeThreads) void k_finalize(const GroupRec* _
 // (class, -R, p) with class 0 = not synchronised for >= H steps, 1 = has a number as score,
 // 2 = NaN score, 3 = in flight (never a candidate; the host keeps n within the number of
 // candidates).  Every fragment counts how many fragments precede it.
-__device__ __forceinline__ void load_priorities(const GroupRec* __restrict__ tbl, int K,
+template <class Groups>
+__device__ __forceinline__ void load_priorities(const Groups& tbl, int K,
                                                 const double* __restrict__ R, int64_t t_g, int64_t H,
                                                 double* sR, unsigned char* sC) {
   for (int p = threadIdx.x; p < K; p += kThreads) {
@@ -830,7 +850,8 @@ __device__ __forceinline__ int priority_rank(int p, int K, const double* sR, con
   return rank;
 }
 
-__global__ __launch_bounds__(kThreads) void k_select(const GroupRec* __restrict__ tbl, int K,
+template <class Groups>
+__global__ __launch_bounds__(kThreads) void k_select(Groups tbl, int K,
                                                       const double* __restrict__ R, int64_t t_g,
                                                       int64_t H, int n, int* __restrict__ sel,
                                                       int* __restrict__ n_sel) {
@@ -846,7 +867,8 @@ __global__ __launch_bounds__(kThreads) void k_select(const GroupRec* __restrict_
 
 // Same priority order, cut by a byte budget: fragments are taken in rank order while their sizes
 // (GroupRec::bytes) still fit; the first that does not fit ends the selection.
-__global__ __launch_bounds__(kThreads) void k_select_bytes(const GroupRec* __restrict__ tbl, int K,
+template <class Groups>
+__global__ __launch_bounds__(kThreads) void k_select_bytes(Groups tbl, int K,
                                                             const double* __restrict__ R, int64_t t_g,
                                                             int64_t H, unsigned long long byte_budget,
                                                             int* __restrict__ sel, int* __restrict__ n_sel) {

@@ -8,6 +8,7 @@ namespace {
 // ------------------------------------------------------------------ host side
 thread_local int g_last_hip_error = 0;
 std::atomic<int> g_blocks_per_cu{0};
+std::atomic<int> g_tables_in_args{1};  // small tables travel inside the kernel arguments (0: always upload)
 
 int hip_fail(hipError_t e) {
   g_last_hip_error = static_cast<int>(e);
@@ -61,16 +62,38 @@ bool overlap(const Span& a, const Span& b) {
   return a0 < b0 + b.bytes && b0 < a0 + a.bytes;
 }
 
-// Host-side plan of one call: the records to upload and the number of tiles.
+// Host-side plan of one call: the records the kernels read and the number of tiles.
 struct Plan {
   std::vector<SegRec> segs;      // S + 1 segment records
   std::vector<GroupRec> groups;  // K + 1 fragment records
   int32_t S = 0, K = 0;
   int tile_shift = kTileShiftLarge;
   uint64_t T = 0;
+  // Small tables are handed to every kernel inside its arguments, which saves the upload launch
+  // in front of it (a quarter of the time of a step on a cache-resident fragment set).  Set when
+  // the plan is made; a caller that needs the tables in the workspace clears it before launching.
+  bool in_args = false;
 };
 
-Walk walk_of(const WorkspaceView& v, const Plan& pl) { return Walk{v.table, pl.T, pl.S, pl.tile_shift}; }
+// What launch_walk needs to launch a streaming kernel over a plan.
+struct HostWalk {
+  const Plan* plan;
+  const SegRec* dev_table;
+};
+HostWalk walk_of(const WorkspaceView& v, const Plan& pl) { return HostWalk{&pl, v.table}; }
+
+SegInline seg_args(const Plan& pl) {
+  SegInline a;
+  std::memset(&a, 0, sizeof(a));
+  std::memcpy(a.r, pl.segs.data(), sizeof(SegRec) * pl.segs.size());
+  return a;
+}
+GroupInline group_args(const Plan& pl) {
+  GroupInline a;
+  std::memset(&a, 0, sizeof(a));
+  std::memcpy(a.r, pl.groups.data(), sizeof(GroupRec) * pl.groups.size());
+  return a;
+}
 
 // What a caller's event mask says about fragment p (no mask: every fragment takes part).
 constexpr uint8_t kMaskArrived = 1, kMaskInFlight = 2;
@@ -136,6 +159,7 @@ int plan_segments(const cocodc_segment_t* segs, int32_t S, int32_t K, uint64_t n
     grp_rec[p].in_flight = (mask && (mask[p] & kMaskInFlight)) ? 1 : 0;
   }
   plan->T = slot;
+  plan->in_args = S <= kInlineRecs && K <= kInlineRecs && g_tables_in_args.load(std::memory_order_relaxed) != 0;
   return COCODC_OK;
 }
 
@@ -158,6 +182,7 @@ int plan_table(const cocodc_fragment_t* frags, int32_t K, uint64_t n_total, cons
 // Both tables go to the head of the workspace (segment records, then fragment records) as kernel
 // arguments of a few small launches: no memcpy node, so a call records into a HIP graph.
 int upload_table(const Plan& pl, const WorkspaceView& v, hipStream_t s) {
+  if (pl.in_args) return COCODC_OK;  // every kernel of this call gets the records with its arguments
   static_assert(sizeof(SegRec) % 16 == 0 && sizeof(GroupRec) % 16 == 0, "tables are moved in 16-byte words");
   const size_t seg_bytes = sizeof(SegRec) * pl.segs.size(), grp_bytes = sizeof(GroupRec) * pl.groups.size();
   std::vector<unsigned char> blob(seg_bytes + grp_bytes);
@@ -271,17 +296,57 @@ int prof_end(int slot, hipStream_t s) {
 // Every streaming kernel is launched here; while the timer is on, each launch is bracketed by a
 // pair of events on the launch stream.
 template <class Op>
-int launch_walk(bool vec, const Walk& wk, const Op& op, double* partials, hipStream_t s) {
-  if (wk.T == 0) return COCODC_OK;
+int launch_walk(bool vec, const HostWalk& hw, const Op& op, double* partials, hipStream_t s) {
+  const Plan& pl = *hw.plan;
+  if (pl.T == 0) return COCODC_OK;
   const int slot = prof_begin(s);
-  const dim3 grid(grid_for(wk.T)), block(kThreads);
-  if (vec) {
-    hipLaunchKernelGGL((k_walk<Op, true>), grid, block, 0, s, wk, op, partials);
+  const dim3 grid(grid_for(pl.T)), block(kThreads);
+  const Walk wk{pl.T, pl.S, pl.tile_shift};
+  if (pl.in_args) {
+    const SegInline tbl = seg_args(pl);
+    if (vec) {
+      hipLaunchKernelGGL((k_walk<Op, true, SegInline>), grid, block, 0, s, tbl, wk, op, partials);
+    } else {
+      hipLaunchKernelGGL((k_walk<Op, false, SegInline>), grid, block, 0, s, tbl, wk, op, partials);
+    }
   } else {
-    hipLaunchKernelGGL((k_walk<Op, false>), grid, block, 0, s, wk, op, partials);
+    const SegTable tbl{hw.dev_table};
+    if (vec) {
+      hipLaunchKernelGGL((k_walk<Op, true, SegTable>), grid, block, 0, s, tbl, wk, op, partials);
+    } else {
+      hipLaunchKernelGGL((k_walk<Op, false, SegTable>), grid, block, 0, s, tbl, wk, op, partials);
+    }
   }
   HIP_TRY(hipGetLastError());
   return prof_end(slot, s);
+}
+
+// Per-fragment sums of the tile partials and Eq. 11.
+int launch_finalize(const Plan& pl, const WorkspaceView& v, int n_acc, int which, int l2, double* R_out,
+                    double* sums_out, int sums_stride, hipStream_t s) {
+  if (pl.in_args) {
+    hipLaunchKernelGGL(k_finalize<GroupInline>, dim3(pl.K), dim3(kFinalizeThreads), 0, s, group_args(pl), v.partials,
+                       n_acc, which, l2, R_out, sums_out, sums_stride);
+  } else {
+    hipLaunchKernelGGL(k_finalize<GroupTable>, dim3(pl.K), dim3(kFinalizeThreads), 0, s, GroupTable{v.groups},
+                       v.partials, n_acc, which, l2, R_out, sums_out, sums_stride);
+  }
+  HIP_TRY(hipGetLastError());
+  return COCODC_OK;
+}
+
+// Algorithm 2, n times.
+int launch_select(const Plan& pl, const WorkspaceView& v, const double* R, int64_t t_g, int64_t H, int n, int32_t* sel,
+                  int32_t* n_sel, hipStream_t s) {
+  if (pl.in_args) {
+    hipLaunchKernelGGL(k_select<GroupInline>, dim3(1), dim3(kThreads), 0, s, group_args(pl), pl.K, R, t_g, H, n, sel,
+                       n_sel);
+  } else {
+    hipLaunchKernelGGL(k_select<GroupTable>, dim3(1), dim3(kThreads), 0, s, GroupTable{v.groups}, pl.K, R, t_g, H, n,
+                       sel, n_sel);
+  }
+  HIP_TRY(hipGetLastError());
+  return COCODC_OK;
 }
 
 // The walk over the one fragment that *chosen (device memory) names; max_tiles = the number of
@@ -315,7 +380,7 @@ bool all_aligned4(std::initializer_list<const void*> ps) {
 }
 
 template <bool NESTEROV, int MERGE>
-int launch_fused(bool vec, const Walk& wk, float* tm, const float* ts, float* tg,
+int launch_fused(bool vec, const HostWalk& wk, float* tm, const float* ts, float* tg,
                  float* m, const float* dg, float* pg, const DevHP& hp, double* partials, hipStream_t s) {
   if (MERGE == 1 || MERGE == 2) {
     if (!ts) {  // the blend and the plain replacement never look at the send-time record
@@ -336,7 +401,7 @@ int launch_fused(bool vec, const Walk& wk, float* tm, const float* ts, float* tg
 }
 
 template <bool NESTEROV>
-int launch_fused_m(int merge, bool vec, const Walk& wk, float* tm, const float* ts,
+int launch_fused_m(int merge, bool vec, const HostWalk& wk, float* tm, const float* ts,
                    float* tg, float* m, const float* dg, float* pg, const DevHP& hp, double* partials,
                    hipStream_t s) {
   switch (merge) {
@@ -349,7 +414,7 @@ int launch_fused_m(int merge, bool vec, const Walk& wk, float* tm, const float* 
 }
 
 template <bool NESTEROV, int MERGE>
-int launch_fused_bf16(bool vec, const Walk& wk, unsigned short* tm, const unsigned short* ts,
+int launch_fused_bf16(bool vec, const HostWalk& wk, unsigned short* tm, const unsigned short* ts,
                       float* tg, float* m, const float* dg, unsigned short* pg, const DevHP& hp, double* partials,
                       hipStream_t s) {
   if (MERGE == 1 || MERGE == 2) {
@@ -371,7 +436,7 @@ int launch_fused_bf16(bool vec, const Walk& wk, unsigned short* tm, const unsign
 }
 
 template <bool NESTEROV>
-int launch_fused_bf16_m(int merge, bool vec, const Walk& wk, unsigned short* tm,
+int launch_fused_bf16_m(int merge, bool vec, const HostWalk& wk, unsigned short* tm,
                         const unsigned short* ts, float* tg, float* m, const float* dg, unsigned short* pg,
                         const DevHP& hp, double* partials, hipStream_t s) {
   switch (merge) {

@@ -214,6 +214,7 @@ int cocodc_loop_step(cocodc_loop_t* loop, int64_t t, const cocodc_loop_buffers_t
   Plan pl;
   if (int rc = plan_table(loop->frags.data(), K, loop->n_total, I_new.data(), tb_new.data(), &pl, mask.data()))
     return rc;
+  if (decide) pl.in_args = false;  // the walk over the chosen fragment reads the fragment records from the workspace
   if (int rc = sync_step_impl(pl, K, loop->n_total, buf->theta_m, buf->theta_m_send, buf->theta_g, buf->momentum,
                               buf->delta_g, nullptr, t, decide ? 1 : 0, &loop->hp, buf->R, buf->sel, buf->n_sel,
                               nullptr, buf->workspace, buf->workspace_bytes, stream))

@@ -442,6 +442,49 @@ def test_bitwise_reproducible_and_independent_of_launch_shape(B, ref):
         assert o["sel_list"] == o0["sel_list"]
 
 
+@pytest.mark.parametrize("name", ["tiny", "125M-mini", "7B-mini"])
+def test_tables_in_kernel_arguments_equal_uploaded_tables(B, name):
+    """Tables of up to 32 segments and fragments travel inside the kernel arguments instead of being
+    written to the workspace first: the fused step, the single steps and the selection give the very
+    same bits either way (7B-mini has exactly 32 fragments, the largest table that takes this path)."""
+    wl = synth.WORKLOADS[name] if name in synth.WORKLOADS else synth.MINI_WORKLOADS[name]
+    bk = synth.bookkeeping(wl, "mixed")
+    ghp = B.hparams(wl.tau, wl.H)
+    st = synth.make_state(wl, "cuda", seed=9)
+    n, K = wl.n_total, wl.K
+    ws = B.new_workspace(K, n)
+    results = []
+    old = B.cocodc_set_tables_in_args(1)
+    try:
+        for in_args in (1, 0, 1):
+            B.cocodc_set_tables_in_args(in_args)
+            s = {k: v.clone() for k, v in st.items()}
+            o = U.run_gpu_fused(B, wl.frags, n, s, bk, wl.budget, ghp, ws)
+            # the single steps on a second copy
+            t = {k: v.clone() for k, v in st.items()}
+            pg, send = torch.zeros(n, device="cuda"), torch.zeros(n, device="cuda")
+            R, S = (torch.zeros(K, dtype=torch.float64, device="cuda") for _ in range(2))
+            sel = torch.full((K,), -1, dtype=torch.int32, device="cuda")
+            n_sel = torch.zeros(1, dtype=torch.int32, device="cuda")
+            assert B.cocodc_pseudograd(wl.frags, n, t["theta_g"], t["theta_m"], pg, send, ws) == 0
+            assert B.cocodc_outer_nesterov(wl.frags, n, t["theta_g"], t["momentum"], t["delta_g"], ghp, ws) == 0
+            assert B.cocodc_delay_compensate(wl.frags, n, t["theta_m"], t["theta_m_send"], t["theta_g"], ghp, ws) == 0
+            assert B.cocodc_fragment_scores(wl.frags, n, t["delta_g"], bk.I_p, 2, R, S, ws) == 0
+            assert B.cocodc_select_fragments(K, R, bk.t_b, bk.t_g, wl.H, wl.budget, sel, n_sel, ws) == 0
+            torch.cuda.synchronize()
+            results.append((s, o, t, pg, send, R, S, sel, n_sel))
+    finally:
+        B.cocodc_set_tables_in_args(old)
+    s0, o0, t0, pg0, send0, R0, S0, sel0, n_sel0 = results[0]
+    for s, o, t, pg, send, R, S, sel, n_sel in results[1:]:
+        for k in ("theta_m", "theta_g", "momentum"):
+            assert torch.equal(s[k], s0[k]) and torch.equal(t[k], t0[k]) and torch.equal(s[k], t[k]), k
+        assert torch.equal(o["pg"], o0["pg"]) and torch.equal(pg, pg0) and torch.equal(send, send0)
+        assert torch.equal(o["R"], o0["R"]) and torch.equal(o["sums"], o0["sums"]) and o["sel_list"] == o0["sel_list"]
+        assert torch.equal(R, R0) and torch.equal(S, S0) and torch.equal(sel, sel0) and torch.equal(n_sel, n_sel0)
+        assert torch.equal(R, o["R"])
+
+
 def test_scores_do_not_depend_on_buffer_alignment(B):
     """The same fragment table over the same values at bases that are 16-byte aligned, 4 bytes off
     and 8 bytes off: stored values, raw sums, scores and selection are bit-identical."""
