@@ -1,8 +1,10 @@
 """ctypes binding of include/cocodc.h: same names, argument marshalling only.
 
-Every step of the path runs in the HIP kernels of libcocodc.so; there is no fallback.  If the
-library has not been built (python -m paper_2504_17672_amd.build) importing this module
-raises.  Buffers are torch CUDA(HIP) tensors (or raw integer device addresses); host-side
+Every step of the path runs in the HIP kernels of libcocodc.so; there is no fallback.
+Importing this module loads that library.  NOTE the one side effect of the import: if the library
+file is missing, the import first tries to compile it (python -m paper_2504_17672_amd.build, i.e.
+one hipcc run of about 20 s; hipcc cross-compiles without a GPU) and raises ImportError if that
+fails.  Build beforehand to keep imports free of compiler runs.  Buffers are torch CUDA(HIP) tensors (or raw integer device addresses); host-side
 tables are Python sequences.  Every function returns the library's status code; wrap a call
 in check() to turn a failure into an exception.
 """

@@ -75,7 +75,7 @@ def test_workspace_size(B):
     a = B.cocodc_workspace_bytes(4, 1 << 20)
     b = B.cocodc_workspace_bytes(4, 1 << 30)
     assert 0 < a < b and a % 256 == 0
-    # a few dozen bytes of partial sums per 64 KiB tile: far below 1 % of one buffer
+    # 32 bytes of partial sums per tile of 4096 elements (16 KiB of one buffer): 0.2 %, far below 1 %
     assert b < 0.01 * 4 * (1 << 30)
 
 
