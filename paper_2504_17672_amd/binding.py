@@ -240,12 +240,15 @@ def spaced_buffers(n_total, count, device="cuda", stride_bytes=None):
     return arena, [arena[k * stride:k * stride + nbytes].view(torch.float32) for k in range(count)]
 
 
-def tuned_spaced_buffers(n_total, frags, device="cuda", count=6, max_arena_bytes=None, verbose=None):
+def tuned_spaced_buffers(n_total, frags, device="cuda", count=6, max_arena_bytes=None, verbose=None, step=None):
     """Like spaced_buffers, but picks the stride by measurement: the best of the candidate
     strides that fit into one allocation of at most max_arena_bytes (default: 92 % of the free
     device memory), each timed with a few launches of the fused step on zero-filled memory.
     Which strides are fastest depends on where the allocation lands, so this is done once per
-    allocation, at set-up.  Returns (arena, [buffers], stride_bytes, {stride_GiB: ms})."""
+    allocation, at set-up.  A caller whose hot call is not the fused step passes step(buffers),
+    a function that enqueues that call (or sequence of calls) on the `count` candidate buffers;
+    it is timed instead (the single steps prefer other strides than the fused step does).
+    Returns (arena, [buffers], stride_bytes, {stride_GiB: ms})."""
     import torch
     GiB = 1 << 30
     nbytes = 4 * int(n_total)
@@ -280,8 +283,11 @@ def tuned_spaced_buffers(n_total, frags, device="cuda", count=6, max_arena_bytes
         best = float("inf")
         for it in range(4):
             start.record()
-            check(cocodc_sync_step(frags, n_total, b[0], b[1], b[2], b[3], b[4], b[5] if count > 5 else None,
-                                   ones, ones, 2, 1, hp, R, sel, n_sel, None, ws))
+            if step is not None:
+                step(b)
+            else:
+                check(cocodc_sync_step(frags, n_total, b[0], b[1], b[2], b[3], b[4], b[5] if count > 5 else None,
+                                       ones, ones, 2, 1, hp, R, sel, n_sel, None, ws))
             stop.record()
             torch.cuda.synchronize()
             if it:
