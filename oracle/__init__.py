@@ -29,7 +29,7 @@ class HParams(C.Structure):
         ("nesterov", C.c_int32), ("drift_sign", C.c_int32),
         ("score_src", C.c_int32), ("norm_kind", C.c_int32),
         ("merge_mode", C.c_int32), ("alpha", C.c_double),
-        ("delta_src", C.c_int32), ("reserved", C.c_int32),
+        ("delta_src", C.c_int32), ("pg_format", C.c_int32),
     ]
 
 
@@ -42,10 +42,10 @@ class Shadow(C.Structure):
 
 
 def hparams(tau, H, lam=0.5, eta=0.7, mu=0.9, nesterov=1, drift_sign=1, score_src=0, norm_kind=2,
-            merge_mode=0, alpha=1.0, delta_src=0):
+            merge_mode=0, alpha=1.0, delta_src=0, pg_format=0):
     return HParams(int(tau), int(H), float(lam), float(eta), float(mu), int(nesterov),
                    int(drift_sign), int(score_src), int(norm_kind), int(merge_mode), float(alpha),
-                   int(delta_src), 0)
+                   int(delta_src), int(pg_format))
 
 
 def lib():
@@ -65,6 +65,10 @@ def lib():
         _lib.cocodc_ref_round_bf16.argtypes = [C.c_double]
         _lib.cocodc_ref_widen_bf16.restype = C.c_double
         _lib.cocodc_ref_widen_bf16.argtypes = [C.c_uint16]
+        _lib.cocodc_ref_round_f16.restype = C.c_uint16
+        _lib.cocodc_ref_round_f16.argtypes = [C.c_double]
+        _lib.cocodc_ref_widen_f16.restype = C.c_double
+        _lib.cocodc_ref_widen_f16.argtypes = [C.c_uint16]
     return _lib
 
 
@@ -273,11 +277,20 @@ def widen_bf16(b):
     return float(lib().cocodc_ref_widen_bf16(int(b)))
 
 
-def pseudograd_bf16(frags, theta_g_snap, theta_m, delta_m_out, theta_m_send_out=None):
-    """theta_m, delta_m_out, theta_m_send_out: uint16 arrays holding bf16 bit patterns."""
+def round_f16(x):
+    return int(lib().cocodc_ref_round_f16(float(x)))
+
+
+def widen_f16(b):
+    return float(lib().cocodc_ref_widen_f16(int(b)))
+
+
+def pseudograd_bf16(frags, theta_g_snap, theta_m, delta_m_out, theta_m_send_out=None, pg_format=0):
+    """theta_m, theta_m_send_out: uint16 arrays holding bf16 bit patterns; delta_m_out: uint16 patterns of
+    bf16 (pg_format 0) or IEEE binary16 (pg_format 1)."""
     return lib().cocodc_ref_pseudograd_bf16(_frag_array(frags), C.c_int32(len(frags)), C.c_uint64(theta_m.size),
                                             _f32(theta_g_snap), _u16(theta_m), _u16(delta_m_out),
-                                            _u16(theta_m_send_out, True))
+                                            _u16(theta_m_send_out, True), C.c_int32(pg_format))
 
 
 def sync_step_bf16(frags, theta_m, theta_m_send, theta_g, momentum, delta_g, delta_m_out, I_p, t_b, t_g, budget, hp,

@@ -55,6 +55,7 @@ int check_hparams(const cocodc_ref_hparams_t* hp) {
   if (hp->norm_kind != 1 && hp->norm_kind != 2) return kErrRange;
   if (hp->merge_mode < 0 || hp->merge_mode > 2) return kErrRange;
   if (hp->delta_src != 0 && hp->delta_src != 1) return kErrRange;
+  if (hp->pg_format != 0 && hp->pg_format != 1) return kErrRange;
   if (!std::isfinite(hp->lambda) || !std::isfinite(hp->eta) || !std::isfinite(hp->mu) ||
       !std::isfinite(hp->alpha))
     return kErrRange;
@@ -512,15 +513,60 @@ uint16_t cocodc_ref_round_bf16(double x) {
   return static_cast<uint16_t>(u >> 16);
 }
 
+// IEEE binary16: 11 significant bits, exponents -14..15, subnormal spacing 2^-24, largest
+// finite value 65504.
+double cocodc_ref_widen_f16(uint16_t b) {
+  const int sign = (b >> 15) & 1, e = (b >> 10) & 0x1F, m = b & 0x3FF;
+  double v;
+  if (e == 0x1F) {
+    v = m ? std::numeric_limits<double>::quiet_NaN() : std::numeric_limits<double>::infinity();
+  } else if (e == 0) {
+    v = std::ldexp(static_cast<double>(m), -24);           // subnormal: m * 2^-24
+  } else {
+    v = std::ldexp(static_cast<double>(1024 + m), e - 25);  // (1 + m/1024) * 2^(e-15)
+  }
+  return sign ? -v : v;
+}
+
+// Nearest binary16 to x, ties to even: scale so that one binary16 step at x's magnitude becomes
+// 1, round to the nearest integer (current rounding mode = to nearest even), and read the
+// exponent and fraction fields off that integer.
+uint16_t cocodc_ref_round_f16(double x) {
+  if (std::isnan(x)) return 0x7E00;
+  const uint16_t sign = std::signbit(x) ? 0x8000 : 0;
+  const double a = std::fabs(x);
+  if (a == 0.0) return sign;
+  if (std::isinf(a)) return sign | 0x7C00;
+  int e = std::ilogb(a);             // a = f * 2^e, 1 <= f < 2
+  if (e < -14) e = -14;              // subnormal range: fixed spacing 2^-24
+  if (e > 15) return sign | 0x7C00;  // beyond the largest exponent
+  double q = std::nearbyint(std::ldexp(a, 10 - e));  // a in units of 2^(e-10): 1024 <= q <= 2048, or q < 1024 (subnormal)
+  if (q >= 2048.0) {                 // rounded up to the next power of two
+    q = 1024.0;
+    e += 1;
+    if (e > 15) return sign | 0x7C00;  // 65520 and above round to infinity
+  }
+  const int qi = static_cast<int>(q);
+  if (qi < 1024) return sign | static_cast<uint16_t>(qi);  // subnormal (or zero): exponent field 0
+  return sign | static_cast<uint16_t>(((e + 15) << 10) | (qi - 1024));
+}
+
+namespace {
+inline uint16_t round_half(double x, int32_t pg_format) {
+  return pg_format ? cocodc_ref_round_f16(x) : cocodc_ref_round_bf16(x);
+}
+}  // namespace
+
 int cocodc_ref_pseudograd_bf16(const cocodc_ref_fragment_t* frags, int32_t K, uint64_t n_total,
                                const float* theta_g_snap, const uint16_t* theta_m,
-                               uint16_t* delta_m_out, uint16_t* theta_m_send_out) {
+                               uint16_t* delta_m_out, uint16_t* theta_m_send_out, int32_t pg_format) {
   if (!theta_g_snap || !theta_m || !delta_m_out) return kErrNull;
+  if (pg_format != 0 && pg_format != 1) return kErrRange;
   if (int rc = check_table(frags, K, n_total)) return rc;
   for (int32_t p = 0; p < K; ++p) {
     for (uint64_t i = frags[p].offset; i < frags[p].offset + frags[p].length; ++i) {
       const double tg = theta_g_snap[i], tm = cocodc_ref_widen_bf16(theta_m[i]);
-      delta_m_out[i] = cocodc_ref_round_bf16(tg - tm);
+      delta_m_out[i] = round_half(tg - tm, pg_format);
       if (theta_m_send_out) theta_m_send_out[i] = theta_m[i];
     }
   }
@@ -555,7 +601,7 @@ int cocodc_ref_sync_step_bf16(const cocodc_ref_fragment_t* frags, int32_t K, uin
       s.g1 += std::fabs(dg);
       s.d2 += d * d;
       s.d1 += std::fabs(d);
-      if (delta_m_out) delta_m_out[i] = cocodc_ref_round_bf16(tg - tm);
+      if (delta_m_out) delta_m_out[i] = round_half(tg - tm, hp->pg_format);
       momentum[i] = static_cast<float>(m1);
       theta_g[i] = G;
       theta_m[i] = cocodc_ref_round_bf16(tm_new);

@@ -56,7 +56,7 @@ typedef struct {
                          equation that introduces Eq. 5); 1 = theta^m_{p,t_p} - theta^g_{p,t_p-H}
                          (the change accumulated over H steps that the text after Eq. 6 describes);
                          1 needs the previous global state: fused step only              */
-  int32_t reserved;   /* 0 */
+  int32_t pg_format;  /* bf16 calls only: the outgoing pseudo-gradient is 0: bfloat16, 1: IEEE binary16 */
 } cocodc_ref_hparams_t;
 
 /* Optional fp64 (unrounded) copies of the three stored outputs of the fused step. */
@@ -170,9 +170,17 @@ int cocodc_ref_sync_step_segmented(const cocodc_ref_segment_t* segs, int32_t S, 
 uint16_t cocodc_ref_round_bf16(double x);
 double cocodc_ref_widen_bf16(uint16_t b);
 
+/* The outgoing pseudo-gradient alone may instead be IEEE binary16 (pg_format 1: 1 sign, 5 exponent,
+ * 10 fraction bits; the usual 16-bit wire format of an all-reduce): the fp64 difference rounded
+ * ONCE to the nearest binary16, ties to even, subnormals (spacing 2^-24) kept, magnitudes of
+ * 65520 and more to infinity, any NaN to 0x7E00. */
+uint16_t cocodc_ref_round_f16(double x);
+double cocodc_ref_widen_f16(uint16_t b);
+
 int cocodc_ref_pseudograd_bf16(const cocodc_ref_fragment_t* frags, int32_t K, uint64_t n_total,
                                const float* theta_g_snap, const uint16_t* theta_m,
-                               uint16_t* delta_m_out, uint16_t* theta_m_send_out /* nullable */);
+                               uint16_t* delta_m_out, uint16_t* theta_m_send_out /* nullable */,
+                               int32_t pg_format);
 
 /* shadow (nullable): unrounded fp64 theta_m / theta_g / momentum as in cocodc_ref_sync_step. */
 int cocodc_ref_sync_step_bf16(const cocodc_ref_fragment_t* frags, int32_t K, uint64_t n_total,

@@ -67,6 +67,10 @@ def test_oracle_pins_under_asan_and_ubsan(tmp_path):
         lib.cocodc_ref_round_bf16.argtypes = [C.c_double]
         lib.cocodc_ref_widen_bf16.restype = C.c_double
         lib.cocodc_ref_widen_bf16.argtypes = [C.c_uint16]
+        lib.cocodc_ref_round_f16.restype = C.c_uint16
+        lib.cocodc_ref_round_f16.argtypes = [C.c_double]
+        lib.cocodc_ref_widen_f16.restype = C.c_double
+        lib.cocodc_ref_widen_f16.argtypes = [C.c_uint16]
         oracle._lib = lib
         import test_oracle_pins as a, test_oracle_segments as b, test_oracle_bf16 as c, test_oracle_loop as d
         n = 0

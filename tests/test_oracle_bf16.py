@@ -109,3 +109,98 @@ def test_bf16_pseudograd_records_the_send_time_parameters(ref):
         exact = Fraction(float(a["theta_g"][i])) - Fraction(ref.widen_bf16(int(a["theta_m"][i])))
         assert pg[i] == ref.round_bf16(float(exact))  # the difference is exact in fp64 here
     assert not pg[:100].any() and not pg[700:].any()
+
+
+# ------------------------------------------------------------------ IEEE binary16 pseudo-gradient
+def test_f16_widen_and_round_are_inverse_on_every_pattern_and_agree_with_numpy(ref):
+    for b in range(65536):
+        x = ref.widen_f16(b)
+        want = float(np.array([b], np.uint16).view(np.float16)[0])
+        if math.isnan(want):
+            assert math.isnan(x) and ref.round_f16(x) == 0x7E00
+        else:
+            assert x == want and ref.round_f16(x) == b
+
+
+F16_TRAPS = [65504.0, 65519.999, 65520.0, 65520.0001, -65520.0, 65536.0, 1e6, -1e300, 2.0 ** -24, 2.0 ** -25,
+             2.0 ** -25 * (1 + 2.0 ** -30), 2.0 ** -25 * (1 - 2.0 ** -30), 3 * 2.0 ** -25, 2.0 ** -14, 2.0 ** -14 - 2.0 ** -25,
+             1 + 2.0 ** -11, 1 + 2.0 ** -11 + 2.0 ** -40, 1 + 2.0 ** -11 - 2.0 ** -40, 1 + 3 * 2.0 ** -11,
+             # a double that rounds to a binary32 lying exactly on a binary16 tie (rounding twice would go wrong)
+             1 + 2.0 ** -11 + 2.0 ** -30, 1 + 3 * 2.0 ** -11 - 2.0 ** -30, -(2 + 2.0 ** -10 + 2.0 ** -29),
+             0.0, -0.0, 1e-320, -4e-46, float("inf"), float("-inf")]
+
+
+def _f16_samples():
+    rng = np.random.default_rng(11)
+    return np.concatenate([rng.normal(0, 1, 20000), rng.normal(0, 0.02, 20000), rng.normal(0, 1e-5, 10000),
+                           rng.normal(0, 1e-7, 5000), rng.normal(0, 3e4, 5000), np.array(F16_TRAPS)])
+
+
+def test_f16_rounding_matches_numpy_from_float64_and_torch_from_float32(ref):
+    """numpy converts a double to binary16 in one rounding.  torch's CPU conversion of a double goes
+    through binary32 (it rounds the traps below twice and gets them wrong), so torch is only asked
+    about values that are binary32 numbers to begin with, where one rounding is all there is."""
+    xs = _f16_samples()
+    got = np.array([ref.round_f16(float(x)) for x in xs], np.uint16)
+    with np.errstate(over="ignore"):
+        want_np = xs.astype(np.float16).view(np.uint16)
+    assert np.array_equal(got, want_np)
+    x32 = xs.astype(np.float32)
+    got32 = np.array([ref.round_f16(float(x)) for x in x32], np.uint16)
+    want_t = torch.from_numpy(x32).to(torch.float16).view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(got32, want_t)
+
+
+def test_f16_rounding_is_nearest_ties_to_even_in_exact_arithmetic(ref):
+    xs = list(_f16_samples()[::23]) + F16_TRAPS
+    for x in xs:
+        x = float(x)
+        if math.isinf(x) or abs(x) >= 65520.0:
+            assert ref.round_f16(x) == (0xFC00 if x < 0 else 0x7C00)
+            continue
+        b = ref.round_f16(x)
+        assert (b & 0x7C00) != 0x7C00                       # finite
+        r = Fraction(ref.widen_f16(b))
+        err = abs(Fraction(x) - r)
+        mag = b & 0x7FFF
+        nbs = []
+        if mag < 0x7BFF:
+            nbs.append(Fraction(ref.widen_f16(b + 1)))
+        else:
+            nbs.append(Fraction(65536) * (-1 if b & 0x8000 else 1))   # the value the next pattern would have
+        nbs.append(Fraction(ref.widen_f16(b - 1)) if mag > 0 else Fraction(ref.widen_f16((b ^ 0x8000) | 1)))
+        for nb in nbs:
+            e2 = abs(Fraction(x) - nb)
+            assert err <= e2, (x, hex(b))
+            if err == e2:
+                assert b % 2 == 0, (x, hex(b))              # a tie goes to the even pattern
+
+
+def test_f16_pseudograd_in_the_bf16_calls(ref):
+    """pg_format 1 changes the format of the outgoing pseudo-gradient and nothing else."""
+    wl = synth.Workload("h", (3000, 1999, 0, 777), tau=2, H=1, budget=2)
+    bk = synth.bookkeeping(wl, "mixed")
+    a = _bf16_state(wl, 13, amplified=True)
+    b = {k: v.copy() for k, v in a.items()}
+    tg0, tm0 = a["theta_g"].copy(), a["theta_m"].copy()
+    pg_a, pg_b = np.zeros(wl.n_total, np.uint16), np.zeros(wl.n_total, np.uint16)
+    oa = ref.sync_step_bf16(wl.frags, a["theta_m"], a["theta_m_send"], a["theta_g"], a["momentum"], a["delta_g"], pg_a,
+                            bk.I_p, bk.t_b, bk.t_g, 2, ref.hparams(2, 1, pg_format=0))
+    ob = ref.sync_step_bf16(wl.frags, b["theta_m"], b["theta_m_send"], b["theta_g"], b["momentum"], b["delta_g"], pg_b,
+                            bk.I_p, bk.t_b, bk.t_g, 2, ref.hparams(2, 1, pg_format=1))
+    assert oa["rc"] == 0 and ob["rc"] == 0
+    for k in a:
+        assert np.array_equal(a[k], b[k]), k
+    assert np.array_equal(oa["R"], ob["R"]) and oa["sel"].tolist() == ob["sel"].tolist()
+    diff = tg0.astype(np.float64) - _widen(tm0).astype(np.float64)      # exact in fp64
+    with np.errstate(over="ignore"):
+        want = diff.astype(np.float16).view(np.uint16)
+    assert np.array_equal(pg_b, want)
+    assert not np.array_equal(pg_a, pg_b)
+    # the single-step call
+    pg_c, send = np.zeros(wl.n_total, np.uint16), np.zeros(wl.n_total, np.uint16)
+    assert ref.pseudograd_bf16(wl.frags, tg0, tm0, pg_c, send, pg_format=1) == 0
+    assert np.array_equal(pg_c, want) and np.array_equal(send, tm0)
+    assert ref.pseudograd_bf16(wl.frags, tg0, tm0, pg_c, send, pg_format=2) < 0
+    assert ref.sync_step_bf16(wl.frags, a["theta_m"], a["theta_m_send"], a["theta_g"], a["momentum"], a["delta_g"],
+                              pg_a, bk.I_p, bk.t_b, bk.t_g, 2, ref.hparams(2, 1, pg_format=3))["rc"] < 0

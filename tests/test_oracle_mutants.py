@@ -9,6 +9,7 @@ import subprocess
 import pytest
 
 import oracle
+import test_oracle_bf16 as half_pins
 import test_oracle_loop as loop_pins
 import test_oracle_pins as pins
 
@@ -66,6 +67,14 @@ MUTANTS = [
      "for (int32_t q = 0; q < K; ++q) if (!(recv_mask[q] & 1)) R[q] = -1.0;\n  return select_among(K, R, t_b, t_g, hp->H, budget, in_flight.data(), sel_out, n_sel_out);\n}"),
     ("event_ignores_in_flight", "in_flight[q] = (recv_mask[q] & 2) ? 1 : 0;", "in_flight[q] = 0;"),
     ("event_in_flight_bit_confused_with_arrived", "in_flight[q] = (recv_mask[q] & 2) ? 1 : 0;", "in_flight[q] = (recv_mask[q] & 1) ? 1 : 0;"),
+    ("f16_truncates", "double q = std::nearbyint(std::ldexp(a, 10 - e));", "double q = std::floor(std::ldexp(a, 10 - e));"),
+    ("f16_subnormals_flushed", "if (qi < 1024) return sign | static_cast<uint16_t>(qi);", "if (qi < 1024) return sign;"),
+    ("f16_wrong_exponent_bias", "((e + 15) << 10)", "((e + 16) << 10)"),
+    ("f16_no_carry_into_the_exponent", "  if (q >= 2048.0) {", "  if (q > 2048.0) {"),
+    ("f16_saturates_instead_of_infinity", "    if (e > 15) return sign | 0x7C00;  // 65520 and above round to infinity",
+     "    if (e > 15) return sign | 0x7BFF;"),
+    ("f16_format_switch_ignored", "return pg_format ? cocodc_ref_round_f16(x) : cocodc_ref_round_bf16(x);",
+     "return cocodc_ref_round_bf16(x);"),
     ("in_flight_counts_against_the_budget", "const int32_t n_sel = budget < candidates ? budget : candidates;",
      "const int32_t n_sel = (budget < K ? budget : K) - (K - candidates) > 0 ? (budget < K ? budget : K) - (K - candidates) : 0;"),
 ]
@@ -101,6 +110,8 @@ BATTERY = [
     pins.test_selection_exhaustive_small,
     lambda ref: loop_pins.test_event_equals_step_on_the_arrived_fragments_then_selection_over_all(ref, (0, 1, 0, 0, 1)),
     loop_pins.test_selection_passes_over_fragments_in_flight,
+    half_pins.test_f16_rounding_matches_numpy_from_float64_and_torch_from_float32,
+    half_pins.test_f16_pseudograd_in_the_bf16_calls,
 ]
 
 
@@ -112,8 +123,12 @@ def _compile(text, path):
                     "-I", os.path.dirname(SRC), "-o", path, src], check=True)
     lib = C.CDLL(path)
     for name in ("pseudograd", "outer_nesterov", "delay_compensate", "fragment_scores", "select_fragments",
-                 "sync_step", "sync_step_mt", "sync_plan", "sync_event"):
+                 "sync_step", "sync_step_mt", "sync_plan", "sync_event", "pseudograd_bf16", "sync_step_bf16"):
         getattr(lib, "cocodc_ref_" + name).restype = C.c_int
+    for name, res, arg in (("round_bf16", C.c_uint16, C.c_double), ("widen_bf16", C.c_double, C.c_uint16),
+                           ("round_f16", C.c_uint16, C.c_double), ("widen_f16", C.c_double, C.c_uint16)):
+        getattr(lib, "cocodc_ref_" + name).restype = res
+        getattr(lib, "cocodc_ref_" + name).argtypes = [arg]
     return lib
 
 
