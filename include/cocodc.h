@@ -115,8 +115,12 @@ typedef struct {
                       /* theta^g_{p,t_p-H}, the change accumulated over the last H steps that the   */
                       /* text after Eq. 6 describes; it needs the previous global state, so only    */
                       /* the fused calls accept it (cocodc_delay_compensate: COCODC_ERR_RANGE)      */
-  int32_t reserved;   /* set to 0                                                           */
+  int32_t pg_format;  /* read by cocodc_sync_step_bf16 only: 16-bit format of the outgoing          */
+                      /* pseudo-gradient, COCODC_PG_BF16 (0, default) or COCODC_PG_F16 (IEEE binary16)  */
 } cocodc_hparams_t;
+
+#define COCODC_PG_BF16 0
+#define COCODC_PG_F16 1
 
 /* Bytes of device workspace that any entry point below needs for (K, n_total).
  * Returns 0 if K is outside [1, COCODC_MAX_FRAGMENTS]. */
@@ -281,10 +285,16 @@ int cocodc_sync_step_segmented(const cocodc_segment_t* segs, int32_t S, int32_t 
  * same fp64 arithmetic as above, and each bf16 output is the fp64 value rounded ONCE to the
  * nearest bf16 (ties to even, subnormals kept, overflow to infinity, NaN -> 0x7FC0).  The
  * fused pass then moves 28 instead of 36 bytes per parameter.  delta_m_out cannot alias
- * delta_g here (different element types).  Everything else as in the fp32 calls. */
+ * delta_g here (different element types).  Everything else as in the fp32 calls.
+ *   The outgoing pseudo-gradient alone -- what goes on the wire -- may instead be IEEE binary16
+ *   (pg_format = COCODC_PG_F16; the argument of cocodc_pseudograd_bf16, the field of the
+ *   hyper-parameters for cocodc_sync_step_bf16): the same fp64 difference rounded ONCE to the
+ *   nearest binary16, ties to even, subnormals (spacing 2^-24) kept, magnitudes of 65520 and
+ *   more to infinity, NaN -> 0x7E00.  Same bytes, same speed; any other value of pg_format is
+ *   COCODC_ERR_RANGE. */
 int cocodc_pseudograd_bf16(const cocodc_fragment_t* frags, int32_t K, uint64_t n_total,
                            const float* theta_g_snap, const uint16_t* theta_m, uint16_t* delta_m_out,
-                           uint16_t* theta_m_send_out /* nullable */, void* workspace,
+                           uint16_t* theta_m_send_out /* nullable */, int32_t pg_format, void* workspace,
                            size_t workspace_bytes, void* stream);
 int cocodc_sync_step_bf16(const cocodc_fragment_t* frags, int32_t K, uint64_t n_total, uint16_t* theta_m,
                           const uint16_t* theta_m_send, float* theta_g, float* momentum,

@@ -67,7 +67,7 @@ class cocodc_hparams_t(C.Structure):
         ("nesterov", C.c_int32), ("drift_sign", C.c_int32),
         ("score_src", C.c_int32), ("norm_kind", C.c_int32),
         ("merge_mode", C.c_int32), ("alpha", C.c_double),
-        ("delta_src", C.c_int32), ("reserved", C.c_int32),
+        ("delta_src", C.c_int32), ("pg_format", C.c_int32),
     ]
 
 
@@ -107,7 +107,7 @@ _lib.cocodc_fragment_scores_segmented.argtypes = [_seg_p, C.c_int32, C.c_int32, 
                                                   _P, _P, _P, C.c_size_t, _P]
 _lib.cocodc_sync_step_segmented.argtypes = [_seg_p, C.c_int32, C.c_int32, C.c_uint64, _P, _P, _P, _P, _P, _P, _i64_p,
                                             _i64_p, C.c_int64, C.c_int32, _hp_p, _P, _P, _P, _P, _P, C.c_size_t, _P]
-_lib.cocodc_pseudograd_bf16.argtypes = [_frag_p, C.c_int32, C.c_uint64, _P, _P, _P, _P, _P, C.c_size_t, _P]
+_lib.cocodc_pseudograd_bf16.argtypes = [_frag_p, C.c_int32, C.c_uint64, _P, _P, _P, _P, C.c_int32, _P, C.c_size_t, _P]
 _lib.cocodc_sync_step_bf16.argtypes = [_frag_p, C.c_int32, C.c_uint64, _P, _P, _P, _P, _P, _P, _i64_p, _i64_p,
                                        C.c_int64, C.c_int32, _hp_p, _P, _P, _P, _P, _P, C.c_size_t, _P]
 _lib.cocodc_select_fragments_bytes.argtypes = [C.c_int32, _P, _i64_p, C.c_int64, C.c_int32, C.POINTER(C.c_uint64),
@@ -156,11 +156,14 @@ def check(status):
     return status
 
 
+COCODC_PG_BF16, COCODC_PG_F16 = 0, 1
+
+
 def hparams(tau, H, lam=0.5, eta=0.7, mu=0.9, nesterov=1, drift_sign=1, score_src=0, norm_kind=2,
-            merge_mode=0, alpha=1.0, delta_src=0):
+            merge_mode=0, alpha=1.0, delta_src=0, pg_format=0):
     return cocodc_hparams_t(int(tau), int(H), float(lam), float(eta), float(mu), int(nesterov),
                             int(drift_sign), int(score_src), int(norm_kind), int(merge_mode),
-                            float(alpha), int(delta_src), 0)
+                            float(alpha), int(delta_src), int(pg_format))
 
 
 def _ptr(x):
@@ -535,11 +538,12 @@ def cocodc_sync_step_segmented(segs, K, n_total, theta_m, theta_m_send, theta_g,
 
 # ---- bfloat16 local parameters (torch.bfloat16 tensors, or int16/uint16 views of them) ----
 def cocodc_pseudograd_bf16(frags, n_total, theta_g_snap, theta_m, delta_m_out, theta_m_send_out, workspace,
-                           workspace_bytes=None, stream=None, K=None):
+                           workspace_bytes=None, stream=None, K=None, pg_format=0):
     fa, k = _frags(frags)
     wp, wb = _ws(workspace, workspace_bytes)
     return _lib.cocodc_pseudograd_bf16(fa, k if K is None else K, int(n_total), _ptr(theta_g_snap), _ptr(theta_m),
-                                       _ptr(delta_m_out), _ptr(theta_m_send_out), wp, wb, _stream(stream))
+                                       _ptr(delta_m_out), _ptr(theta_m_send_out), int(pg_format), wp, wb,
+                                       _stream(stream))
 
 
 def cocodc_sync_step_bf16(frags, n_total, theta_m, theta_m_send, theta_g, momentum, delta_g, delta_m_out, I_p, t_b,

@@ -407,8 +407,10 @@ int cocodc_sync_step_segmented(const cocodc_segment_t* segs, int32_t S, int32_t 
 
 int cocodc_pseudograd_bf16(const cocodc_fragment_t* frags, int32_t K, uint64_t n_total,
                            const float* theta_g_snap, const uint16_t* theta_m, uint16_t* delta_m_out,
-                           uint16_t* theta_m_send_out, void* workspace, size_t workspace_bytes_, void* stream) {
+                           uint16_t* theta_m_send_out, int32_t pg_format, void* workspace, size_t workspace_bytes_,
+                           void* stream) {
   if (!theta_g_snap || !theta_m || !delta_m_out) return COCODC_ERR_NULL;
+  if (pg_format != COCODC_PG_BF16 && pg_format != COCODC_PG_F16) return COCODC_ERR_RANGE;
   if (!aligned(theta_g_snap, 4) || !aligned(theta_m, 2) || !aligned(delta_m_out, 2) || !aligned(theta_m_send_out, 2))
     return COCODC_ERR_ALIGN;
   Plan pl;
@@ -423,12 +425,21 @@ int cocodc_pseudograd_bf16(const cocodc_fragment_t* frags, int32_t K, uint64_t n
   WorkspaceView v = view(workspace, pl.S, K);
   if (int rc = upload_table(pl, v, s)) return rc;
   const bool vec = all_aligned16({theta_g_snap, theta_m, delta_m_out, theta_m_send_out});
+  const HostWalk wk = walk_of(v, pl);
+  if (pg_format == COCODC_PG_F16) {
+    if (theta_m_send_out) {
+      PseudoGradBf16Op<true, true> op{theta_g_snap, theta_m, delta_m_out, theta_m_send_out};
+      return launch_walk(vec, wk, op, v.partials, s);
+    }
+    PseudoGradBf16Op<false, true> op{theta_g_snap, theta_m, delta_m_out, nullptr};
+    return launch_walk(vec, wk, op, v.partials, s);
+  }
   if (theta_m_send_out) {
     PseudoGradBf16Op<true> op{theta_g_snap, theta_m, delta_m_out, theta_m_send_out};
-    return launch_walk(vec, walk_of(v, pl), op, v.partials, s);
+    return launch_walk(vec, wk, op, v.partials, s);
   }
   PseudoGradBf16Op<false> op{theta_g_snap, theta_m, delta_m_out, nullptr};
-  return launch_walk(vec, walk_of(v, pl), op, v.partials, s);
+  return launch_walk(vec, wk, op, v.partials, s);
 }
 
 int cocodc_sync_step_bf16(const cocodc_fragment_t* frags, int32_t K, uint64_t n_total, uint16_t* theta_m,
@@ -464,10 +475,11 @@ int cocodc_sync_step_bf16(const cocodc_fragment_t* frags, int32_t K, uint64_t n_
   if (int rc = upload_table(pl, v, s)) return rc;
   const bool vec = all_aligned16({theta_m, theta_m_send, theta_g, momentum, delta_g, delta_m_out});
   const DevHP d = to_dev(*hp);
+  const bool pg_f16 = hp->pg_format == COCODC_PG_F16;
   int rc = hp->nesterov ? launch_fused_bf16_m<true>(merge_variant(*hp), vec, walk_of(v, pl), theta_m, theta_m_send,
-                                                    theta_g, momentum, delta_g, delta_m_out, d, v.partials, s)
+                                                    theta_g, momentum, delta_g, delta_m_out, pg_f16, d, v.partials, s)
                         : launch_fused_bf16_m<false>(merge_variant(*hp), vec, walk_of(v, pl), theta_m, theta_m_send,
-                                                     theta_g, momentum, delta_g, delta_m_out, d, v.partials, s);
+                                                     theta_g, momentum, delta_g, delta_m_out, pg_f16, d, v.partials, s);
   if (rc) return rc;
   const int which = (hp->score_src ? 2 : 0) + (hp->norm_kind == 2 ? 0 : 1);
   if (int rc2 = launch_finalize(pl, v, kSums, which, hp->norm_kind == 2 ? 1 : 0, R_out, sums_out, kSums, s)) return rc2;

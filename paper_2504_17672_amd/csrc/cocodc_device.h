@@ -210,6 +210,33 @@ __device__ __forceinline__ unsigned short round_bf16(double x) {
   return static_cast<unsigned short>(x != x ? 0x7FC0u : r);
 }
 
+// Nearest IEEE binary16 to an fp64 value in ONE rounding, ties to even; subnormals (spacing
+// 2^-24) kept, 65520 and above to infinity, any NaN -> 0x7E00.
+// binary32 carries 13 more significant bits than binary16 and reaches far below its subnormals,
+// so the value is first brought to binary32 "rounded to odd" (the truncated magnitude, with the
+// last bit set whenever anything was cut off), which no later rounding to fewer bits can be
+// fooled by; the hardware conversion binary32 -> binary16 (to nearest even) then gives the same
+// pattern as rounding the fp64 value directly.
+__device__ __forceinline__ unsigned short round_f16(double x) {
+  const float f = static_cast<float>(x);  // hardware conversion, to nearest
+  unsigned u = __float_as_uint(f);
+  const double back = static_cast<double>(f);
+  if (back != x && (u & 0x7F800000u) != 0x7F800000u) {  // inexact (and neither overflowed nor NaN)
+    if (fabs(back) > fabs(x)) u -= 1u;                  // back to the truncated magnitude
+    u |= 1u;
+  }
+  const _Float16 h = static_cast<_Float16>(__uint_as_float(u));
+  unsigned short r;
+  __builtin_memcpy(&r, &h, sizeof(r));
+  return static_cast<unsigned short>(x != x ? 0x7E00u : r);
+}
+
+// The 16-bit pattern of an outgoing pseudo-gradient: bfloat16 or IEEE binary16.
+template <bool F16>
+__device__ __forceinline__ unsigned short round_pg16(double x) {
+  return F16 ? round_f16(x) : round_bf16(x);
+}
+
 // ------------------------------------------------------------------ per-element arithmetic
 // Eq. 2 with OuterOptim = SGD with momentum: m' = mu*m + dg ; step = dg + mu*m' (Nesterov)
 // or m' (heavy ball) ; G = theta_g - eta*step.  Returns G rounded to fp32 (the value that is
@@ -481,7 +508,7 @@ struct MergeOp {
 
 // The fused step with bfloat16 local parameters: theta_m, theta_send and the outgoing
 // pseudo-gradient are bf16 (2 bytes), theta_g, momentum, delta_g stay fp32: 28 B/param.
-template <bool NESTEROV, int MERGE, bool HAS_PG, bool HAS_SEND = true>
+template <bool NESTEROV, int MERGE, bool HAS_PG, bool HAS_SEND = true, bool PG_F16 = false>
 struct FusedBf16Op {
   static constexpr int kAcc = 4;
   static constexpr int kVec = 4;       // 128-bit fp32 accesses, 64-bit bf16 accesses (8-wide measured slower)
@@ -534,7 +561,7 @@ struct FusedBf16Op {
       lane_set(o_tm, k, round_bf16(tm1));
       lane_set(o_tg, k, G);
       lane_set(o_m, k, m1);
-      if (HAS_PG) lane_set(o_pg, k, round_bf16(static_cast<double>(tg) - static_cast<double>(tm)));
+      if (HAS_PG) lane_set(o_pg, k, round_pg16<PG_F16>(static_cast<double>(tg) - static_cast<double>(tm)));
     }
     store_stream_u16<V, A>(theta_m + i, o_tm);
     store_stream<V, A>(theta_g + i, o_tg);
@@ -543,7 +570,7 @@ struct FusedBf16Op {
   }
 };
 
-template <bool HAS_SEND>
+template <bool HAS_SEND, bool PG_F16 = false>
 struct PseudoGradBf16Op {
   static constexpr int kAcc = 0;
   static constexpr int kVec = 4;
@@ -570,8 +597,8 @@ struct PseudoGradBf16Op {
     typename VecU16<V>::type o;
 #pragma unroll
     for (int k = 0; k < V; ++k) {
-      lane_set(o, k, round_bf16(static_cast<double>(lane_get(r.tg, k)) -
-                                static_cast<double>(widen_bf16(lane_get(r.tm, k)))));
+      lane_set(o, k, round_pg16<PG_F16>(static_cast<double>(lane_get(r.tg, k)) -
+                                        static_cast<double>(widen_bf16(lane_get(r.tm, k)))));
     }
     store_stream_u16<V, A>(pg + i, o);
     if (HAS_SEND) store_stream_u16<V, A>(send_out + i, r.tm);

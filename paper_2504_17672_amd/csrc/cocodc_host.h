@@ -217,6 +217,7 @@ int check_hparams(const cocodc_hparams_t* hp) {
   if (hp->norm_kind != 1 && hp->norm_kind != 2) return COCODC_ERR_RANGE;
   if (hp->merge_mode < 0 || hp->merge_mode > 2) return COCODC_ERR_RANGE;
   if (hp->delta_src != 0 && hp->delta_src != 1) return COCODC_ERR_RANGE;
+  if (hp->pg_format != COCODC_PG_BF16 && hp->pg_format != COCODC_PG_F16) return COCODC_ERR_RANGE;
   if (!std::isfinite(hp->lambda) || !std::isfinite(hp->eta) || !std::isfinite(hp->mu) ||
       !std::isfinite(hp->alpha))
     return COCODC_ERR_NONFINITE;
@@ -413,19 +414,29 @@ int launch_fused_m(int merge, bool vec, const HostWalk& wk, float* tm, const flo
   }
 }
 
+// The binary16 pseudo-gradient is an output format: it only exists where a pseudo-gradient is written.
 template <bool NESTEROV, int MERGE>
 int launch_fused_bf16(bool vec, const HostWalk& wk, unsigned short* tm, const unsigned short* ts,
-                      float* tg, float* m, const float* dg, unsigned short* pg, const DevHP& hp, double* partials,
-                      hipStream_t s) {
+                      float* tg, float* m, const float* dg, unsigned short* pg, bool pg_f16, const DevHP& hp,
+                      double* partials, hipStream_t s) {
   if (MERGE == 1 || MERGE == 2) {
     if (!ts) {
-      if (pg) {
-        FusedBf16Op<NESTEROV, (MERGE == 1 || MERGE == 2) ? MERGE : 1, true, false> op{tm, nullptr, tg, m, dg, pg, hp};
+      constexpr int M = (MERGE == 1 || MERGE == 2) ? MERGE : 1;
+      if (pg && pg_f16) {
+        FusedBf16Op<NESTEROV, M, true, false, true> op{tm, nullptr, tg, m, dg, pg, hp};
         return launch_walk(vec, wk, op, partials, s);
       }
-      FusedBf16Op<NESTEROV, (MERGE == 1 || MERGE == 2) ? MERGE : 1, false, false> op{tm, nullptr, tg, m, dg, nullptr, hp};
+      if (pg) {
+        FusedBf16Op<NESTEROV, M, true, false> op{tm, nullptr, tg, m, dg, pg, hp};
+        return launch_walk(vec, wk, op, partials, s);
+      }
+      FusedBf16Op<NESTEROV, M, false, false> op{tm, nullptr, tg, m, dg, nullptr, hp};
       return launch_walk(vec, wk, op, partials, s);
     }
+  }
+  if (pg && pg_f16) {
+    FusedBf16Op<NESTEROV, MERGE, true, true, true> op{tm, ts, tg, m, dg, pg, hp};
+    return launch_walk(vec, wk, op, partials, s);
   }
   if (pg) {
     FusedBf16Op<NESTEROV, MERGE, true> op{tm, ts, tg, m, dg, pg, hp};
@@ -438,13 +449,13 @@ int launch_fused_bf16(bool vec, const HostWalk& wk, unsigned short* tm, const un
 template <bool NESTEROV>
 int launch_fused_bf16_m(int merge, bool vec, const HostWalk& wk, unsigned short* tm,
                         const unsigned short* ts, float* tg, float* m, const float* dg, unsigned short* pg,
-                        const DevHP& hp, double* partials, hipStream_t s) {
+                        bool pg_f16, const DevHP& hp, double* partials, hipStream_t s) {
   switch (merge) {
-    case 0: return launch_fused_bf16<NESTEROV, 0>(vec, wk, tm, ts, tg, m, dg, pg, hp, partials, s);
-    case 1: return launch_fused_bf16<NESTEROV, 1>(vec, wk, tm, ts, tg, m, dg, pg, hp, partials, s);
-    case 2: return launch_fused_bf16<NESTEROV, 2>(vec, wk, tm, ts, tg, m, dg, pg, hp, partials, s);
-    case 4: return launch_fused_bf16<NESTEROV, 4>(vec, wk, tm, ts, tg, m, dg, pg, hp, partials, s);
-    default: return launch_fused_bf16<NESTEROV, 3>(vec, wk, tm, ts, tg, m, dg, pg, hp, partials, s);
+    case 0: return launch_fused_bf16<NESTEROV, 0>(vec, wk, tm, ts, tg, m, dg, pg, pg_f16, hp, partials, s);
+    case 1: return launch_fused_bf16<NESTEROV, 1>(vec, wk, tm, ts, tg, m, dg, pg, pg_f16, hp, partials, s);
+    case 2: return launch_fused_bf16<NESTEROV, 2>(vec, wk, tm, ts, tg, m, dg, pg, pg_f16, hp, partials, s);
+    case 4: return launch_fused_bf16<NESTEROV, 4>(vec, wk, tm, ts, tg, m, dg, pg, pg_f16, hp, partials, s);
+    default: return launch_fused_bf16<NESTEROV, 3>(vec, wk, tm, ts, tg, m, dg, pg, pg_f16, hp, partials, s);
   }
 }
 

@@ -141,7 +141,7 @@ def test_invalid_arguments_are_rejected_before_any_device_work(B):
     assert step(budget=-1) == B.COCODC_ERR_RANGE
     assert step(n=(1 << 44) + 4, wsb=1 << 62) == B.COCODC_ERR_RANGE
     for bad in (dict(tau=-1), dict(H=0), dict(nesterov=2), dict(drift_sign=0), dict(score_src=2),
-                dict(norm_kind=3), dict(merge_mode=3), dict(delta_src=2)):
+                dict(norm_kind=3), dict(merge_mode=3), dict(delta_src=2), dict(pg_format=2), dict(pg_format=-1)):
         kw = dict(tau=5, H=100)
         kw.update(bad)
         assert step(hp=B.hparams(**kw)) == B.COCODC_ERR_RANGE, bad
@@ -184,6 +184,8 @@ def test_invalid_arguments_are_rejected_before_any_device_work(B):
     assert event([1, 1], wsb=wsb - 1) == B.COCODC_ERR_WORKSPACE
     assert step(ws=tm) == B.COCODC_ERR_ALIAS
 
+    assert B.cocodc_pseudograd_bf16(frags, n, tg, tm, pg, None, ws, wsb, stream=0, pg_format=2) == B.COCODC_ERR_RANGE
+    assert B.cocodc_pseudograd_bf16(frags, n, tg, tm, None, None, ws, wsb, stream=0, pg_format=1) == B.COCODC_ERR_NULL
     assert B.cocodc_pseudograd(frags, n, tg, tm, None, None, ws, wsb, stream=0) == B.COCODC_ERR_NULL
     assert B.cocodc_pseudograd(frags, n, tg, tm, tm, None, ws, wsb, stream=0) == B.COCODC_ERR_ALIAS
     assert B.cocodc_outer_nesterov(frags, n, tg, m, tg, hp, ws, wsb, stream=0) == B.COCODC_ERR_ALIAS

@@ -131,6 +131,74 @@ def test_bf16_full_125m_every_element(B, ref):
     _case(B, ref, synth.WORKLOADS["125M"], seed=0)
 
 
+# ------------------------------------------------------------------ IEEE binary16 pseudo-gradient
+@pytest.mark.parametrize("name", ["125M-mini", "7B-mini"])
+def test_f16_pseudograd_mini_workloads(B, ref, name):
+    wl = synth.MINI_WORKLOADS[name]
+    _case(B, ref, wl, seed=0, pg_format=1)
+    _case(B, ref, wl, seed=1, variant="mixed", pg_format=1, view_off=1)
+
+
+def test_f16_pseudograd_amplified_specials_and_switches(B, ref):
+    wl = synth.Workload("f16-amp", (40000, 33333, 12345), tau=2, H=1, budget=2)
+    _case(B, ref, wl, seed=3, amplified=True, pg_format=1)
+    _case(B, ref, wl, seed=3, amplified=True, nesterov=0, drift_sign=-1, delta_src=1, pg_format=1)
+    _case(B, ref, wl, seed=4, merge_mode=1, alpha=0.3, send=False, pg_format=1)
+    _case(B, ref, wl, seed=4, merge_mode=2, pg_format=1, view_off=3)
+    _case(B, ref, wl, seed=5, pg=False, pg_format=1)
+
+
+def test_f16_rounding_on_the_gpu_every_pattern_ties_and_double_rounding_traps(B, ref):
+    """cocodc_pseudograd_bf16 with pg_format = binary16 on differences chosen to sit on, just above and just
+    below every kind of rounding boundary: every binary16 value itself, the midpoint of every pair of
+    neighbours (a tie), midpoints moved by one binary32 step, and midpoints moved by an amount far below
+    binary32 resolution (a conversion that went through binary32 and rounded twice would get those wrong).
+    The GPU and the oracle (pinned to exact arithmetic) must agree on every bit."""
+    pat = np.arange(0x7C00, dtype=np.uint16)                       # every finite non-negative binary16
+    val = pat.view(np.float16).astype(np.float64)
+    nxt = np.append(val[1:], 65536.0)                                 # the value the next pattern has / would have
+    mid = (val + nxt) / 2                                             # exact: 12 significant bits
+    mid32 = mid.astype(np.float32)
+    assert np.array_equal(mid32.astype(np.float64), mid)
+    tg_parts, tm_parts = [], []
+
+    def add(tg32, tm_value):
+        tg_parts.append(tg32.astype(np.float32))
+        tm_parts.append(np.full(tg32.size, tm_value, np.float32))
+    add(val.astype(np.float32), 0.0)                                  # the values themselves
+    add(mid32, 0.0)                                                   # exact ties
+    add(np.nextafter(mid32, np.float32(np.inf)), 0.0)                 # one binary32 step above / below a tie
+    add(np.nextafter(mid32, np.float32(-np.inf)), 0.0)
+    for k in (-30, -40, -60, -100):                                   # tie -+ 2^k: not a binary32 number
+        add(mid32, 2.0 ** k)
+        add(mid32, -(2.0 ** k))
+    add(np.array([65504, 65519.99, 65520, 65521, 1e30, np.inf, np.nan, 2.0 ** -25, 2.0 ** -26, 1e-40, 0.0],
+                 np.float32), 0.0)
+    tg = np.concatenate(tg_parts)
+    tm = np.concatenate(tm_parts)
+    tg = np.concatenate([tg, -tg])
+    tm = np.concatenate([tm, -tm])
+    n = tg.size
+    tm_bf16 = torch.from_numpy(tm).to(torch.bfloat16)
+    assert torch.equal(tm_bf16.float(), torch.from_numpy(tm))         # the offsets are bf16 numbers
+    d_tg, d_tm = torch.from_numpy(tg).cuda(), tm_bf16.cuda()
+    pg = torch.zeros(n, dtype=torch.int16, device="cuda")
+    ws = B.new_workspace(1, n)
+    print(f"case f16 rounding n={n}", flush=True)
+    assert B.cocodc_pseudograd_bf16([(0, n)], n, d_tg, d_tm, pg, None, ws, pg_format=B.COCODC_PG_F16) == 0
+    torch.cuda.synchronize()
+    h_pg = np.zeros(n, np.uint16)
+    assert ref.pseudograd_bf16([(0, n)], tg, _u16(tm_bf16), h_pg, None, pg_format=1) == 0
+    got = pg.cpu().numpy().view(np.uint16)
+    bad = np.nonzero(got != h_pg)[0]
+    assert bad.size == 0, [(float(tg[i]), float(tm[i]), hex(got[i]), hex(h_pg[i])) for i in bad[:5]]
+    # and the bf16 format of the same differences (the default of the same call)
+    assert B.cocodc_pseudograd_bf16([(0, n)], n, d_tg, d_tm, pg, None, ws) == 0
+    torch.cuda.synchronize()
+    assert ref.pseudograd_bf16([(0, n)], tg, _u16(tm_bf16), h_pg, None) == 0
+    assert np.array_equal(pg.cpu().numpy().view(np.uint16), h_pg)
+
+
 def test_bf16_pseudograd_entry_point(B, ref):
     wl = synth.Workload("bf16-pg", (50001, 16384, 3, 70000), tau=5, H=100)
     st = synth.make_state(wl, "cuda", seed=8)
@@ -146,6 +214,12 @@ def test_bf16_pseudograd_entry_point(B, ref):
     assert ref.pseudograd_bf16(frags, st["theta_g"].cpu().numpy(), _u16(tm), h_pg, h_send) == 0
     assert np.array_equal(_u16(pg), h_pg) and np.array_equal(_u16(send), h_send)
     assert B.cocodc_pseudograd_bf16(frags, n, st["theta_g"], tm, pg, None, ws) == 0
+    assert B.cocodc_pseudograd_bf16(frags, n, st["theta_g"], tm, pg, send, ws, pg_format=B.COCODC_PG_F16) == 0
+    torch.cuda.synchronize()
+    assert ref.pseudograd_bf16(frags, st["theta_g"].cpu().numpy(), _u16(tm), h_pg, h_send, pg_format=1) == 0
+    assert np.array_equal(pg.view(torch.int16).cpu().numpy().view(np.uint16), h_pg)
+    assert np.array_equal(_u16(send), h_send)
+    assert B.cocodc_pseudograd_bf16(frags, n, st["theta_g"], tm, pg, None, ws, pg_format=7) == B.COCODC_ERR_RANGE
     assert B.cocodc_pseudograd_bf16(frags, n, st["theta_g"], tm, tm, None, ws) == B.COCODC_ERR_ALIAS
     assert B.cocodc_pseudograd_bf16(frags, n, st["theta_g"], tm.data_ptr() + 1, pg, None, ws) == B.COCODC_ERR_ALIGN
 
@@ -171,4 +245,4 @@ def test_bf16_random_cases(B, ref, seed):
               lam=rng.choice([0.0, 0.5, 1.0, 3.0]), eta=rng.choice([0.7, 1.0]), mu=rng.choice([0.9, 0.0]),
               nesterov=rng.choice([1, 0]), drift_sign=rng.choice([1, -1]), score_src=score_src,
               norm_kind=rng.choice([2, 1]), merge_mode=merge_mode, alpha=rng.choice([1.0, 0.5]),
-              delta_src=rng.choice([0, 1]) if merge_mode == 0 else 0)
+              delta_src=rng.choice([0, 1]) if merge_mode == 0 else 0, pg_format=rng.choice([0, 0, 1]))
