@@ -200,3 +200,44 @@ def test_invalid_arguments_are_rejected_before_any_device_work(B):
     assert B.cocodc_select_fragments(2, R, t_b, 10, 100, -1, sel, nsel, ws, wsb, stream=0) == B.COCODC_ERR_RANGE
     assert B.cocodc_select_fragments(2, R, None, 10, 100, 1, sel, nsel, ws, wsb, stream=0) == B.COCODC_ERR_NULL
     assert B.cocodc_select_fragments(2, R, t_b, 10, 100, 1, R, nsel, ws, wsb, stream=0) == B.COCODC_ERR_ALIAS
+
+
+def test_loop_step_rejects_bad_buffers_before_any_device_work(B):
+    """Fake (never dereferenced) device addresses: cocodc_loop_step checks every pointer of its buffer
+    struct, their alignment and overlap, the workspace size and the step number before it enqueues
+    anything, and a rejected step leaves the schedule as it was."""
+    import ctypes as C
+    n, K = 4096, 2
+    frags = [(0, 2048), (2048, 2048)]
+    rc, loop = B.cocodc_loop_create(frags, n, B.hparams(2, 10), 1.0, 1.0, 5.0)
+    assert rc == 0
+    base = 0x20000000
+    addr = dict(theta_m=base, theta_m_send=base + 0x100000, theta_g=base + 0x200000, momentum=base + 0x300000,
+                delta_g=base + 0x400000, delta_m_out=base + 0x500000, R=base + 0x600000, sel=base + 0x700000,
+                n_sel=base + 0x800000, workspace=base + 0x900000)
+    wsb = B.cocodc_workspace_bytes(K, n)
+
+    def step(t=5, wsb=wsb, **kw):
+        a = dict(addr)
+        a.update(kw)
+        buf = B.cocodc_loop_buffers_t(a["theta_m"], a["theta_m_send"], a["theta_g"], a["momentum"], a["delta_g"],
+                                      a["delta_m_out"], a["R"], a["sel"], a["n_sel"], a["workspace"], wsb)
+        return B.cocodc_loop_step(loop, t, buf, stream=0)[0]
+    try:
+        for name in addr:
+            assert step(**{name: None}) == B.COCODC_ERR_NULL, name
+        assert step(theta_g=addr["theta_g"] + 2) == B.COCODC_ERR_ALIGN
+        assert step(R=addr["R"] + 4) == B.COCODC_ERR_ALIGN
+        assert step(workspace=addr["workspace"] + 64) == B.COCODC_ERR_ALIGN
+        assert step(wsb=wsb - 1) == B.COCODC_ERR_WORKSPACE
+        assert step(delta_m_out=addr["theta_m"]) == B.COCODC_ERR_ALIAS
+        assert step(momentum=addr["theta_g"] + 4 * n - 16) == B.COCODC_ERR_ALIAS
+        assert step(delta_m_out=addr["delta_g"] + 16) == B.COCODC_ERR_ALIAS      # only the exact in-place buffer is allowed
+        assert step(t=0) == B.COCODC_ERR_RANGE and step(t=-3) == B.COCODC_ERR_RANGE
+        assert B.cocodc_loop_state(loop) == (0, [0, 0], [0, 0], [-1, -1])
+        assert B.cocodc_loop_last_sent(loop) == (0, -1, -1)
+        assert B.cocodc_loop_due(loop, 100) == (0, [])
+        assert step(t=3) == 0          # h = 5: neither an arrival nor a decision at step 3, nothing is enqueued
+        assert step(t=3) == B.COCODC_ERR_RANGE and step(t=2) == B.COCODC_ERR_RANGE   # steps never go back
+    finally:
+        B.cocodc_loop_destroy(loop)
