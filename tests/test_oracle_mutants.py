@@ -79,7 +79,11 @@ MUTANTS = [
      "const int32_t n_sel = (budget < K ? budget : K) - (K - candidates) > 0 ? (budget < K ? budget : K) - (K - candidates) : 0;"),
 ]
 
+# (quick pins first: a planted mistake stops the battery at the first pin that sees it)
 BATTERY = [
+    half_pins.test_f16_rounding_matches_numpy_from_float64_and_torch_from_float32,
+    half_pins.test_f16_pseudograd_in_the_bf16_calls,
+    lambda ref: loop_pins.test_event_equals_step_on_the_arrived_fragments_then_selection_over_all(ref, (0, 1, 0, 0, 1)),
     pins.test_pseudograd_is_fp32_subtraction_global_minus_local,
     pins.test_pseudograd_sign_and_zero,
     pins.test_unit_outer_step_moves_global_state_to_worker_average,
@@ -107,11 +111,8 @@ BATTERY = [
     pins.test_planner_floor_of_k,
     lambda ref: pins.test_fused_equals_sequence_of_primitives(ref, True),
     pins.test_score_source_and_norm_switches,
-    pins.test_selection_exhaustive_small,
-    lambda ref: loop_pins.test_event_equals_step_on_the_arrived_fragments_then_selection_over_all(ref, (0, 1, 0, 0, 1)),
     loop_pins.test_selection_passes_over_fragments_in_flight,
-    half_pins.test_f16_rounding_matches_numpy_from_float64_and_torch_from_float32,
-    half_pins.test_f16_pseudograd_in_the_bf16_calls,
+    pins.test_selection_exhaustive_small,
 ]
 
 
