@@ -76,3 +76,53 @@ def test_noalloc_rejects_what_does_not_fit(B):
     assert rc == B.COCODC_ERR_WORKSPACE
     assert B.cocodc_sync_step_noalloc([(0, 16)], 16, None, None, None, None, None, None, [1], [0], 10, 1,
                                       B.hparams(5, 100), None, None, None, None, stream=0) == B.COCODC_ERR_NULL
+
+
+@pytest.mark.parametrize("K", [4, 40])
+def test_noalloc_records_into_a_graph(B, K):
+    """The callers this entry point is for: a step recorded into a HIP graph (the first call on the
+    GPU, which looks the array's address up, is made before the capture) and replayed between eager work;
+    every replay must give what the eager cocodc_sync_step chain gives.  K = 40 takes the path that writes
+    the table into the array with small upload kernels, K = 4 the one that passes it in the kernel arguments."""
+    wl = synth.Workload(f"noalloc-graph-{K}", tuple(30000 + 777 * (p % 5) for p in range(K)), tau=5, H=100, budget=3)
+    n = wl.n_total
+    bk = synth.bookkeeping(wl, "mixed")
+    hp = B.hparams(wl.tau, wl.H)
+    init = synth.make_state(wl, "cuda", seed=31)
+    work = {k: v.clone() for k, v in init.items()}
+    pg = torch.zeros(n, device="cuda")
+    out = U.gpu_outputs(K)
+
+    def call_noalloc():
+        B.check(B.cocodc_sync_step_noalloc(wl.frags, n, work["theta_m"], work["theta_m_send"], work["theta_g"],
+                                           work["momentum"], work["delta_g"], pg, bk.I_p, bk.t_b, bk.t_g, wl.budget, hp,
+                                           out["R"], out["sel"], out["n_sel"], out["sums"]))
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        call_noalloc()                                  # outside the capture: address look-up, warm-up
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph, stream=side):
+        call_noalloc()
+    ref_state = {k: v.clone() for k, v in init.items()}
+    ref_pg = torch.zeros(n, device="cuda")
+    ref_out = U.gpu_outputs(K)
+    ref_ws = B.new_workspace(K, n)
+    for k in work:
+        work[k].copy_(init[k])
+    print(f"case noalloc graph K={K} n={n}", flush=True)
+    for replay in range(4):
+        B.check(B.cocodc_sync_step(wl.frags, n, ref_state["theta_m"], ref_state["theta_m_send"], ref_state["theta_g"],
+                                   ref_state["momentum"], ref_state["delta_g"], ref_pg, bk.I_p, bk.t_b, bk.t_g,
+                                   wl.budget, hp, ref_out["R"], ref_out["sel"], ref_out["n_sel"], ref_out["sums"], ref_ws))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for k in work:
+            assert torch.equal(work[k], ref_state[k]), (replay, k)
+        assert torch.equal(pg, ref_pg)
+        assert torch.equal(out["R"], ref_out["R"]) and torch.equal(out["sums"], ref_out["sums"])
+        assert torch.equal(out["sel"], ref_out["sel"]) and torch.equal(out["n_sel"], ref_out["n_sel"])
+        torch.empty(1 << 20, device="cuda").normal_().mul_(2.0)   # unrelated eager kernels between the replays
