@@ -17,19 +17,30 @@ When a fragment is sent again at the very step its previous synchronisation comp
 when a decision step coincides with an arrival), Eq. 11 as printed has I_p = t_p - t_{p,b} = 0.
 Sec. 3.2 keeps R_p = infinity for fragments that have not yet completed a synchronisation, so a
 fragment that has completed one must get a finite score: the interval is taken as one step.
+
+Fragments may be strided shards (Sec. 4.1: shard k = layers k, k + K, ... of a layer-ordered buffer):
+pass segs = [(offset, length, fragment), ...] and K instead of frags.  A shard's pieces are walked in
+the order listed; everything else is the same loop.
 """
 import numpy as np
 
-from . import pseudograd, select_fragments, sync_plan, sync_step
+from . import pseudograd, select_fragments, sync_plan, sync_step, sync_step_segmented
 
 
 class RefLoop:
     # The interval of Eq. 11 never counts as less than this many steps (see the module text).
     min_interval = 1
 
-    def __init__(self, frags, hp, gamma, T_c, T_s):
-        self.frags = [(int(o), int(l)) for o, l in frags]
-        self.K = len(self.frags)
+    def __init__(self, frags, hp, gamma, T_c, T_s, segs=None, K=None):
+        if segs is None:
+            self.frags = [(int(o), int(l)) for o, l in frags]
+            self.K = len(self.frags)
+            self.pieces = None
+        else:
+            assert frags is None and K is not None
+            self.frags = None
+            self.K = int(K)
+            self.pieces = [[(int(o), int(l)) for o, l, f in segs if int(f) == p] for p in range(self.K)]
         self.hp = hp
         self.gamma, self.T_c, self.T_s = float(gamma), float(T_c), float(T_s)
         self.t_b = [0] * self.K
@@ -55,8 +66,12 @@ class RefLoop:
         received = []
         for p in self.due(t):
             I = max(self.min_interval, self.in_flight[p] - self.t_b[p])
-            out = sync_step([self.frags[p]], theta_m, theta_m_send, theta_g, momentum, delta_g, None,
-                            [I], [self.t_b[p]], t, 0, self.hp)
+            if self.pieces is None:
+                out = sync_step([self.frags[p]], theta_m, theta_m_send, theta_g, momentum, delta_g, None,
+                                [I], [self.t_b[p]], t, 0, self.hp)
+            else:   # the shard alone, as the one fragment of a segmented step
+                out = sync_step_segmented([(o, l, 0) for o, l in self.pieces[p]], 1, theta_m, theta_m_send, theta_g,
+                                          momentum, delta_g, None, [I], [self.t_b[p]], t, 0, self.hp)
             assert out["rc"] == 0
             self.R[p] = out["R"][0]
             self.I_p[p] = I
@@ -72,6 +87,8 @@ class RefLoop:
                     sent = q
                     break
             if sent >= 0:
-                assert pseudograd([self.frags[sent]], theta_g, theta_m, delta_m_out, theta_m_send) == 0
+                where = [self.frags[sent]] if self.pieces is None else self.pieces[sent]
+                if where:
+                    assert pseudograd(where, theta_g, theta_m, delta_m_out, theta_m_send) == 0
                 self.in_flight[sent] = t
         return received, sent

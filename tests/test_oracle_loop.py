@@ -11,11 +11,11 @@ import torch
 from paper_2504_17672_amd import synth
 
 
-def make_run(ref, wl, gamma, T_c, T_s, steps, seed=0, closed=True):
+def make_run(ref, wl, gamma, T_c, T_s, steps, seed=0, closed=True, segs=None, K=None):
     from oracle.loop import RefLoop
     st = {k: v.numpy() for k, v in synth.make_state(wl, "cpu", seed=seed).items()}
     hp = ref.hparams(wl.tau, wl.H, wl.lam, wl.eta, wl.mu)
-    loop = RefLoop(wl.frags, hp, gamma, T_c, T_s)
+    loop = RefLoop(wl.frags, hp, gamma, T_c, T_s) if segs is None else RefLoop(None, hp, gamma, T_c, T_s, segs=segs, K=K)
     send_buf = st["delta_g"] if closed else np.zeros_like(st["delta_g"])
     g = torch.Generator().manual_seed(1234 + seed)
     log = []
@@ -24,8 +24,8 @@ def make_run(ref, wl, gamma, T_c, T_s, steps, seed=0, closed=True):
         st["theta_m"] += drift  # the worker's local training step
         if not closed:
             for p in loop.due(t):
-                o, l = wl.frags[p]
-                st["delta_g"][o:o + l] = torch.empty(l).normal_(0.0, 1e-3, generator=g).numpy()
+                for o, l in ([wl.frags[p]] if segs is None else loop.pieces[p]):
+                    st["delta_g"][o:o + l] = torch.empty(l).normal_(0.0, 1e-3, generator=g).numpy()
         before_tb, before_R = list(loop.t_b), loop.R.copy()
         flying_before = list(loop.in_flight)
         rec, sent = loop.step(t, st["theta_m"], st["theta_m_send"], st["theta_g"], st["momentum"], st["delta_g"],
@@ -325,3 +325,61 @@ def test_the_interval_pin_sees_the_reading_it_guards(ref, monkeypatch):
     monkeypatch.setattr(RefLoop, "min_interval", 0)
     with pytest.raises(AssertionError):
         test_send_interval_equal_to_overlap_keeps_scores_finite(ref)
+
+
+# ------------------------------------------------------------------ strided shards in the loop
+def _logs_and_state(run):
+    loop, st, log = run
+    return ([(e["t"], tuple(e["received"]), e["sent"]) for e in log if e["received"] or e["sent"] >= 0],
+            loop.t_b, loop.I_p, loop.in_flight, loop.R.tolist(), st)
+
+
+def test_loop_over_shards_of_one_piece_each_is_the_loop_over_fragments(ref):
+    wl = synth.Workload("seg1", (900, 801, 0, 700), tau=3, H=40)
+    segs = [(o, l, p) for p, (o, l) in enumerate(wl.frags)]
+    a = _logs_and_state(make_run(ref, wl, 1.0, 1.0, 4.0, 200, closed=False))
+    b = _logs_and_state(make_run(ref, wl, 1.0, 1.0, 4.0, 200, closed=False, segs=segs, K=4))
+    assert a[:5] == b[:5] and len(a[0]) > 40
+    for k in a[5]:
+        assert np.array_equal(a[5][k], b[5][k]), k
+
+
+def test_loop_over_shards_does_not_care_how_a_shard_is_cut_or_where_it_is_listed(ref):
+    """Adjacent pieces of a shard listed in order are the same shard; the order in which DIFFERENT shards'
+    pieces are listed does not matter either."""
+    wl = synth.Workload("seg2", (2400,), tau=3, H=40)          # the buffer; the shards are given by the segments
+    whole = [(0, 600, 0), (600, 600, 1), (1200, 600, 2), (1800, 600, 0)]            # shard 0 = two pieces
+    cut = [(1200, 100, 2), (0, 250, 0), (600, 600, 1), (250, 350, 0), (1300, 500, 2), (1800, 1, 0), (1801, 599, 0)]
+    a = _logs_and_state(make_run(ref, wl, 1.0, 1.0, 4.0, 240, segs=whole, K=3))
+    b = _logs_and_state(make_run(ref, wl, 1.0, 1.0, 4.0, 240, segs=cut, K=3))
+    assert a[:5] == b[:5] and len(a[0]) > 40
+    for k in a[5]:
+        assert np.array_equal(a[5][k], b[5][k]), k
+
+
+def test_loop_on_the_papers_strided_shards(ref):
+    """Sec. 4.1: 12 layers in K = 4 strided shards (shard k = layers k, k+4, k+8), H = 100, tau = 5,
+    gamma = 0.4: 8 sends per H steps, the first four are shards 0..3, every element a shard owns (and no
+    other) is what a send writes."""
+    segs, n = synth.strided_segments(12, 8, 16, 4)             # small layers, the same structure
+    wl = synth.Workload("strided", (n,), tau=5, H=100)
+    loop, st, log = make_run(ref, wl, 0.4, 1.0, 5.0, 250, closed=False, segs=segs, K=4)
+    assert (loop.N, loop.h) == (8, 12)
+    sends = [(e["t"], e["sent"]) for e in log if e["sent"] >= 0]
+    assert [t for t, _ in sends][:8] == [12, 24, 36, 48, 60, 72, 84, 96] and [p for _, p in sends][:4] == [0, 1, 2, 3]
+    assert all(len(loop.pieces[p]) == (4 if p == 0 else 3) for p in range(4))      # shard 0 also owns the embedding
+    owned = [np.zeros(n, bool) for _ in range(4)]
+    for o, l, f in segs:
+        owned[f][o:o + l] = True
+    assert (sum(m.astype(int) for m in owned) == 1).all()
+    # one step of the loop by hand: a send of shard 2 writes shard 2's elements of the send buffer only
+    from oracle.loop import RefLoop
+    lp = RefLoop(None, ref.hparams(5, 100), 0.4, 1.0, 5.0, segs=segs, K=4)
+    lp.R[:] = [1.0, 2.0, 3.0, 0.5]
+    lp.t_b = [10, 10, 10, 10]
+    s2 = {k: v.numpy() for k, v in synth.make_state(wl, "cpu", seed=5).items()}
+    out = np.full(n, 7.0, np.float32)
+    rec, sent = lp.step(12, s2["theta_m"], s2["theta_m_send"], s2["theta_g"], s2["momentum"], s2["delta_g"], out)
+    assert (rec, sent) == ([], 2)
+    assert np.array_equal(out[owned[2]], (s2["theta_g"] - s2["theta_m"])[owned[2]]) and (out[~owned[2]] == 7.0).all()
+    assert np.array_equal(s2["theta_m_send"][owned[2]], s2["theta_m"][owned[2]])
