@@ -288,7 +288,19 @@ def main():
         return
 
     if args.loop_steps:
-        rc, loop = B.cocodc_loop_create(wl.frags, n, hp, 1.0, 1.0, float(wl.tau))  # T_s = tau * T_c
+        lens = [l for _, l in wl.frags]
+        if args.strided_shards:   # the paper's partition: shard k = layers k, k + K, ... (Sec. 4.1)
+            assert wl.model, "--strided-shards needs a model-shaped workload"
+            lsegs, n_seg = synth.strided_segments(*wl.model, args.strided_shards)
+            assert n_seg == n
+            K = args.strided_shards
+            lens = [sum(l for _, l, f in lsegs if f == p) for p in range(K)]
+            R = torch.zeros(K, dtype=torch.float64, device=dev)
+            sel = torch.full((K,), -1, dtype=torch.int32, device=dev)
+            ws = B.new_workspace_segmented(len(lsegs), K, n, dev)
+            rc, loop = B.cocodc_loop_create_segmented(lsegs, K, n, hp, 1.0, 1.0, float(wl.tau))
+        else:
+            rc, loop = B.cocodc_loop_create(wl.frags, n, hp, 1.0, 1.0, float(wl.tau))  # T_s = tau * T_c
         B.check(rc)
         B.check(B.cocodc_loop_reset_scores(loop, R))
         lb = B.loop_buffers(st["theta_m"], st["theta_m_send"], st["theta_g"], st["momentum"], st["delta_g"],
@@ -311,12 +323,12 @@ def main():
         torch.cuda.synchronize()
         t_all = time.perf_counter() - t_all
         B.cocodc_loop_destroy(loop)
-        lens = [l for _, l in wl.frags]
         rec_p = sum(lens[p] for _, rec, _ in ev for p in rec)
         snd_p = sum(lens[s] for _, _, s in ev if s >= 0)
         only_rec = [(dt, sum(lens[p] for p in rec)) for dt, rec, s in ev if rec and s < 0]
         only_snd = [(dt, lens[s]) for dt, rec, s in ev if not rec and s >= 0]
-        out = {"mode": "loop", "workload": wl.name, "inner_steps": args.loop_steps, "tau": wl.tau, "H": wl.H,
+        out = {"mode": "loop", "workload": wl.name, "inner_steps": args.loop_steps, "tau": wl.tau, "H": wl.H, "K": K,
+               "fragments": f"{K} strided shards" if args.strided_shards else "contiguous",
                "N": N_plan, "h": h_plan, "events": len(ev), "received_params": rec_p, "sent_params": snd_p,
                "loop_seconds": round(t_all, 4), "host_seconds_inside_loop_step": round(host_s, 4),
                "receive_Gparams_per_s": round(sum(p for _, p in only_rec) / max(sum(d for d, _ in only_rec), 1e-12) / 1e9, 2),

@@ -341,6 +341,13 @@ typedef struct {
 int cocodc_loop_create(const cocodc_fragment_t* frags, int32_t K, uint64_t n_total,
                        const cocodc_hparams_t* hp, double gamma, double T_c, double T_s,
                        cocodc_loop_t** loop_out);
+/* The same schedule for fragments made of several segments (the strided shards of Sec. 4.1:
+ * K = 4 shards of a 12-layer model, shard k = layers k, k+4, k+8): segs as for
+ * cocodc_sync_step_segmented.  The workspace of the loop's buffers must then hold
+ * cocodc_workspace_bytes_segmented(S, K, n_total). */
+int cocodc_loop_create_segmented(const cocodc_segment_t* segs, int32_t S, int32_t K, uint64_t n_total,
+                                 const cocodc_hparams_t* hp, double gamma, double T_c, double T_s,
+                                 cocodc_loop_t** loop_out);
 void cocodc_loop_destroy(cocodc_loop_t* loop);
 
 /* Writes +infinity to the K scores (enqueued on `stream`); call once before the first step. */

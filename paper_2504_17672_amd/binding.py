@@ -43,7 +43,7 @@ EXPORTS = (
     "cocodc_sync_event", "cocodc_sync_plan",
     "cocodc_workspace_bytes_segmented", "cocodc_fragment_scores_segmented", "cocodc_sync_step_segmented",
     "cocodc_pseudograd_bf16", "cocodc_sync_step_bf16", "cocodc_select_fragments_bytes",
-    "cocodc_loop_create", "cocodc_loop_destroy", "cocodc_loop_reset_scores", "cocodc_loop_observe",
+    "cocodc_loop_create", "cocodc_loop_create_segmented", "cocodc_loop_destroy", "cocodc_loop_reset_scores", "cocodc_loop_observe",
     "cocodc_loop_plan", "cocodc_loop_due", "cocodc_loop_step", "cocodc_loop_state", "cocodc_loop_last_sent",
     "cocodc_tile_elements", "cocodc_debug_tile_plan", "cocodc_debug_stream_mix",
     "cocodc_layout_stride_bytes", "cocodc_last_hip_error", "cocodc_status_string", "cocodc_set_blocks_per_cu",
@@ -115,6 +115,8 @@ _lib.cocodc_select_fragments_bytes.argtypes = [C.c_int32, _P, _i64_p, C.c_int64,
 _i32_p = C.POINTER(C.c_int32)
 _lib.cocodc_loop_create.argtypes = [_frag_p, C.c_int32, C.c_uint64, _hp_p, C.c_double, C.c_double, C.c_double,
                                     C.POINTER(C.c_void_p)]
+_lib.cocodc_loop_create_segmented.argtypes = [_seg_p, C.c_int32, C.c_int32, C.c_uint64, _hp_p, C.c_double, C.c_double,
+                                              C.c_double, C.POINTER(C.c_void_p)]
 _lib.cocodc_loop_destroy.argtypes = [_P]
 _lib.cocodc_loop_destroy.restype = None
 _lib.cocodc_loop_reset_scores.argtypes = [_P, _P, _P]
@@ -431,6 +433,16 @@ def cocodc_loop_create(frags, n_total, hp, gamma, T_c, T_s, K=None):
     rc = _lib.cocodc_loop_create(fa, k if K is None else K, int(n_total), C.byref(hp) if hp is not None else None,
                                  float(gamma), float(T_c), float(T_s), C.byref(h))
     return rc, ((h, k) if rc == 0 else None)
+
+
+def cocodc_loop_create_segmented(segs, K, n_total, hp, gamma, T_c, T_s, S=None):
+    """Returns (status, handle) for fragments given as [(offset, length, fragment), ...]."""
+    sa, n = _segs(segs)
+    h = C.c_void_p(None)
+    rc = _lib.cocodc_loop_create_segmented(sa, n if S is None else S, int(K), int(n_total),
+                                           C.byref(hp) if hp is not None else None, float(gamma), float(T_c),
+                                           float(T_s), C.byref(h))
+    return rc, ((h, int(K)) if rc == 0 else None)
 
 
 def cocodc_loop_destroy(handle):

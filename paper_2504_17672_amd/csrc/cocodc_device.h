@@ -40,15 +40,13 @@ static_assert(sizeof(SegRec) == 32, "SegRec layout");
 struct GroupRec {
   uint64_t slot_begin;   // index of the fragment's first tile in the global tile list
   uint64_t bytes;        // its size, for the selection under a byte budget
-  uint64_t f_offset;     // the fragment's own element range when it is one contiguous piece
-  uint64_t f_length;     //   (what the send-time walk over a fragment chosen on the device needs)
   int64_t I_p;           // steps between the fragment's last two completed syncs (Eq. 11)
   int64_t t_b;           // step of its last completed sync (Algorithm 2)
   uint32_t takes_part;   // 1: this call updates the fragment and its score; 0: it leaves both alone
   uint32_t in_flight;    // 1: an all-reduce of the fragment is under way: Algorithm 2 passes it over
   uint64_t reserved;
 };
-static_assert(sizeof(GroupRec) == 64, "GroupRec layout");
+static_assert(sizeof(GroupRec) == 48, "GroupRec layout");
 
 // What a streaming kernel walks: S segment records (plus a closing one whose slot_begin is the
 // number of tiles T) and the tile size.  The records themselves come either from the workspace
@@ -720,29 +718,40 @@ __device__ __forceinline__ void walk_tile(const Op& op, uint64_t lo, uint64_t hi
 #else
 #define COCODC_OCCUPANCY
 #endif
+// The segment that tile w belongs to: the last record whose slot_begin is <= w (records of empty
+// segments share their successor's slot_begin, so they are never the last).  A workgroup lives for
+// one tile of a few microseconds, so this is a bisection, not a scan.
+template <class Segs>
+__device__ __forceinline__ int segment_of_tile(const Segs& tbl, int S, uint64_t w) {
+  int p = 0, hi = S;
+  while (hi - p > 1) {
+    const int mid = (p + hi) >> 1;
+    if (tbl[mid].slot_begin <= w) p = mid; else hi = mid;
+  }
+  return p;
+}
+
+// The element range [lo, hi) of tile w of segment p.
+template <class Segs>
+__device__ __forceinline__ void tile_bounds(const Segs& tbl, int p, uint64_t w, int tile_shift, uint64_t* lo,
+                                            uint64_t* hi) {
+  const uint64_t f_off = tbl[p].offset, f_end = f_off + tbl[p].length;
+  const uint64_t win = (tbl[p].tile0 + (w - tbl[p].slot_begin)) << tile_shift;
+  const uint64_t win_end = win + (uint64_t(1) << tile_shift);
+  *lo = f_off > win ? f_off : win;
+  *hi = f_end < win_end ? f_end : win_end;
+}
+
 template <class Op, bool VEC, class Segs>
 __global__ __launch_bounds__(kThreads) COCODC_OCCUPANCY void k_walk(Segs tbl, Walk wk, Op op, double* __restrict__ partials) {
   __shared__ double lds[kWaves][kSums];
   const uint64_t T = wk.T;
   const int tile_shift = wk.tile_shift;
-  // The segment of the first tile: the last record whose slot_begin is <= the tile index (records
-  // of empty segments share their successor's slot_begin, so they are never the last).  A
-  // workgroup lives for one tile of a few microseconds, so this is a bisection, not a scan.
-  int p = 0;
-  if (blockIdx.x < T) {
-    int hi = wk.S;
-    while (hi - p > 1) {
-      const int mid = (p + hi) >> 1;
-      if (tbl[mid].slot_begin <= blockIdx.x) p = mid; else hi = mid;
-    }
-  }
+  int p = blockIdx.x < T ? segment_of_tile(tbl, wk.S, blockIdx.x) : 0;
   for (uint64_t w = blockIdx.x; w < T; w += gridDim.x) {
     while (w >= tbl[p + 1].slot_begin) ++p;  // uniform; later tiles of a persistent grid
-    const uint64_t f_off = tbl[p].offset, f_end = f_off + tbl[p].length;
-    const uint64_t win = (tbl[p].tile0 + (w - tbl[p].slot_begin)) << tile_shift;
-    const uint64_t win_end = win + (uint64_t(1) << tile_shift);
-    const uint64_t lo = f_off > win ? f_off : win;
-    const uint64_t hi = f_end < win_end ? f_end : win_end;
+    uint64_t lo, hi;
+    tile_bounds(tbl, p, w, tile_shift, &lo, &hi);
 
     double acc[Op::kAcc > 0 ? Op::kAcc : 1];
 #pragma unroll
@@ -761,28 +770,27 @@ __global__ __launch_bounds__(kThreads) COCODC_OCCUPANCY void k_walk(Segs tbl, Wa
 }
 
 // The same walk over ONE fragment that is named in device memory: *chosen is the index of a
-// contiguous fragment picked by an earlier kernel on the same stream (Algorithm 2), so the host
-// does not have to know it to launch the work.  groups[p] carries the fragment's range.  The
-// grid is sized by the host for the largest fragment that could have been chosen; workgroups
-// beyond the chosen fragment's tiles return at once, and all of them do when *chosen is negative
-// (nothing was eligible).  Element-wise operations only (no per-fragment sums).
-template <class Op, bool VEC>
-__global__ __launch_bounds__(kThreads) COCODC_OCCUPANCY void k_walk_chosen(const GroupRec* __restrict__ groups, int K,
+// fragment picked by an earlier kernel on the same stream (Algorithm 2), so the host does not
+// have to know it to launch the work.  tbl / groups are the tables of ALL fragments (nothing
+// masked out); the chosen fragment owns the tile slots [groups[p].slot_begin,
+// groups[p+1].slot_begin), whatever number of segments it consists of.  The grid is sized by the
+// host for the largest fragment that could have been chosen; workgroups beyond the chosen
+// fragment's tiles return at once, and all of them do when *chosen is out of range (nothing was
+// eligible).  Element-wise operations only (no per-fragment sums).
+template <class Op, bool VEC, class Segs, class Groups>
+__global__ __launch_bounds__(kThreads) COCODC_OCCUPANCY void k_walk_chosen(Segs tbl, int S, Groups groups, int K,
                                                                           const int* __restrict__ chosen,
                                                                           int tile_shift, Op op) {
   static_assert(Op::kAcc == 0, "the walk over a chosen fragment keeps no sums");
-  const int p = *chosen;
-  if (p < 0 || p >= K) return;
-  const uint64_t f_off = groups[p].f_offset, f_len = groups[p].f_length;
-  if (f_len == 0) return;
-  const uint64_t f_end = f_off + f_len;
-  const uint64_t tile0 = f_off >> tile_shift;
-  const uint64_t n_tiles = ((f_end - 1) >> tile_shift) - tile0 + 1;
-  for (uint64_t w = blockIdx.x; w < n_tiles; w += gridDim.x) {
-    const uint64_t win = (tile0 + w) << tile_shift;
-    const uint64_t win_end = win + (uint64_t(1) << tile_shift);
-    const uint64_t lo = f_off > win ? f_off : win;
-    const uint64_t hi = f_end < win_end ? f_end : win_end;
+  const int q = *chosen;
+  if (q < 0 || q >= K) return;
+  const uint64_t s0 = groups[q].slot_begin, s1 = groups[q + 1].slot_begin;
+  if (s0 + blockIdx.x >= s1) return;
+  int p = segment_of_tile(tbl, S, s0 + blockIdx.x);
+  for (uint64_t w = s0 + blockIdx.x; w < s1; w += gridDim.x) {
+    while (w >= tbl[p + 1].slot_begin) ++p;
+    uint64_t lo, hi;
+    tile_bounds(tbl, p, w, tile_shift, &lo, &hi);
     double acc[1] = {0.0};
     walk_tile<Op, VEC>(op, lo, hi, acc);
   }

@@ -163,20 +163,14 @@ int plan_segments(const cocodc_segment_t* segs, int32_t S, int32_t K, uint64_t n
   return COCODC_OK;
 }
 
-// Contiguous fragments: fragment p is the single segment frags[p]; its fragment record also
-// carries that range (whatever the mask says) for a walk over a fragment chosen on the device.
+// Contiguous fragments: fragment p is the single segment frags[p].
 int plan_table(const cocodc_fragment_t* frags, int32_t K, uint64_t n_total, const int64_t* I_p,
                const int64_t* t_b, Plan* plan, const uint8_t* mask = nullptr) {
   if (!frags) return COCODC_ERR_NULL;
   if (K < 1 || K > COCODC_MAX_FRAGMENTS) return COCODC_ERR_RANGE;
   std::vector<cocodc_segment_t> segs(static_cast<size_t>(K));
   for (int32_t p = 0; p < K; ++p) segs[p] = cocodc_segment_t{frags[p].offset, frags[p].length, p, 0};
-  if (int rc = plan_segments(segs.data(), K, K, n_total, I_p, t_b, plan, mask)) return rc;
-  for (int32_t p = 0; p < K; ++p) {
-    plan->groups[p].f_offset = frags[p].offset;
-    plan->groups[p].f_length = frags[p].length;
-  }
-  return COCODC_OK;
+  return plan_segments(segs.data(), K, K, n_total, I_p, t_b, plan, mask);
 }
 
 // Both tables go to the head of the workspace (segment records, then fragment records) as kernel
@@ -350,18 +344,36 @@ int launch_select(const Plan& pl, const WorkspaceView& v, const double* R, int64
   return COCODC_OK;
 }
 
-// The walk over the one fragment that *chosen (device memory) names; max_tiles = the number of
-// tiles of the largest fragment it could name.
+// The walk over the one fragment that *chosen (device memory) names.  `full` is the plan of ALL
+// fragments (no mask): its tables are what the kernel walks (from its arguments when they are
+// small, else from the workspace, where upload_table(full, ...) has put them); max_tiles_ = the
+// number of tiles of the largest fragment that could be named.
 template <class Op>
-int launch_walk_chosen(bool vec, const GroupRec* groups, int32_t K, const int32_t* chosen, int tile_shift,
+int launch_walk_chosen(bool vec, const Plan& full, const WorkspaceView& v, const int32_t* chosen,
                        uint64_t max_tiles_, const Op& op, hipStream_t s) {
   if (max_tiles_ == 0) return COCODC_OK;
   const int slot = prof_begin(s);
   const dim3 grid(grid_for(max_tiles_)), block(kThreads);
-  if (vec) {
-    hipLaunchKernelGGL((k_walk_chosen<Op, true>), grid, block, 0, s, groups, K, chosen, tile_shift, op);
+  if (full.in_args) {
+    const SegInline tbl = seg_args(full);
+    const GroupInline grp = group_args(full);
+    if (vec) {
+      hipLaunchKernelGGL((k_walk_chosen<Op, true, SegInline, GroupInline>), grid, block, 0, s, tbl, full.S, grp, full.K,
+                         chosen, full.tile_shift, op);
+    } else {
+      hipLaunchKernelGGL((k_walk_chosen<Op, false, SegInline, GroupInline>), grid, block, 0, s, tbl, full.S, grp, full.K,
+                         chosen, full.tile_shift, op);
+    }
   } else {
-    hipLaunchKernelGGL((k_walk_chosen<Op, false>), grid, block, 0, s, groups, K, chosen, tile_shift, op);
+    const SegTable tbl{v.table};
+    const GroupTable grp{v.groups};
+    if (vec) {
+      hipLaunchKernelGGL((k_walk_chosen<Op, true, SegTable, GroupTable>), grid, block, 0, s, tbl, full.S, grp, full.K,
+                         chosen, full.tile_shift, op);
+    } else {
+      hipLaunchKernelGGL((k_walk_chosen<Op, false, SegTable, GroupTable>), grid, block, 0, s, tbl, full.S, grp, full.K,
+                         chosen, full.tile_shift, op);
+    }
   }
   HIP_TRY(hipGetLastError());
   return prof_end(slot, s);

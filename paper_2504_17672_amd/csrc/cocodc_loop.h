@@ -10,7 +10,8 @@
 #pragma once
 
 struct cocodc_loop {
-  std::vector<cocodc_fragment_t> frags;
+  std::vector<cocodc_segment_t> segs;  // the fragments as lists of segments (a contiguous fragment is one)
+  int32_t K = 0;
   uint64_t n_total = 0;
   cocodc_hparams_t hp{};
   double gamma = 1.0, T_c = 1.0, T_s = 1.0;
@@ -29,7 +30,7 @@ struct cocodc_loop {
 namespace {
 int replan(cocodc_loop* L) {
   int64_t N = 0, h = 0;
-  if (int rc = cocodc_sync_plan(static_cast<int32_t>(L->frags.size()), L->hp.H, L->gamma, L->T_c, L->T_s, &N, &h))
+  if (int rc = cocodc_sync_plan(L->K, L->hp.H, L->gamma, L->T_c, L->T_s, &N, &h))
     return rc;
   L->N = N;
   L->h = h < 1 ? 1 : h;  // more syncs than steps: at most one send per step
@@ -44,7 +45,7 @@ int resolve_pending(cocodc_loop* L) {
   const int32_t p = *L->chosen_host;
   L->last_sent_t = L->pending_t;
   L->last_sent = -1;
-  if (p >= 0 && p < static_cast<int32_t>(L->frags.size()) && L->in_flight[p] < 0) {
+  if (p >= 0 && p < L->K && L->in_flight[p] < 0) {
     L->in_flight[p] = L->pending_t;
     L->last_sent = p;
   }
@@ -58,16 +59,17 @@ bool due_at(const cocodc_loop* L, size_t p, int64_t t) {
 
 extern "C" {
 
-int cocodc_loop_create(const cocodc_fragment_t* frags, int32_t K, uint64_t n_total,
-                       const cocodc_hparams_t* hp, double gamma, double T_c, double T_s,
-                       cocodc_loop_t** loop_out) {
+int cocodc_loop_create_segmented(const cocodc_segment_t* segs, int32_t S, int32_t K, uint64_t n_total,
+                                 const cocodc_hparams_t* hp, double gamma, double T_c, double T_s,
+                                 cocodc_loop_t** loop_out) {
   if (!loop_out) return COCODC_ERR_NULL;
   *loop_out = nullptr;
   if (int rc = check_hparams(hp)) return rc;
   Plan pl;
-  if (int rc = plan_table(frags, K, n_total, nullptr, nullptr, &pl)) return rc;
+  if (int rc = plan_segments(segs, S, K, n_total, nullptr, nullptr, &pl)) return rc;
   cocodc_loop* L = new cocodc_loop();
-  L->frags.assign(frags, frags + K);
+  L->segs.assign(segs, segs + S);
+  L->K = K;
   L->n_total = n_total;
   L->hp = *hp;
   L->gamma = gamma;
@@ -84,6 +86,18 @@ int cocodc_loop_create(const cocodc_fragment_t* frags, int32_t K, uint64_t n_tot
   return COCODC_OK;
 }
 
+int cocodc_loop_create(const cocodc_fragment_t* frags, int32_t K, uint64_t n_total,
+                       const cocodc_hparams_t* hp, double gamma, double T_c, double T_s,
+                       cocodc_loop_t** loop_out) {
+  if (!loop_out) return COCODC_ERR_NULL;
+  *loop_out = nullptr;
+  if (!frags) return COCODC_ERR_NULL;
+  if (K < 1 || K > COCODC_MAX_FRAGMENTS) return COCODC_ERR_RANGE;
+  std::vector<cocodc_segment_t> segs(static_cast<size_t>(K));
+  for (int32_t p = 0; p < K; ++p) segs[p] = cocodc_segment_t{frags[p].offset, frags[p].length, p, 0};
+  return cocodc_loop_create_segmented(segs.data(), K, K, n_total, hp, gamma, T_c, T_s, loop_out);
+}
+
 void cocodc_loop_destroy(cocodc_loop_t* loop) {
   if (!loop) return;
   if (loop->pending) (void)hipEventSynchronize(loop->chosen_ready);
@@ -95,7 +109,7 @@ void cocodc_loop_destroy(cocodc_loop_t* loop) {
 int cocodc_loop_reset_scores(cocodc_loop_t* loop, double* R, void* stream) {
   if (!loop || !R) return COCODC_ERR_NULL;
   if (!aligned(R, 8)) return COCODC_ERR_ALIGN;
-  const int K = static_cast<int>(loop->frags.size());
+  const int K = loop->K;
   hipLaunchKernelGGL(k_fill_inf, dim3((K + 255) / 256), dim3(256), 0, static_cast<hipStream_t>(stream), R, K);
   HIP_TRY(hipGetLastError());
   return COCODC_OK;
@@ -125,7 +139,7 @@ int cocodc_loop_due(cocodc_loop_t* loop, int64_t t, int32_t* due_out, int32_t* n
     if (int rc = resolve_pending(loop)) return rc;
   }
   int32_t n = 0;
-  for (size_t p = 0; p < loop->frags.size(); ++p) {
+  for (size_t p = 0; p < loop->t_b.size(); ++p) {
     if (due_at(loop, p, t)) due_out[n++] = static_cast<int32_t>(p);
   }
   *n_due_out = n;
@@ -135,7 +149,7 @@ int cocodc_loop_due(cocodc_loop_t* loop, int64_t t, int32_t* due_out, int32_t* n
 int cocodc_loop_state(cocodc_loop_t* loop, int64_t* t_b_out, int64_t* I_p_out, int64_t* in_flight_out) {
   if (!loop || !t_b_out || !I_p_out || !in_flight_out) return COCODC_ERR_NULL;
   if (int rc = resolve_pending(loop)) return rc;
-  for (size_t p = 0; p < loop->frags.size(); ++p) {
+  for (size_t p = 0; p < loop->t_b.size(); ++p) {
     t_b_out[p] = loop->t_b[p];
     I_p_out[p] = loop->I_p[p];
     in_flight_out[p] = loop->in_flight[p];
@@ -155,7 +169,8 @@ int cocodc_loop_step(cocodc_loop_t* loop, int64_t t, const cocodc_loop_buffers_t
                      int32_t* received_out, int32_t* n_received_out, int32_t* sent_out) {
   if (!loop || !buf || !received_out || !n_received_out || !sent_out) return COCODC_ERR_NULL;
   if (t < 1 || t <= loop->last_t) return COCODC_ERR_RANGE;  // steps are numbered 1, 2, ... and never go back
-  const int32_t K = static_cast<int32_t>(loop->frags.size());
+  const int32_t K = loop->K;
+  const int32_t S = static_cast<int32_t>(loop->segs.size());
   // Everything either kind of event could need is checked before anything is enqueued, so that a
   // rejected step leaves the buffers and the schedule as they were.
   if (!buf->delta_m_out || !buf->theta_m_send) return COCODC_ERR_NULL;
@@ -163,7 +178,7 @@ int cocodc_loop_step(cocodc_loop_t* loop, int64_t t, const cocodc_loop_buffers_t
   if (int rc = sync_step_check(buf->theta_m, buf->theta_m_send, buf->theta_g, buf->momentum, buf->delta_g,
                                buf->delta_m_out, &kOne, &kOne, 1, &loop->hp, buf->R, buf->sel, buf->n_sel, nullptr))
     return rc;
-  if (int rc = check_workspace(buf->workspace, buf->workspace_bytes, K, K, loop->n_total)) return rc;
+  if (int rc = check_workspace(buf->workspace, buf->workspace_bytes, S, K, loop->n_total)) return rc;
   if (int rc = sync_step_overlaps(K, loop->n_total, buf->theta_m, buf->theta_m_send, buf->theta_g, buf->momentum,
                                   buf->delta_g, buf->delta_m_out, 1, buf->R, buf->sel, buf->n_sel, nullptr,
                                   buf->workspace, buf->workspace_bytes))
@@ -194,15 +209,10 @@ int cocodc_loop_step(cocodc_loop_t* loop, int64_t t, const cocodc_loop_buffers_t
     received_out[n_rec++] = p;
   }
   int32_t n_flying = 0;
-  uint64_t widest = 0;  // tiles of the largest fragment Algorithm 2 could choose
-  const int sh = tile_shift_for(loop->n_total);
   for (int32_t p = 0; p < K; ++p) {
     if (fly_new[p] >= 0) {
       mask[p] |= kMaskInFlight;
       ++n_flying;
-    } else if (loop->frags[p].length) {
-      const uint64_t o = loop->frags[p].offset, e = o + loop->frags[p].length;
-      widest = std::max<uint64_t>(widest, ((e - 1) >> sh) - (o >> sh) + 1);
     }
   }
   const bool decide = decision_step && n_flying < K;  // (a pending decision was read back above)
@@ -212,9 +222,8 @@ int cocodc_loop_step(cocodc_loop_t* loop, int64_t t, const cocodc_loop_buffers_t
   }
 
   Plan pl;
-  if (int rc = plan_table(loop->frags.data(), K, loop->n_total, I_new.data(), tb_new.data(), &pl, mask.data()))
+  if (int rc = plan_segments(loop->segs.data(), S, K, loop->n_total, I_new.data(), tb_new.data(), &pl, mask.data()))
     return rc;
-  if (decide) pl.in_args = false;  // the walk over the chosen fragment reads the fragment records from the workspace
   if (int rc = sync_step_impl(pl, K, loop->n_total, buf->theta_m, buf->theta_m_send, buf->theta_g, buf->momentum,
                               buf->delta_g, nullptr, t, decide ? 1 : 0, &loop->hp, buf->R, buf->sel, buf->n_sel,
                               nullptr, buf->workspace, buf->workspace_bytes, stream))
@@ -226,11 +235,21 @@ int cocodc_loop_step(cocodc_loop_t* loop, int64_t t, const cocodc_loop_buffers_t
   *n_received_out = n_rec;
   if (!decide) return COCODC_OK;
 
-  // The chosen fragment's pseudo-gradient and send-time record, for whichever fragment sel[0] names.
-  WorkspaceView v = view(buf->workspace, pl.S, K);
+  // The chosen fragment's pseudo-gradient and send-time record, for whichever fragment sel[0]
+  // names: a walk over that fragment's tiles in the table of ALL fragments (the event above
+  // worked on the table of the arrived ones).  Stream order lets a large table reuse the head of
+  // the workspace: the event's kernels are done with theirs when the upload runs.
+  Plan full;
+  if (int rc = plan_segments(loop->segs.data(), S, K, loop->n_total, nullptr, nullptr, &full)) return rc;
+  uint64_t widest = 0;  // tiles of the largest fragment Algorithm 2 could choose
+  for (int32_t p = 0; p < K; ++p) {
+    if (loop->in_flight[p] < 0) widest = std::max<uint64_t>(widest, full.groups[p + 1].slot_begin - full.groups[p].slot_begin);
+  }
+  WorkspaceView v = view(buf->workspace, full.S, K);
+  if (int rc = upload_table(full, v, s)) return rc;
   const bool vec = all_aligned16({buf->theta_g, buf->theta_m, buf->delta_m_out, buf->theta_m_send});
   PseudoGradOp<true> op{buf->theta_g, buf->theta_m, buf->delta_m_out, buf->theta_m_send};
-  if (int rc = launch_walk_chosen(vec, v.groups, K, buf->sel, sh, widest, op, s)) return rc;
+  if (int rc = launch_walk_chosen(vec, full, v, buf->sel, widest, op, s)) return rc;
   if (!loop->chosen_host) {
     HIP_TRY(hipHostMalloc(reinterpret_cast<void**>(&loop->chosen_host), sizeof(int32_t), hipHostMallocDefault));
     HIP_TRY(hipEventCreateWithFlags(&loop->chosen_ready, hipEventDisableTiming));

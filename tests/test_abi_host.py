@@ -202,6 +202,23 @@ def test_invalid_arguments_are_rejected_before_any_device_work(B):
     assert B.cocodc_select_fragments(2, R, t_b, 10, 100, 1, R, nsel, ws, wsb, stream=0) == B.COCODC_ERR_ALIAS
 
 
+def test_loop_create_checks_its_table(B):
+    hp = B.hparams(5, 100)
+    ok = [(0, 10, 0), (10, 10, 1), (30, 5, 0)]
+    rc, loop = B.cocodc_loop_create_segmented(ok, 2, 40, hp, 0.4, 1.0, 5.0)
+    assert rc == 0 and B.cocodc_loop_plan(loop) == (0, 8, 12)
+    B.cocodc_loop_destroy(loop)
+    assert B.cocodc_loop_create_segmented([(0, 10, 0), (5, 10, 1)], 2, 40, hp, 0.4, 1.0, 5.0)[0] == B.COCODC_ERR_RANGE
+    assert B.cocodc_loop_create_segmented([(0, 10, 2)], 2, 40, hp, 0.4, 1.0, 5.0)[0] == B.COCODC_ERR_RANGE
+    assert B.cocodc_loop_create_segmented([(35, 10, 0)], 2, 40, hp, 0.4, 1.0, 5.0)[0] == B.COCODC_ERR_RANGE
+    assert B.cocodc_loop_create_segmented(None, 2, 40, hp, 0.4, 1.0, 5.0, S=3)[0] == B.COCODC_ERR_NULL
+    assert B.cocodc_loop_create_segmented(ok, 0, 40, hp, 0.4, 1.0, 5.0)[0] == B.COCODC_ERR_RANGE
+    assert B.cocodc_loop_create_segmented(ok, 2, 40, None, 0.4, 1.0, 5.0)[0] == B.COCODC_ERR_NULL
+    assert B.cocodc_loop_create_segmented(ok, 2, 40, hp, 0.0, 1.0, 5.0)[0] == B.COCODC_ERR_RANGE
+    assert B.cocodc_loop_create([(0, 10), (5, 10)], 20, hp, 0.4, 1.0, 5.0)[0] == B.COCODC_ERR_RANGE
+    assert B.cocodc_loop_create(None, 20, hp, 0.4, 1.0, 5.0, K=2)[0] == B.COCODC_ERR_NULL
+
+
 def test_loop_step_rejects_bad_buffers_before_any_device_work(B):
     """Fake (never dereferenced) device addresses: cocodc_loop_step checks every pointer of its buffer
     struct, their alignment and overlap, the workspace size and the step number before it enqueues

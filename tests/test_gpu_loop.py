@@ -19,7 +19,7 @@ def B():
     return binding
 
 
-def _run_both(B, ref, wl, gamma, T_c, T_s, steps, closed, seed=0, observe_at=None, lazy=False):
+def _run_both(B, ref, wl, gamma, T_c, T_s, steps, closed, seed=0, observe_at=None, lazy=False, segs=None, K=None):
     """lazy=False: the test asks after every step which fragment was sent (cocodc_loop_last_sent) and
     compares the bookkeeping; lazy=True: it never asks, so the schedule reads each decision back only
     when it needs it itself, and the logs of received fragments and the final state are compared."""
@@ -27,16 +27,24 @@ def _run_both(B, ref, wl, gamma, T_c, T_s, steps, closed, seed=0, observe_at=Non
     print(f"case loop {wl.name} K={wl.K} n={wl.n_total} steps={steps} closed={closed} lazy={lazy}", flush=True)
     st = synth.make_state(wl, "cuda", seed=seed)
     host = U.host_copy(st)
-    n, K = wl.n_total, wl.K
+    n = wl.n_total
     ghp = B.hparams(wl.tau, wl.H, wl.lam, wl.eta, wl.mu)
     rhp = ref.hparams(wl.tau, wl.H, wl.lam, wl.eta, wl.mu)
-    rc, loop = B.cocodc_loop_create(wl.frags, n, ghp, gamma, T_c, T_s)
+    if segs is None:
+        K = wl.K
+        rc, loop = B.cocodc_loop_create(wl.frags, n, ghp, gamma, T_c, T_s)
+        rloop = RefLoop(wl.frags, rhp, gamma, T_c, T_s)
+        ws = B.new_workspace(K, n)
+        pieces = [[f] for f in wl.frags]
+    else:   # fragments made of several segments (strided shards)
+        rc, loop = B.cocodc_loop_create_segmented(segs, K, n, ghp, gamma, T_c, T_s)
+        rloop = RefLoop(None, rhp, gamma, T_c, T_s, segs=segs, K=K)
+        ws = B.new_workspace_segmented(len(segs), K, n)
+        pieces = rloop.pieces
     assert rc == 0
-    rloop = RefLoop(wl.frags, rhp, gamma, T_c, T_s)
     R = torch.zeros(K, dtype=torch.float64, device="cuda")
     sel = torch.zeros(K, dtype=torch.int32, device="cuda")
     n_sel = torch.zeros(1, dtype=torch.int32, device="cuda")
-    ws = B.new_workspace(K, n)
     assert B.cocodc_loop_reset_scores(loop, R) == 0
     if closed:
         send_dev, send_host = st["delta_g"], host["delta_g"]
@@ -55,10 +63,10 @@ def _run_both(B, ref, wl, gamma, T_c, T_s, steps, closed, seed=0, observe_at=Non
             assert rc == 0 and due == rloop.due(t)
             if not closed:
                 for p in due:
-                    o, l = wl.frags[p]
-                    fresh = torch.empty(l, device="cuda").normal_(0.0, 1e-3, generator=g)
-                    st["delta_g"][o:o + l] = fresh
-                    host["delta_g"][o:o + l] = fresh.cpu().numpy()
+                    for o, l in pieces[p]:
+                        fresh = torch.empty(l, device="cuda").normal_(0.0, 1e-3, generator=g)
+                        st["delta_g"][o:o + l] = fresh
+                        host["delta_g"][o:o + l] = fresh.cpu().numpy()
             if observe_at and t in observe_at:
                 a, b, beta = observe_at[t]
                 assert B.cocodc_loop_observe(loop, a, b, beta) == 0
@@ -136,6 +144,32 @@ def test_loop_send_interval_equal_to_overlap(B, ref):
     wl = synth.Workload("loop-h-eq-tau", (30000, 25000, 20001, 15000), tau=5, H=100)
     _run_both(B, ref, wl, 1.0, 1.0, 5.0, 300, closed=True)
     _run_both(B, ref, wl, 1.0, 1.0, 5.0, 300, closed=True, lazy=True)
+
+
+def test_loop_on_the_papers_strided_shards(B, ref):
+    """Sec. 4.1: 12 layers in K = 4 strided shards, H = 100, tau = 5, gamma = 0.4 (125M-mini layer
+    sizes): every shard is 3 or 4 segments of a layer-ordered buffer."""
+    segs, n = synth.strided_segments(12, 96, 256, 4)
+    wl = synth.Workload("loop-strided", (n,), tau=5, H=100)
+    for lazy, closed in ((False, True), (True, False)):
+        n_sent, n_rec = _run_both(B, ref, wl, 0.4, 1.0, 5.0, 250, closed=closed, lazy=lazy, segs=segs, K=4)
+        assert n_sent == 250 // 12
+
+
+def test_loop_on_many_small_shards_with_tables_in_the_workspace(B, ref):
+    """More than 32 segments: the tables are written to the workspace (by the event, then again for
+    the send); shards of unequal numbers of pieces, one shard without any piece, unaligned pieces."""
+    import random
+    rng = random.Random(9)
+    segs, off, K = [], 3, 6
+    for j in range(70):
+        ln = rng.choice([1, 5, 2047, 2048, 4097, rng.randrange(1, 9000)])
+        segs.append((off, ln, rng.choice([0, 1, 2, 4, 5])))       # shard 3 owns nothing
+        off += ln + rng.choice([0, 1, 7])
+    rng.shuffle(segs)
+    wl = synth.Workload("loop-many", (off + 5,), tau=4, H=30)
+    _run_both(B, ref, wl, 1.0, 1.0, 3.0, 200, closed=False, segs=segs, K=K)
+    _run_both(B, ref, wl, 1.0, 1.0, 3.0, 200, closed=True, lazy=True, segs=segs, K=K)
 
 
 def test_loop_step_rejections_change_nothing(B):
