@@ -333,7 +333,9 @@ def main():
                "loop_seconds": round(t_all, 4), "host_seconds_inside_loop_step": round(host_s, 4),
                "receive_Gparams_per_s": round(sum(p for _, p in only_rec) / max(sum(d for d, _ in only_rec), 1e-12) / 1e9, 2),
                "send_Gparams_per_s": round(sum(p for _, p in only_snd) / max(sum(d for d, _ in only_snd), 1e-12) / 1e9, 2),
-               "receive_bytes_per_param": 32, "send_bytes_per_param": 16}
+               "receive_bytes_per_param": 32, "send_bytes_per_param": 16,
+               "all_events_GBps": round(sum(32 * sum(lens[p] for p in rec) + (16 * lens[s] if s >= 0 else 0)
+                                            for _, rec, s in ev) / max(sum(d for d, _, _ in ev), 1e-12) / 1e9, 1)}
         print(json.dumps(out), flush=True)
         return
 

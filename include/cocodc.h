@@ -24,7 +24,8 @@
  *   t_b and the hyper-parameter struct are HOST pointers; they are consumed before the
  *   call returns and may be freed or changed right after it.
  * Ownership.  The caller owns every buffer, including the workspace.  The library
- *   allocates no device memory.  A workspace of cocodc_workspace_bytes(K, n_total)
+ *   allocates no device memory (its code carries one fixed 64 MiB device array per GPU,
+ *   used by cocodc_sync_step_noalloc only).  A workspace of cocodc_workspace_bytes(K, n_total)
  *   bytes, 256-byte aligned, holds the device copy of the fragment table and the
  *   partial sums; it carries no state between calls, but two calls that are in flight
  *   at the same time (different streams) must use different workspaces.
@@ -38,7 +39,9 @@
  * Aliasing.  Distinct arguments must not overlap, with one exception: delta_m_out may
  *   be exactly delta_g (the all-reduce buffer is reused in place).
  * Streams.  `stream` is a hipStream_t passed as void* (NULL = the default stream).
- *   All work is enqueued on it and the call returns without synchronising.
+ *   All work is enqueued on it and the call returns without synchronising (the only waits
+ *   in the library are on the loop's own 4-byte read-back of a send decision, see
+ *   cocodc_loop_step, and in cocodc_profiler_collect).
  * Errors.  Every function returns COCODC_OK (0) or a negative cocodc_status_t.
  *   Arguments are validated on the host before anything is enqueued: on an error
  *   other than COCODC_ERR_HIP nothing has been launched and no buffer was touched.
@@ -330,7 +333,8 @@ typedef struct {
   double* R;             /* K scores R_p                                                        */
   int32_t* sel;          /* K int32 scratch for the selection                                   */
   int32_t* n_sel;        /* 1 int32 scratch                                                     */
-  void* workspace;       /* cocodc_workspace_bytes(K, n_total)                                  */
+  void* workspace;       /* cocodc_workspace_bytes(K, n_total), or ..._segmented(S, K, n_total) */
+                         /* for a loop made with cocodc_loop_create_segmented                   */
   size_t workspace_bytes;
 } cocodc_loop_buffers_t;
 
