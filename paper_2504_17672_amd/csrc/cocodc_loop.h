@@ -250,10 +250,9 @@ int cocodc_loop_step(cocodc_loop_t* loop, int64_t t, const cocodc_loop_buffers_t
   const bool vec = all_aligned16({buf->theta_g, buf->theta_m, buf->delta_m_out, buf->theta_m_send});
   PseudoGradOp<true> op{buf->theta_g, buf->theta_m, buf->delta_m_out, buf->theta_m_send};
   if (int rc = launch_walk_chosen(vec, full, v, buf->sel, widest, op, s)) return rc;
-  if (!loop->chosen_host) {
+  if (!loop->chosen_host)
     HIP_TRY(hipHostMalloc(reinterpret_cast<void**>(&loop->chosen_host), sizeof(int32_t), hipHostMallocDefault));
-    HIP_TRY(hipEventCreateWithFlags(&loop->chosen_ready, hipEventDisableTiming));
-  }
+  if (!loop->chosen_ready) HIP_TRY(hipEventCreateWithFlags(&loop->chosen_ready, hipEventDisableTiming));
   *loop->chosen_host = -1;
   HIP_TRY(hipMemcpyAsync(loop->chosen_host, buf->sel, sizeof(int32_t), hipMemcpyDeviceToHost, s));
   HIP_TRY(hipEventRecord(loop->chosen_ready, s));
