@@ -172,6 +172,93 @@ def test_loop_on_many_small_shards_with_tables_in_the_workspace(B, ref):
     _run_both(B, ref, wl, 1.0, 1.0, 3.0, 200, closed=True, lazy=True, segs=segs, K=K)
 
 
+def test_workers_choose_alike_without_coordination(B, ref):
+    """Sec. 3.2: every worker holds the same history of averaged pseudo-gradients, so all compute the same
+    scores and send the same fragment without a message.  M = 3 loops on this GPU with different local
+    parameters and drift; the test plays the all-reduce (Eq. 1: mean of the workers' pseudo-gradients,
+    handed back tau steps later).  Checked at every step: the same event everywhere, identical scores,
+    global parameters and momenta on all workers.  M loop oracles run the same protocol on the host from
+    their own outputs; every worker's event log and final buffers equal its oracle's."""
+    from oracle.loop import RefLoop
+    M, tau, H, steps = 3, 4, 60, 240
+    wl = synth.Workload("workers", (70000, 50001, 90000, 30003), tau=tau, H=H)
+    n, K = wl.n_total, wl.K
+    print(f"case loop workers M={M} K={K} n={n} steps={steps}", flush=True)
+    ghp = B.hparams(tau, H, wl.lam, wl.eta, wl.mu)
+    rhp = ref.hparams(tau, H, wl.lam, wl.eta, wl.mu)
+    base = synth.make_state(wl, "cuda", seed=1)
+    workers = []
+    for m in range(M):
+        st = {k: v.clone() for k, v in base.items()}
+        st["theta_m"] += 0.001 * (m + 1)
+        st["theta_m_send"] = st["theta_m"].clone()
+        rc, loop = B.cocodc_loop_create(wl.frags, n, ghp, 1.0, 1.0, 6.0)
+        assert rc == 0
+        R = torch.zeros(K, dtype=torch.float64, device="cuda")
+        sel = torch.zeros(K, dtype=torch.int32, device="cuda")
+        n_sel = torch.zeros(1, dtype=torch.int32, device="cuda")
+        assert B.cocodc_loop_reset_scores(loop, R) == 0
+        out = torch.zeros(n, device="cuda")
+        ws = B.new_workspace(K, n)
+        bufs = B.loop_buffers(st["theta_m"], st["theta_m_send"], st["theta_g"], st["momentum"], st["delta_g"], out,
+                              R, sel, n_sel, ws)
+        workers.append(dict(st=st, loop=loop, R=R, out=out, bufs=bufs, keep=(sel, n_sel, ws),
+                            g=torch.Generator(device="cuda").manual_seed(100 + m),
+                            host=U.host_copy(st), host_out=np.zeros(n, np.float32), rloop=RefLoop(wl.frags, rhp, 1.0, 1.0, 6.0)))
+    in_air, n_sends = {}, 0
+    try:
+        for t in range(1, steps + 1):
+            for p, (t_arr, avg, ravg) in list(in_air.items()):
+                if t_arr == t:
+                    o, l = wl.frags[p]
+                    for w in workers:
+                        w["st"]["delta_g"][o:o + l] = avg
+                        w["host"]["delta_g"][o:o + l] = ravg
+                    del in_air[p]
+            events = []
+            for w in workers:
+                drift = torch.empty(n, device="cuda").normal_(0.0, 1e-4, generator=w["g"])
+                w["st"]["theta_m"] += drift
+                w["host"]["theta_m"] += drift.cpu().numpy()
+                rc, rec, sent = B.cocodc_loop_step(w["loop"], t, w["bufs"])
+                assert rc == 0, B.cocodc_status_string(rc)
+                if sent == B.COCODC_LOOP_SENT_PENDING:
+                    rc, t_sent, sent = B.cocodc_loop_last_sent(w["loop"])
+                    assert rc == 0 and t_sent == t
+                h = w["host"]
+                rrec, rsent = w["rloop"].step(t, h["theta_m"], h["theta_m_send"], h["theta_g"], h["momentum"],
+                                              h["delta_g"], w["host_out"])
+                assert (tuple(rec), sent) == (tuple(rrec), rsent), (t, rec, sent, rrec, rsent)
+                events.append((tuple(rec), sent))
+            assert len(set(events)) == 1, (t, events)
+            sent = events[0][1]
+            if sent >= 0:
+                o, l = wl.frags[sent]
+                # Eq. 1 as the harness computes it on either side: the fp32 pseudo-gradients added in fp64 in
+                # worker order, divided by M, stored as fp32
+                a = [w["out"][o:o + l].double() for w in workers]
+                r = [w["host_out"][o:o + l].astype(np.float64) for w in workers]
+                mean = (((a[0] + a[1]) + a[2]) / float(M)).float()
+                rmean = (((r[0] + r[1]) + r[2]) / float(M)).astype(np.float32)
+                assert np.array_equal(mean.cpu().numpy(), rmean), t
+                in_air[sent] = (t + tau, mean, rmean)
+                n_sends += 1
+            for w in workers[1:]:
+                assert torch.equal(w["R"].view(torch.int64), workers[0]["R"].view(torch.int64))
+                for k in ("theta_g", "momentum"):
+                    assert torch.equal(w["st"][k].view(torch.int32), workers[0]["st"][k].view(torch.int32)), (t, k)
+        torch.cuda.synchronize()
+        for w in workers:
+            for k in ("theta_m", "theta_m_send", "theta_g", "momentum", "delta_g"):
+                assert np.array_equal(w["st"][k].cpu().numpy(), w["host"][k]), k
+        assert not torch.equal(workers[0]["st"]["theta_m"], workers[1]["st"]["theta_m"])
+        assert n_sends == steps // 6
+    finally:
+        for w in workers:
+            B.cocodc_loop_destroy(w["loop"])
+    print(f"   {n_sends} sends, the same on all {M} workers", flush=True)
+
+
 def test_loop_step_rejections_change_nothing(B):
     wl = synth.Workload("loop-rej", (5000, 3000), tau=2, H=10)
     st = synth.make_state(wl, "cuda", seed=3)

@@ -383,3 +383,50 @@ def test_loop_on_the_papers_strided_shards(ref):
     assert (rec, sent) == ([], 2)
     assert np.array_equal(out[owned[2]], (s2["theta_g"] - s2["theta_m"])[owned[2]]) and (out[~owned[2]] == 7.0).all()
     assert np.array_equal(s2["theta_m_send"][owned[2]], s2["theta_m"][owned[2]])
+
+
+# ------------------------------------------------------------------ several workers, no coordination
+def test_workers_that_share_the_averaged_history_choose_alike(ref):
+    """Sec. 3.2: every worker sees the same globally averaged pseudo-gradients, so every worker computes the
+    same scores and picks the same fragment without exchanging a message, and all hold the same global
+    state.  M = 3 workers with different local parameters and different local drift; the harness plays the
+    all-reduce (Eq. 1: the mean of the workers' pseudo-gradients, delivered tau steps after the send)."""
+    from oracle.loop import RefLoop
+    M, tau, H = 3, 4, 60
+    wl = synth.Workload("workers", (700, 500, 900, 300), tau=tau, H=H)
+    hp = ref.hparams(tau, H)
+    base = {k: v.numpy() for k, v in synth.make_state(wl, "cpu", seed=1).items()}
+    workers = []
+    for m in range(M):
+        st = {k: v.copy() for k, v in base.items()}                  # the same global state and momentum ...
+        st["theta_m"] = st["theta_m"] + np.float32(0.001 * (m + 1))   # ... different local parameters
+        st["theta_m_send"] = st["theta_m"].copy()
+        workers.append(dict(st=st, loop=RefLoop(wl.frags, hp, 1.0, 1.0, 6.0), out=np.zeros(wl.n_total, np.float32),
+                            g=torch.Generator().manual_seed(100 + m)))
+    in_air = {}       # fragment -> (arrival step, averaged pseudo-gradient)
+    n_sends = 0
+    for t in range(1, 241):
+        for p, (t_arr, avg) in list(in_air.items()):
+            if t_arr == t:
+                o, l = wl.frags[p]
+                for w in workers:
+                    w["st"]["delta_g"][o:o + l] = avg
+                del in_air[p]
+        choices = []
+        for w in workers:
+            w["st"]["theta_m"] += torch.empty(wl.n_total).normal_(0.0, 1e-4, generator=w["g"]).numpy()
+            rec, sent = w["loop"].step(t, w["st"]["theta_m"], w["st"]["theta_m_send"], w["st"]["theta_g"],
+                                       w["st"]["momentum"], w["st"]["delta_g"], w["out"])
+            choices.append((tuple(rec), sent))
+        assert len(set(choices)) == 1, (t, choices)              # same arrivals, same decision, everywhere
+        sent = choices[0][1]
+        if sent >= 0:
+            o, l = wl.frags[sent]
+            mean = np.mean([w["out"][o:o + l].astype(np.float64) for w in workers], axis=0).astype(np.float32)
+            in_air[sent] = (t + tau, mean)
+            n_sends += 1
+        for w in workers[1:]:
+            assert np.array_equal(w["loop"].R, workers[0]["loop"].R)
+            assert np.array_equal(w["st"]["theta_g"], workers[0]["st"]["theta_g"])
+            assert np.array_equal(w["st"]["momentum"], workers[0]["st"]["momentum"])
+    assert n_sends == 240 // 6 and not np.array_equal(workers[0]["st"]["theta_m"], workers[1]["st"]["theta_m"])
