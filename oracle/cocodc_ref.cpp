@@ -573,6 +573,57 @@ int cocodc_ref_pseudograd_bf16(const cocodc_ref_fragment_t* frags, int32_t K, ui
   return kOk;
 }
 
+namespace {
+// One element of the fused step when the local parameters, their send-time record and the outgoing
+// pseudo-gradient are 16-bit: widened exactly on load, the arithmetic of sync_element, one rounding
+// on store (local parameters to bf16, pseudo-gradient to hp.pg_format).
+inline void sync_element_bf16(uint64_t i, uint16_t* theta_m, const uint16_t* theta_send, float* theta_g,
+                              float* momentum, const float* delta_g, uint16_t* delta_m_out,
+                              const cocodc_ref_hparams_t& hp, Sums* s, const cocodc_ref_shadow_t* sh) {
+  const double tg = theta_g[i], tm = cocodc_ref_widen_bf16(theta_m[i]);
+  const double ts = theta_send ? cocodc_ref_widen_bf16(theta_send[i]) : tm;
+  const double m0 = momentum[i], dg = delta_g[i];
+  double m1;
+  const double G64 = outer_update(tg, m0, dg, hp, &m1);   // Eq. 2
+  const float G = static_cast<float>(G64);                 // the stored fp32 global state
+  const double d = drift_times_tau(ts, tm, hp);            // Eq. 4 times tau
+  const double tm_new = merge_local(static_cast<double>(G), ts, tm, d, hp, tg);  // Eq. 7, 8
+  s->g2 += dg * dg;
+  s->g1 += std::fabs(dg);
+  s->d2 += d * d;
+  s->d1 += std::fabs(d);
+  if (delta_m_out) delta_m_out[i] = round_half(tg - tm, hp.pg_format);
+  momentum[i] = static_cast<float>(m1);
+  theta_g[i] = G;
+  theta_m[i] = cocodc_ref_round_bf16(tm_new);
+  if (sh) {
+    if (sh->theta_m) sh->theta_m[i] = tm_new;
+    if (sh->theta_g) sh->theta_g[i] = G64;
+    if (sh->momentum) sh->momentum[i] = m1;
+  }
+}
+
+inline void store_sums(const Sums& s, int32_t p, double* sums_out) {
+  if (!sums_out) return;
+  sums_out[4 * p + 0] = s.g2;
+  sums_out[4 * p + 1] = s.g1;
+  sums_out[4 * p + 2] = s.d2;
+  sums_out[4 * p + 3] = s.d1;
+}
+
+int check_sync_bf16(const uint16_t* theta_m, const uint16_t* theta_m_send, const float* theta_g,
+                    const float* momentum, const float* delta_g, const int64_t* I_p, const int64_t* t_b,
+                    int32_t budget, const cocodc_ref_hparams_t* hp, const double* R, const int32_t* sel_out,
+                    const int32_t* n_sel_out) {
+  if (!theta_m || !theta_g || !momentum || !delta_g) return kErrNull;
+  if (!I_p || !t_b || !R || !sel_out || !n_sel_out) return kErrNull;
+  if (int rc = check_hparams(hp)) return rc;
+  if (!theta_m_send && (hp->merge_mode == 0 || hp->score_src == 1)) return kErrNull;
+  if (budget < 0) return kErrRange;
+  return kOk;
+}
+}  // namespace
+
 int cocodc_ref_sync_step_bf16(const cocodc_ref_fragment_t* frags, int32_t K, uint64_t n_total,
                               uint16_t* theta_m, const uint16_t* theta_m_send, float* theta_g,
                               float* momentum, const float* delta_g, uint16_t* delta_m_out,
@@ -580,46 +631,77 @@ int cocodc_ref_sync_step_bf16(const cocodc_ref_fragment_t* frags, int32_t K, uin
                               const cocodc_ref_hparams_t* hp, double* R_out, int32_t* sel_out,
                               int32_t* n_sel_out, double* sums_out,
                               const cocodc_ref_shadow_t* shadow) {
-  if (!theta_m || !theta_g || !momentum || !delta_g) return kErrNull;
-  if (!I_p || !t_b || !R_out || !sel_out || !n_sel_out) return kErrNull;
+  if (int rc = check_sync_bf16(theta_m, theta_m_send, theta_g, momentum, delta_g, I_p, t_b, budget, hp, R_out,
+                               sel_out, n_sel_out))
+    return rc;
   if (int rc = check_table(frags, K, n_total)) return rc;
-  if (int rc = check_hparams(hp)) return rc;
-  if (!theta_m_send && (hp->merge_mode == 0 || hp->score_src == 1)) return kErrNull;
-  if (budget < 0) return kErrRange;
   for (int32_t p = 0; p < K; ++p) {
     Sums s;
     for (uint64_t i = frags[p].offset; i < frags[p].offset + frags[p].length; ++i) {
-      const double tg = theta_g[i], tm = cocodc_ref_widen_bf16(theta_m[i]);
-      const double ts = theta_m_send ? cocodc_ref_widen_bf16(theta_m_send[i]) : tm;
-      const double m0 = momentum[i], dg = delta_g[i];
-      double m1;
-      const double G64 = outer_update(tg, m0, dg, *hp, &m1);   // Eq. 2
-      const float G = static_cast<float>(G64);                  // the stored fp32 global state
-      const double d = drift_times_tau(ts, tm, *hp);            // Eq. 4 times tau
-      const double tm_new = merge_local(static_cast<double>(G), ts, tm, d, *hp, tg);  // Eq. 7, 8
-      s.g2 += dg * dg;
-      s.g1 += std::fabs(dg);
-      s.d2 += d * d;
-      s.d1 += std::fabs(d);
-      if (delta_m_out) delta_m_out[i] = round_half(tg - tm, hp->pg_format);
-      momentum[i] = static_cast<float>(m1);
-      theta_g[i] = G;
-      theta_m[i] = cocodc_ref_round_bf16(tm_new);
-      if (shadow) {
-        if (shadow->theta_m) shadow->theta_m[i] = tm_new;
-        if (shadow->theta_g) shadow->theta_g[i] = G64;
-        if (shadow->momentum) shadow->momentum[i] = m1;
+      sync_element_bf16(i, theta_m, theta_m_send, theta_g, momentum, delta_g, delta_m_out, *hp, &s, shadow);
+    }
+    R_out[p] = score_from_sums(s, I_p[p], *hp);
+    store_sums(s, p, sums_out);
+  }
+  return cocodc_ref_select_fragments(K, R_out, t_b, t_g, hp->H, budget, sel_out, n_sel_out);
+}
+
+/* The same step over fragments made of segments (the strided shards of Sec. 4.1 with the 16-bit
+ * local parameters of its mixed-precision training): a fragment's segments are walked in the order
+ * listed. */
+int cocodc_ref_sync_step_bf16_segmented(const cocodc_ref_segment_t* segs, int32_t S, int32_t K,
+                                        uint64_t n_total, uint16_t* theta_m, const uint16_t* theta_m_send,
+                                        float* theta_g, float* momentum, const float* delta_g,
+                                        uint16_t* delta_m_out, const int64_t* I_p, const int64_t* t_b,
+                                        int64_t t_g, int32_t budget, const cocodc_ref_hparams_t* hp,
+                                        double* R_out, int32_t* sel_out, int32_t* n_sel_out,
+                                        double* sums_out) {
+  if (int rc = check_sync_bf16(theta_m, theta_m_send, theta_g, momentum, delta_g, I_p, t_b, budget, hp, R_out,
+                               sel_out, n_sel_out))
+    return rc;
+  if (int rc = check_segments(segs, S, K, n_total)) return rc;
+  for (int32_t p = 0; p < K; ++p) {
+    Sums s;
+    for (int32_t j = 0; j < S; ++j) {
+      if (segs[j].fragment != p) continue;
+      for (uint64_t i = segs[j].offset; i < segs[j].offset + segs[j].length; ++i) {
+        sync_element_bf16(i, theta_m, theta_m_send, theta_g, momentum, delta_g, delta_m_out, *hp, &s, nullptr);
       }
     }
     R_out[p] = score_from_sums(s, I_p[p], *hp);
-    if (sums_out) {
-      sums_out[4 * p + 0] = s.g2;
-      sums_out[4 * p + 1] = s.g1;
-      sums_out[4 * p + 2] = s.d2;
-      sums_out[4 * p + 3] = s.d1;
-    }
+    store_sums(s, p, sums_out);
   }
   return cocodc_ref_select_fragments(K, R_out, t_b, t_g, hp->H, budget, sel_out, n_sel_out);
+}
+
+/* One event of the loop of Sec. 3.2 on 16-bit local parameters; recv_mask as for
+ * cocodc_ref_sync_event (bit 0: has just arrived, bit 1: in flight). */
+int cocodc_ref_sync_event_bf16(const cocodc_ref_fragment_t* frags, int32_t K, uint64_t n_total,
+                               const uint8_t* recv_mask, uint16_t* theta_m, const uint16_t* theta_m_send,
+                               float* theta_g, float* momentum, const float* delta_g,
+                               uint16_t* delta_m_out, const int64_t* I_p, const int64_t* t_b, int64_t t_g,
+                               int32_t budget, const cocodc_ref_hparams_t* hp, double* R, int32_t* sel_out,
+                               int32_t* n_sel_out, double* sums_out) {
+  if (!recv_mask) return kErrNull;
+  if (int rc = check_sync_bf16(theta_m, theta_m_send, theta_g, momentum, delta_g, I_p, t_b, budget, hp, R,
+                               sel_out, n_sel_out))
+    return rc;
+  if (int rc = check_table(frags, K, n_total)) return rc;
+  std::vector<uint8_t> in_flight(static_cast<size_t>(K), 0);
+  for (int32_t q = 0; q < K; ++q) {
+    if (recv_mask[q] > 3) return kErrRange;
+    in_flight[q] = (recv_mask[q] & 2) ? 1 : 0;
+  }
+  for (int32_t q = 0; q < K; ++q) {
+    if (!(recv_mask[q] & 1)) continue;
+    Sums s;
+    for (uint64_t i = frags[q].offset; i < frags[q].offset + frags[q].length; ++i) {
+      sync_element_bf16(i, theta_m, theta_m_send, theta_g, momentum, delta_g, delta_m_out, *hp, &s, nullptr);
+    }
+    R[q] = score_from_sums(s, I_p[q], *hp);
+    store_sums(s, q, sums_out);
+  }
+  return select_among(K, R, t_b, t_g, hp->H, budget, in_flight.data(), sel_out, n_sel_out);
 }
 
 // Eq. 9: N = max(K, floor(gamma * H * T_c / T_s)); Eq. 10: h = floor(H / N).

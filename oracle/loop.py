@@ -21,17 +21,23 @@ fragment that has completed one must get a finite score: the interval is taken a
 Fragments may be strided shards (Sec. 4.1: shard k = layers k, k + K, ... of a layer-ordered buffer):
 pass segs = [(offset, length, fragment), ...] and K instead of frags.  A shard's pieces are walked in
 the order listed; everything else is the same loop.
+
+half=True: the local parameters, their send-time record and the send buffer hold 16-bit patterns
+(uint16 arrays: bf16 parameters as in the mixed-precision training of Sec. 4.1, pseudo-gradient in
+hp.pg_format); the loop is the same, built on the 16-bit single steps.
 """
 import numpy as np
 
-from . import pseudograd, select_fragments, sync_plan, sync_step, sync_step_segmented
+from . import (pseudograd, pseudograd_bf16, select_fragments, sync_plan, sync_step, sync_step_bf16,
+               sync_step_bf16_segmented, sync_step_segmented)
 
 
 class RefLoop:
     # The interval of Eq. 11 never counts as less than this many steps (see the module text).
     min_interval = 1
 
-    def __init__(self, frags, hp, gamma, T_c, T_s, segs=None, K=None):
+    def __init__(self, frags, hp, gamma, T_c, T_s, segs=None, K=None, half=False):
+        self.half = bool(half)
         if segs is None:
             self.frags = [(int(o), int(l)) for o, l in frags]
             self.K = len(self.frags)
@@ -66,12 +72,13 @@ class RefLoop:
         received = []
         for p in self.due(t):
             I = max(self.min_interval, self.in_flight[p] - self.t_b[p])
+            one, many = (sync_step_bf16, sync_step_bf16_segmented) if self.half else (sync_step, sync_step_segmented)
             if self.pieces is None:
-                out = sync_step([self.frags[p]], theta_m, theta_m_send, theta_g, momentum, delta_g, None,
-                                [I], [self.t_b[p]], t, 0, self.hp)
+                out = one([self.frags[p]], theta_m, theta_m_send, theta_g, momentum, delta_g, None,
+                          [I], [self.t_b[p]], t, 0, self.hp)
             else:   # the shard alone, as the one fragment of a segmented step
-                out = sync_step_segmented([(o, l, 0) for o, l in self.pieces[p]], 1, theta_m, theta_m_send, theta_g,
-                                          momentum, delta_g, None, [I], [self.t_b[p]], t, 0, self.hp)
+                out = many([(o, l, 0) for o, l in self.pieces[p]], 1, theta_m, theta_m_send, theta_g,
+                           momentum, delta_g, None, [I], [self.t_b[p]], t, 0, self.hp)
             assert out["rc"] == 0
             self.R[p] = out["R"][0]
             self.I_p[p] = I
@@ -88,7 +95,9 @@ class RefLoop:
                     break
             if sent >= 0:
                 where = [self.frags[sent]] if self.pieces is None else self.pieces[sent]
-                if where:
+                if where and self.half:
+                    assert pseudograd_bf16(where, theta_g, theta_m, delta_m_out, theta_m_send, self.hp.pg_format) == 0
+                elif where:
                     assert pseudograd(where, theta_g, theta_m, delta_m_out, theta_m_send) == 0
                 self.in_flight[sent] = t
         return received, sent

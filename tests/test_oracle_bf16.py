@@ -6,6 +6,7 @@ import math
 from fractions import Fraction
 
 import numpy as np
+import pytest
 import torch
 
 from paper_2504_17672_amd import synth
@@ -205,3 +206,121 @@ def test_f16_pseudograd_in_the_bf16_calls(ref):
     assert ref.pseudograd_bf16(wl.frags, tg0, tm0, pg_c, send, pg_format=2) < 0
     assert ref.sync_step_bf16(wl.frags, a["theta_m"], a["theta_m_send"], a["theta_g"], a["momentum"], a["delta_g"],
                               pg_a, bk.I_p, bk.t_b, bk.t_g, 2, ref.hparams(2, 1, pg_format=3))["rc"] < 0
+
+
+# ------------------------------------------------------------------ 16-bit parameters on strided shards, events
+def _run_bf16_seg(ref, segs, K, st, hp, I_p, t_b, budget=2):
+    pg = np.full(st["theta_m"].size, 0x7FC0, np.uint16)
+    out = ref.sync_step_bf16_segmented(segs, K, st["theta_m"], st["theta_m_send"], st["theta_g"], st["momentum"],
+                                       st["delta_g"], pg, I_p, t_b, 100, budget, hp)
+    assert out["rc"] == 0
+    return out, pg
+
+
+def test_bf16_segmented_step_against_the_contiguous_and_the_fp32_segmented_steps(ref):
+    """(a) one segment per fragment, and a fragment cut into adjacent pieces, are the contiguous 16-bit step
+    bit for bit; (b) on strided shards (Sec. 4.1) it is the fp32 segmented step on the widened inputs with
+    the local parameters and the pseudo-gradient rounded once: the two already pinned functions fix it."""
+    wl = synth.Workload("b", (3000, 1999, 0, 777), tau=5, H=100, budget=2)
+    bk = synth.bookkeeping(wl, "mixed")
+    for pg_format in (0, 1):
+        hp = ref.hparams(5, 100, pg_format=pg_format)
+        a = _bf16_state(wl, 21)
+        b = {k: v.copy() for k, v in a.items()}
+        c = {k: v.copy() for k, v in a.items()}
+        pg_a = np.full(wl.n_total, 0x7FC0, np.uint16)
+        oa = ref.sync_step_bf16(wl.frags, a["theta_m"], a["theta_m_send"], a["theta_g"], a["momentum"], a["delta_g"],
+                                pg_a, bk.I_p, bk.t_b, 100, 2, hp)
+        ob, pg_b = _run_bf16_seg(ref, [(o, l, p) for p, (o, l) in enumerate(wl.frags)], wl.K, b, hp, bk.I_p, bk.t_b)
+        cut = []
+        for p, (o, l) in enumerate(wl.frags):
+            cut += [(o, l // 3, p), (o + l // 3, l - l // 3, p)]
+        oc, pg_c = _run_bf16_seg(ref, cut, wl.K, c, hp, bk.I_p, bk.t_b)
+        for other, o2, pg2 in ((b, ob, pg_b), (c, oc, pg_c)):
+            for k in a:
+                assert np.array_equal(a[k], other[k]), k
+            assert np.array_equal(pg_a, pg2)
+            assert np.array_equal(oa["R"], o2["R"]) and np.array_equal(oa["sums"], o2["sums"])
+            assert oa["sel"].tolist() == o2["sel"].tolist()
+
+        # (b) 12 layers of unequal size in K = 4 strided shards, with a gap that nobody owns
+        sizes = [300, 170, 411, 96, 250, 333, 128, 77, 205, 190, 64, 501]
+        offs = np.concatenate(([40], 40 + np.cumsum(sizes)[:-1]))
+        segs = [(int(offs[j]), sizes[j], j % 4) for j in range(12)]
+        n = 40 + sum(sizes) + 25
+        wl2 = synth.Workload("b2", (n,), tau=5, H=100)
+        s16 = _bf16_state(wl2, 22)
+        w = {k: (v.copy() if v.dtype == np.float32 else _widen(v)) for k, v in s16.items()}
+        before = {k: v.copy() for k, v in s16.items()}
+        I_p, t_b = [3, 5, 2, 7], [90, 95, 97, 60]
+        o16, pg16 = _run_bf16_seg(ref, segs, 4, s16, hp, I_p, t_b)
+        pg32 = np.zeros(n, np.float32)
+        o32 = ref.sync_step_segmented(segs, 4, w["theta_m"], w["theta_m_send"], w["theta_g"], w["momentum"],
+                                      w["delta_g"], pg32, I_p, t_b, 100, 2, hp, shadow=True)
+        assert o32["rc"] == 0
+        assert np.array_equal(s16["theta_g"], w["theta_g"]) and np.array_equal(s16["momentum"], w["momentum"])
+        assert np.array_equal(o16["R"], o32["R"]) and np.array_equal(o16["sums"], o32["sums"])
+        assert o16["sel"].tolist() == o32["sel"].tolist()
+        rnd = ref.round_f16 if pg_format else ref.round_bf16
+        owned = np.zeros(n, bool)
+        for o, l, _ in segs:
+            owned[o:o + l] = True
+        want_tm = np.array([ref.round_bf16(v) for v in o32["theta_m64"]], dtype=np.uint16)
+        assert np.array_equal(s16["theta_m"][owned], want_tm[owned])
+        diff = before["theta_g"].astype(np.float64) - _widen(before["theta_m"]).astype(np.float64)
+        want_pg = np.array([rnd(v) for v in diff], dtype=np.uint16)
+        assert np.array_equal(pg16[owned], want_pg[owned])
+        # what no shard owns is left alone
+        assert np.array_equal(s16["theta_m"][~owned], before["theta_m"][~owned])
+        assert (pg16[~owned] == 0x7FC0).all()
+        for k in ("theta_g", "momentum", "delta_g", "theta_m_send"):
+            assert np.array_equal(s16[k][~owned], before[k][~owned])
+
+
+@pytest.mark.parametrize("mask", [(1, 1, 1, 1, 1), (0, 1, 0, 2, 1), (0, 0, 0, 0, 0), (1, 2, 2, 0, 2), (3, 0, 1, 0, 0)])
+def test_bf16_event_is_the_bf16_step_on_the_arrived_fragments_then_selection(ref, mask):
+    """The 16-bit event == the 16-bit step restricted to the arrived fragments (everything else untouched),
+    then Alg. 2 over old and new scores with the fragments in flight struck out of the priority order."""
+    frags = [(3, 700), (703, 0), (710, 1), (800, 4100), (5000, 333)]
+    K, n = len(frags), 5400
+    wl = synth.Workload("e", (n,), tau=2, H=3)
+    hp = ref.hparams(2, 3, lam=0.5, pg_format=1)
+    I_p = [4, 9, 2, 6, 3]
+    t_b = [90, 99, 40, 95, 97]
+    R_old = np.array([0.25, np.inf, 7.0, 0.5, 0.125])
+    a = _bf16_state(wl, 31, amplified=True)
+    b = {k: v.copy() for k, v in a.items()}
+    orig = {k: v.copy() for k, v in a.items()}
+    pg_a = np.full(n, 0x7E00, np.uint16)
+    pg_b = pg_a.copy()
+    sums_a = np.full((K, 4), -3.0)
+    R_a = R_old.copy()
+    out = ref.sync_event_bf16(frags, mask, a["theta_m"], a["theta_m_send"], a["theta_g"], a["momentum"], a["delta_g"],
+                              pg_a, I_p, t_b, 100, 2, hp, R_a, sums=sums_a)
+    assert out["rc"] == 0
+    arrived = [q for q in range(K) if mask[q] & 1]
+    R_b = R_old.copy()
+    sums_b = np.full((K, 4), -3.0)
+    if arrived:
+        sub = ref.sync_step_bf16([frags[q] for q in arrived], b["theta_m"], b["theta_m_send"], b["theta_g"],
+                                 b["momentum"], b["delta_g"], pg_b, [I_p[q] for q in arrived],
+                                 [t_b[q] for q in arrived], 100, 0, hp)
+        assert sub["rc"] == 0
+        for j, q in enumerate(arrived):
+            R_b[q] = sub["R"][j]
+            sums_b[q] = sub["sums"][j]
+    rc, order = ref.select_fragments(R_b, t_b, 100, hp.H, K)
+    assert rc == 0
+    want = [q for q in order.tolist() if not mask[q] & 2][:2]
+    for k in a:
+        assert np.array_equal(a[k], b[k]), k
+    assert np.array_equal(pg_a, pg_b)
+    assert np.array_equal(R_a, R_b) and np.array_equal(sums_a, sums_b)
+    assert out["sel"].tolist() == want
+    if arrived:
+        assert not np.array_equal(a["theta_m"], orig["theta_m"])
+    else:
+        for k in a:
+            assert np.array_equal(a[k], orig[k])
+    assert ref.sync_event_bf16(frags, [4, 0, 0, 0, 0], a["theta_m"], a["theta_m_send"], a["theta_g"], a["momentum"],
+                               a["delta_g"], pg_a, I_p, t_b, 100, 2, hp, R_a)["rc"] < 0

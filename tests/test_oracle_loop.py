@@ -430,3 +430,82 @@ def test_workers_that_share_the_averaged_history_choose_alike(ref):
             assert np.array_equal(w["st"]["theta_g"], workers[0]["st"]["theta_g"])
             assert np.array_equal(w["st"]["momentum"], workers[0]["st"]["momentum"])
     assert n_sends == 240 // 6 and not np.array_equal(workers[0]["st"]["theta_m"], workers[1]["st"]["theta_m"])
+
+
+# ------------------------------------------------------------------ the loop on 16-bit local parameters
+def _to_bf16_bits(x32):
+    return torch.from_numpy(x32).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16).copy()
+
+
+def _from_bf16_bits(u16):
+    return torch.from_numpy(u16.view(np.int16)).view(torch.bfloat16).float().numpy()
+
+
+@pytest.mark.parametrize("strided", [False, True])
+def test_half_loop_follows_the_fp32_loop_wherever_only_the_averages_matter(ref, strided):
+    """Scores (Eq. 11), global states and momenta (Eq. 2) depend on the history of averaged pseudo-gradients
+    alone, not on the local parameters.  Fed the same averages, the loop on bf16 local parameters must
+    therefore make the same event log as the (pinned) fp32 loop and hold bit-identical scores, global states
+    and momenta, while its 16-bit buffers get the 16-bit single steps: at each send the record equals the
+    parameters and the outgoing pseudo-gradient is theta^g - theta^m rounded once to hp.pg_format."""
+    from oracle.loop import RefLoop
+    tau, H = 3, 40
+    if strided:
+        sizes = [300, 170, 411, 96, 250, 333, 128, 77, 205, 190, 64, 501]
+        offs = np.concatenate(([0], np.cumsum(sizes)[:-1]))
+        segs = [(int(offs[j]), sizes[j], j % 4) for j in range(12)]
+        K, n = 4, sum(sizes)
+        wl = synth.Workload("half", (n,), tau=tau, H=H)
+        mk = lambda hp, half: RefLoop(None, hp, 1.0, 1.0, 4.0, segs=segs, K=K, half=half)
+    else:
+        wl = synth.Workload("half", (700, 1, 0, 330, 409), tau=tau, H=H)
+        K, n = wl.K, wl.n_total
+        mk = lambda hp, half: RefLoop(wl.frags, hp, 1.0, 1.0, 4.0, half=half)
+    for pg_format in (0, 1):
+        hp = ref.hparams(tau, H, pg_format=pg_format)
+        rnd = ref.round_f16 if pg_format else ref.round_bf16
+        a = {k: v.numpy() for k, v in synth.make_state(wl, "cpu", seed=5).items()}
+        b = {k: v.copy() for k, v in a.items()}
+        b["theta_m"], b["theta_m_send"] = _to_bf16_bits(a["theta_m"]), _to_bf16_bits(a["theta_m_send"])
+        la, lb = mk(hp, False), mk(hp, True)
+        pieces = la.pieces if strided else [[f] for f in wl.frags]
+        out_a, out_b = np.zeros(n, np.float32), np.full(n, 0xFFFF, np.uint16)
+        g = torch.Generator().manual_seed(9)
+        n_sent = 0
+        for t in range(1, 201):
+            drift = torch.empty(n).normal_(0.0, 1e-3, generator=g).numpy()
+            a["theta_m"] += drift
+            b["theta_m"] = _to_bf16_bits(_from_bf16_bits(b["theta_m"]) + drift)
+            assert la.due(t) == lb.due(t)
+            for p in la.due(t):
+                for o, l in pieces[p]:
+                    fresh = torch.empty(l).normal_(0.0, 1e-3, generator=g).numpy()
+                    a["delta_g"][o:o + l] = fresh
+                    b["delta_g"][o:o + l] = fresh
+            tm_before, tg_before, out_before = b["theta_m"].copy(), b["theta_g"].copy(), out_b.copy()
+            ea = la.step(t, a["theta_m"], a["theta_m_send"], a["theta_g"], a["momentum"], a["delta_g"], out_a)
+            eb = lb.step(t, b["theta_m"], b["theta_m_send"], b["theta_g"], b["momentum"], b["delta_g"], out_b)
+            assert ea == eb, (t, ea, eb)
+            assert np.array_equal(la.R.view(np.uint64), lb.R.view(np.uint64))
+            assert (la.t_b, la.I_p, la.in_flight) == (lb.t_b, lb.I_p, lb.in_flight)
+            assert np.array_equal(a["theta_g"], b["theta_g"]) and np.array_equal(a["momentum"], b["momentum"])
+            sent = eb[1]
+            touched = np.zeros(n, bool)
+            if sent >= 0:
+                n_sent += 1
+                for o, l in pieces[sent]:
+                    touched[o:o + l] = True
+                    assert np.array_equal(b["theta_m_send"][o:o + l], b["theta_m"][o:o + l])
+                    # the send happens after this step's receives: on the buffers as they are now
+                    # (a fragment is never received and sent again at one step unless h == tau)
+                    for i in ({o, o + l // 2, o + l - 1} if l else ()):
+                        want = rnd(float(b["theta_g"][i]) - float(_from_bf16_bits(b["theta_m"][i:i + 1])[0]))
+                        assert out_b[i] == want, (t, i)
+            assert np.array_equal(out_b[~touched], out_before[~touched])
+            received = np.zeros(n, bool)
+            for p in eb[0]:
+                for o, l in pieces[p]:
+                    received[o:o + l] = True
+            assert np.array_equal(b["theta_m"][~received], tm_before[~received])
+            assert np.array_equal(b["theta_g"][~received], tg_before[~received])
+        assert n_sent == 200 // 4

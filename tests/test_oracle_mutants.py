@@ -75,6 +75,15 @@ MUTANTS = [
      "    if (e > 15) return sign | 0x7BFF;"),
     ("f16_format_switch_ignored", "return pg_format ? cocodc_ref_round_f16(x) : cocodc_ref_round_bf16(x);",
      "return cocodc_ref_round_bf16(x);"),
+    ("half_pg_sign", "round_half(tg - tm, hp.pg_format)", "round_half(tm - tg, hp.pg_format)"),
+    ("half_send_record_ignored", "theta_send ? cocodc_ref_widen_bf16(theta_send[i]) : tm;", "tm;"),
+    ("half_params_rounded_toward_zero", "theta_m[i] = cocodc_ref_round_bf16(tm_new);",
+     "theta_m[i] = cocodc_ref_round_bf16(tm_new); if (std::fabs(cocodc_ref_widen_bf16(theta_m[i])) > std::fabs(tm_new)) theta_m[i] -= 1;"),
+    ("half_outer_step_sign", "outer_update(tg, m0, dg, hp, &m1);   // Eq. 2", "outer_update(tg, m0, -dg, hp, &m1);   // Eq. 2"),
+    ("half_event_interval_of_fragment_0", "R[q] = score_from_sums(s, I_p[q], *hp);\n    store_sums",
+     "R[q] = score_from_sums(s, I_p[0], *hp);\n    store_sums"),
+    ("half_sums_stored_for_fragment_0", "store_sums(s, q, sums_out);", "store_sums(s, 0, sums_out);"),
+    ("segments_of_every_fragment_walked", "if (segs[j].fragment != p) continue;", ""),
     ("in_flight_counts_against_the_budget", "const int32_t n_sel = budget < candidates ? budget : candidates;",
      "const int32_t n_sel = (budget < K ? budget : K) - (K - candidates) > 0 ? (budget < K ? budget : K) - (K - candidates) : 0;"),
 ]
@@ -84,6 +93,9 @@ BATTERY = [
     half_pins.test_f16_rounding_matches_numpy_from_float64_and_torch_from_float32,
     half_pins.test_f16_pseudograd_in_the_bf16_calls,
     lambda ref: loop_pins.test_event_equals_step_on_the_arrived_fragments_then_selection_over_all(ref, (0, 1, 0, 0, 1)),
+    half_pins.test_bf16_step_is_the_fp32_step_on_widened_inputs_rounded_once,
+    half_pins.test_bf16_segmented_step_against_the_contiguous_and_the_fp32_segmented_steps,
+    lambda ref: half_pins.test_bf16_event_is_the_bf16_step_on_the_arrived_fragments_then_selection(ref, (0, 1, 0, 2, 1)),
     pins.test_pseudograd_is_fp32_subtraction_global_minus_local,
     pins.test_pseudograd_sign_and_zero,
     pins.test_unit_outer_step_moves_global_state_to_worker_average,
@@ -124,7 +136,8 @@ def _compile(text, path):
                     "-I", os.path.dirname(SRC), "-o", path, src], check=True)
     lib = C.CDLL(path)
     for name in ("pseudograd", "outer_nesterov", "delay_compensate", "fragment_scores", "select_fragments",
-                 "sync_step", "sync_step_mt", "sync_plan", "sync_event", "pseudograd_bf16", "sync_step_bf16"):
+                 "sync_step", "sync_step_mt", "sync_plan", "sync_event", "pseudograd_bf16", "sync_step_bf16",
+                 "sync_step_segmented", "sync_step_bf16_segmented", "sync_event_bf16"):
         getattr(lib, "cocodc_ref_" + name).restype = C.c_int
     for name, res, arg in (("round_bf16", C.c_uint16, C.c_double), ("widen_bf16", C.c_double, C.c_uint16),
                            ("round_f16", C.c_uint16, C.c_double), ("widen_f16", C.c_double, C.c_uint16)):
