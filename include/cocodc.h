@@ -118,7 +118,7 @@ typedef struct {
                       /* theta^g_{p,t_p-H}, the change accumulated over the last H steps that the   */
                       /* text after Eq. 6 describes; it needs the previous global state, so only    */
                       /* the fused calls accept it (cocodc_delay_compensate: COCODC_ERR_RANGE)      */
-  int32_t pg_format;  /* read by cocodc_sync_step_bf16 only: 16-bit format of the outgoing          */
+  int32_t pg_format;  /* read by the bf16 calls only: 16-bit format of the outgoing                 */
                       /* pseudo-gradient, COCODC_PG_BF16 (0, default) or COCODC_PG_F16 (IEEE binary16)  */
 } cocodc_hparams_t;
 
@@ -281,7 +281,7 @@ int cocodc_sync_step_segmented(const cocodc_segment_t* segs, int32_t S, int32_t 
                                void* stream);
 
 /* ---- bfloat16 local parameters ----
- * The paper's workers train in bf16 mixed precision (Sec. 4.1).  In these two calls theta_m,
+ * The paper's workers train in bf16 mixed precision (Sec. 4.1).  In these calls theta_m,
  * theta_m_send and the outgoing pseudo-gradient are bfloat16 (raw 16-bit patterns, 2-byte
  * aligned; 16-byte aligned for the fast path), while the global state, the outer momentum and
  * delta_g stay fp32 master copies.  Every bf16 input is widened exactly, the update is the
@@ -306,6 +306,29 @@ int cocodc_sync_step_bf16(const cocodc_fragment_t* frags, int32_t K, uint64_t n_
                           double* R_out, int32_t* sel_out, int32_t* n_sel_out,
                           double* sums_out /* nullable */, void* workspace, size_t workspace_bytes,
                           void* stream);
+/* cocodc_sync_step_bf16 for fragments made of several segments: Sec. 4.1 as the paper runs it,
+ * strided shards of a model trained in bf16 mixed precision.  segs, the per-fragment arrays and
+ * the workspace size as for cocodc_sync_step_segmented; buffers as for cocodc_sync_step_bf16. */
+int cocodc_sync_step_bf16_segmented(const cocodc_segment_t* segs, int32_t S, int32_t K, uint64_t n_total,
+                                    uint16_t* theta_m, const uint16_t* theta_m_send, float* theta_g,
+                                    float* momentum, const float* delta_g,
+                                    uint16_t* delta_m_out /* nullable */, const int64_t* I_p,
+                                    const int64_t* t_b, int64_t t_g, int32_t budget,
+                                    const cocodc_hparams_t* hp, double* R_out, int32_t* sel_out,
+                                    int32_t* n_sel_out, double* sums_out /* nullable */, void* workspace,
+                                    size_t workspace_bytes, void* stream);
+/* cocodc_sync_event (one event of the loop of Sec. 3.2) on bf16 local parameters: recv_mask, R
+ * (read and written), t_b and the selection among the fragments not in flight as there; buffers
+ * and rounding as for cocodc_sync_step_bf16. */
+int cocodc_sync_event_bf16(const cocodc_fragment_t* frags, int32_t K, uint64_t n_total,
+                           const uint8_t* recv_mask, uint16_t* theta_m,
+                           const uint16_t* theta_m_send /* nullable as in cocodc_sync_step */,
+                           float* theta_g, float* momentum, const float* delta_g,
+                           uint16_t* delta_m_out /* nullable */, const int64_t* I_p, const int64_t* t_b,
+                           int64_t t_g, int32_t budget, const cocodc_hparams_t* hp,
+                           double* R /* in and out */, int32_t* sel_out, int32_t* n_sel_out,
+                           double* sums_out /* nullable */, void* workspace, size_t workspace_bytes,
+                           void* stream);
 
 /* Host-only planner, Eq. 9 and Eq. 10: N = max(K, floor(gamma*H*T_c/T_s)) target
  * synchronisations per H steps and h = floor(H/N) steps between two sends.
@@ -392,6 +415,27 @@ int cocodc_loop_due(cocodc_loop_t* loop, int64_t t, int32_t* due_out, int32_t* n
 #define COCODC_LOOP_SENT_PENDING (-2)
 int cocodc_loop_step(cocodc_loop_t* loop, int64_t t, const cocodc_loop_buffers_t* buf, void* stream,
                      int32_t* received_out, int32_t* n_received_out, int32_t* sent_out);
+
+/* The same step for a worker whose local parameters are bf16 (Sec. 4.1: bf16 mixed precision):
+ * theta_m, theta_m_send and delta_m_out are 16-bit patterns as in cocodc_sync_step_bf16, the
+ * outgoing pseudo-gradient in the format hp->pg_format of the hyper-parameters the loop was
+ * created with; delta_g (the arriving average) stays fp32, so the send buffer cannot be delta_g.
+ * A loop object is used with one of the two step functions throughout. */
+typedef struct {
+  uint16_t* theta_m;      /* bf16 local parameters                                         */
+  uint16_t* theta_m_send; /* bf16 send-time records                                        */
+  float* theta_g;
+  float* momentum;
+  float* delta_g;
+  uint16_t* delta_m_out;  /* bf16 or binary16 pseudo-gradient of the fragment that is sent */
+  double* R;
+  int32_t* sel;
+  int32_t* n_sel;
+  void* workspace;
+  size_t workspace_bytes;
+} cocodc_loop_buffers_bf16_t;
+int cocodc_loop_step_bf16(cocodc_loop_t* loop, int64_t t, const cocodc_loop_buffers_bf16_t* buf, void* stream,
+                          int32_t* received_out, int32_t* n_received_out, int32_t* sent_out);
 
 /* The most recent send decision: the step it was taken at and the fragment (-1, -1 before the
  * first; fragment -1 if nothing was eligible).  Waits until that decision has been copied to the

@@ -42,9 +42,10 @@ EXPORTS = (
     "cocodc_fragment_scores", "cocodc_select_fragments", "cocodc_sync_step", "cocodc_sync_step_noalloc",
     "cocodc_sync_event", "cocodc_sync_plan",
     "cocodc_workspace_bytes_segmented", "cocodc_fragment_scores_segmented", "cocodc_sync_step_segmented",
-    "cocodc_pseudograd_bf16", "cocodc_sync_step_bf16", "cocodc_select_fragments_bytes",
+    "cocodc_pseudograd_bf16", "cocodc_sync_step_bf16", "cocodc_sync_step_bf16_segmented", "cocodc_sync_event_bf16",
+    "cocodc_select_fragments_bytes",
     "cocodc_loop_create", "cocodc_loop_create_segmented", "cocodc_loop_destroy", "cocodc_loop_reset_scores", "cocodc_loop_observe",
-    "cocodc_loop_plan", "cocodc_loop_due", "cocodc_loop_step", "cocodc_loop_state", "cocodc_loop_last_sent",
+    "cocodc_loop_plan", "cocodc_loop_due", "cocodc_loop_step", "cocodc_loop_step_bf16", "cocodc_loop_state", "cocodc_loop_last_sent",
     "cocodc_tile_elements", "cocodc_debug_tile_plan", "cocodc_debug_stream_mix",
     "cocodc_layout_stride_bytes", "cocodc_last_hip_error", "cocodc_status_string", "cocodc_set_blocks_per_cu",
     "cocodc_set_tables_in_args",
@@ -110,6 +111,8 @@ _lib.cocodc_sync_step_segmented.argtypes = [_seg_p, C.c_int32, C.c_int32, C.c_ui
 _lib.cocodc_pseudograd_bf16.argtypes = [_frag_p, C.c_int32, C.c_uint64, _P, _P, _P, _P, C.c_int32, _P, C.c_size_t, _P]
 _lib.cocodc_sync_step_bf16.argtypes = [_frag_p, C.c_int32, C.c_uint64, _P, _P, _P, _P, _P, _P, _i64_p, _i64_p,
                                        C.c_int64, C.c_int32, _hp_p, _P, _P, _P, _P, _P, C.c_size_t, _P]
+_lib.cocodc_sync_step_bf16_segmented.argtypes = _lib.cocodc_sync_step_segmented.argtypes
+_lib.cocodc_sync_event_bf16.argtypes = _lib.cocodc_sync_event.argtypes
 _lib.cocodc_select_fragments_bytes.argtypes = [C.c_int32, _P, _i64_p, C.c_int64, C.c_int32, C.POINTER(C.c_uint64),
                                                C.c_uint64, _P, _P, _P, C.c_size_t, _P]
 _i32_p = C.POINTER(C.c_int32)
@@ -124,6 +127,8 @@ _lib.cocodc_loop_observe.argtypes = [_P, C.c_double, C.c_double, C.c_double]
 _lib.cocodc_loop_plan.argtypes = [_P, _i64_p, _i64_p]
 _lib.cocodc_loop_due.argtypes = [_P, C.c_int64, _i32_p, _i32_p]
 _lib.cocodc_loop_step.argtypes = [_P, C.c_int64, C.POINTER(cocodc_loop_buffers_t), _P, _i32_p, _i32_p, _i32_p]
+# (the 16-bit buffer struct has the layout of cocodc_loop_buffers_t: eleven pointers and a size)
+_lib.cocodc_loop_step_bf16.argtypes = _lib.cocodc_loop_step.argtypes
 _lib.cocodc_loop_state.argtypes = [_P, _i64_p, _i64_p, _i64_p]
 _lib.cocodc_loop_last_sent.argtypes = [_P, _i64_p, _i32_p]
 _lib.cocodc_tile_elements.restype = C.c_uint64
@@ -498,6 +503,16 @@ def cocodc_loop_step(handle, t, buffers, stream=None):
     return rc, [int(rec[i]) for i in range(n.value)], sent.value
 
 
+def cocodc_loop_step_bf16(handle, t, buffers, stream=None):
+    """cocodc_loop_step on bf16 local parameters: `buffers` from loop_buffers() with 16-bit theta_m,
+    theta_m_send and delta_m_out tensors."""
+    rec = (C.c_int32 * max(handle[1], 1))()
+    n, sent = C.c_int32(0), C.c_int32(-1)
+    rc = _lib.cocodc_loop_step_bf16(handle[0], int(t), C.byref(buffers), _stream(stream), rec, C.byref(n),
+                                    C.byref(sent))
+    return rc, [int(rec[i]) for i in range(n.value)], sent.value
+
+
 def cocodc_loop_state(handle):
     """Returns (status, t_b, I_p, in_flight) as lists of K ints."""
     K = max(handle[1], 1)
@@ -568,6 +583,34 @@ def cocodc_sync_step_bf16(frags, n_total, theta_m, theta_m_send, theta_g, moment
                                       _i64(t_b), int(t_g), int(budget), C.byref(hp) if hp is not None else None,
                                       _ptr(R_out), _ptr(sel_out), _ptr(n_sel_out), _ptr(sums_out), wp, wb,
                                       _stream(stream))
+
+
+def cocodc_sync_step_bf16_segmented(segs, K, n_total, theta_m, theta_m_send, theta_g, momentum, delta_g, delta_m_out,
+                                    I_p, t_b, t_g, budget, hp, R_out, sel_out, n_sel_out, sums_out, workspace,
+                                    workspace_bytes=None, stream=None, S=None):
+    sa, n = _segs(segs)
+    wp, wb = _ws(workspace, workspace_bytes)
+    return _lib.cocodc_sync_step_bf16_segmented(sa, n if S is None else S, int(K), int(n_total), _ptr(theta_m),
+                                                _ptr(theta_m_send), _ptr(theta_g), _ptr(momentum), _ptr(delta_g),
+                                                _ptr(delta_m_out), _i64(I_p), _i64(t_b), int(t_g), int(budget),
+                                                C.byref(hp) if hp is not None else None, _ptr(R_out), _ptr(sel_out),
+                                                _ptr(n_sel_out), _ptr(sums_out), wp, wb, _stream(stream))
+
+
+def cocodc_sync_event_bf16(frags, n_total, recv_mask, theta_m, theta_m_send, theta_g, momentum, delta_g, delta_m_out,
+                           I_p, t_b, t_g, budget, hp, R, sel_out, n_sel_out, sums_out, workspace,
+                           workspace_bytes=None, stream=None, K=None):
+    """cocodc_sync_event with 16-bit theta_m / theta_m_send / delta_m_out."""
+    fa, k = _frags(frags)
+    wp, wb = _ws(workspace, workspace_bytes)
+    mask = None
+    if recv_mask is not None:
+        mask = (C.c_uint8 * max(len(recv_mask), 1))(*[int(m) & 0xFF for m in recv_mask])
+    return _lib.cocodc_sync_event_bf16(fa, k if K is None else K, int(n_total), mask, _ptr(theta_m),
+                                       _ptr(theta_m_send), _ptr(theta_g), _ptr(momentum), _ptr(delta_g),
+                                       _ptr(delta_m_out), _i64(I_p), _i64(t_b), int(t_g), int(budget),
+                                       C.byref(hp) if hp is not None else None, _ptr(R), _ptr(sel_out),
+                                       _ptr(n_sel_out), _ptr(sums_out), wp, wb, _stream(stream))
 
 
 def cocodc_tile_elements(n_total):

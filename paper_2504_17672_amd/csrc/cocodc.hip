@@ -442,12 +442,12 @@ int cocodc_pseudograd_bf16(const cocodc_fragment_t* frags, int32_t K, uint64_t n
   return launch_walk(vec, wk, op, v.partials, s);
 }
 
-int cocodc_sync_step_bf16(const cocodc_fragment_t* frags, int32_t K, uint64_t n_total, uint16_t* theta_m,
-                          const uint16_t* theta_m_send, float* theta_g, float* momentum, const float* delta_g,
-                          uint16_t* delta_m_out, const int64_t* I_p, const int64_t* t_b, int64_t t_g,
-                          int32_t budget, const cocodc_hparams_t* hp, double* R_out, int32_t* sel_out,
-                          int32_t* n_sel_out, double* sums_out, void* workspace, size_t workspace_bytes_,
-                          void* stream) {
+// ---- the fused step on 16-bit local parameters --------------------------------------------------
+static int sync_step_bf16_check(const uint16_t* theta_m, const uint16_t* theta_m_send, const float* theta_g,
+                                const float* momentum, const float* delta_g, const uint16_t* delta_m_out,
+                                const int64_t* I_p, const int64_t* t_b, int32_t budget, const cocodc_hparams_t* hp,
+                                const double* R_out, const int32_t* sel_out, const int32_t* n_sel_out,
+                                const double* sums_out) {
   if (!theta_m || !theta_g || !momentum || !delta_g) return COCODC_ERR_NULL;
   if (!I_p || !t_b || !R_out || !sel_out || !n_sel_out) return COCODC_ERR_NULL;
   if (!all_aligned4({theta_g, momentum, delta_g, sel_out, n_sel_out})) return COCODC_ERR_ALIGN;
@@ -456,13 +456,19 @@ int cocodc_sync_step_bf16(const cocodc_fragment_t* frags, int32_t K, uint64_t n_
   if (int rc = check_hparams(hp)) return rc;
   if (!theta_m_send && (hp->merge_mode == 0 || hp->score_src == 1)) return COCODC_ERR_NULL;
   if (budget < 0) return COCODC_ERR_RANGE;
-  Plan pl;
-  if (int rc = plan_table(frags, K, n_total, I_p, t_b, &pl)) return rc;
-  if (int rc = check_workspace(workspace, workspace_bytes_, pl.S, K, n_total)) return rc;
-  const int n = budget < K ? budget : K;
+  return COCODC_OK;
+}
+
+// No two buffers of the 16-bit step may overlap (the incoming average is fp32 and the outgoing
+// pseudo-gradient 16-bit, so there is no in-place exchange buffer here).
+static int sync_step_bf16_overlaps(int32_t K, uint64_t n_total, const uint16_t* theta_m, const uint16_t* theta_m_send,
+                                   const float* theta_g, const float* momentum, const float* delta_g,
+                                   const uint16_t* delta_m_out, int n_sel_max, const double* R_out,
+                                   const int32_t* sel_out, const int32_t* n_sel_out, const double* sums_out,
+                                   const void* workspace, size_t workspace_bytes_) {
   const Span sp[] = {{theta_m, n_total * 2},      {theta_m_send, n_total * 2},    {theta_g, n_total * 4},
                      {momentum, n_total * 4},     {delta_g, n_total * 4},         {delta_m_out, n_total * 2},
-                     {R_out, sizeof(double) * K}, {sel_out, sizeof(int32_t) * n}, {n_sel_out, sizeof(int32_t)},
+                     {R_out, sizeof(double) * K}, {sel_out, sizeof(int32_t) * n_sel_max}, {n_sel_out, sizeof(int32_t)},
                      {sums_out, sizeof(double) * 4 * K}, {workspace, workspace_bytes_}};
   const int ns = static_cast<int>(sizeof(sp) / sizeof(sp[0]));
   for (int i = 0; i < ns; ++i) {
@@ -470,20 +476,86 @@ int cocodc_sync_step_bf16(const cocodc_fragment_t* frags, int32_t K, uint64_t n_
       if (overlap(sp[i], sp[j])) return COCODC_ERR_ALIAS;
     }
   }
+  return COCODC_OK;
+}
+
+static int sync_step_bf16_impl(Plan& pl, int32_t K, uint64_t n_total, uint16_t* theta_m, const uint16_t* theta_m_send,
+                               float* theta_g, float* momentum, const float* delta_g, uint16_t* delta_m_out,
+                               int64_t t_g, int32_t budget, const cocodc_hparams_t* hp, double* R_out,
+                               int32_t* sel_out, int32_t* n_sel_out, double* sums_out, void* workspace,
+                               size_t workspace_bytes_, void* stream) {
+  if (int rc = check_workspace(workspace, workspace_bytes_, pl.S, K, n_total)) return rc;
+  int candidates = 0, taking_part = 0;  // fragments Algorithm 2 may choose; fragments this call updates
+  for (int32_t p = 0; p < K; ++p) {
+    candidates += pl.groups[p].in_flight ? 0 : 1;
+    taking_part += pl.groups[p].takes_part ? 1 : 0;
+  }
+  const int n = budget < candidates ? budget : candidates;
+  if (int rc = sync_step_bf16_overlaps(K, n_total, theta_m, theta_m_send, theta_g, momentum, delta_g, delta_m_out, n,
+                                       R_out, sel_out, n_sel_out, sums_out, workspace, workspace_bytes_))
+    return rc;
   hipStream_t s = static_cast<hipStream_t>(stream);
   WorkspaceView v = view(workspace, pl.S, K);
   if (int rc = upload_table(pl, v, s)) return rc;
-  const bool vec = all_aligned16({theta_m, theta_m_send, theta_g, momentum, delta_g, delta_m_out});
-  const DevHP d = to_dev(*hp);
-  const bool pg_f16 = hp->pg_format == COCODC_PG_F16;
-  int rc = hp->nesterov ? launch_fused_bf16_m<true>(merge_variant(*hp), vec, walk_of(v, pl), theta_m, theta_m_send,
-                                                    theta_g, momentum, delta_g, delta_m_out, pg_f16, d, v.partials, s)
-                        : launch_fused_bf16_m<false>(merge_variant(*hp), vec, walk_of(v, pl), theta_m, theta_m_send,
-                                                     theta_g, momentum, delta_g, delta_m_out, pg_f16, d, v.partials, s);
-  if (rc) return rc;
-  const int which = (hp->score_src ? 2 : 0) + (hp->norm_kind == 2 ? 0 : 1);
-  if (int rc2 = launch_finalize(pl, v, kSums, which, hp->norm_kind == 2 ? 1 : 0, R_out, sums_out, kSums, s)) return rc2;
+  if (taking_part > 0) {
+    const bool vec = all_aligned16({theta_m, theta_m_send, theta_g, momentum, delta_g, delta_m_out});
+    const DevHP d = to_dev(*hp);
+    const bool pg_f16 = hp->pg_format == COCODC_PG_F16;
+    int rc = hp->nesterov ? launch_fused_bf16_m<true>(merge_variant(*hp), vec, walk_of(v, pl), theta_m, theta_m_send,
+                                                      theta_g, momentum, delta_g, delta_m_out, pg_f16, d, v.partials, s)
+                          : launch_fused_bf16_m<false>(merge_variant(*hp), vec, walk_of(v, pl), theta_m, theta_m_send,
+                                                       theta_g, momentum, delta_g, delta_m_out, pg_f16, d, v.partials, s);
+    if (rc) return rc;
+    const int which = (hp->score_src ? 2 : 0) + (hp->norm_kind == 2 ? 0 : 1);
+    if (int rc2 = launch_finalize(pl, v, kSums, which, hp->norm_kind == 2 ? 1 : 0, R_out, sums_out, kSums, s)) return rc2;
+  }
   return launch_select(pl, v, R_out, t_g, static_cast<int64_t>(hp->H), n, sel_out, n_sel_out, s);
+}
+
+int cocodc_sync_step_bf16(const cocodc_fragment_t* frags, int32_t K, uint64_t n_total, uint16_t* theta_m,
+                          const uint16_t* theta_m_send, float* theta_g, float* momentum, const float* delta_g,
+                          uint16_t* delta_m_out, const int64_t* I_p, const int64_t* t_b, int64_t t_g,
+                          int32_t budget, const cocodc_hparams_t* hp, double* R_out, int32_t* sel_out,
+                          int32_t* n_sel_out, double* sums_out, void* workspace, size_t workspace_bytes_,
+                          void* stream) {
+  if (int rc = sync_step_bf16_check(theta_m, theta_m_send, theta_g, momentum, delta_g, delta_m_out, I_p, t_b, budget,
+                                    hp, R_out, sel_out, n_sel_out, sums_out))
+    return rc;
+  Plan pl;
+  if (int rc = plan_table(frags, K, n_total, I_p, t_b, &pl)) return rc;
+  return sync_step_bf16_impl(pl, K, n_total, theta_m, theta_m_send, theta_g, momentum, delta_g, delta_m_out, t_g,
+                             budget, hp, R_out, sel_out, n_sel_out, sums_out, workspace, workspace_bytes_, stream);
+}
+
+int cocodc_sync_step_bf16_segmented(const cocodc_segment_t* segs, int32_t S, int32_t K, uint64_t n_total,
+                                    uint16_t* theta_m, const uint16_t* theta_m_send, float* theta_g, float* momentum,
+                                    const float* delta_g, uint16_t* delta_m_out, const int64_t* I_p,
+                                    const int64_t* t_b, int64_t t_g, int32_t budget, const cocodc_hparams_t* hp,
+                                    double* R_out, int32_t* sel_out, int32_t* n_sel_out, double* sums_out,
+                                    void* workspace, size_t workspace_bytes_, void* stream) {
+  if (int rc = sync_step_bf16_check(theta_m, theta_m_send, theta_g, momentum, delta_g, delta_m_out, I_p, t_b, budget,
+                                    hp, R_out, sel_out, n_sel_out, sums_out))
+    return rc;
+  Plan pl;
+  if (int rc = plan_segments(segs, S, K, n_total, I_p, t_b, &pl)) return rc;
+  return sync_step_bf16_impl(pl, K, n_total, theta_m, theta_m_send, theta_g, momentum, delta_g, delta_m_out, t_g,
+                             budget, hp, R_out, sel_out, n_sel_out, sums_out, workspace, workspace_bytes_, stream);
+}
+
+int cocodc_sync_event_bf16(const cocodc_fragment_t* frags, int32_t K, uint64_t n_total, const uint8_t* recv_mask,
+                           uint16_t* theta_m, const uint16_t* theta_m_send, float* theta_g, float* momentum,
+                           const float* delta_g, uint16_t* delta_m_out, const int64_t* I_p, const int64_t* t_b,
+                           int64_t t_g, int32_t budget, const cocodc_hparams_t* hp, double* R, int32_t* sel_out,
+                           int32_t* n_sel_out, double* sums_out, void* workspace, size_t workspace_bytes_,
+                           void* stream) {
+  if (!recv_mask) return COCODC_ERR_NULL;
+  if (int rc = sync_step_bf16_check(theta_m, theta_m_send, theta_g, momentum, delta_g, delta_m_out, I_p, t_b, budget,
+                                    hp, R, sel_out, n_sel_out, sums_out))
+    return rc;
+  Plan pl;
+  if (int rc = plan_table(frags, K, n_total, I_p, t_b, &pl, recv_mask)) return rc;
+  return sync_step_bf16_impl(pl, K, n_total, theta_m, theta_m_send, theta_g, momentum, delta_g, delta_m_out, t_g,
+                             budget, hp, R, sel_out, n_sel_out, sums_out, workspace, workspace_bytes_, stream);
 }
 
 int cocodc_select_fragments_bytes(int32_t K, const double* R, const int64_t* t_b, int64_t t_g, int32_t H,

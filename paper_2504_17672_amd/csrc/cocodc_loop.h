@@ -165,24 +165,96 @@ int cocodc_loop_last_sent(cocodc_loop_t* loop, int64_t* t_sent_out, int32_t* sen
   return COCODC_OK;
 }
 
-int cocodc_loop_step(cocodc_loop_t* loop, int64_t t, const cocodc_loop_buffers_t* buf, void* stream,
-                     int32_t* received_out, int32_t* n_received_out, int32_t* sent_out) {
-  if (!loop || !buf || !received_out || !n_received_out || !sent_out) return COCODC_ERR_NULL;
+}  // extern "C"
+
+namespace {
+// The buffers of a loop step in either precision: the local parameters, their send-time record
+// and the send buffer are fp32 (half == false) or 16-bit patterns (half == true).
+struct LoopIO {
+  bool half;
+  void* theta_m;
+  void* theta_m_send;
+  float* theta_g;
+  float* momentum;
+  float* delta_g;
+  void* delta_m_out;
+  double* R;
+  int32_t* sel;
+  int32_t* n_sel;
+  void* workspace;
+  size_t workspace_bytes;
+};
+
+// Everything either kind of event could need, checked without touching the device.
+int loop_io_check(const cocodc_loop* L, const LoopIO& io) {
+  static const int64_t kOne = 1;
+  const int32_t K = L->K;
+  const int32_t S = static_cast<int32_t>(L->segs.size());
+  if (!io.delta_m_out || !io.theta_m_send) return COCODC_ERR_NULL;
+  if (io.half) {
+    const uint16_t* tm = static_cast<const uint16_t*>(io.theta_m);
+    const uint16_t* ts = static_cast<const uint16_t*>(io.theta_m_send);
+    const uint16_t* out = static_cast<const uint16_t*>(io.delta_m_out);
+    if (int rc = sync_step_bf16_check(tm, ts, io.theta_g, io.momentum, io.delta_g, out, &kOne, &kOne, 1, &L->hp, io.R,
+                                      io.sel, io.n_sel, nullptr))
+      return rc;
+    if (int rc = check_workspace(io.workspace, io.workspace_bytes, S, K, L->n_total)) return rc;
+    return sync_step_bf16_overlaps(K, L->n_total, tm, ts, io.theta_g, io.momentum, io.delta_g, out, 1, io.R, io.sel,
+                                   io.n_sel, nullptr, io.workspace, io.workspace_bytes);
+  }
+  float* tm = static_cast<float*>(io.theta_m);
+  const float* ts = static_cast<const float*>(io.theta_m_send);
+  float* out = static_cast<float*>(io.delta_m_out);
+  if (int rc = sync_step_check(tm, ts, io.theta_g, io.momentum, io.delta_g, out, &kOne, &kOne, 1, &L->hp, io.R, io.sel,
+                               io.n_sel, nullptr))
+    return rc;
+  if (int rc = check_workspace(io.workspace, io.workspace_bytes, S, K, L->n_total)) return rc;
+  return sync_step_overlaps(K, L->n_total, tm, ts, io.theta_g, io.momentum, io.delta_g, out, 1, io.R, io.sel, io.n_sel,
+                            nullptr, io.workspace, io.workspace_bytes);
+}
+
+// The fused step on the arrived fragments and Algorithm 2 among those not in flight.
+int loop_event(const cocodc_loop* L, Plan& pl, const LoopIO& io, int64_t t, int32_t budget, void* stream) {
+  if (io.half) {
+    return sync_step_bf16_impl(pl, L->K, L->n_total, static_cast<uint16_t*>(io.theta_m),
+                               static_cast<const uint16_t*>(io.theta_m_send), io.theta_g, io.momentum, io.delta_g,
+                               nullptr, t, budget, &L->hp, io.R, io.sel, io.n_sel, nullptr, io.workspace,
+                               io.workspace_bytes, stream);
+  }
+  return sync_step_impl(pl, L->K, L->n_total, static_cast<float*>(io.theta_m),
+                        static_cast<const float*>(io.theta_m_send), io.theta_g, io.momentum, io.delta_g, nullptr, t,
+                        budget, &L->hp, io.R, io.sel, io.n_sel, nullptr, io.workspace, io.workspace_bytes, stream);
+}
+
+// Pseudo-gradient and send-time record of the fragment that sel[0] names.
+int loop_send(const cocodc_loop* L, const Plan& full, const WorkspaceView& v, const LoopIO& io, uint64_t widest,
+              hipStream_t s) {
+  const bool vec = all_aligned16({io.theta_g, io.theta_m, io.delta_m_out, io.theta_m_send});
+  if (!io.half) {
+    PseudoGradOp<true> op{io.theta_g, static_cast<const float*>(io.theta_m), static_cast<float*>(io.delta_m_out),
+                          static_cast<float*>(io.theta_m_send)};
+    return launch_walk_chosen(vec, full, v, io.sel, widest, op, s);
+  }
+  const unsigned short* tm = static_cast<const unsigned short*>(io.theta_m);
+  unsigned short* out = static_cast<unsigned short*>(io.delta_m_out);
+  unsigned short* rec = static_cast<unsigned short*>(io.theta_m_send);
+  if (L->hp.pg_format == COCODC_PG_F16) {
+    PseudoGradBf16Op<true, true> op{io.theta_g, tm, out, rec};
+    return launch_walk_chosen(vec, full, v, io.sel, widest, op, s);
+  }
+  PseudoGradBf16Op<true, false> op{io.theta_g, tm, out, rec};
+  return launch_walk_chosen(vec, full, v, io.sel, widest, op, s);
+}
+
+int loop_step_impl(cocodc_loop* loop, int64_t t, const LoopIO& io, void* stream, int32_t* received_out,
+                   int32_t* n_received_out, int32_t* sent_out) {
+  if (!received_out || !n_received_out || !sent_out) return COCODC_ERR_NULL;
   if (t < 1 || t <= loop->last_t) return COCODC_ERR_RANGE;  // steps are numbered 1, 2, ... and never go back
   const int32_t K = loop->K;
   const int32_t S = static_cast<int32_t>(loop->segs.size());
-  // Everything either kind of event could need is checked before anything is enqueued, so that a
-  // rejected step leaves the buffers and the schedule as they were.
-  if (!buf->delta_m_out || !buf->theta_m_send) return COCODC_ERR_NULL;
-  static const int64_t kOne = 1;
-  if (int rc = sync_step_check(buf->theta_m, buf->theta_m_send, buf->theta_g, buf->momentum, buf->delta_g,
-                               buf->delta_m_out, &kOne, &kOne, 1, &loop->hp, buf->R, buf->sel, buf->n_sel, nullptr))
-    return rc;
-  if (int rc = check_workspace(buf->workspace, buf->workspace_bytes, S, K, loop->n_total)) return rc;
-  if (int rc = sync_step_overlaps(K, loop->n_total, buf->theta_m, buf->theta_m_send, buf->theta_g, buf->momentum,
-                                  buf->delta_g, buf->delta_m_out, 1, buf->R, buf->sel, buf->n_sel, nullptr,
-                                  buf->workspace, buf->workspace_bytes))
-    return rc;
+  // Checked before anything is enqueued, so that a rejected step leaves the buffers and the
+  // schedule as they were.
+  if (int rc = loop_io_check(loop, io)) return rc;
   *n_received_out = 0;
   *sent_out = -1;
   hipStream_t s = static_cast<hipStream_t>(stream);
@@ -224,10 +296,7 @@ int cocodc_loop_step(cocodc_loop_t* loop, int64_t t, const cocodc_loop_buffers_t
   Plan pl;
   if (int rc = plan_segments(loop->segs.data(), S, K, loop->n_total, I_new.data(), tb_new.data(), &pl, mask.data()))
     return rc;
-  if (int rc = sync_step_impl(pl, K, loop->n_total, buf->theta_m, buf->theta_m_send, buf->theta_g, buf->momentum,
-                              buf->delta_g, nullptr, t, decide ? 1 : 0, &loop->hp, buf->R, buf->sel, buf->n_sel,
-                              nullptr, buf->workspace, buf->workspace_bytes, stream))
-    return rc;
+  if (int rc = loop_event(loop, pl, io, t, decide ? 1 : 0, stream)) return rc;
   loop->I_p.swap(I_new);
   loop->t_b.swap(tb_new);
   loop->in_flight.swap(fly_new);
@@ -245,21 +314,38 @@ int cocodc_loop_step(cocodc_loop_t* loop, int64_t t, const cocodc_loop_buffers_t
   for (int32_t p = 0; p < K; ++p) {
     if (loop->in_flight[p] < 0) widest = std::max<uint64_t>(widest, full.groups[p + 1].slot_begin - full.groups[p].slot_begin);
   }
-  WorkspaceView v = view(buf->workspace, full.S, K);
+  WorkspaceView v = view(io.workspace, full.S, K);
   if (int rc = upload_table(full, v, s)) return rc;
-  const bool vec = all_aligned16({buf->theta_g, buf->theta_m, buf->delta_m_out, buf->theta_m_send});
-  PseudoGradOp<true> op{buf->theta_g, buf->theta_m, buf->delta_m_out, buf->theta_m_send};
-  if (int rc = launch_walk_chosen(vec, full, v, buf->sel, widest, op, s)) return rc;
+  if (int rc = loop_send(loop, full, v, io, widest, s)) return rc;
   if (!loop->chosen_host)
     HIP_TRY(hipHostMalloc(reinterpret_cast<void**>(&loop->chosen_host), sizeof(int32_t), hipHostMallocDefault));
   if (!loop->chosen_ready) HIP_TRY(hipEventCreateWithFlags(&loop->chosen_ready, hipEventDisableTiming));
   *loop->chosen_host = -1;
-  HIP_TRY(hipMemcpyAsync(loop->chosen_host, buf->sel, sizeof(int32_t), hipMemcpyDeviceToHost, s));
+  HIP_TRY(hipMemcpyAsync(loop->chosen_host, io.sel, sizeof(int32_t), hipMemcpyDeviceToHost, s));
   HIP_TRY(hipEventRecord(loop->chosen_ready, s));
   loop->pending = true;
   loop->pending_t = t;
   *sent_out = COCODC_LOOP_SENT_PENDING;
   return COCODC_OK;
+}
+}  // namespace
+
+extern "C" {
+
+int cocodc_loop_step(cocodc_loop_t* loop, int64_t t, const cocodc_loop_buffers_t* buf, void* stream,
+                     int32_t* received_out, int32_t* n_received_out, int32_t* sent_out) {
+  if (!loop || !buf) return COCODC_ERR_NULL;
+  const LoopIO io{false,   buf->theta_m, buf->theta_m_send, buf->theta_g, buf->momentum,  buf->delta_g, buf->delta_m_out,
+                  buf->R,  buf->sel,     buf->n_sel,        buf->workspace, buf->workspace_bytes};
+  return loop_step_impl(loop, t, io, stream, received_out, n_received_out, sent_out);
+}
+
+int cocodc_loop_step_bf16(cocodc_loop_t* loop, int64_t t, const cocodc_loop_buffers_bf16_t* buf, void* stream,
+                          int32_t* received_out, int32_t* n_received_out, int32_t* sent_out) {
+  if (!loop || !buf) return COCODC_ERR_NULL;
+  const LoopIO io{true,    buf->theta_m, buf->theta_m_send, buf->theta_g, buf->momentum,  buf->delta_g, buf->delta_m_out,
+                  buf->R,  buf->sel,     buf->n_sel,        buf->workspace, buf->workspace_bytes};
+  return loop_step_impl(loop, t, io, stream, received_out, n_received_out, sent_out);
 }
 
 }  // extern "C"

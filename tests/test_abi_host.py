@@ -258,3 +258,73 @@ def test_loop_step_rejects_bad_buffers_before_any_device_work(B):
         assert step(t=3) == B.COCODC_ERR_RANGE and step(t=2) == B.COCODC_ERR_RANGE   # steps never go back
     finally:
         B.cocodc_loop_destroy(loop)
+
+
+def test_bf16_entry_points_reject_bad_arguments_before_any_device_work(B):
+    """Fake (never dereferenced) device addresses through the 16-bit fused step on segments, the 16-bit event
+    and the 16-bit loop step."""
+    n, K = 4096, 2
+    base = 0x30000000
+    tm, ts, tg, m, dg, pg = (base + i * 0x100000 for i in range(6))
+    R, sel, nsel, sums, ws = (base + 0x1000000 + i * 0x100000 for i in range(5))
+    frags = [(0, 2048), (2048, 2048)]
+    segs = [(0, 1000, 0), (1000, 1048, 1), (2048, 2048, 0)]
+    hp = B.hparams(5, 100, pg_format=B.COCODC_PG_F16)
+    I_p, t_b = [1, 1], [0, 0]
+    wss = B.cocodc_workspace_bytes_segmented(len(segs), K, n)
+
+    def seg(**kw):
+        a = dict(segs=segs, tm=tm, pg=pg, hp=hp, R=R, ws=ws, wsb=wss, I_p=I_p, budget=1)
+        a.update(kw)
+        return B.cocodc_sync_step_bf16_segmented(a["segs"], K, n, a["tm"], ts, tg, m, dg, a["pg"], a["I_p"], t_b, 10,
+                                                 a["budget"], a["hp"], a["R"], sel, nsel, sums, a["ws"], a["wsb"],
+                                                 stream=0)
+    assert seg(tm=None) == B.COCODC_ERR_NULL and seg(I_p=None) == B.COCODC_ERR_NULL and seg(hp=None) == B.COCODC_ERR_NULL
+    assert seg(tm=tm + 1) == B.COCODC_ERR_ALIGN and seg(R=R + 4) == B.COCODC_ERR_ALIGN
+    assert seg(segs=[(0, 1000, 0), (999, 10, 1)]) == B.COCODC_ERR_RANGE
+    assert seg(segs=[(0, 1000, 2)]) == B.COCODC_ERR_RANGE
+    assert seg(budget=-1) == B.COCODC_ERR_RANGE
+    assert seg(hp=B.hparams(5, 100, pg_format=2)) == B.COCODC_ERR_RANGE
+    assert seg(wsb=wss - 1) == B.COCODC_ERR_WORKSPACE
+    assert seg(pg=tm) == B.COCODC_ERR_ALIAS
+    assert seg(pg=dg) == B.COCODC_ERR_ALIAS          # a 16-bit pseudo-gradient cannot share the fp32 average's buffer
+    assert seg(ws=tm) == B.COCODC_ERR_ALIAS
+
+    wsb = B.cocodc_workspace_bytes(K, n)
+
+    def event(mask, **kw):
+        a = dict(tm=tm, R=R, ws=ws, wsb=wsb, frags=frags, pg=pg)
+        a.update(kw)
+        return B.cocodc_sync_event_bf16(a["frags"], n, mask, a["tm"], ts, tg, m, dg, a["pg"], I_p, t_b, 10, 1, hp,
+                                        a["R"], sel, nsel, sums, a["ws"], a["wsb"], stream=0)
+    assert event(None) == B.COCODC_ERR_NULL
+    assert event([1, 0], tm=None) == B.COCODC_ERR_NULL
+    assert event([1, 0], R=R + 4) == B.COCODC_ERR_ALIGN
+    assert event([4, 0]) == B.COCODC_ERR_RANGE
+    assert event([0, 0], frags=[(0, 2048), (2047, 2049)]) == B.COCODC_ERR_RANGE
+    assert event([1, 1], wsb=wsb - 1) == B.COCODC_ERR_WORKSPACE
+    assert event([1, 2], pg=ts) == B.COCODC_ERR_ALIAS
+
+    rc, loop = B.cocodc_loop_create(frags, n, B.hparams(2, 10), 1.0, 1.0, 5.0)
+    assert rc == 0
+    addr = dict(theta_m=tm, theta_m_send=ts, theta_g=tg, momentum=m, delta_g=dg, delta_m_out=pg, R=R, sel=sel,
+                n_sel=nsel, workspace=ws)
+
+    def step(t=5, wsb=wsb, **kw):
+        a = dict(addr)
+        a.update(kw)
+        buf = B.cocodc_loop_buffers_t(a["theta_m"], a["theta_m_send"], a["theta_g"], a["momentum"], a["delta_g"],
+                                      a["delta_m_out"], a["R"], a["sel"], a["n_sel"], a["workspace"], wsb)
+        return B.cocodc_loop_step_bf16(loop, t, buf, stream=0)[0]
+    try:
+        for name in addr:
+            assert step(**{name: None}) == B.COCODC_ERR_NULL, name
+        assert step(theta_m=tm + 1) == B.COCODC_ERR_ALIGN and step(theta_g=tg + 2) == B.COCODC_ERR_ALIGN
+        assert step(wsb=wsb - 1) == B.COCODC_ERR_WORKSPACE
+        assert step(delta_m_out=dg) == B.COCODC_ERR_ALIAS       # no in-place exchange buffer in 16 bits
+        assert step(theta_m_send=tm + 2 * n - 2) == B.COCODC_ERR_ALIAS
+        assert step(t=0) == B.COCODC_ERR_RANGE
+        assert B.cocodc_loop_state(loop) == (0, [0, 0], [0, 0], [-1, -1])
+        assert step(t=3) == 0 and step(t=3) == B.COCODC_ERR_RANGE
+    finally:
+        B.cocodc_loop_destroy(loop)
