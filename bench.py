@@ -287,6 +287,28 @@ def main():
                                     "speedup_over_sequence": round(seq_wall / fused_wall, 3)}}), flush=True)
         return
 
+    cpu = None
+    if not args.no_cpu and not args.bf16 and not args.loop_steps:  # the timed CPU oracle is the fp32 step
+        sample = 1 if K > 1 else 0
+        print(f"[bench] timing the CPU oracle on fragment {sample}", file=sys.stderr, flush=True)
+        cpu = cpu_baseline(wl, st, bk, sample)
+        print(f"[bench] cpu baseline {cpu}", file=sys.stderr, flush=True)
+
+    if args.bf16:
+        # same placement: each bf16 buffer occupies the first half of its fp32-sized slot
+        # converted in place, chunk by chunk in ascending order: a converted chunk always lies below
+        # the fp32 chunk it came from, so no source element is overwritten before it is read
+        for name in ("theta_m", "theta_m_send"):
+            src = st[name]
+            dst = src.view(torch.bfloat16)
+            for lo in range(0, n, 1 << 28):
+                hi = min(n, lo + (1 << 28))
+                dst[lo:hi].copy_(src[lo:hi].to(torch.bfloat16))  # dst[lo:hi] lies below src[lo:hi]: safe ascending
+            st[name] = dst[:n]
+        if pg is not None:
+            pg = pg.view(torch.bfloat16)[:n]
+        send = st["theta_m_send"] if mode == 0 else None
+
     if args.loop_steps:
         lens = [l for _, l in wl.frags]
         if args.strided_shards:   # the paper's partition: shard k = layers k, k + K, ... (Sec. 4.1)
@@ -303,15 +325,22 @@ def main():
             rc, loop = B.cocodc_loop_create(wl.frags, n, hp, 1.0, 1.0, float(wl.tau))  # T_s = tau * T_c
         B.check(rc)
         B.check(B.cocodc_loop_reset_scores(loop, R))
+        if args.bf16:   # the arriving average is fp32, the outgoing pseudo-gradient 16-bit: two buffers
+            assert pg is not None, "the bf16 loop needs the send buffer"
+            loop_step, send_buf = B.cocodc_loop_step_bf16, pg
+            rec_bytes, snd_bytes = 26, 10
+        else:           # one worker, closed loop: the pseudo-gradient is written over delta_g
+            loop_step, send_buf = B.cocodc_loop_step, st["delta_g"]
+            rec_bytes, snd_bytes = 32, 16
         lb = B.loop_buffers(st["theta_m"], st["theta_m_send"], st["theta_g"], st["momentum"], st["delta_g"],
-                            st["delta_g"], R, sel, n_sel, ws)
+                            send_buf, R, sel, n_sel, ws)
         _, N_plan, h_plan = B.cocodc_loop_plan(loop)
         ev, host_s = [], 0.0
         torch.cuda.synchronize()
         t_all = time.perf_counter()
         for t in range(1, args.loop_steps + 1):
             t0 = time.perf_counter()
-            rc, rec, sent = B.cocodc_loop_step(loop, t, lb)
+            rc, rec, sent = loop_step(loop, t, lb)
             B.check(rc)
             host_s += time.perf_counter() - t0   # the call itself never waits for the stream
             if rec or sent == B.COCODC_LOOP_SENT_PENDING:
@@ -333,33 +362,12 @@ def main():
                "loop_seconds": round(t_all, 4), "host_seconds_inside_loop_step": round(host_s, 4),
                "receive_Gparams_per_s": round(sum(p for _, p in only_rec) / max(sum(d for d, _ in only_rec), 1e-12) / 1e9, 2),
                "send_Gparams_per_s": round(sum(p for _, p in only_snd) / max(sum(d for d, _ in only_snd), 1e-12) / 1e9, 2),
-               "receive_bytes_per_param": 32, "send_bytes_per_param": 16,
-               "all_events_GBps": round(sum(32 * sum(lens[p] for p in rec) + (16 * lens[s] if s >= 0 else 0)
+               "dtype": "bf16 local parameters, fp32 global state" if args.bf16 else "f32",
+               "receive_bytes_per_param": rec_bytes, "send_bytes_per_param": snd_bytes,
+               "all_events_GBps": round(sum(rec_bytes * sum(lens[p] for p in rec) + (snd_bytes * lens[s] if s >= 0 else 0)
                                             for _, rec, s in ev) / max(sum(d for d, _, _ in ev), 1e-12) / 1e9, 1)}
         print(json.dumps(out), flush=True)
         return
-
-    cpu = None
-    if not args.no_cpu and not args.bf16:  # the timed CPU oracle is the fp32 step
-        sample = 1 if K > 1 else 0
-        print(f"[bench] timing the CPU oracle on fragment {sample}", file=sys.stderr, flush=True)
-        cpu = cpu_baseline(wl, st, bk, sample)
-        print(f"[bench] cpu baseline {cpu}", file=sys.stderr, flush=True)
-
-    if args.bf16:
-        # same placement: each bf16 buffer occupies the first half of its fp32-sized slot
-        # converted in place, chunk by chunk in ascending order: a converted chunk always lies below
-        # the fp32 chunk it came from, so no source element is overwritten before it is read
-        for name in ("theta_m", "theta_m_send"):
-            src = st[name]
-            dst = src.view(torch.bfloat16)
-            for lo in range(0, n, 1 << 28):
-                hi = min(n, lo + (1 << 28))
-                dst[lo:hi].copy_(src[lo:hi].to(torch.bfloat16))  # dst[lo:hi] lies below src[lo:hi]: safe ascending
-            st[name] = dst[:n]
-        if pg is not None:
-            pg = pg.view(torch.bfloat16)[:n]
-        send = st["theta_m_send"] if mode == 0 else None
 
     segs = None
     if args.strided_shards:
