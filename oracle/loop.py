@@ -5,8 +5,8 @@ One worker, inner steps t = 1, 2, ...; all buffers are host numpy arrays.  Per s
 worker's local update:
   1. every fragment whose all-reduce was launched tau (or more) steps ago completes: the fused
      oracle step on that fragment alone, with I_p = t_p - t_{p,b} (Eq. 11), taken as 1 when it
-     would be 0; then t_{p,b} <- t ("the step at which the previous synchronisation was
-     completed");
+     would be 0; then t_{p,b} <- t (Sec. 3.2 defines t_{p,b} as the step at which the
+     fragment's previous synchronisation completed);
   2. every h steps (Eq. 10; h = floor(H/N), at least 1, N from Eq. 9) the next fragment is
      chosen by Algorithm 2 with t_g = t among the fragments that are not in flight; its
      pseudo-gradient is written to the send buffer and its parameters are recorded.
