@@ -95,6 +95,59 @@ def cpu_baseline(wl, st, bk, sample_frag, repeats=2):
     }
 
 
+def placement_probe(B, torch, wl, dev):
+    """Times the fused step (algorithmic GB/s, best of 3 launches after one warm-up) for many placements of
+    the six buffers inside one allocation of 95 % of the free device memory.  Offsets are whole GiB from the
+    start of that allocation; the buffer order is theta_m, theta_m_send, theta_g, momentum, delta_g, pg."""
+    n, K, GiB = wl.n_total, wl.K, 1 << 30
+    nb = 4 * n
+    free, total = torch.cuda.mem_get_info(dev)
+    arena_gib = int(free * 0.95) // GiB
+    arena = torch.empty(arena_gib * GiB, dtype=torch.uint8, device=dev)
+    for off in range(0, arena.numel(), 8 * GiB):
+        arena[off:off + 8 * GiB].zero_()
+    ws = B.new_workspace(K, n, dev)
+    R = torch.zeros(K, dtype=torch.float64, device=dev)
+    sel = torch.zeros(K, dtype=torch.int32, device=dev)
+    n_sel = torch.zeros(1, dtype=torch.int32, device=dev)
+    hp, ones = B.hparams(5, 100), [1] * K
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    b = (nb + GiB - 1) // GiB          # a buffer, in whole GiB
+    top = arena_gib - b                # the last offset a buffer can start at
+
+    def gbps(bases_gib):
+        bases = sorted(int(o) * GiB for o in bases_gib)
+        assert bases[0] >= 0 and bases[-1] + nb <= arena.numel() and all(x + nb <= y for x, y in zip(bases, bases[1:]))
+        t = [arena[int(o) * GiB:int(o) * GiB + nb].view(torch.float32) for o in bases_gib]
+        best = float("inf")
+        for it in range(4):
+            e0.record()
+            B.check(B.cocodc_sync_step(wl.frags, n, t[0], t[1], t[2], t[3], t[4], t[5], ones, ones, 2, 1, hp, R, sel,
+                                       n_sel, None, ws))
+            e1.record()
+            torch.cuda.synchronize()
+            if it:
+                best = min(best, e0.elapsed_time(e1))
+        return round(36 * n / (best * 1e-3) / 1e9)
+
+    step = 8 if b <= 8 else 10
+    out = {"mode": "placement-probe", "workload": wl.name, "buffer_GiB": round(nb / GiB, 3),
+           "device_memory_GiB": round(total / GiB, 2), "allocation_GiB": arena_gib,
+           "unit": "algorithmic GB/s of the fused step; offsets in GiB from the start of the allocation"}
+    out["all_six_back_to_back_from_X"] = {X: gbps([X + k * b for k in range(6)])
+                                          for X in range(0, top - 5 * b + 1, step)}
+    print("[bench] back to back done", file=sys.stderr, flush=True)
+    out["five_back_to_back_from_0_and_pg_at_X"] = {X: gbps([0, b, 2 * b, 3 * b, 4 * b, X])
+                                                   for X in range(5 * b, top + 1, step)}
+    out["five_back_to_back_from_0_and_theta_m_at_X"] = {X: gbps([X, 0, b, 2 * b, 3 * b, 4 * b])
+                                                        for X in range(5 * b, top + 1, step)}
+    print("[bench] one buffer moved done", file=sys.stderr, flush=True)
+    out["theta_m_theta_g_delta_g_from_0_and_the_other_three_from_X"] = {
+        X: gbps([0, X, b, X + b, 2 * b, X + 2 * b]) for X in range(3 * b, top - 2 * b + 1, step)}
+    out["uniform_stride_S"] = {S: gbps([k * S for k in range(6)]) for S in range(b, top // 5 + 1, 4)}
+    print(json.dumps(out), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -133,6 +186,11 @@ def main():
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
                     help="instead of the benchmark, run 5 plain device copies of MIB mebibytes (a kernel "
                          "of known traffic, to scale rocprofv3 FETCH_SIZE / WRITE_SIZE readings) and exit")
+    ap.add_argument("--placement-probe", action="store_true",
+                    help="instead of the benchmark, time the fused step with the six buffers at many places of "
+                         "one allocation that covers nearly all of the device memory (all back to back from X; "
+                         "one buffer moved to X; two groups of three; uniform strides) and print one JSON line: "
+                         "shows which parts of the memory a working set must touch to run fast")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives are part of the path); "
@@ -159,6 +217,9 @@ def main():
         return
     wl = synth.WORKLOADS[args.workload]
     K, n = wl.K, wl.n_total
+    if args.placement_probe:
+        placement_probe(B, torch, wl, dev)
+        return
     print(f"[bench] workload {wl.name}: K={K} n={n} resident {5 * 4 * n / 1e9:.1f} GB", file=sys.stderr, flush=True)
     layout, arena, bufs, probe = args.layout, None, None, {}
     stride = B.cocodc_layout_stride_bytes(n) if args.stride_gib is None else int(args.stride_gib * (1 << 30))

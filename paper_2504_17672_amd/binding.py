@@ -254,7 +254,9 @@ def tuned_spaced_buffers(n_total, frags, device="cuda", count=6, max_arena_bytes
     """Like spaced_buffers, but picks the stride by measurement: the best of the candidate
     strides that fit into one allocation of at most max_arena_bytes (default: 92 % of the free
     device memory), each timed with a few launches of the fused step on zero-filled memory.
-    Which strides are fastest depends on where the allocation lands, so this is done once per
+    Which strides are fastest depends on where the allocation lands (a placement is fast when
+    the buffers do not all lie within the same 96 GiB third of the device memory, and a few
+    percent faster still when they are spread over all three), so this is done once per
     allocation, at set-up.  A caller whose hot call is not the fused step passes step(buffers),
     a function that enqueues that call (or sequence of calls) on the `count` candidate buffers;
     it is timed instead (the single steps prefer other strides than the fused step does).
