@@ -162,10 +162,12 @@ def main():
     ap.add_argument("--merge-mode", default="dc", choices=["dc", "blend", "replace"],
                     help="dc: delay compensation (Eq. 8, default); blend: Streaming-DiLoCo merge (Eq. 3, "
                          "alpha 0.5, no send-time record: 32 B/param); replace: blocking-DiLoCo merge")
-    ap.add_argument("--layout", default="tuned", choices=["tuned", "spaced", "packed"],
+    ap.add_argument("--layout", default="tuned", choices=["tuned", "spaced", "packed", "compact"],
                     help="tuned: the six buffers are carved out of one allocation at the stride that a "
                          "short probe at set-up finds fastest; spaced: fixed stride "
-                         "cocodc_layout_stride_bytes(); packed: six separate allocations")
+                         "cocodc_layout_stride_bytes(); packed: six separate allocations; compact: back to "
+                         "back in one allocation of their own size, the fastest of a few made after "
+                         "temporary ballast allocations of different sizes (layout.compact_fast_buffers)")
     ap.add_argument("--stride-gib", type=float, default=None, help="override the spaced-layout stride")
     ap.add_argument("--bf16", action="store_true",
                     help="bf16 local parameters, send-time record and pseudo-gradient, fp32 global state "
@@ -199,6 +201,7 @@ def main():
 
     import torch
     from paper_2504_17672_amd import binding as B
+    from paper_2504_17672_amd import layout as L
     from paper_2504_17672_amd import synth
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
@@ -226,10 +229,10 @@ def main():
     if layout in ("spaced", "tuned"):
         try:
             if layout == "tuned" and args.stride_gib is None:
-                arena, carved, stride, probe = B.tuned_spaced_buffers(
+                arena, carved, stride, probe = L.tuned_spaced_buffers(
                     n, wl.frags, dev, verbose=lambda m: print("[bench] layout probe:", m, file=sys.stderr, flush=True))
             else:
-                arena, carved = B.spaced_buffers(n, 6, dev, None if args.stride_gib is None else stride)
+                arena, carved = L.spaced_buffers(n, 6, dev, None if args.stride_gib is None else stride)
                 stride = carved[1].data_ptr() - carved[0].data_ptr()
             names = ("theta_m", "theta_m_send", "theta_g", "momentum", "delta_g", "pg")
             bufs = dict(zip(names, carved))
@@ -237,6 +240,11 @@ def main():
             print("[bench] not enough free HBM for the spaced layout; using separate allocations",
                   file=sys.stderr, flush=True)
             layout = "packed"
+    if layout == "compact":
+        arena, carved, probe_compact = L.compact_fast_buffers(
+            n, wl.frags, dev, verbose=lambda m: print("[bench] layout probe:", m, file=sys.stderr, flush=True))
+        stride = carved[1].data_ptr() - carved[0].data_ptr()
+        bufs = dict(zip(("theta_m", "theta_m_send", "theta_g", "momentum", "delta_g", "pg"), carved))
     st = synth.make_state(wl, dev, seed=0, buffers=bufs)
     bk = synth.bookkeeping(wl)
     if args.no_pg:
@@ -505,6 +513,8 @@ def main():
     if arena is not None:
         layout_detail.update(stride_GiB=round(stride / GiB, 2), arena_GiB=round(arena.numel() / GiB, 1),
                              used_span_GiB=round((5 * stride + nbytes) / GiB, 1))
+    if layout == "compact":
+        layout_detail["probe_GBps_by_ballast_GiB"] = {f"{g:g}": v for g, v in probe_compact.items()}
     if probe:
         gbps = {g: 36 * n / (ms * 1e-3) / 1e9 for g, ms in probe.items()}
         layout_detail["probe_GBps_by_stride_GiB"] = {f"{g:g}": round(v, 0) for g, v in sorted(gbps.items())}
@@ -513,7 +523,7 @@ def main():
         layout_detail["span_GiB_at_that_stride"] = round((5 * ok[0] * GiB + nbytes) / GiB, 1) if ok else None
     packed = None
     plain = (arena is not None and not args.graph and not args.bf16 and segs is None and mode == 0 and pg is not None)
-    if plain and not args.no_packed_pass:
+    if plain and not args.no_packed_pass and layout != "compact":   # (the compact layout is back to back itself)
         pstride = (nbytes + 255) // 256 * 256
         pviews = [arena[k * pstride:k * pstride + nbytes].view(torch.float32) for k in range(6)]
         pbufs = dict(zip(("theta_m", "theta_m_send", "theta_g", "momentum", "delta_g", "pg"), pviews))

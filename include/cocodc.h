@@ -458,7 +458,7 @@ int cocodc_loop_state(cocodc_loop_t* loop, int64_t* t_b_out, int64_t* I_p_out, i
  * also when the six lie back to back across the 96 GiB or the 192 GiB mark; 6.45-6.55 TB/s with
  * the bases 33-47 GiB apart, which spreads them over all three).  An allocation's place in the
  * device memory cannot be asked for, so a layout that matters is better probed than computed: see
- * tuned_spaced_buffers in the Python binding.  The gaps can hold any other data.  Returns
+ * tuned_spaced_buffers in the Python package's layout module.  The gaps can hold any other data.  Returns
  * max(40 GiB, buffer size rounded up to 1 GiB), moved off multiples of 32 GiB.  Purely
  * advisory: every entry point accepts any placement.  Host-only. */
 uint64_t cocodc_layout_stride_bytes(uint64_t n_total);

@@ -231,87 +231,6 @@ def cocodc_layout_stride_bytes(n_total):
     return int(_lib.cocodc_layout_stride_bytes(int(n_total)))
 
 
-def spaced_buffers(n_total, count, device="cuda", stride_bytes=None):
-    """`count` flat fp32 buffers of n_total elements carved out of one device allocation, their
-    bases cocodc_layout_stride_bytes(n_total) apart (less if the free device memory does not
-    allow it).  Returns (arena, [buffers]); keep the arena alive as long as the buffers are
-    used.  Memory between the buffers is free for other data."""
-    import torch
-    nbytes = 4 * int(n_total)
-    if stride_bytes is None:
-        GiB = 1 << 30
-        free, _ = torch.cuda.mem_get_info(device)
-        fit = (int(free * 0.92) - nbytes) // (count - 1) // GiB * GiB
-        stride = max(min(cocodc_layout_stride_bytes(n_total), fit), (nbytes + 255) // 256 * 256)
-    else:
-        stride = int(stride_bytes)
-    assert stride % 16 == 0 and stride >= nbytes
-    arena = torch.empty((count - 1) * stride + nbytes, dtype=torch.uint8, device=device)
-    return arena, [arena[k * stride:k * stride + nbytes].view(torch.float32) for k in range(count)]
-
-
-def tuned_spaced_buffers(n_total, frags, device="cuda", count=6, max_arena_bytes=None, verbose=None, step=None):
-    """Like spaced_buffers, but picks the stride by measurement: the best of the candidate
-    strides that fit into one allocation of at most max_arena_bytes (default: 92 % of the free
-    device memory), each timed with a few launches of the fused step on zero-filled memory.
-    Which strides are fastest depends on where the allocation lands (a placement is fast when
-    the buffers do not all lie within the same 96 GiB third of the device memory, and a few
-    percent faster still when they are spread over all three), so this is done once per
-    allocation, at set-up.  A caller whose hot call is not the fused step passes step(buffers),
-    a function that enqueues that call (or sequence of calls) on the `count` candidate buffers;
-    it is timed instead (the single steps prefer other strides than the fused step does).
-    Returns (arena, [buffers], stride_bytes, {stride_GiB: ms})."""
-    import torch
-    GiB = 1 << 30
-    nbytes = 4 * int(n_total)
-    if max_arena_bytes is None:
-        free, _ = torch.cuda.mem_get_info(device)
-        max_arena_bytes = int(free * 0.92)
-    back_to_back = (nbytes + GiB - 1) // GiB * GiB   # the smallest stride on the 1 GiB grid
-    lo = max(13 * GiB, back_to_back)
-    hi = (max_arena_bytes - nbytes) // (count - 1) // GiB * GiB
-    base = cocodc_layout_stride_bytes(n_total)
-    if hi < lo:
-        arena, bufs = spaced_buffers(n_total, count, device)
-        return arena, bufs, base, {}
-    # every 2 GiB from 13 GiB on (where the fast placements start), and below that every 1 GiB from
-    # back-to-back on, so that the probe also tells how small an arena still runs fast
-    cands = sorted(set(range(lo, hi + 1, 2 * GiB)) | set(range(back_to_back, lo, GiB)) |
-                   ({base} if lo <= base <= hi else set()))
-    arena = torch.empty((count - 1) * cands[-1] + nbytes, dtype=torch.uint8, device=device)
-    for off in range(0, arena.numel(), 8 * GiB):
-        arena[off:off + 8 * GiB].zero_()
-    K = len(frags)
-    ws = new_workspace(K, n_total, device)
-    R = torch.zeros(K, dtype=torch.float64, device=device)
-    sel = torch.zeros(K, dtype=torch.int32, device=device)
-    n_sel = torch.zeros(1, dtype=torch.int32, device=device)
-    hp = hparams(5, 100)
-    ones = [1] * K
-    timings = {}
-    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    for stride in cands:
-        b = [arena[k * stride:k * stride + nbytes].view(torch.float32) for k in range(count)]
-        best = float("inf")
-        for it in range(4):
-            start.record()
-            if step is not None:
-                step(b)
-            else:
-                check(cocodc_sync_step(frags, n_total, b[0], b[1], b[2], b[3], b[4], b[5] if count > 5 else None,
-                                       ones, ones, 2, 1, hp, R, sel, n_sel, None, ws))
-            stop.record()
-            torch.cuda.synchronize()
-            if it:
-                best = min(best, start.elapsed_time(stop))
-        timings[stride / GiB] = best
-        if verbose:
-            verbose(f"stride {stride / GiB:.0f} GiB: {best:.3f} ms")
-    stride = int(min(timings, key=timings.get) * GiB)
-    bufs = [arena[k * stride:k * stride + nbytes].view(torch.float32) for k in range(count)]
-    return arena, bufs, stride, timings
-
-
 def cocodc_pseudograd(frags, n_total, theta_g_snap, theta_m, delta_m_out, theta_m_send_out, workspace,
                       workspace_bytes=None, stream=None, K=None):
     fa, k = _frags(frags)

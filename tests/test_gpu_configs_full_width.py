@@ -19,6 +19,7 @@ import numpy as np
 import pytest
 import torch
 
+from paper_2504_17672_amd import layout as L
 from paper_2504_17672_amd import synth
 
 import parity_util as U
@@ -51,7 +52,7 @@ def _bench_layout(B, wl, arena_fraction=0.8):
     """The six buffers as bench.py places them (one allocation, stride found by its set-up probe)."""
     torch.cuda.empty_cache()
     free, _ = torch.cuda.mem_get_info()
-    arena, carved, stride, _ = B.tuned_spaced_buffers(wl.n_total, wl.frags, "cuda",
+    arena, carved, stride, _ = L.tuned_spaced_buffers(wl.n_total, wl.frags, "cuda",
                                                       max_arena_bytes=int(free * arena_fraction))
     names = NAMES + ("pg",)
     return arena, dict(zip(names, carved)), stride
