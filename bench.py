@@ -148,6 +148,74 @@ def placement_probe(B, torch, wl, dev):
     print(json.dumps(out), flush=True)
 
 
+def region_probe(B, torch, wl, dev):
+    """Times every entry point that streams several buffers with each of its buffers in each third of the
+    device memory (all 3^k assignments; for the fused step theta_m stays in the first third, the thirds being
+    interchangeable), inside one allocation of 95 % of the free memory made first in the process.  Offsets
+    assume that this allocation maps onto the memory from the bottom up (bench.py --placement-probe shows the
+    steps where that predicts them).  Prints one JSON line: algorithmic GB/s per assignment, best first."""
+    import itertools
+    n, K, GiB = wl.n_total, wl.K, 1 << 30
+    nb = 4 * n
+    free, total = torch.cuda.mem_get_info(dev)
+    start = total - free
+    arena = torch.empty(int(free * 0.95) // GiB * GiB, dtype=torch.uint8, device=dev)
+    for off in range(0, arena.numel(), 8 * GiB):
+        arena[off:off + 8 * GiB].zero_()
+    ws = B.new_workspace(K, n, dev)
+    R = torch.zeros(K, dtype=torch.float64, device=dev)
+    sel = torch.zeros(K, dtype=torch.int32, device=dev)
+    n_sel = torch.zeros(1, dtype=torch.int32, device=dev)
+    hp, ones, fr = B.hparams(5, 100), [1] * K, wl.frags
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    slot = (nb + GiB - 1) // GiB * GiB + GiB
+
+    def buf(region, k):
+        o = max(region * (96 << 30) - start, 0) + 2 * GiB + k * slot
+        assert o + nb <= min((region + 1) * (96 << 30) - start, arena.numel())
+        return arena[o:o + nb].view(torch.float32)
+
+    def gbps(call, bpp, assign):
+        bufs = [buf(r, sum(1 for j in range(i) if assign[j] == r)) for i, r in enumerate(assign)]
+        best = float("inf")
+        for it in range(4):
+            e0.record()
+            B.check(call(bufs))
+            e1.record()
+            torch.cuda.synchronize()
+            if it:
+                best = min(best, e0.elapsed_time(e1))
+        return round(bpp * n / (best * 1e-3) / 1e9)
+
+    entries = [
+        ("cocodc_pseudograd + send-time record", "reads theta_g, theta_m; writes pg, theta_m_send", 16, 4, False,
+         lambda b: B.cocodc_pseudograd(fr, n, b[0], b[1], b[2], b[3], ws)),
+        ("cocodc_pseudograd", "reads theta_g, theta_m; writes pg", 12, 3, False,
+         lambda b: B.cocodc_pseudograd(fr, n, b[0], b[1], b[2], None, ws)),
+        ("cocodc_outer_nesterov", "theta_g in place, momentum in place, reads delta_g", 20, 3, False,
+         lambda b: B.cocodc_outer_nesterov(fr, n, b[0], b[1], b[2], hp, ws)),
+        ("cocodc_delay_compensate", "theta_m in place, reads theta_m_send, theta_g", 16, 3, False,
+         lambda b: B.cocodc_delay_compensate(fr, n, b[0], b[1], b[2], hp, ws)),
+        ("cocodc_sync_step", "theta_m in place, reads theta_m_send, theta_g in place, momentum in place, reads "
+         "delta_g, writes pg", 36, 6, True,
+         lambda b: B.cocodc_sync_step(fr, n, b[0], b[1], b[2], b[3], b[4], b[5], ones, ones, 2, 1, hp, R, sel, n_sel,
+                                      None, ws)),
+    ]
+    out = {"mode": "region-probe", "workload": wl.name, "buffer_GiB": round(nb / GiB, 3),
+           "unit": "algorithmic GB/s; an assignment lists the third (0, 1, 2) of the device memory of each buffer in "
+                   "the order given", "entries": []}
+    for name, order, bpp, k, first_fixed, call in entries:
+        rows = []
+        for assign in itertools.product(range(3), repeat=k):
+            if first_fixed and assign[0] != 0:
+                continue
+            rows.append([gbps(call, bpp, assign), "".join(map(str, assign))])
+        rows.sort(reverse=True)
+        out["entries"].append({"entry": name, "buffers": order, "bytes_per_param": bpp, "by_assignment": rows})
+        print(f"[bench] {name} done", file=sys.stderr, flush=True)
+    print(json.dumps(out), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -162,12 +230,17 @@ def main():
     ap.add_argument("--merge-mode", default="dc", choices=["dc", "blend", "replace"],
                     help="dc: delay compensation (Eq. 8, default); blend: Streaming-DiLoCo merge (Eq. 3, "
                          "alpha 0.5, no send-time record: 32 B/param); replace: blocking-DiLoCo merge")
-    ap.add_argument("--layout", default="tuned", choices=["tuned", "spaced", "packed", "compact"],
+    ap.add_argument("--layout", default="tuned", choices=["tuned", "spaced", "packed", "compact", "regions"],
                     help="tuned: the six buffers are carved out of one allocation at the stride that a "
                          "short probe at set-up finds fastest; spaced: fixed stride "
                          "cocodc_layout_stride_bytes(); packed: six separate allocations; compact: back to "
                          "back in one allocation of their own size, the fastest of a few made after "
-                         "temporary ballast allocations of different sizes (layout.compact_fast_buffers)")
+                         "temporary ballast allocations of different sizes (layout.compact_fast_buffers); "
+                         "regions: each buffer in a chosen third of the device memory (--regions; "
+                         "layout.region_buffers)")
+    ap.add_argument("--regions", default="0,0,0,1,1,2",
+                    help="with --layout regions: the third (0, 1, 2) of the device memory for theta_m, "
+                         "theta_m_send, theta_g, momentum, delta_g and the pseudo-gradient buffer")
     ap.add_argument("--stride-gib", type=float, default=None, help="override the spaced-layout stride")
     ap.add_argument("--bf16", action="store_true",
                     help="bf16 local parameters, send-time record and pseudo-gradient, fp32 global state "
@@ -193,6 +266,9 @@ def main():
                          "one allocation that covers nearly all of the device memory (all back to back from X; "
                          "one buffer moved to X; two groups of three; uniform strides) and print one JSON line: "
                          "shows which parts of the memory a working set must touch to run fast")
+    ap.add_argument("--region-probe", action="store_true",
+                    help="instead of the benchmark, time the single-step entry points and the fused step with each "
+                         "of their buffers in each third of the device memory and print one JSON line")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives are part of the path); "
@@ -223,6 +299,9 @@ def main():
     if args.placement_probe:
         placement_probe(B, torch, wl, dev)
         return
+    if args.region_probe:
+        region_probe(B, torch, wl, dev)
+        return
     print(f"[bench] workload {wl.name}: K={K} n={n} resident {5 * 4 * n / 1e9:.1f} GB", file=sys.stderr, flush=True)
     layout, arena, bufs, probe = args.layout, None, None, {}
     stride = B.cocodc_layout_stride_bytes(n) if args.stride_gib is None else int(args.stride_gib * (1 << 30))
@@ -240,6 +319,12 @@ def main():
             print("[bench] not enough free HBM for the spaced layout; using separate allocations",
                   file=sys.stderr, flush=True)
             layout = "packed"
+    if layout == "regions":
+        regions = tuple(int(x) for x in args.regions.split(","))
+        assert len(regions) == 6 and all(0 <= r <= 2 for r in regions)
+        arena, carved, offs = L.region_buffers(n, regions, dev)
+        stride = 0
+        bufs = dict(zip(("theta_m", "theta_m_send", "theta_g", "momentum", "delta_g", "pg"), carved))
     if layout == "compact":
         arena, carved, probe_compact = L.compact_fast_buffers(
             n, wl.frags, dev, verbose=lambda m: print("[bench] layout probe:", m, file=sys.stderr, flush=True))
@@ -342,7 +427,8 @@ def main():
             bk.t_b, bk.t_g, wl.budget, hp, R, sel, n_sel, None, ws)))
         assert bool(torch.isfinite(th["theta_m"][:1 << 20]).all().item())
         print(json.dumps({"mode": "primitives", "workload": wl.name, "params": n, "steps": args.steps,
-                          "layout": layout, "stride_GiB": round(stride / (1 << 30), 2), "entries": rows,
+                          "layout": layout + (" " + args.regions if layout == "regions" else ""),
+                          "stride_GiB": round(stride / (1 << 30), 2), "entries": rows,
                           "select_ms_per_call": round(sel_ms, 4), "torch_references": ref_rows,
                           "five_calls_in_sequence": {"bytes_per_param": 52, "ms": round(seq_wall, 4),
                                                      "Gparams_per_s": round(n / seq_wall / 1e6, 2)},
@@ -510,7 +596,10 @@ def main():
     GiB = 1 << 30
     nbytes = 4 * n
     layout_detail = {"kind": layout}
-    if arena is not None:
+    if layout == "regions":
+        layout_detail.update(regions=list(regions), offsets_GiB=[round(o / GiB, 2) for o in offs],
+                             arena_GiB=round(arena.numel() / GiB, 1))
+    elif arena is not None:
         layout_detail.update(stride_GiB=round(stride / GiB, 2), arena_GiB=round(arena.numel() / GiB, 1),
                              used_span_GiB=round((5 * stride + nbytes) / GiB, 1))
     if layout == "compact":
@@ -523,7 +612,7 @@ def main():
         layout_detail["span_GiB_at_that_stride"] = round((5 * ok[0] * GiB + nbytes) / GiB, 1) if ok else None
     packed = None
     plain = (arena is not None and not args.graph and not args.bf16 and segs is None and mode == 0 and pg is not None)
-    if plain and not args.no_packed_pass and layout != "compact":   # (the compact layout is back to back itself)
+    if plain and not args.no_packed_pass and layout not in ("compact", "regions"):   # (compact is back to back itself)
         pstride = (nbytes + 255) // 256 * 256
         pviews = [arena[k * pstride:k * pstride + nbytes].view(torch.float32) for k in range(6)]
         pbufs = dict(zip(("theta_m", "theta_m_send", "theta_g", "momentum", "delta_g", "pg"), pviews))
@@ -572,8 +661,10 @@ def main():
                    "launch": "hip graph replay" if args.graph else "eager",
                    "fragments": (f"{args.strided_shards} strided shards of {len(segs)} segments" if segs
                                  else "contiguous"),
-                   "layout": (f"{layout}: one allocation, buffer bases {stride / (1 << 30):.2f} GiB apart"
-                              if layout != "packed" else "packed: separate allocations"),
+                   "layout": ("packed: separate allocations" if layout == "packed" else
+                              f"regions: one allocation, the buffers in thirds {args.regions} of the device memory"
+                              if layout == "regions" else
+                              f"{layout}: one allocation, buffer bases {stride / (1 << 30):.2f} GiB apart"),
                    "layout_detail": layout_detail,
                    "selected": selected},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",

@@ -146,3 +146,41 @@ def tuned_spaced_buffers(n_total, frags, device="cuda", count=6, max_arena_bytes
     stride = int(min(timings, key=timings.get) * GiB)
     bufs = [arena[k * stride:k * stride + nbytes].view(torch.float32) for k in range(count)]
     return arena, bufs, stride, timings
+
+
+# Region (third of the device memory) of theta_m, theta_m_send, theta_g, momentum, delta_g and the
+# pseudo-gradient buffer that served every entry point well in the enumeration of all assignments
+# (bench.py --region-probe): the written buffers are not all in one region, the buffers that the
+# send step reads (theta_g, theta_m) share one and the ones it writes lie elsewhere.
+DEFAULT_REGIONS = (0, 0, 0, 1, 1, 2)
+REGION_BYTES = 96 << 30
+
+
+def region_buffers(n_total, regions=DEFAULT_REGIONS, device="cuda", arena_fraction=0.95):
+    """len(regions) flat fp32 buffers of n_total elements, buffer i inside the regions[i]-th third
+    (96 GiB) of the device memory: one allocation of arena_fraction of the free memory is made and
+    the buffers are carved out of it at offsets that fall into the wanted thirds IF the allocation
+    maps onto the device memory from its bottom upwards in one piece.  That held for an allocation
+    of 95 % of the memory made first in a fresh process (the speed steps of bench.py
+    --placement-probe sit at the same offsets in every run), and nothing guarantees it: treat the
+    result as a candidate placement and time it.  The rest of the allocation is free for the
+    caller's other data.  Returns (arena, [buffers], [offsets in bytes])."""
+    import torch
+    GiB = 1 << 30
+    nbytes = (4 * int(n_total) + 255) // 256 * 256
+    free, total = torch.cuda.mem_get_info(device)
+    start = total - free                           # where the allocation begins if memory is handed out bottom-up
+    arena_bytes = int(free * arena_fraction) // GiB * GiB
+    slot = (nbytes + GiB - 1) // GiB * GiB + GiB   # buffers of one region lie a whole GiB apart
+    offsets, used = [], {}
+    for r in regions:
+        k = used.get(r, 0)
+        used[r] = k + 1
+        lo = max(r * REGION_BYTES - start, 0) + 2 * GiB   # 2 GiB clear of the region's lower end
+        off = (lo + k * slot) // 256 * 256
+        if off + nbytes > min((r + 1) * REGION_BYTES - start, arena_bytes):
+            raise ValueError(f"region {r} cannot hold {used[r]} buffers of {nbytes / GiB:.1f} GiB")
+        offsets.append(off)
+    arena = torch.empty(arena_bytes, dtype=torch.uint8, device=device)
+    bufs = [arena[o:o + 4 * int(n_total)].view(torch.float32) for o in offsets]
+    return arena, bufs, offsets
