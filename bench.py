@@ -57,8 +57,10 @@ def profiled_traffic(workload, bf16):
     return int(m_traffic.group(1)), f"profiles/{name}"
 
 
-def cpu_baseline(wl, st, bk, sample_frag, repeats=2):
-    """Times the oracle (as it stands) on one fragment of the workload, on the host cores."""
+def cpu_baseline(wl, st, bk, sample_frag, seconds_per_leg=6.0):
+    """Times the oracle (as it stands) on one fragment of the workload, on the host cores: first on one
+    thread, then chunk-parallel on all of them, each leg repeated for about seconds_per_leg (at least three
+    runs); the best run of a leg counts, the median is reported beside it."""
     import numpy as np
     import oracle as ref
     off, ln = wl.frags[sample_frag]
@@ -69,8 +71,8 @@ def cpu_baseline(wl, st, bk, sample_frag, repeats=2):
     pg = np.empty(ln, np.float32)
 
     def run(n_threads):
-        best, used = float("inf"), 1
-        for _ in range(repeats):
+        times, used, spent = [], 1, 0.0
+        while len(times) < 3 or (spent < seconds_per_leg and len(times) < 200):
             h = {k: v.copy() for k, v in host0.items()}
             t0 = time.perf_counter()
             out = ref.sync_step(frags, h["theta_m"], h["theta_m_send"], h["theta_g"], h["momentum"],
@@ -78,18 +80,21 @@ def cpu_baseline(wl, st, bk, sample_frag, repeats=2):
             dt = time.perf_counter() - t0
             assert out["rc"] == 0
             used = out.get("threads", 1)
-            best = min(best, dt)
-        return best, used
+            times.append(dt)
+            spent += dt
+        times.sort()
+        return times[0], times[len(times) // 2], len(times), used
 
-    t1, _ = run(None)
+    t1, t1_med, n1, _ = run(None)
     avail = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else (os.cpu_count() or 1)
     env = os.environ.get("OMP_NUM_THREADS")
     want = min(avail, int(env)) if env and env.isdigit() else avail
-    tm, used = run(max(1, want))
+    tm, tm_med, nm, used = run(max(1, want))
     return {
         "value": round(ln / tm / 1e9, 4), "unit": "Gparams/s", "cores": int(used), "kind": "oracle",
         "sample": f"fragment {sample_frag} of {wl.name} ({ln} params), fused oracle step, "
-                  f"chunk-parallel over {used} threads, best of {repeats}",
+                  f"chunk-parallel over {used} threads, best of {nm} runs (median {ln / tm_med / 1e9:.3f}); "
+                  f"single thread: best of {n1} runs (median {ln / t1_med / 1e9:.3f})",
         "single_thread_value": round(ln / t1 / 1e9, 4),
         "host_cpus_visible": avail,
     }
