@@ -452,9 +452,9 @@ int cocodc_loop_state(cocodc_loop_t* loop, int64_t* t_b_out, int64_t* I_p_out, i
 /* Recommended distance in bytes between the base addresses of the flat buffers that one
  * call streams through together (theta_m, theta_m_send, theta_g, momentum, delta_g,
  * delta_m_out), for buffers of n_total fp32 elements carved out of ONE device allocation.
- * On MI355X the fused pass runs up to 18 % faster when the concurrently streamed buffers do not
- * all lie within the same third of the device memory (measured: 5.5-5.7 TB/s with all six
- * inside one 96 GiB third, wherever; 6.2-6.5 TB/s as soon as one of them lies in another third,
+ * On MI355X the fused pass runs up to 18 % faster when the buffers it writes do not all lie
+ * within the same third of the device memory (measured: 5.5-5.7 TB/s with all six buffers
+ * inside one 96 GiB third, wherever; 6.2-6.5 TB/s as soon as a written one lies in another third,
  * also when the six lie back to back across the 96 GiB or the 192 GiB mark; 6.45-6.55 TB/s with
  * the bases 33-47 GiB apart, which spreads them over all three).  An allocation's place in the
  * device memory cannot be asked for, so a layout that matters is better probed than computed: see

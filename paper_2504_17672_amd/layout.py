@@ -1,7 +1,8 @@
 """Where the flat buffers are put in the device memory (no paper counterpart; advisory: every entry point
 of the library accepts any placement).  On MI355X the fused step runs up to 18 % faster when the buffers it
-streams together do not all lie within the same 96 GiB third of the device memory, and a few percent faster
-still when they are spread over all three.  Which physical memory an allocation gets cannot be asked for, so
+writes do not all lie within the same 96 GiB third of the device memory (the single steps likewise: written
+buffers in different thirds, buffers that are only read together), and a few percent faster still when the
+buffers are spread over all three.  Which physical memory an allocation gets cannot be asked for, so
 the helpers here place by measurement: they time a few launches of the fused step on candidate placements at
 set-up and keep the fastest.  They use torch for the allocations and the timing events, nothing else."""
 from .binding import (check, cocodc_layout_stride_bytes, cocodc_sync_step, hparams, new_workspace)
