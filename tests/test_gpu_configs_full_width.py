@@ -148,6 +148,87 @@ def test_7b_every_element_of_all_fragments(B, ref):
           f"wall {time.perf_counter() - t0:.1f} s", flush=True)
 
 
+def test_7b_bf16_every_element_of_all_fragments(B, ref):
+    """The bf16 variant at the width and in the placement bench.py --bf16 times: bf16 local parameters and
+    send-time record converted in place in the tuned layout, one fused call over all 32 fragments, then every
+    fragment through the oracle's bf16 step; every stored value (bf16 and fp32) bit-identical."""
+    t0 = time.perf_counter()
+    wl = synth.WORKLOADS["7B"]
+    n, K = wl.n_total, wl.K
+    arena, bufs, stride = _bench_layout(B, wl)
+    print(f"case 7B bf16 full width K={K} n={n} layout=tuned stride={stride / 2**30:.0f} GiB", flush=True)
+    record = {}
+    st = synth.make_state(wl, "cuda", seed=0, buffers=bufs, record=record)
+    for name in ("theta_m", "theta_m_send"):       # each bf16 buffer takes the first half of its fp32 slot
+        src = st[name]
+        dst = src.view(torch.bfloat16)
+        for lo in range(0, n, 1 << 28):
+            hi = min(n, lo + (1 << 28))
+            dst[lo:hi].copy_(src[lo:hi].to(torch.bfloat16))   # the target lies below its source: safe in ascending order
+        st[name] = dst[:n]
+    pg = bufs["pg"].view(torch.bfloat16)[:n]
+    pg.fill_(555.0)
+    bk = synth.bookkeeping(wl)
+    ghp, rhp = B.hparams(wl.tau, wl.H, wl.lam, wl.eta, wl.mu), ref.hparams(wl.tau, wl.H, wl.lam, wl.eta, wl.mu)
+    i16 = lambda t: t.view(torch.int16)  # noqa: E731
+    before = {"theta_m_send": i16(st["theta_m_send"]).sum(dtype=torch.int64).item(), "delta_g": _checksum(st["delta_g"])}
+    out = U.gpu_outputs(K)
+    ws = B.new_workspace(K, n)
+    rc = B.cocodc_sync_step_bf16(wl.frags, n, st["theta_m"], st["theta_m_send"], st["theta_g"], st["momentum"],
+                                 st["delta_g"], pg, bk.I_p, bk.t_b, bk.t_g, wl.budget, ghp, out["R"], out["sel"],
+                                 out["n_sel"], out["sums"], ws)
+    assert rc == 0, B.cocodc_status_string(rc)
+    torch.cuda.synchronize()
+    assert i16(st["theta_m_send"]).sum(dtype=torch.int64).item() == before["theta_m_send"]
+    assert _checksum(st["delta_g"]) == before["delta_g"]
+    m = max(wl.frag_lengths)
+    h32 = {k: U.pinned(m) for k in ("theta_g", "momentum", "delta_g")}
+    h16 = {k: U.pinned(m, torch.int16) for k in ("theta_m", "theta_m_send", "pg")}
+    d32 = torch.empty(m, dtype=torch.float32, device="cuda")
+    d16 = torch.empty(m, dtype=torch.int16, device="cuda")
+    scratch = torch.empty(1 << 28, dtype=torch.float32, device="cuda")
+    R_ref, sums_ref = np.zeros(K), np.zeros((K, 4))
+    from concurrent.futures import ThreadPoolExecutor
+    threads = _threads()
+    pool = ThreadPoolExecutor(max_workers=threads)
+    for p, (off, ln) in enumerate(wl.frags):
+        h16["theta_m"][:ln].copy_(i16(synth.original_slice(record, "theta_m", off, off + ln, "cuda", scratch)
+                                      .to(torch.bfloat16)))
+        h16["theta_m_send"][:ln].copy_(i16(st["theta_m_send"][off:off + ln]))
+        for k in ("theta_g", "momentum"):
+            h32[k][:ln].copy_(synth.original_slice(record, k, off, off + ln, "cuda", scratch))
+        h32["delta_g"][:ln].copy_(st["delta_g"][off:off + ln])
+        torch.cuda.synchronize()
+        u16 = {k: v[:ln].numpy().view(np.uint16) for k, v in h16.items()}
+        f32 = {k: v[:ln].numpy() for k, v in h32.items()}
+        # the oracle's bf16 step has no threaded form: the fragment is cut into pieces that run side by side on
+        # the same host arrays (element-wise work on disjoint ranges), and the pieces' raw sums are added in order
+        cuts = np.linspace(0, ln, threads + 1).astype(np.int64)
+        pieces = [(int(a), int(b - a)) for a, b in zip(cuts[:-1], cuts[1:])]
+
+        def piece(fr):
+            return ref.sync_step_bf16([fr], u16["theta_m"], u16["theta_m_send"], f32["theta_g"], f32["momentum"],
+                                      f32["delta_g"], u16["pg"], [1], [bk.t_b[p]], bk.t_g, 0, rhp)
+        outs = list(pool.map(piece, pieces))
+        assert all(o["rc"] == 0 for o in outs)
+        sums_ref[p] = np.sum([o["sums"][0] for o in outs], axis=0)
+        R_ref[p] = np.sqrt(sums_ref[p][0]) / bk.I_p[p] if bk.I_p[p] > 0 else np.inf
+        for k, g in (("theta_m", st["theta_m"]), ("pg", pg)):
+            d16[:ln].copy_(h16[k][:ln])
+            assert torch.equal(i16(g[off:off + ln]), d16[:ln]), (p, k)
+        for k in ("theta_g", "momentum"):
+            if not U.bits_equal(st[k][off:off + ln], h32[k], d32):
+                raise AssertionError((p, k, U.mismatch_report(st[k][off:off + ln], h32[k], d32)))
+    pool.shutdown()
+    e_R, e_S = _compare_scores(out["R"].cpu().numpy(), out["sums"].cpu().numpy(), R_ref, sums_ref)
+    rc, want = ref.select_fragments(R_ref, bk.t_b, bk.t_g, wl.H, wl.budget)
+    assert rc == 0
+    go = dict(R=out["R"], sel_list=out["sel"][:int(out["n_sel"].item())].cpu().tolist())
+    margin = U.compare_selection(go, dict(R=R_ref, sel=want), bk, wl.H, frag_lengths=wl.frag_lengths)
+    print(f"   all {K} fragments bit-identical to the oracle's bf16 step; scores {e_R:.2e}, sums {e_S:.2e}, "
+          f"margin {margin}; selected {go['sel_list']}; wall {time.perf_counter() - t0:.1f} s", flush=True)
+
+
 # ------------------------------------------------------------------ config 3: 350M, lambda sweep
 def test_350m_lambda_sweep_and_amplified_variant_at_full_width(B, ref):
     t0 = time.perf_counter()
