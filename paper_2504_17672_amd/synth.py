@@ -78,7 +78,7 @@ def _scaled(name, n_layers, d, ffn, lpf, **kw) -> Workload:
 
 def strided_segments(n_layers: int, d: int, ffn: int, n_shards: int):
     """The strided sharding of the paper's experiments (Sec. 4.1: 12 layers, 4 shards of about 3
-    layers each, "strided pattern") on a layer-ordered flat buffer
+    layers each, taken with a stride) on a layer-ordered flat buffer
     [embedding + final norm | layer 0 | layer 1 | ...]: shard k owns layers k, k + n_shards, ...;
     the embedding block goes with shard 0.  Returns [(offset, length, fragment), ...] in buffer
     order and the total number of elements."""

@@ -148,6 +148,57 @@ def test_7b_every_element_of_all_fragments(B, ref):
           f"wall {time.perf_counter() - t0:.1f} s", flush=True)
 
 
+def test_7b_in_eight_strided_shards_every_element(B, ref):
+    """bench.py --strided-shards 8 at full width: the 7B set's layers in 8 strided shards (Sec. 4.1: shard k =
+    layers k, k + 8, ...) on the layer-ordered buffers, one segmented fused call, every segment through the
+    oracle; a shard's raw sums are its segments' sums added in the order listed."""
+    t0 = time.perf_counter()
+    wl = synth.WORKLOADS["7B"]
+    n, Ks = wl.n_total, 8
+    segs, n_seg = synth.strided_segments(*wl.model, Ks)
+    assert n_seg == n
+    arena, bufs, stride = _bench_layout(B, wl)
+    print(f"case 7B strided full width K={Ks} S={len(segs)} n={n} stride={stride / 2**30:.0f} GiB", flush=True)
+    record = {}
+    st = synth.make_state(wl, "cuda", seed=0, buffers=bufs, record=record)
+    pg = bufs["pg"]
+    pg.fill_(555.0)
+    h = max(1, wl.H // Ks)
+    I_p = [h * (1 + p % 3) for p in range(Ks)]
+    t_g = 10 * wl.H
+    t_b = [t_g - i for i in I_p]
+    ghp, rhp = B.hparams(wl.tau, wl.H, wl.lam, wl.eta, wl.mu), ref.hparams(wl.tau, wl.H, wl.lam, wl.eta, wl.mu)
+    out = U.gpu_outputs(Ks)
+    ws = B.new_workspace_segmented(len(segs), Ks, n)
+    rc = B.cocodc_sync_step_segmented(segs, Ks, n, st["theta_m"], st["theta_m_send"], st["theta_g"], st["momentum"],
+                                      st["delta_g"], pg, I_p, t_b, t_g, 2, ghp, out["R"], out["sel"], out["n_sel"],
+                                      out["sums"], ws)
+    assert rc == 0, B.cocodc_status_string(rc)
+    torch.cuda.synchronize()
+    checker = FragmentChecker(ref, max(l for _, l, _ in segs))
+    scratch = torch.empty(1 << 28, dtype=torch.float32, device="cuda")
+    sums_ref = np.zeros((Ks, 4))
+    covered = 0
+    for j, (off, ln, p) in enumerate(segs):
+        inputs = {k: synth.original_slice(record, k, off, off + ln, "cuda", scratch) for k in IN_PLACE}
+        inputs["theta_m_send"] = st["theta_m_send"][off:off + ln]
+        inputs["delta_g"] = st["delta_g"][off:off + ln]
+        after = {k: st[k][off:off + ln] for k in IN_PLACE}
+        _, sums = checker.check(ln, inputs, after, pg[off:off + ln], 1, t_b[p], t_g, rhp, f"7B strided segment {j}")
+        sums_ref[p] += sums
+        covered += ln
+    assert covered == n
+    R_ref = np.sqrt(sums_ref[:, 0]) / np.array(I_p, dtype=np.float64)
+    e_R, e_S = _compare_scores(out["R"].cpu().numpy(), out["sums"].cpu().numpy(), R_ref, sums_ref)
+    rc, want = ref.select_fragments(R_ref, t_b, t_g, wl.H, 2)
+    assert rc == 0
+    go = dict(R=out["R"], sel_list=out["sel"][:int(out["n_sel"].item())].cpu().tolist())
+    bk = synth.Bookkeeping(t_g=t_g, t_b=t_b, I_p=I_p)
+    margin = U.compare_selection(go, dict(R=R_ref, sel=want), bk, wl.H)
+    print(f"   all {len(segs)} segments bit-identical to the oracle; scores {e_R:.2e}, sums {e_S:.2e}, margin {margin}; "
+          f"selected {go['sel_list']}; wall {time.perf_counter() - t0:.1f} s", flush=True)
+
+
 def test_7b_bf16_every_element_of_all_fragments(B, ref):
     """The bf16 variant at the width and in the placement bench.py --bf16 times: bf16 local parameters and
     send-time record converted in place in the tuned layout, one fused call over all 32 fragments, then every
