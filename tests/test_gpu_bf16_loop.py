@@ -280,3 +280,12 @@ def test_bf16_loop_many_pieces_deep_overlap(B, ref):
     rng.shuffle(segs)
     _loop_case(B, ref, off + 5, 11, 30, 1.0, 1.0, 3.0, 200, segs=segs, K=K)
     _loop_case(B, ref, off + 5, 11, 30, 1.0, 1.0, 3.0, 200, segs=segs, K=K, lazy=True, pg_format=1)
+
+
+def test_bf16_loop_on_buffers_large_enough_for_the_wide_tiles(B, ref):
+    """More than 2^24 elements: 4 096-element tiles in the 16-bit event and in the 16-bit walk over the chosen
+    fragment."""
+    wl = synth.Workload("loop16-wide-tiles", (6000000, 5000001, 4999999, 1500003), tau=5, H=100)
+    assert wl.n_total > 1 << 24 and B.cocodc_tile_elements(wl.n_total) == 4096
+    n_sent, n_rec = _loop_case(B, ref, wl.n_total, 5, 100, 0.4, 1.0, 5.0, 110, frags=wl.frags, pg_format=1)
+    assert n_sent == 110 // 12 and n_rec == n_sent - 1

@@ -146,6 +146,16 @@ def test_loop_send_interval_equal_to_overlap(B, ref):
     _run_both(B, ref, wl, 1.0, 1.0, 5.0, 300, closed=True, lazy=True)
 
 
+def test_loop_on_buffers_large_enough_for_the_wide_tiles(B, ref):
+    """More than 2^24 elements: the tile walk switches to 4 096-element tiles, for the masked event and for the
+    walk over the fragment chosen on the device alike."""
+    wl = synth.Workload("loop-wide-tiles", (6000000, 5000001, 4999999, 1500003), tau=5, H=100)
+    assert wl.n_total > 1 << 24 and B.cocodc_tile_elements(wl.n_total) == 4096
+    n_sent, n_rec = _run_both(B, ref, wl, 0.4, 1.0, 5.0, 110, closed=True)
+    assert n_sent == 110 // 12 and n_rec == n_sent - 1
+    _run_both(B, ref, wl, 0.4, 1.0, 5.0, 110, closed=False, lazy=True)
+
+
 def test_loop_on_the_papers_strided_shards(B, ref):
     """Sec. 4.1: 12 layers in K = 4 strided shards, H = 100, tau = 5, gamma = 0.4 (125M-mini layer
     sizes): every shard is 3 or 4 segments of a layer-ordered buffer."""
