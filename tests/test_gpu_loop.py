@@ -156,6 +156,17 @@ def test_loop_on_buffers_large_enough_for_the_wide_tiles(B, ref):
     _run_both(B, ref, wl, 0.4, 1.0, 5.0, 110, closed=False, lazy=True)
 
 
+def test_loop_degenerate_schedules(B, ref):
+    """One fragment only; no overlap at all (tau = 0: a fragment sent at step t is received at the next step);
+    more synchronisations asked for than there are steps (Eq. 10 gives h = 0, taken as one send per step)."""
+    one = synth.Workload("loop-one-fragment", (50001,), tau=2, H=6)
+    _run_both(B, ref, one, 1.0, 1.0, 2.0, 60, closed=True)
+    no_overlap = synth.Workload("loop-tau-0", (20000, 1, 30001), tau=0, H=4)
+    n_sent, n_rec = _run_both(B, ref, no_overlap, 1.0, 1.0, 0.5, 60, closed=False)   # N = 8 > H: h = 1
+    assert n_sent == 60 and n_rec == 59
+    _run_both(B, ref, no_overlap, 1.0, 1.0, 0.5, 60, closed=True, lazy=True)
+
+
 def test_loop_on_the_papers_strided_shards(B, ref):
     """Sec. 4.1: 12 layers in K = 4 strided shards, H = 100, tau = 5, gamma = 0.4 (125M-mini layer
     sizes): every shard is 3 or 4 segments of a layer-ordered buffer."""
