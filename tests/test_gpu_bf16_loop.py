@@ -289,3 +289,52 @@ def test_bf16_loop_on_buffers_large_enough_for_the_wide_tiles(B, ref):
     assert wl.n_total > 1 << 24 and B.cocodc_tile_elements(wl.n_total) == 4096
     n_sent, n_rec = _loop_case(B, ref, wl.n_total, 5, 100, 0.4, 1.0, 5.0, 110, frags=wl.frags, pg_format=1)
     assert n_sent == 110 // 12 and n_rec == n_sent - 1
+
+
+@pytest.mark.parametrize("seed", range(2))
+def test_random_bf16_segmented_cases(B, ref, seed):
+    """The seeded random sweep of the fp32 entry points (random tables with empty and one-element fragments, gaps,
+    any base alignment, every hyper-parameter switch, buffers beyond 2^24 elements) through the 16-bit segmented
+    step: every fragment cut into random pieces, the pieces of all fragments shuffled, both wire formats."""
+    from test_gpu_random_sweep import _random_case
+    rng = random.Random(3000 + seed)
+    for case in range(20):
+        c = _random_case(rng)
+        K = len(c["frags"])
+        segs = []
+        for p, (o, l) in enumerate(c["frags"]):
+            cuts = sorted(rng.randrange(0, l + 1) for _ in range(rng.choice([0, 0, 1, 2, 5]))) if l else []
+            edges = [0] + cuts + [l]
+            segs += [(o + a, b - a, p) for a, b in zip(edges, edges[1:])]
+        rng.shuffle(segs)
+        n_alloc = c["n"] + ((1 << 24) if c["pad_big"] else 0) + 8
+        hpk = dict(c["hp"], pg_format=rng.choice([0, 1]))
+        tau, H = hpk.pop("tau"), hpk.pop("H")
+        print(f"case bf16 segmented random seed={seed} #{case} S={len(segs)} K={K} n={n_alloc} "
+              f"view_off={c['view_off']} amplified={c['amplified']} budget={c['budget']} hp={hpk}", flush=True)
+        dev, host = _half_state(n_alloc, tau, H, seed * 100 + case, c["amplified"], c["view_off"])
+        ghp, rhp = B.hparams(tau, H, **hpk), ref.hparams(tau, H, **hpk)
+        ws = B.new_workspace_segmented(len(segs), K, n_alloc)
+        out = U.gpu_outputs(K)
+        pg, h_pg = _pg_buffers(n_alloc)
+        rc = B.cocodc_sync_step_bf16_segmented(segs, K, n_alloc, dev["theta_m"], dev["theta_m_send"], dev["theta_g"],
+                                               dev["momentum"], dev["delta_g"], pg, c["I_p"], c["t_b"], 1000,
+                                               c["budget"], ghp, out["R"], out["sel"], out["n_sel"], out["sums"], ws)
+        assert rc == 0, B.cocodc_status_string(rc)
+        torch.cuda.synchronize()
+        ro = ref.sync_step_bf16_segmented(segs, K, host["theta_m"], host["theta_m_send"], host["theta_g"],
+                                          host["momentum"], host["delta_g"], h_pg, c["I_p"], c["t_b"], 1000,
+                                          c["budget"], rhp)
+        assert ro["rc"] == 0
+        _same_buffers(dev, host)
+        assert np.array_equal(_u16(pg), h_pg)
+        Rg, Rr = out["R"].cpu().numpy(), ro["R"]
+        fin = np.isfinite(Rr)
+        assert np.array_equal(np.isposinf(Rg), np.isposinf(Rr)) and np.array_equal(np.isnan(Rg), np.isnan(Rr))
+        assert U.rel_err(Rg[fin], Rr[fin]) <= U.SCORE_TOL_TIGHT
+        ok = np.isfinite(ro["sums"])
+        assert U.rel_err(out["sums"].cpu().numpy()[ok], ro["sums"][ok]) <= U.SCORE_TOL_TIGHT
+        out["sel_list"] = out["sel"][:int(out["n_sel"].item())].cpu().tolist()
+        assert len(out["sel_list"]) == min(c["budget"], K)
+        if not np.isnan(Rr).any():
+            U.compare_selection(out, ro, synth.Bookkeeping(t_g=1000, t_b=c["t_b"], I_p=c["I_p"]), H)
