@@ -505,7 +505,8 @@ int cocodc_set_blocks_per_cu(int blocks_per_cu);
  * normally travel inside the arguments of every kernel of a call, which saves the small upload
  * launch in front of them; larger tables are written to the head of the workspace first.
  * enabled = 0 makes every call upload (to compare the two paths; results never depend on it).
- * Returns the previous setting.  Process-wide. */
+ * Returns the previous setting.  Process-wide; a loop object plans the table of its send step when
+ * it is created and keeps the setting of that moment for it. */
 int cocodc_set_tables_in_args(int enabled);
 
 /* Kernel timer for benchmarks.  After cocodc_profiler_enable(n) every launch of a

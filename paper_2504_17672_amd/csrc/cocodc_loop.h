@@ -11,6 +11,7 @@
 
 struct cocodc_loop {
   std::vector<cocodc_segment_t> segs;  // the fragments as lists of segments (a contiguous fragment is one)
+  Plan full;                           // the tile plan of ALL fragments (the send step walks the chosen one in it)
   int32_t K = 0;
   uint64_t n_total = 0;
   cocodc_hparams_t hp{};
@@ -69,6 +70,7 @@ int cocodc_loop_create_segmented(const cocodc_segment_t* segs, int32_t S, int32_
   if (int rc = plan_segments(segs, S, K, n_total, nullptr, nullptr, &pl)) return rc;
   cocodc_loop* L = new cocodc_loop();
   L->segs.assign(segs, segs + S);
+  L->full = std::move(pl);
   L->K = K;
   L->n_total = n_total;
   L->hp = *hp;
@@ -308,8 +310,7 @@ int loop_step_impl(cocodc_loop* loop, int64_t t, const LoopIO& io, void* stream,
   // names: a walk over that fragment's tiles in the table of ALL fragments (the event above
   // worked on the table of the arrived ones).  Stream order lets a large table reuse the head of
   // the workspace: the event's kernels are done with theirs when the upload runs.
-  Plan full;
-  if (int rc = plan_segments(loop->segs.data(), S, K, loop->n_total, nullptr, nullptr, &full)) return rc;
+  const Plan& full = loop->full;  // depends on the table alone: made once, when the loop was created
   uint64_t widest = 0;  // tiles of the largest fragment Algorithm 2 could choose
   for (int32_t p = 0; p < K; ++p) {
     if (loop->in_flight[p] < 0) widest = std::max<uint64_t>(widest, full.groups[p + 1].slot_begin - full.groups[p].slot_begin);
