@@ -485,6 +485,48 @@ int cocodc_ref_sync_step_segmented(const cocodc_ref_segment_t* segs, int32_t S, 
   return cocodc_ref_select_fragments(K, R_out, t_b, t_g, hp->H, budget, sel_out, n_sel_out);
 }
 
+/* One event of the loop of Sec. 3.2 for fragments made of segments (the strided shards of Sec. 4.1):
+ * recv_mask per FRAGMENT as in cocodc_ref_sync_event; an arrived fragment's segments are walked in the
+ * order listed. */
+int cocodc_ref_sync_event_segmented(const cocodc_ref_segment_t* segs, int32_t S, int32_t K,
+                                    uint64_t n_total, const uint8_t* recv_mask, float* theta_m,
+                                    const float* theta_m_send, float* theta_g, float* momentum,
+                                    const float* delta_g, float* delta_m_out, const int64_t* I_p,
+                                    const int64_t* t_b, int64_t t_g, int32_t budget,
+                                    const cocodc_ref_hparams_t* hp, double* R, int32_t* sel_out,
+                                    int32_t* n_sel_out, double* sums_out) {
+  if (!recv_mask || !theta_m || !theta_g || !momentum || !delta_g) return kErrNull;
+  if (!I_p || !t_b || !R || !sel_out || !n_sel_out) return kErrNull;
+  if (int rc = check_segments(segs, S, K, n_total)) return rc;
+  if (int rc = check_hparams(hp)) return rc;
+  if (!theta_m_send && (hp->merge_mode == 0 || hp->score_src == 1)) return kErrNull;
+  if (budget < 0) return kErrRange;
+  std::vector<uint8_t> in_flight(static_cast<size_t>(K), 0);
+  for (int32_t q = 0; q < K; ++q) {
+    if (recv_mask[q] > 3) return kErrRange;
+    in_flight[q] = (recv_mask[q] & 2) ? 1 : 0;
+  }
+  for (int32_t q = 0; q < K; ++q) {
+    if (!(recv_mask[q] & 1)) continue;
+    Sums s;
+    for (int32_t j = 0; j < S; ++j) {
+      if (segs[j].fragment != q) continue;
+      for (uint64_t i = segs[j].offset; i < segs[j].offset + segs[j].length; ++i) {
+        sync_element(i, theta_m, theta_m_send, theta_g, momentum, delta_g, delta_m_out, *hp, &s,
+                     nullptr);
+      }
+    }
+    R[q] = score_from_sums(s, I_p[q], *hp);
+    if (sums_out) {
+      sums_out[4 * q + 0] = s.g2;
+      sums_out[4 * q + 1] = s.g1;
+      sums_out[4 * q + 2] = s.d2;
+      sums_out[4 * q + 3] = s.d1;
+    }
+  }
+  return select_among(K, R, t_b, t_g, hp->H, budget, in_flight.data(), sel_out, n_sel_out);
+}
+
 // ---- bf16 local parameters ------------------------------------------------------------
 // bfloat16 = the upper half of an IEEE binary32: 8 significant bits, exponents -126..127,
 // subnormal spacing 2^-133.

@@ -192,6 +192,15 @@ int cocodc_ref_sync_step_bf16(const cocodc_ref_fragment_t* frags, int32_t K, uin
                               int32_t* n_sel_out, double* sums_out /* nullable */,
                               const cocodc_ref_shadow_t* shadow /* nullable */);
 
+/* cocodc_ref_sync_event for fragments made of segments (recv_mask, I_p, t_b, R, sums_out per fragment). */
+int cocodc_ref_sync_event_segmented(const cocodc_ref_segment_t* segs, int32_t S, int32_t K,
+                                    uint64_t n_total, const uint8_t* recv_mask, float* theta_m,
+                                    const float* theta_m_send, float* theta_g, float* momentum,
+                                    const float* delta_g, float* delta_m_out /* nullable */,
+                                    const int64_t* I_p, const int64_t* t_b, int64_t t_g, int32_t budget,
+                                    const cocodc_ref_hparams_t* hp, double* R, int32_t* sel_out,
+                                    int32_t* n_sel_out, double* sums_out /* nullable */);
+
 /* cocodc_ref_sync_step_bf16 over fragments made of segments (Sec. 4.1: strided shards, mixed-precision
  * local parameters); a fragment's segments are walked in the order listed. */
 int cocodc_ref_sync_step_bf16_segmented(const cocodc_ref_segment_t* segs, int32_t S, int32_t K,

@@ -2,6 +2,7 @@
 contiguous ones where a fragment is one piece, must not care how a contiguous run is cut into
 adjacent pieces, and must agree with library norms over the concatenated pieces.  CPU only."""
 import numpy as np
+import pytest
 import torch
 
 from paper_2504_17672_amd import synth
@@ -100,3 +101,64 @@ def test_untouched_elements_empty_fragments_and_errors(ref):
     assert ref.fragment_scores_segmented([(0, 10, 0), (5, 10, 1)], 2, x, [1, 1])[0] == -3  # overlap
     assert ref.fragment_scores_segmented([(0, 10, 2)], 2, x, [1, 1])[0] == -3            # fragment id
     assert ref.fragment_scores_segmented([(2995, 10, 0)], 1, x, [1])[0] == -3            # out of range
+
+
+# ------------------------------------------------------------------ one loop event on strided shards
+@pytest.mark.parametrize("mask", [(1, 1, 1, 1), (0, 1, 2, 1), (0, 0, 0, 0), (3, 2, 0, 1), (2, 2, 2, 2)])
+def test_segmented_event_is_the_segmented_step_on_the_arrived_shards_then_selection(ref, mask):
+    """The event on strided shards == the (pinned) segmented step on the arrived shards alone, everything else
+    untouched, then Alg. 2 over old and new scores with the shards in flight struck out; and with one segment
+    per fragment it is the contiguous event bit for bit."""
+    sizes = [300, 170, 411, 96, 250, 333, 128, 77, 205, 190, 64, 501]
+    offs = np.concatenate(([7], 7 + np.cumsum(sizes)[:-1]))
+    segs = [(int(offs[j]), sizes[j], j % 4) for j in range(12)]
+    K, n = 4, 7 + sum(sizes) + 9
+    hp = ref.hparams(2, 3, lam=0.5)
+    I_p, t_b = [4, 9, 2, 6], [90, 99, 40, 97]
+    R_old = np.array([0.25, np.inf, 7.0, 0.5])
+    a = _state(n, 41, amplified=True)
+    b = {k: v.copy() for k, v in a.items()}
+    orig = {k: v.copy() for k, v in a.items()}
+    pg_a = np.full(n, 555.0, np.float32)
+    pg_b = pg_a.copy()
+    sums_a = np.full((K, 4), -3.0)
+    R_a = R_old.copy()
+    out = ref.sync_event_segmented(segs, K, mask, a["theta_m"], a["theta_m_send"], a["theta_g"], a["momentum"],
+                                   a["delta_g"], pg_a, I_p, t_b, 100, 2, hp, R_a, sums=sums_a)
+    assert out["rc"] == 0
+    arrived = [q for q in range(K) if mask[q] & 1]
+    R_b, sums_b = R_old.copy(), np.full((K, 4), -3.0)
+    if arrived:
+        sub = [(o, l, arrived.index(f)) for o, l, f in segs if f in arrived]
+        so = ref.sync_step_segmented(sub, len(arrived), b["theta_m"], b["theta_m_send"], b["theta_g"], b["momentum"],
+                                     b["delta_g"], pg_b, [I_p[q] for q in arrived], [t_b[q] for q in arrived], 100, 0, hp)
+        assert so["rc"] == 0
+        for j, q in enumerate(arrived):
+            R_b[q], sums_b[q] = so["R"][j], so["sums"][j]
+    rc, order = ref.select_fragments(R_b, t_b, 100, hp.H, K)
+    assert rc == 0
+    for k in a:
+        assert np.array_equal(a[k], b[k]), k
+    assert np.array_equal(pg_a, pg_b)
+    assert np.array_equal(R_a, R_b) and np.array_equal(sums_a, sums_b)
+    assert out["sel"].tolist() == [q for q in order.tolist() if not mask[q] & 2][:2]
+    if not arrived:
+        for k in a:
+            assert np.array_equal(a[k], orig[k])
+    # one segment per fragment: the contiguous event
+    frags = [(5, 700), (705, 0), (710, 1), (800, 900)]
+    c = _state(n, 42)
+    d = {k: v.copy() for k, v in c.items()}
+    R_c, R_d = R_old.copy(), R_old.copy()
+    pg_c, pg_d = np.zeros(n, np.float32), np.zeros(n, np.float32)
+    oc = ref.sync_event(frags, mask, c["theta_m"], c["theta_m_send"], c["theta_g"], c["momentum"], c["delta_g"], pg_c,
+                        I_p, t_b, 100, 3, hp, R_c)
+    od = ref.sync_event_segmented([(o, l, p) for p, (o, l) in enumerate(frags)], K, mask, d["theta_m"],
+                                  d["theta_m_send"], d["theta_g"], d["momentum"], d["delta_g"], pg_d, I_p, t_b, 100, 3,
+                                  hp, R_d)
+    assert oc["rc"] == 0 and od["rc"] == 0 and oc["sel"].tolist() == od["sel"].tolist()
+    for k in c:
+        assert np.array_equal(c[k], d[k]), k
+    assert np.array_equal(pg_c, pg_d) and np.array_equal(R_c, R_d)
+    assert ref.sync_event_segmented(segs, K, [4, 0, 0, 0], a["theta_m"], a["theta_m_send"], a["theta_g"], a["momentum"],
+                                    a["delta_g"], pg_a, I_p, t_b, 100, 2, hp, R_a)["rc"] < 0
