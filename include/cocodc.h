@@ -280,6 +280,19 @@ int cocodc_sync_step_segmented(const cocodc_segment_t* segs, int32_t S, int32_t 
                                double* sums_out /* nullable */, void* workspace, size_t workspace_bytes,
                                void* stream);
 
+/* cocodc_sync_event for fragments made of several segments (one event of the loop of Sec. 3.2 on
+ * the strided shards of Sec. 4.1): recv_mask, I_p, t_b, R (read and written) and sums_out are per
+ * FRAGMENT; segs and the workspace size as for cocodc_sync_step_segmented. */
+int cocodc_sync_event_segmented(const cocodc_segment_t* segs, int32_t S, int32_t K, uint64_t n_total,
+                                const uint8_t* recv_mask, float* theta_m,
+                                const float* theta_m_send /* nullable as in cocodc_sync_step */,
+                                float* theta_g, float* momentum, const float* delta_g,
+                                float* delta_m_out /* nullable */, const int64_t* I_p, const int64_t* t_b,
+                                int64_t t_g, int32_t budget, const cocodc_hparams_t* hp,
+                                double* R /* in and out */, int32_t* sel_out, int32_t* n_sel_out,
+                                double* sums_out /* nullable */, void* workspace, size_t workspace_bytes,
+                                void* stream);
+
 /* ---- bfloat16 local parameters ----
  * The paper's workers train in bf16 mixed precision (Sec. 4.1).  In these calls theta_m,
  * theta_m_send and the outgoing pseudo-gradient are bfloat16 (raw 16-bit patterns, 2-byte

@@ -405,6 +405,22 @@ int cocodc_sync_step_segmented(const cocodc_segment_t* segs, int32_t S, int32_t 
                         hp, R_out, sel_out, n_sel_out, sums_out, workspace, workspace_bytes_, stream);
 }
 
+int cocodc_sync_event_segmented(const cocodc_segment_t* segs, int32_t S, int32_t K, uint64_t n_total,
+                                const uint8_t* recv_mask, float* theta_m, const float* theta_m_send, float* theta_g,
+                                float* momentum, const float* delta_g, float* delta_m_out, const int64_t* I_p,
+                                const int64_t* t_b, int64_t t_g, int32_t budget, const cocodc_hparams_t* hp, double* R,
+                                int32_t* sel_out, int32_t* n_sel_out, double* sums_out, void* workspace,
+                                size_t workspace_bytes_, void* stream) {
+  if (!recv_mask) return COCODC_ERR_NULL;
+  if (int rc = sync_step_check(theta_m, theta_m_send, theta_g, momentum, delta_g, delta_m_out, I_p, t_b, budget, hp,
+                               R, sel_out, n_sel_out, sums_out))
+    return rc;
+  Plan pl;
+  if (int rc = plan_segments(segs, S, K, n_total, I_p, t_b, &pl, recv_mask)) return rc;
+  return sync_step_impl(pl, K, n_total, theta_m, theta_m_send, theta_g, momentum, delta_g, delta_m_out, t_g, budget,
+                        hp, R, sel_out, n_sel_out, sums_out, workspace, workspace_bytes_, stream);
+}
+
 int cocodc_pseudograd_bf16(const cocodc_fragment_t* frags, int32_t K, uint64_t n_total,
                            const float* theta_g_snap, const uint16_t* theta_m, uint16_t* delta_m_out,
                            uint16_t* theta_m_send_out, int32_t pg_format, void* workspace, size_t workspace_bytes_,

@@ -328,3 +328,28 @@ def test_bf16_entry_points_reject_bad_arguments_before_any_device_work(B):
         assert step(t=3) == 0 and step(t=3) == B.COCODC_ERR_RANGE
     finally:
         B.cocodc_loop_destroy(loop)
+
+
+def test_segmented_event_rejects_bad_arguments_before_any_device_work(B):
+    n, K = 4096, 2
+    base = 0x40000000
+    tm, ts, tg, m, dg, pg = (base + i * 0x100000 for i in range(6))
+    R, sel, nsel, sums, ws = (base + 0x1000000 + i * 0x100000 for i in range(5))
+    segs = [(0, 1000, 0), (1000, 1048, 1), (2048, 2048, 0)]
+    hp = B.hparams(5, 100)
+    I_p, t_b = [1, 1], [0, 0]
+    wss = B.cocodc_workspace_bytes_segmented(len(segs), K, n)
+
+    def event(mask, **kw):
+        a = dict(segs=segs, tm=tm, R=R, ws=ws, wsb=wss, pg=pg, K=K)
+        a.update(kw)
+        return B.cocodc_sync_event_segmented(a["segs"], a["K"], n, mask, a["tm"], ts, tg, m, dg, a["pg"], I_p, t_b, 10,
+                                             1, hp, a["R"], sel, nsel, sums, a["ws"], a["wsb"], stream=0)
+    assert event(None) == B.COCODC_ERR_NULL
+    assert event([1, 0], tm=None) == B.COCODC_ERR_NULL
+    assert event([1, 0], R=R + 4) == B.COCODC_ERR_ALIGN
+    assert event([1, 8]) == B.COCODC_ERR_RANGE
+    assert event([0, 0], segs=[(0, 1000, 0), (999, 10, 1)]) == B.COCODC_ERR_RANGE   # checked whatever the mask says
+    assert event([1, 0], segs=[(0, 1000, 2)]) == B.COCODC_ERR_RANGE
+    assert event([1, 1], wsb=wss - 1) == B.COCODC_ERR_WORKSPACE
+    assert event([1, 2], pg=tm) == B.COCODC_ERR_ALIAS

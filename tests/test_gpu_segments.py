@@ -146,3 +146,73 @@ def test_segmented_rejections(B):
     assert call([(4090, 10, 0)]) == B.COCODC_ERR_RANGE
     assert call(None, S=2) == B.COCODC_ERR_NULL
     assert call([(0, 10, 0)] * 1, wsb=64) == B.COCODC_ERR_WORKSPACE
+
+
+def test_segmented_event_random_masks(B, ref):
+    """cocodc_sync_event_segmented: 30 random events on random segment tables (fragments cut into shuffled
+    pieces, empty fragments, unaligned bases, buffers beyond 2^24 elements, every hyper-parameter switch),
+    shards marked arrived and / or in flight, old scores with infinities and a NaN that must survive untouched."""
+    import random
+    from test_gpu_random_sweep import _random_case
+    rng = random.Random(4000)
+    for case in range(30):
+        c = _random_case(rng)
+        K = len(c["frags"])
+        segs = []
+        for p, (o, l) in enumerate(c["frags"]):
+            cuts = sorted(rng.randrange(0, l + 1) for _ in range(rng.choice([0, 0, 1, 2, 5]))) if l else []
+            edges = [0] + cuts + [l]
+            segs += [(o + a, b - a, p) for a, b in zip(edges, edges[1:])]
+        rng.shuffle(segs)
+        n_alloc = c["n"] + ((1 << 24) if c["pad_big"] else 0)
+        mask = [int(rng.random() < rng.choice([0.0, 0.3, 1.0])) for _ in range(K)]
+        if case % 2:
+            mask = [m | (2 if rng.random() < 0.4 else 0) for m in mask]
+        hpk = dict(c["hp"])
+        tau, H = hpk.pop("tau"), hpk.pop("H")
+        print(f"case segmented event #{case} S={len(segs)} K={K} n={n_alloc} mask={mask} view_off={c['view_off']} "
+              f"hp={c['hp']}", flush=True)
+        base = synth.Workload("rnd", (n_alloc + c["view_off"],), tau=tau, H=H)
+        st = {k: v[c["view_off"]:] for k, v in
+              synth.make_state(base, "cuda", seed=500 + case, amplified=c["amplified"]).items()}
+        host = U.host_copy(st)
+        ghp, rhp = B.hparams(tau, H, **hpk), ref.hparams(tau, H, **hpk)
+        R0 = np.array([rng.choice([np.inf, 0.0, 0.5, 2.0, rng.random(), np.nan if K > 3 and rng.random() < 0.1 else 1.5])
+                       for _ in range(K)])
+        R_dev = torch.from_numpy(R0.copy()).cuda()
+        sums_dev = torch.full((K, 4), -3.0, dtype=torch.float64, device="cuda")
+        out = U.gpu_outputs(K)
+        pg = torch.full((n_alloc,), 555.0, device="cuda")
+        ws = B.new_workspace_segmented(len(segs), K, n_alloc)
+        rc = B.cocodc_sync_event_segmented(segs, K, n_alloc, mask, st["theta_m"], st["theta_m_send"], st["theta_g"],
+                                           st["momentum"], st["delta_g"], pg, c["I_p"], c["t_b"], 1000, c["budget"],
+                                           ghp, R_dev, out["sel"], out["n_sel"], sums_dev, ws)
+        assert rc == 0, B.cocodc_status_string(rc)
+        torch.cuda.synchronize()
+        R_ref, sums_ref = R0.copy(), np.full((K, 4), -3.0)
+        h_pg = np.full(n_alloc, 555.0, np.float32)
+        ro = ref.sync_event_segmented(segs, K, mask, host["theta_m"], host["theta_m_send"], host["theta_g"],
+                                      host["momentum"], host["delta_g"], h_pg, c["I_p"], c["t_b"], 1000, c["budget"],
+                                      rhp, R_ref, sums=sums_ref)
+        assert ro["rc"] == 0
+        for k in ("theta_m", "theta_g", "momentum", "theta_m_send", "delta_g"):
+            assert np.array_equal(st[k].cpu().numpy().view(np.uint32), host[k].view(np.uint32)), k
+        assert np.array_equal(pg.cpu().numpy().view(np.uint32), h_pg.view(np.uint32))
+        Rg = R_dev.cpu().numpy()
+        arrived = np.array([m & 1 for m in mask], bool)
+        assert np.array_equal(Rg[~arrived].view(np.uint64), R0[~arrived].view(np.uint64))
+        fin = arrived & np.isfinite(R_ref)
+        assert np.array_equal(np.isposinf(Rg[arrived]), np.isposinf(R_ref[arrived]))
+        assert np.array_equal(np.isnan(Rg[arrived]), np.isnan(R_ref[arrived]))
+        assert U.rel_err(Rg[fin], R_ref[fin]) <= U.SCORE_TOL_TIGHT
+        sg = sums_dev.cpu().numpy()
+        assert np.array_equal(sg[~arrived], sums_ref[~arrived])
+        ok = arrived[:, None] & np.isfinite(sums_ref)
+        assert U.rel_err(sg[ok], sums_ref[ok]) <= U.SCORE_TOL_TIGHT
+        n_sel = int(out["n_sel"].item())
+        assert n_sel == min(c["budget"], sum(1 for m in mask if not m & 2))
+        got = out["sel"][:n_sel].cpu().tolist()
+        rc_o, order = ref.select_fragments(Rg, c["t_b"], 1000, H, K)
+        assert rc_o == 0 and got == [q for q in order.tolist() if not mask[q] & 2][:n_sel]
+        if not np.isnan(R_ref).any() and not np.isnan(Rg).any():
+            assert got == ro["sel"].tolist()

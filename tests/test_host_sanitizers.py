@@ -124,6 +124,7 @@ def test_library_host_side_under_asan_and_ubsan(tmp_path):
         t.test_invalid_arguments_are_rejected_before_any_device_work(mod)
         t.test_loop_step_rejects_bad_buffers_before_any_device_work(mod)
         t.test_bf16_entry_points_reject_bad_arguments_before_any_device_work(mod)
+        t.test_segmented_event_rejects_bad_arguments_before_any_device_work(mod)
         p.test_boundary_tables(mod)
         import random
         for seed in range(200):
