@@ -59,7 +59,7 @@ def lib():
         for name in ("pseudograd", "outer_nesterov", "delay_compensate", "fragment_scores",
                      "select_fragments", "sync_step", "sync_step_mt", "sync_plan",
                      "fragment_scores_segmented", "sync_step_segmented", "pseudograd_bf16", "sync_step_bf16",
-                     "select_fragments_bytes", "sync_event", "sync_step_bf16_segmented", "sync_event_bf16", "sync_event_segmented"):
+                     "select_fragments_bytes", "sync_event", "sync_step_bf16_segmented", "sync_event_bf16", "sync_event_segmented", "sync_event_bf16_segmented"):
             getattr(_lib, "cocodc_ref_" + name).restype = C.c_int
         _lib.cocodc_ref_round_bf16.restype = C.c_uint16
         _lib.cocodc_ref_round_bf16.argtypes = [C.c_double]
@@ -372,6 +372,24 @@ def sync_event_bf16(frags, recv_mask, theta_m, theta_m_send, theta_g, momentum, 
         _frag_array(frags), C.c_int32(K), C.c_uint64(n), C.c_void_p(mask.ctypes.data), _u16(theta_m),
         _u16(theta_m_send, True), _f32(theta_g), _f32(momentum), _f32(delta_g), _u16(delta_m_out, True), ip, tb,
         C.c_int64(t_g), C.c_int32(budget), C.byref(hp), C.c_void_p(R.ctypes.data), C.c_void_p(sel.ctypes.data),
+        C.byref(n_sel), C.c_void_p(sums.ctypes.data) if sums is not None else None)
+    return dict(rc=rc, sel=sel[:max(n_sel.value, 0)].copy())
+
+
+def sync_event_bf16_segmented(segs, K, recv_mask, theta_m, theta_m_send, theta_g, momentum, delta_g, delta_m_out, I_p,
+                              t_b, t_g, budget, hp, R, sums=None):
+    """sync_event_bf16 for fragments made of segments; R (K) updated in place."""
+    n = theta_m.size
+    assert R.dtype == np.float64 and R.size == K
+    mask = np.ascontiguousarray(np.asarray(recv_mask, dtype=np.uint8))
+    sel = np.full(K, -1, dtype=np.int32)
+    n_sel = C.c_int32(-1)
+    keep1, ip = _i64(I_p)
+    keep2, tb = _i64(t_b)
+    rc = lib().cocodc_ref_sync_event_bf16_segmented(
+        _seg_array(segs), C.c_int32(len(segs)), C.c_int32(K), C.c_uint64(n), C.c_void_p(mask.ctypes.data),
+        _u16(theta_m), _u16(theta_m_send, True), _f32(theta_g), _f32(momentum), _f32(delta_g), _u16(delta_m_out, True),
+        ip, tb, C.c_int64(t_g), C.c_int32(budget), C.byref(hp), C.c_void_p(R.ctypes.data), C.c_void_p(sel.ctypes.data),
         C.byref(n_sel), C.c_void_p(sums.ctypes.data) if sums is not None else None)
     return dict(rc=rc, sel=sel[:max(n_sel.value, 0)].copy())
 

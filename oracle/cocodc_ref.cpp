@@ -746,6 +746,40 @@ int cocodc_ref_sync_event_bf16(const cocodc_ref_fragment_t* frags, int32_t K, ui
   return select_among(K, R, t_b, t_g, hp->H, budget, in_flight.data(), sel_out, n_sel_out);
 }
 
+/* The 16-bit event for fragments made of segments: the paper's own configuration in one call per event
+ * (strided shards, bf16 local parameters; Sec. 3.2, Sec. 4.1). */
+int cocodc_ref_sync_event_bf16_segmented(const cocodc_ref_segment_t* segs, int32_t S, int32_t K,
+                                         uint64_t n_total, const uint8_t* recv_mask, uint16_t* theta_m,
+                                         const uint16_t* theta_m_send, float* theta_g, float* momentum,
+                                         const float* delta_g, uint16_t* delta_m_out, const int64_t* I_p,
+                                         const int64_t* t_b, int64_t t_g, int32_t budget,
+                                         const cocodc_ref_hparams_t* hp, double* R, int32_t* sel_out,
+                                         int32_t* n_sel_out, double* sums_out) {
+  if (!recv_mask) return kErrNull;
+  if (int rc = check_sync_bf16(theta_m, theta_m_send, theta_g, momentum, delta_g, I_p, t_b, budget, hp, R,
+                               sel_out, n_sel_out))
+    return rc;
+  if (int rc = check_segments(segs, S, K, n_total)) return rc;
+  std::vector<uint8_t> in_flight(static_cast<size_t>(K), 0);
+  for (int32_t q = 0; q < K; ++q) {
+    if (recv_mask[q] > 3) return kErrRange;
+    in_flight[q] = (recv_mask[q] & 2) ? 1 : 0;
+  }
+  for (int32_t q = 0; q < K; ++q) {
+    if (!(recv_mask[q] & 1)) continue;
+    Sums s;
+    for (int32_t j = 0; j < S; ++j) {
+      if (segs[j].fragment != q) continue;
+      for (uint64_t i = segs[j].offset; i < segs[j].offset + segs[j].length; ++i) {
+        sync_element_bf16(i, theta_m, theta_m_send, theta_g, momentum, delta_g, delta_m_out, *hp, &s, nullptr);
+      }
+    }
+    R[q] = score_from_sums(s, I_p[q], *hp);
+    store_sums(s, q, sums_out);
+  }
+  return select_among(K, R, t_b, t_g, hp->H, budget, in_flight.data(), sel_out, n_sel_out);
+}
+
 // Eq. 9: N = max(K, floor(gamma * H * T_c / T_s)); Eq. 10: h = floor(H / N).
 int cocodc_ref_sync_plan(int32_t K, int32_t H, double gamma, double T_c, double T_s,
                          int64_t* N_out, int64_t* h_out) {

@@ -219,6 +219,16 @@ int cocodc_ref_sync_event_bf16(const cocodc_ref_fragment_t* frags, int32_t K, ui
                                int64_t t_g, int32_t budget, const cocodc_ref_hparams_t* hp, double* R,
                                int32_t* sel_out, int32_t* n_sel_out, double* sums_out /* nullable */);
 
+/* cocodc_ref_sync_event_bf16 for fragments made of segments. */
+int cocodc_ref_sync_event_bf16_segmented(const cocodc_ref_segment_t* segs, int32_t S, int32_t K,
+                                         uint64_t n_total, const uint8_t* recv_mask, uint16_t* theta_m,
+                                         const uint16_t* theta_m_send, float* theta_g, float* momentum,
+                                         const float* delta_g, uint16_t* delta_m_out /* nullable */,
+                                         const int64_t* I_p, const int64_t* t_b, int64_t t_g,
+                                         int32_t budget, const cocodc_ref_hparams_t* hp, double* R,
+                                         int32_t* sel_out, int32_t* n_sel_out,
+                                         double* sums_out /* nullable */);
+
 /* Eq. 9 and Eq. 10: N = max(K, floor(gamma*H*T_c/T_s)), h = floor(H/N). */
 int cocodc_ref_sync_plan(int32_t K, int32_t H, double gamma, double T_c, double T_s,
                          int64_t* N_out, int64_t* h_out);

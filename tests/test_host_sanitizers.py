@@ -61,7 +61,7 @@ def test_oracle_pins_under_asan_and_ubsan(tmp_path):
             pass
         for name in ("pseudograd", "outer_nesterov", "delay_compensate", "fragment_scores", "select_fragments",
                      "sync_step", "sync_step_mt", "sync_plan", "fragment_scores_segmented", "sync_step_segmented",
-                     "pseudograd_bf16", "sync_step_bf16", "select_fragments_bytes", "sync_event", "sync_step_bf16_segmented", "sync_event_bf16", "sync_event_segmented"):
+                     "pseudograd_bf16", "sync_step_bf16", "select_fragments_bytes", "sync_event", "sync_step_bf16_segmented", "sync_event_bf16", "sync_event_segmented", "sync_event_bf16_segmented"):
             getattr(lib, "cocodc_ref_" + name).restype = C.c_int
         lib.cocodc_ref_round_bf16.restype = C.c_uint16
         lib.cocodc_ref_round_bf16.argtypes = [C.c_double]

@@ -324,3 +324,55 @@ def test_bf16_event_is_the_bf16_step_on_the_arrived_fragments_then_selection(ref
             assert np.array_equal(a[k], orig[k])
     assert ref.sync_event_bf16(frags, [4, 0, 0, 0, 0], a["theta_m"], a["theta_m_send"], a["theta_g"], a["momentum"],
                                a["delta_g"], pg_a, I_p, t_b, 100, 2, hp, R_a)["rc"] < 0
+
+
+@pytest.mark.parametrize("mask", [(1, 1, 1, 1), (0, 1, 2, 1), (0, 0, 0, 0), (3, 2, 0, 1)])
+def test_bf16_segmented_event_is_the_bf16_segmented_step_on_the_arrived_shards_then_selection(ref, mask):
+    """The 16-bit event on strided shards == the (pinned) 16-bit segmented step on the arrived shards alone, then
+    Alg. 2 with the shards in flight struck out; with one segment per fragment it is the contiguous 16-bit event."""
+    sizes = [300, 170, 411, 96, 250, 333, 128, 77, 205, 190, 64, 501]
+    offs = np.concatenate(([7], 7 + np.cumsum(sizes)[:-1]))
+    segs = [(int(offs[j]), sizes[j], j % 4) for j in range(12)]
+    K, n = 4, 7 + sum(sizes) + 9
+    wl = synth.Workload("e", (n,), tau=2, H=3)
+    hp = ref.hparams(2, 3, lam=0.5, pg_format=1)
+    I_p, t_b = [4, 9, 2, 6], [90, 99, 40, 97]
+    R_old = np.array([0.25, np.inf, 7.0, 0.5])
+    a = _bf16_state(wl, 51, amplified=True)
+    b = {k: v.copy() for k, v in a.items()}
+    pg_a = np.full(n, 0x7E00, np.uint16)
+    pg_b = pg_a.copy()
+    sums_a, R_a = np.full((K, 4), -3.0), R_old.copy()
+    out = ref.sync_event_bf16_segmented(segs, K, mask, a["theta_m"], a["theta_m_send"], a["theta_g"], a["momentum"],
+                                        a["delta_g"], pg_a, I_p, t_b, 100, 2, hp, R_a, sums=sums_a)
+    assert out["rc"] == 0
+    arrived = [q for q in range(K) if mask[q] & 1]
+    R_b, sums_b = R_old.copy(), np.full((K, 4), -3.0)
+    if arrived:
+        sub = [(o, l, arrived.index(f)) for o, l, f in segs if f in arrived]
+        so = ref.sync_step_bf16_segmented(sub, len(arrived), b["theta_m"], b["theta_m_send"], b["theta_g"], b["momentum"],
+                                          b["delta_g"], pg_b, [I_p[q] for q in arrived], [t_b[q] for q in arrived],
+                                          100, 0, hp)
+        assert so["rc"] == 0
+        for j, q in enumerate(arrived):
+            R_b[q], sums_b[q] = so["R"][j], so["sums"][j]
+    rc, order = ref.select_fragments(R_b, t_b, 100, hp.H, K)
+    assert rc == 0
+    for k in a:
+        assert np.array_equal(a[k], b[k]), k
+    assert np.array_equal(pg_a, pg_b) and np.array_equal(R_a, R_b) and np.array_equal(sums_a, sums_b)
+    assert out["sel"].tolist() == [q for q in order.tolist() if not mask[q] & 2][:2]
+    frags = [(5, 700), (705, 0), (710, 1), (800, 900)]
+    c = _bf16_state(wl, 52)
+    d = {k: v.copy() for k, v in c.items()}
+    R_c, R_d = R_old.copy(), R_old.copy()
+    pg_c, pg_d = np.zeros(n, np.uint16), np.zeros(n, np.uint16)
+    oc = ref.sync_event_bf16(frags, mask, c["theta_m"], c["theta_m_send"], c["theta_g"], c["momentum"], c["delta_g"],
+                             pg_c, I_p, t_b, 100, 3, hp, R_c)
+    od = ref.sync_event_bf16_segmented([(o, l, p) for p, (o, l) in enumerate(frags)], K, mask, d["theta_m"],
+                                       d["theta_m_send"], d["theta_g"], d["momentum"], d["delta_g"], pg_d, I_p, t_b,
+                                       100, 3, hp, R_d)
+    assert oc["rc"] == 0 and od["rc"] == 0 and oc["sel"].tolist() == od["sel"].tolist()
+    for k in c:
+        assert np.array_equal(c[k], d[k]), k
+    assert np.array_equal(pg_c, pg_d) and np.array_equal(R_c, R_d)

@@ -88,6 +88,8 @@ MUTANTS = [
     ("segmented_event_walks_every_shard", "if (segs[j].fragment != q) continue;", ""),
     ("segmented_event_scores_with_interval_of_shard_0", "R[q] = score_from_sums(s, I_p[q], *hp);\n    if (sums_out) {\n      sums_out[4 * q + 0] = s.g2;\n      sums_out[4 * q + 1] = s.g1;\n      sums_out[4 * q + 2] = s.d2;\n      sums_out[4 * q + 3] = s.d1;\n    }\n  }\n  return select_among(K, R, t_b, t_g, hp->H, budget, in_flight.data(), sel_out, n_sel_out);\n}\n\n// ---- bf16",
      "R[q] = score_from_sums(s, I_p[0], *hp);\n    if (sums_out) {\n      sums_out[4 * q + 0] = s.g2;\n      sums_out[4 * q + 1] = s.g1;\n      sums_out[4 * q + 2] = s.d2;\n      sums_out[4 * q + 3] = s.d1;\n    }\n  }\n  return select_among(K, R, t_b, t_g, hp->H, budget, in_flight.data(), sel_out, n_sel_out);\n}\n\n// ---- bf16"),
+    ("half_segmented_event_sums_of_shard_0", "store_sums(s, q, sums_out);\n  }\n  return select_among(K, R, t_b, t_g, hp->H, budget, in_flight.data(), sel_out, n_sel_out);\n}\n\n// Eq. 9",
+     "store_sums(s, 0, sums_out);\n  }\n  return select_among(K, R, t_b, t_g, hp->H, budget, in_flight.data(), sel_out, n_sel_out);\n}\n\n// Eq. 9"),
     ("in_flight_counts_against_the_budget", "const int32_t n_sel = budget < candidates ? budget : candidates;",
      "const int32_t n_sel = (budget < K ? budget : K) - (K - candidates) > 0 ? (budget < K ? budget : K) - (K - candidates) : 0;"),
 ]
@@ -98,6 +100,7 @@ BATTERY = [
     half_pins.test_f16_pseudograd_in_the_bf16_calls,
     lambda ref: loop_pins.test_event_equals_step_on_the_arrived_fragments_then_selection_over_all(ref, (0, 1, 0, 0, 1)),
     lambda ref: seg_pins.test_segmented_event_is_the_segmented_step_on_the_arrived_shards_then_selection(ref, (0, 1, 2, 1)),
+    lambda ref: half_pins.test_bf16_segmented_event_is_the_bf16_segmented_step_on_the_arrived_shards_then_selection(ref, (0, 1, 2, 1)),
     half_pins.test_bf16_step_is_the_fp32_step_on_widened_inputs_rounded_once,
     half_pins.test_bf16_segmented_step_against_the_contiguous_and_the_fp32_segmented_steps,
     lambda ref: half_pins.test_bf16_event_is_the_bf16_step_on_the_arrived_fragments_then_selection(ref, (0, 1, 0, 2, 1)),
@@ -142,7 +145,7 @@ def _compile(text, path):
     lib = C.CDLL(path)
     for name in ("pseudograd", "outer_nesterov", "delay_compensate", "fragment_scores", "select_fragments",
                  "sync_step", "sync_step_mt", "sync_plan", "sync_event", "pseudograd_bf16", "sync_step_bf16",
-                 "sync_step_segmented", "sync_step_bf16_segmented", "sync_event_bf16", "sync_event_segmented"):
+                 "sync_step_segmented", "sync_step_bf16_segmented", "sync_event_bf16", "sync_event_segmented", "sync_event_bf16_segmented"):
         getattr(lib, "cocodc_ref_" + name).restype = C.c_int
     for name, res, arg in (("round_bf16", C.c_uint16, C.c_double), ("widen_bf16", C.c_double, C.c_uint16),
                            ("round_f16", C.c_uint16, C.c_double), ("widen_f16", C.c_double, C.c_uint16)):
