@@ -343,6 +343,19 @@ int cocodc_sync_event_bf16(const cocodc_fragment_t* frags, int32_t K, uint64_t n
                            double* sums_out /* nullable */, void* workspace, size_t workspace_bytes,
                            void* stream);
 
+/* cocodc_sync_event_bf16 for fragments made of several segments: one event of the loop of Sec. 3.2
+ * in the paper's own configuration (strided shards, bf16 local parameters).  Mask, scores and
+ * bookkeeping per fragment; segs and workspace size as for cocodc_sync_step_segmented. */
+int cocodc_sync_event_bf16_segmented(const cocodc_segment_t* segs, int32_t S, int32_t K, uint64_t n_total,
+                                     const uint8_t* recv_mask, uint16_t* theta_m,
+                                     const uint16_t* theta_m_send /* nullable as in cocodc_sync_step */,
+                                     float* theta_g, float* momentum, const float* delta_g,
+                                     uint16_t* delta_m_out /* nullable */, const int64_t* I_p,
+                                     const int64_t* t_b, int64_t t_g, int32_t budget,
+                                     const cocodc_hparams_t* hp, double* R /* in and out */,
+                                     int32_t* sel_out, int32_t* n_sel_out, double* sums_out /* nullable */,
+                                     void* workspace, size_t workspace_bytes, void* stream);
+
 /* Host-only planner, Eq. 9 and Eq. 10: N = max(K, floor(gamma*H*T_c/T_s)) target
  * synchronisations per H steps and h = floor(H/N) steps between two sends.
  * gamma in (0,1]; T_c, T_s > 0 (any common unit).  No GPU work. */

@@ -44,6 +44,7 @@ EXPORTS = (
     "cocodc_workspace_bytes_segmented", "cocodc_fragment_scores_segmented", "cocodc_sync_step_segmented",
     "cocodc_sync_event_segmented",
     "cocodc_pseudograd_bf16", "cocodc_sync_step_bf16", "cocodc_sync_step_bf16_segmented", "cocodc_sync_event_bf16",
+    "cocodc_sync_event_bf16_segmented",
     "cocodc_select_fragments_bytes",
     "cocodc_loop_create", "cocodc_loop_create_segmented", "cocodc_loop_destroy", "cocodc_loop_reset_scores", "cocodc_loop_observe",
     "cocodc_loop_plan", "cocodc_loop_due", "cocodc_loop_step", "cocodc_loop_step_bf16", "cocodc_loop_state", "cocodc_loop_last_sent",
@@ -116,6 +117,7 @@ _lib.cocodc_sync_step_bf16.argtypes = [_frag_p, C.c_int32, C.c_uint64, _P, _P, _
                                        C.c_int64, C.c_int32, _hp_p, _P, _P, _P, _P, _P, C.c_size_t, _P]
 _lib.cocodc_sync_step_bf16_segmented.argtypes = _lib.cocodc_sync_step_segmented.argtypes
 _lib.cocodc_sync_event_bf16.argtypes = _lib.cocodc_sync_event.argtypes
+_lib.cocodc_sync_event_bf16_segmented.argtypes = _lib.cocodc_sync_event_segmented.argtypes
 _lib.cocodc_select_fragments_bytes.argtypes = [C.c_int32, _P, _i64_p, C.c_int64, C.c_int32, C.POINTER(C.c_uint64),
                                                C.c_uint64, _P, _P, _P, C.c_size_t, _P]
 _i32_p = C.POINTER(C.c_int32)
@@ -551,6 +553,22 @@ def cocodc_sync_event_bf16(frags, n_total, recv_mask, theta_m, theta_m_send, the
                                        _ptr(delta_m_out), _i64(I_p), _i64(t_b), int(t_g), int(budget),
                                        C.byref(hp) if hp is not None else None, _ptr(R), _ptr(sel_out),
                                        _ptr(n_sel_out), _ptr(sums_out), wp, wb, _stream(stream))
+
+
+def cocodc_sync_event_bf16_segmented(segs, K, n_total, recv_mask, theta_m, theta_m_send, theta_g, momentum, delta_g,
+                                     delta_m_out, I_p, t_b, t_g, budget, hp, R, sel_out, n_sel_out, sums_out, workspace,
+                                     workspace_bytes=None, stream=None, S=None):
+    """cocodc_sync_event_segmented with 16-bit theta_m / theta_m_send / delta_m_out."""
+    sa, n = _segs(segs)
+    wp, wb = _ws(workspace, workspace_bytes)
+    mask = None
+    if recv_mask is not None:
+        mask = (C.c_uint8 * max(len(recv_mask), 1))(*[int(m) & 0xFF for m in recv_mask])
+    return _lib.cocodc_sync_event_bf16_segmented(sa, n if S is None else S, int(K), int(n_total), mask, _ptr(theta_m),
+                                                 _ptr(theta_m_send), _ptr(theta_g), _ptr(momentum), _ptr(delta_g),
+                                                 _ptr(delta_m_out), _i64(I_p), _i64(t_b), int(t_g), int(budget),
+                                                 C.byref(hp) if hp is not None else None, _ptr(R), _ptr(sel_out),
+                                                 _ptr(n_sel_out), _ptr(sums_out), wp, wb, _stream(stream))
 
 
 def cocodc_tile_elements(n_total):

@@ -574,6 +574,22 @@ int cocodc_sync_event_bf16(const cocodc_fragment_t* frags, int32_t K, uint64_t n
                              budget, hp, R, sel_out, n_sel_out, sums_out, workspace, workspace_bytes_, stream);
 }
 
+int cocodc_sync_event_bf16_segmented(const cocodc_segment_t* segs, int32_t S, int32_t K, uint64_t n_total,
+                                     const uint8_t* recv_mask, uint16_t* theta_m, const uint16_t* theta_m_send,
+                                     float* theta_g, float* momentum, const float* delta_g, uint16_t* delta_m_out,
+                                     const int64_t* I_p, const int64_t* t_b, int64_t t_g, int32_t budget,
+                                     const cocodc_hparams_t* hp, double* R, int32_t* sel_out, int32_t* n_sel_out,
+                                     double* sums_out, void* workspace, size_t workspace_bytes_, void* stream) {
+  if (!recv_mask) return COCODC_ERR_NULL;
+  if (int rc = sync_step_bf16_check(theta_m, theta_m_send, theta_g, momentum, delta_g, delta_m_out, I_p, t_b, budget,
+                                    hp, R, sel_out, n_sel_out, sums_out))
+    return rc;
+  Plan pl;
+  if (int rc = plan_segments(segs, S, K, n_total, I_p, t_b, &pl, recv_mask)) return rc;
+  return sync_step_bf16_impl(pl, K, n_total, theta_m, theta_m_send, theta_g, momentum, delta_g, delta_m_out, t_g,
+                             budget, hp, R, sel_out, n_sel_out, sums_out, workspace, workspace_bytes_, stream);
+}
+
 int cocodc_select_fragments_bytes(int32_t K, const double* R, const int64_t* t_b, int64_t t_g, int32_t H,
                                   const uint64_t* frag_bytes, uint64_t byte_budget, int32_t* sel_out,
                                   int32_t* n_sel_out, void* workspace, size_t workspace_bytes_, void* stream) {

@@ -353,3 +353,15 @@ def test_segmented_event_rejects_bad_arguments_before_any_device_work(B):
     assert event([1, 0], segs=[(0, 1000, 2)]) == B.COCODC_ERR_RANGE
     assert event([1, 1], wsb=wss - 1) == B.COCODC_ERR_WORKSPACE
     assert event([1, 2], pg=tm) == B.COCODC_ERR_ALIAS
+
+    def event16(mask, **kw):
+        a = dict(segs=segs, tm=tm, R=R, wsb=wss, pg=pg)
+        a.update(kw)
+        return B.cocodc_sync_event_bf16_segmented(a["segs"], K, n, mask, a["tm"], ts, tg, m, dg, a["pg"], I_p, t_b, 10,
+                                                  1, hp, a["R"], sel, nsel, sums, ws, a["wsb"], stream=0)
+    assert event16(None) == B.COCODC_ERR_NULL
+    assert event16([1, 0], tm=tm + 1) == B.COCODC_ERR_ALIGN
+    assert event16([1, 8]) == B.COCODC_ERR_RANGE
+    assert event16([1, 0], segs=[(0, 1000, 0), (999, 10, 1)]) == B.COCODC_ERR_RANGE
+    assert event16([1, 1], wsb=wss - 1) == B.COCODC_ERR_WORKSPACE
+    assert event16([1, 2], pg=dg) == B.COCODC_ERR_ALIAS

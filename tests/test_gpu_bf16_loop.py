@@ -338,3 +338,67 @@ def test_random_bf16_segmented_cases(B, ref, seed):
         assert len(out["sel_list"]) == min(c["budget"], K)
         if not np.isnan(Rr).any():
             U.compare_selection(out, ro, synth.Bookkeeping(t_g=1000, t_b=c["t_b"], I_p=c["I_p"]), H)
+
+
+def test_bf16_segmented_event_random_masks(B, ref):
+    """cocodc_sync_event_bf16_segmented: 24 random events on shuffled segment tables (the paper's configuration in
+    one call per event: strided shards, bf16 local parameters), marks for arrived and in-flight shards, both wire
+    formats; stored values bit-identical, untouched scores preserved, selection identical."""
+    from test_gpu_random_sweep import _random_case
+    rng = random.Random(5000)
+    for case in range(24):
+        c = _random_case(rng)
+        K = len(c["frags"])
+        segs = []
+        for p, (o, l) in enumerate(c["frags"]):
+            cuts = sorted(rng.randrange(0, l + 1) for _ in range(rng.choice([0, 0, 1, 2, 5]))) if l else []
+            edges = [0] + cuts + [l]
+            segs += [(o + a, b - a, p) for a, b in zip(edges, edges[1:])]
+        rng.shuffle(segs)
+        n_alloc = c["n"] + ((1 << 24) if c["pad_big"] else 0) + 8
+        mask = [int(rng.random() < rng.choice([0.0, 0.3, 1.0])) for _ in range(K)]
+        if case % 2:
+            mask = [m | (2 if rng.random() < 0.4 else 0) for m in mask]
+        hpk = dict(c["hp"], pg_format=rng.choice([0, 1]))
+        tau, H = hpk.pop("tau"), hpk.pop("H")
+        print(f"case bf16 segmented event #{case} S={len(segs)} K={K} n={n_alloc} mask={mask} "
+              f"view_off={c['view_off']} hp={hpk}", flush=True)
+        dev, host = _half_state(n_alloc, tau, H, 700 + case, c["amplified"], c["view_off"])
+        ghp, rhp = B.hparams(tau, H, **hpk), ref.hparams(tau, H, **hpk)
+        R0 = np.array([rng.choice([np.inf, 0.0, 0.5, 2.0, rng.random(), np.nan if K > 3 and rng.random() < 0.1 else 1.5])
+                       for _ in range(K)])
+        R_dev = torch.from_numpy(R0.copy()).cuda()
+        sums_dev = torch.full((K, 4), -3.0, dtype=torch.float64, device="cuda")
+        out = U.gpu_outputs(K)
+        pg, h_pg = _pg_buffers(n_alloc)
+        ws = B.new_workspace_segmented(len(segs), K, n_alloc)
+        rc = B.cocodc_sync_event_bf16_segmented(segs, K, n_alloc, mask, dev["theta_m"], dev["theta_m_send"],
+                                                dev["theta_g"], dev["momentum"], dev["delta_g"], pg, c["I_p"], c["t_b"],
+                                                1000, c["budget"], ghp, R_dev, out["sel"], out["n_sel"], sums_dev, ws)
+        assert rc == 0, B.cocodc_status_string(rc)
+        torch.cuda.synchronize()
+        R_ref, sums_ref = R0.copy(), np.full((K, 4), -3.0)
+        ro = ref.sync_event_bf16_segmented(segs, K, mask, host["theta_m"], host["theta_m_send"], host["theta_g"],
+                                           host["momentum"], host["delta_g"], h_pg, c["I_p"], c["t_b"], 1000,
+                                           c["budget"], rhp, R_ref, sums=sums_ref)
+        assert ro["rc"] == 0
+        _same_buffers(dev, host)
+        assert np.array_equal(_u16(pg), h_pg)
+        Rg = R_dev.cpu().numpy()
+        arrived = np.array([m & 1 for m in mask], bool)
+        assert np.array_equal(Rg[~arrived].view(np.uint64), R0[~arrived].view(np.uint64))
+        fin = arrived & np.isfinite(R_ref)
+        assert np.array_equal(np.isposinf(Rg[arrived]), np.isposinf(R_ref[arrived]))
+        assert np.array_equal(np.isnan(Rg[arrived]), np.isnan(R_ref[arrived]))
+        assert U.rel_err(Rg[fin], R_ref[fin]) <= U.SCORE_TOL_TIGHT
+        sg = sums_dev.cpu().numpy()
+        assert np.array_equal(sg[~arrived], sums_ref[~arrived])
+        ok = arrived[:, None] & np.isfinite(sums_ref)
+        assert U.rel_err(sg[ok], sums_ref[ok]) <= U.SCORE_TOL_TIGHT
+        n_sel = int(out["n_sel"].item())
+        assert n_sel == min(c["budget"], sum(1 for m in mask if not m & 2))
+        got = out["sel"][:n_sel].cpu().tolist()
+        rc_o, order = ref.select_fragments(Rg, c["t_b"], 1000, H, K)
+        assert rc_o == 0 and got == [q for q in order.tolist() if not mask[q] & 2][:n_sel]
+        if not np.isnan(R_ref).any() and not np.isnan(Rg).any():
+            assert got == ro["sel"].tolist()
