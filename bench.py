@@ -496,6 +496,7 @@ def main():
                             send_buf, R, sel, n_sel, ws)
         _, N_plan, h_plan = B.cocodc_loop_plan(loop)
         ev, host_s = [], 0.0
+        B.check(B.cocodc_profiler_enable(2 * args.loop_steps + 8))   # HIP events around the two streaming kernels
         torch.cuda.synchronize()
         t_all = time.perf_counter()
         for t in range(1, args.loop_steps + 1):
@@ -512,6 +513,18 @@ def main():
         torch.cuda.synchronize()
         t_all = time.perf_counter() - t_all
         B.cocodc_loop_destroy(loop)
+        n_k, k_ms = B.cocodc_profiler_collect(2 * args.loop_steps + 8)
+        B.cocodc_profiler_disable()
+        # kernel durations in launch order: per event the fused step on the arrived fragments (if any arrived and
+        # are not empty), then the walk over the chosen fragment (if one was chosen and is not empty)
+        it_ms, rec_k, snd_k = iter(k_ms[:max(n_k, 0)]), [0, 0.0], [0, 0.0]
+        for _, rec, snt in ev:
+            if sum(lens[p] for p in rec) > 0:
+                rec_k[0] += sum(lens[p] for p in rec)
+                rec_k[1] += next(it_ms, 0.0)
+            if snt >= 0 and lens[snt] > 0:
+                snd_k[0] += lens[snt]
+                snd_k[1] += next(it_ms, 0.0)
         rec_p = sum(lens[p] for _, rec, _ in ev for p in rec)
         snd_p = sum(lens[s] for _, _, s in ev if s >= 0)
         only_rec = [(dt, sum(lens[p] for p in rec)) for dt, rec, s in ev if rec and s < 0]
@@ -522,6 +535,8 @@ def main():
                "loop_seconds": round(t_all, 4), "host_seconds_inside_loop_step": round(host_s, 4),
                "receive_Gparams_per_s": round(sum(p for _, p in only_rec) / max(sum(d for d, _ in only_rec), 1e-12) / 1e9, 2),
                "send_Gparams_per_s": round(sum(p for _, p in only_snd) / max(sum(d for d, _ in only_snd), 1e-12) / 1e9, 2),
+               "receive_kernel_GBps": round(rec_bytes * rec_k[0] / max(rec_k[1], 1e-9) / 1e6, 1),
+               "send_kernel_GBps": round(snd_bytes * snd_k[0] / max(snd_k[1], 1e-9) / 1e6, 1),
                "dtype": "bf16 local parameters, fp32 global state" if args.bf16 else "f32",
                "receive_bytes_per_param": rec_bytes, "send_bytes_per_param": snd_bytes,
                "all_events_GBps": round(sum(rec_bytes * sum(lens[p] for p in rec) + (snd_bytes * lens[s] if s >= 0 else 0)
